@@ -1,0 +1,279 @@
+"""CPU oracle of the DoubleSqueeze step -- TEST INFRASTRUCTURE ONLY.
+
+Thin numpy/ctypes front end of ``ds_oracle.c`` (plain C, fp32 state, fp64 group sums).
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py``
+may import this package; the product path (``paper_1905_05957_amd``) never does, and this
+package imports nothing from it.
+
+The functions mirror Algorithm 1 of the paper: ``worker_compress`` (worker block),
+``server_aggregate_compress`` (parameter-server block), ``apply_update`` (model update),
+plus the compressors' encoders/decoders of Sections 3.2 and 5.1 for direct pinning.
+
+A message ("payload") is a dict of numpy arrays, one leading row axis:
+  SIGN     : sign_words [rows, W] uint64, scales [rows, S] float32
+  TOPK     : idx [rows, k] int32 (ascending), val [rows, k] float32
+  QSGD     : levels [rows, ceil(d/2)] uint8, sign_words [rows, W] uint64, scales [rows, Bq]
+  IDENTITY : dense [rows, d] float32
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass, field
+from typing import Optional
+
+import numpy as np
+
+IDENTITY, SIGN, TOPK, QSGD = 0, 1, 2, 3
+SERVER_STREAM = 0xFFFFFFFF
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ds_oracle.c")
+_LIB = os.path.join(_HERE, "libds_oracle.so")
+
+# -ffp-contract=off: no silent fused multiply-adds; every fma in the source is explicit.
+_CFLAGS = ["-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
+           "-Wall", "-Wextra"]
+
+
+def build(force: bool = False) -> str:
+    """Compile ds_oracle.c with gcc into libds_oracle.so (next to the source)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.run(["gcc", *_CFLAGS, "-o", tmp, _SRC, "-lm"], check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+class _Config(C.Structure):
+    _fields_ = [("comp", C.c_int32), ("n", C.c_int32), ("d", C.c_int64),
+                ("grad_bf16", C.c_int32), ("n_groups", C.c_int32),
+                ("group_off", C.POINTER(C.c_int64)), ("k", C.c_int64),
+                ("bucket", C.c_int32), ("levels", C.c_int32), ("seed", C.c_uint64)]
+
+
+class _Msg(C.Structure):
+    _fields_ = [("sign_words", C.c_void_p), ("scales", C.c_void_p), ("levels", C.c_void_p),
+                ("idx", C.c_void_p), ("val", C.c_void_p), ("dense", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = C.CDLL(build())
+        vp, i64, i32, u64, u32, f32 = (C.c_void_p, C.c_int64, C.c_int32, C.c_uint64,
+                                       C.c_uint32, C.c_float)
+        L.dso_philox4x32_10.argtypes = [vp, vp, vp]
+        L.dso_philox4x32_10.restype = None
+        L.dso_uniform24.argtypes = [u64, u64, u32, i64]
+        L.dso_uniform24.restype = f32
+        L.dso_sign_encode.argtypes = [vp, i64, vp, i32, vp, vp]
+        L.dso_sign_encode.restype = None
+        L.dso_sign_decode.argtypes = [vp, vp, i64, vp, i32, vp]
+        L.dso_sign_decode.restype = None
+        L.dso_topk_encode.argtypes = [vp, i64, i64, vp, vp]
+        L.dso_topk_encode.restype = C.c_int
+        L.dso_topk_decode.argtypes = [vp, vp, i64, i64, vp]
+        L.dso_topk_decode.restype = None
+        L.dso_qsgd_encode.argtypes = [vp, i64, i32, i32, u64, u64, u32, vp, vp, vp]
+        L.dso_qsgd_encode.restype = None
+        L.dso_qsgd_decode.argtypes = [vp, vp, vp, i64, i32, i32, vp]
+        L.dso_qsgd_decode.restype = None
+        L.dso_worker_compress.argtypes = [vp, u64, vp, i64, vp, i64, vp]
+        L.dso_worker_compress.restype = C.c_int
+        L.dso_server_aggregate_compress.argtypes = [vp, u64, vp, vp, vp]
+        L.dso_server_aggregate_compress.restype = C.c_int
+        L.dso_apply_update.argtypes = [vp, vp, vp, vp, f32, f32]
+        L.dso_apply_update.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data
+
+
+def _chk(a: np.ndarray, dtype, name: str) -> np.ndarray:
+    if a.dtype != np.dtype(dtype) or not a.flags["C_CONTIGUOUS"]:
+        raise TypeError(f"{name}: need C-contiguous {np.dtype(dtype)}, got {a.dtype}")
+    return a
+
+
+@dataclass
+class Config:
+    """What one DoubleSqueeze context is configured for (one compressor, n, d, grouping)."""
+    comp: int
+    n: int
+    d: int
+    grad_bf16: bool = False
+    group_off: Optional[np.ndarray] = None   # SIGN: int64 [S+1]
+    k: int = 0
+    bucket: int = 512
+    levels: int = 15
+    seed: int = 0
+    _keep: list = field(default_factory=list, repr=False)
+
+    def __post_init__(self):
+        if self.comp == SIGN:
+            if self.group_off is None:
+                self.group_off = np.array([0, self.d], dtype=np.int64)
+            self.group_off = np.ascontiguousarray(self.group_off, dtype=np.int64)
+            assert self.group_off[0] == 0 and self.group_off[-1] == self.d
+            assert np.all(np.diff(self.group_off) > 0)
+
+    @property
+    def n_groups(self) -> int:
+        return 0 if self.group_off is None else len(self.group_off) - 1
+
+    @property
+    def n_words(self) -> int:
+        return (self.d + 63) // 64
+
+    @property
+    def n_buckets(self) -> int:
+        return (self.d + self.bucket - 1) // self.bucket
+
+    def c_struct(self) -> _Config:
+        go = None
+        if self.group_off is not None:
+            go = self.group_off.ctypes.data_as(C.POINTER(C.c_int64))
+        return _Config(self.comp, self.n, self.d, int(self.grad_bf16), self.n_groups, go,
+                       self.k, self.bucket, self.levels, self.seed)
+
+
+def chunk_offsets(d: int, chunk: int) -> np.ndarray:
+    """Scale groups of `chunk` consecutive elements with a short last group."""
+    off = np.arange(0, d, chunk, dtype=np.int64)
+    return np.concatenate([off, np.array([d], dtype=np.int64)])
+
+
+def alloc_payload(cfg: Config, rows: int) -> dict:
+    d = cfg.d
+    if cfg.comp == IDENTITY:
+        return {"dense": np.zeros((rows, d), np.float32)}
+    if cfg.comp == SIGN:
+        return {"sign_words": np.zeros((rows, cfg.n_words), np.uint64),
+                "scales": np.zeros((rows, cfg.n_groups), np.float32)}
+    if cfg.comp == TOPK:
+        return {"idx": np.zeros((rows, cfg.k), np.int32), "val": np.zeros((rows, cfg.k), np.float32)}
+    if cfg.comp == QSGD:
+        return {"levels": np.zeros((rows, (d + 1) // 2), np.uint8),
+                "sign_words": np.zeros((rows, cfg.n_words), np.uint64),
+                "scales": np.zeros((rows, cfg.n_buckets), np.float32)}
+    raise ValueError(cfg.comp)
+
+
+_DT = {"sign_words": np.uint64, "scales": np.float32, "levels": np.uint8, "idx": np.int32,
+       "val": np.float32, "dense": np.float32}
+
+
+def _msgs(payload: dict, rows: int):
+    arr = (_Msg * rows)()
+    for r in range(rows):
+        kw = {}
+        for name, a in payload.items():
+            _chk(a, _DT[name], name)
+            assert a.shape[0] == rows, (name, a.shape, rows)
+            kw[name] = a[r].ctypes.data
+        arr[r] = _Msg(**kw)
+    return arr
+
+
+def _rc(rc: int, what: str):
+    if rc != 0:
+        raise RuntimeError(f"oracle {what} failed with code {rc}")
+
+
+def worker_compress(cfg: Config, step: int, g: np.ndarray, delta: np.ndarray) -> dict:
+    """Worker block of Algorithm 1 for all n workers; `delta` [n,d] is updated in place."""
+    n, d = cfg.n, cfg.d
+    _chk(g, np.uint16 if cfg.grad_bf16 else np.float32, "g")
+    _chk(delta, np.float32, "delta")
+    assert g.shape == (n, d) and delta.shape == (n, d)
+    out = alloc_payload(cfg, n)
+    msgs = _msgs(out, n)
+    cs = cfg.c_struct()
+    _rc(lib().dso_worker_compress(C.addressof(cs), step, g.ctypes.data, d, delta.ctypes.data, d,
+                                  C.addressof(msgs)), "worker_compress")
+    return out
+
+
+def server_aggregate_compress(cfg: Config, step: int, payload_w: dict, delta_s: np.ndarray) -> dict:
+    """Parameter-server block of Algorithm 1; `delta_s` [d] is updated in place."""
+    _chk(delta_s, np.float32, "delta_s")
+    assert delta_s.shape == (cfg.d,)
+    out = alloc_payload(cfg, 1)
+    mi, mo = _msgs(payload_w, cfg.n), _msgs(out, 1)
+    cs = cfg.c_struct()
+    _rc(lib().dso_server_aggregate_compress(C.addressof(cs), step, C.addressof(mi),
+                                            delta_s.ctypes.data, C.addressof(mo)), "server")
+    return out
+
+
+def apply_update(cfg: Config, payload_s: dict, x: np.ndarray, m: Optional[np.ndarray],
+                 gamma: float, beta: float = 0.0) -> None:
+    """Model update of Algorithm 1 (optionally through a momentum buffer m); in place."""
+    _chk(x, np.float32, "x")
+    if m is not None:
+        _chk(m, np.float32, "m")
+    ms = _msgs(payload_s, 1)
+    cs = cfg.c_struct()
+    _rc(lib().dso_apply_update(C.addressof(cs), C.addressof(ms), x.ctypes.data, _ptr(m),
+                               gamma, beta), "apply_update")
+
+
+def decode(cfg: Config, payload: dict, row: int = 0) -> np.ndarray:
+    """Dense fp32 vector a message row stands for (the decoder the server uses)."""
+    d = cfg.d
+    q = np.zeros(d, np.float32)
+    L = lib()
+    if cfg.comp == IDENTITY:
+        q[:] = payload["dense"][row]
+    elif cfg.comp == SIGN:
+        L.dso_sign_decode(payload["sign_words"][row].ctypes.data, payload["scales"][row].ctypes.data,
+                          d, cfg.group_off.ctypes.data, cfg.n_groups, q.ctypes.data)
+    elif cfg.comp == TOPK:
+        L.dso_topk_decode(payload["idx"][row].ctypes.data, payload["val"][row].ctypes.data,
+                          cfg.k, d, q.ctypes.data)
+    elif cfg.comp == QSGD:
+        L.dso_qsgd_decode(payload["levels"][row].ctypes.data, payload["sign_words"][row].ctypes.data,
+                          payload["scales"][row].ctypes.data, d, cfg.bucket, cfg.levels,
+                          q.ctypes.data)
+    return q
+
+
+def encode(cfg: Config, step: int, stream: int, v: np.ndarray) -> dict:
+    """Q[v] for one vector (one message row)."""
+    _chk(v, np.float32, "v")
+    assert v.shape == (cfg.d,)
+    out = alloc_payload(cfg, 1)
+    L = lib()
+    if cfg.comp == IDENTITY:
+        out["dense"][0] = v
+    elif cfg.comp == SIGN:
+        L.dso_sign_encode(v.ctypes.data, cfg.d, cfg.group_off.ctypes.data, cfg.n_groups,
+                          out["sign_words"].ctypes.data, out["scales"].ctypes.data)
+    elif cfg.comp == TOPK:
+        _rc(L.dso_topk_encode(v.ctypes.data, cfg.d, cfg.k, out["idx"].ctypes.data,
+                              out["val"].ctypes.data), "topk_encode")
+    elif cfg.comp == QSGD:
+        L.dso_qsgd_encode(v.ctypes.data, cfg.d, cfg.bucket, cfg.levels, cfg.seed, step, stream,
+                          out["levels"].ctypes.data, out["sign_words"].ctypes.data,
+                          out["scales"].ctypes.data)
+    return out
+
+
+def philox4x32_10(ctr, key) -> np.ndarray:
+    c = np.asarray(ctr, dtype=np.uint32).copy()
+    k = np.asarray(key, dtype=np.uint32).copy()
+    o = np.zeros(4, np.uint32)
+    lib().dso_philox4x32_10(c.ctypes.data, k.ctypes.data, o.ctypes.data)
+    return o
+
+
+def uniform24(seed: int, step: int, stream: int, j: int) -> float:
+    return float(lib().dso_uniform24(seed, step, stream, j))
