@@ -1,0 +1,177 @@
+/*
+ * ds.h -- C-ABI of the MI355X (gfx950) DoubleSqueeze step library, libds_hip.so.
+ *
+ * The three step calls follow Algorithm 1 and Section 3.1 of
+ *   Tang, Yu, Lian, Zhang, Liu, "DoubleSqueeze: Parallel Stochastic Gradient Descent with
+ *   Double-pass Error-Compensated Compression", ICML 2019,
+ * with the n workers laid out as the n rows of one [n, d] tensor on one GPU:
+ *
+ *   ds_worker_compress            "On worker", first block of Algorithm 1:
+ *                                 v_i = g_i + delta_i ; payload_i = Q[v_i] ;
+ *                                 delta_i <- v_i - Q[v_i]
+ *   ds_server_aggregate_compress  "On parameter server":
+ *                                 v = delta + (1/n) sum_i Q[v_i] ; payload = Q[v] ;
+ *                                 delta <- v - Q[v]
+ *   ds_apply_update               "On worker", second block:  x <- x - gamma Q[v]
+ *
+ * Q[.] is pluggable (Section 3.2, "Compression options"): 1-bit sign with a scale
+ * (Section 5.1 "1-bit compression"), top-k by absolute value (Section 5.1 "Top-k
+ * compression"), two-point unbiased randomised quantisation (Section 3.2 "Randomized
+ * Quantization", bucketed with an L2 norm), and the identity (Section 5.1 "Vanilla SGD").
+ *
+ * Conventions that hold for every call
+ *   - Every data pointer is DEVICE memory owned by the caller (base address 16-byte
+ *     aligned).  The library never frees or keeps a caller pointer after the call.
+ *     ds_config_t::seg_offsets is the one HOST pointer; it is copied by ds_create.
+ *   - State (delta, delta_s, x, m) is updated in place.
+ *   - Calls are asynchronous: they enqueue kernels on the given HIP stream
+ *     (hipStream_t passed as void*, NULL = the default stream) and return.
+ *   - Errors are return codes only.  Argument errors are detected before anything is
+ *     launched and leave every buffer untouched.
+ *   - `step` is the caller's iteration counter t; together with the seed it is the only
+ *     random state (counter-based Philox4x32-10), so a run can be resumed by passing the
+ *     same buffers and the next step.
+ *   - A context is bound to the device that was current in ds_create, holds scratch
+ *     memory sized for its configuration, and is not thread-safe.
+ *   - Non-finite inputs are not detected; they propagate.
+ *   - Arithmetic: fp32, one rounding per operation, no contraction; group sums of |v| and
+ *     v^2 are accumulated in fp64 and rounded once.
+ */
+#ifndef DS_H_
+#define DS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DS_OK = 0,
+    DS_ERR_NULL = 1,        /* a required pointer is NULL */
+    DS_ERR_SHAPE = 2,       /* n, d, strides, rows out of range */
+    DS_ERR_CONFIG = 3,      /* inconsistent configuration */
+    DS_ERR_ALIGN = 4,       /* a base pointer is not 16-byte aligned */
+    DS_ERR_UNSUPPORTED = 5, /* valid but not implemented */
+    DS_ERR_DEVICE = 6       /* a HIP runtime call failed */
+} ds_status_t;
+
+typedef enum {
+    DS_COMP_IDENTITY = 0,
+    DS_COMP_SIGN = 1,
+    DS_COMP_TOPK = 2,
+    DS_COMP_QSGD = 3
+} ds_compressor_t;
+
+typedef enum { DS_F32 = 0, DS_BF16 = 1 } ds_dtype_t;
+
+/* Scale groups of the 1-bit compressor (the paper uses one scale per vector, Section 5.1;
+ * per-segment and per-chunk scales are the workloads' refinement of the same rule). */
+typedef enum {
+    DS_SCALE_WHOLE = 0,     /* one group: the whole vector */
+    DS_SCALE_SEGMENTS = 1,  /* caller-given consecutive segments */
+    DS_SCALE_CHUNK = 2      /* fixed-size chunks, last one short */
+} ds_scale_mode_t;
+
+typedef struct {
+    int32_t comp;             /* ds_compressor_t */
+    int32_t n;                /* workers, >= 1 */
+    int64_t d;                /* elements per vector, 1 .. 2^31-1 */
+    int32_t grad_dtype;       /* ds_dtype_t of g; delta, x, m are always fp32 */
+    int32_t scale_mode;       /* SIGN: ds_scale_mode_t */
+    int64_t chunk;            /* SIGN + CHUNK: elements per chunk, >= 1 */
+    const int64_t *seg_offsets; /* SIGN + SEGMENTS: HOST array of n_seg+1 offsets,
+                                 [0] = 0, [n_seg] = d, strictly increasing; copied */
+    int32_t n_seg;
+    int32_t levels;           /* QSGD: s, number of non-zero levels, 1 .. 15 */
+    int64_t k;                /* TOPK: entries kept per vector, 1 .. d */
+    int32_t bucket;           /* QSGD: elements per bucket, a multiple of 64 */
+    int32_t reserved;
+    uint64_t seed;            /* QSGD: Philox key */
+} ds_config_t;
+
+typedef struct ds_ctx ds_ctx_t;
+
+/* One kept entry of the top-k message. */
+typedef struct { int32_t idx; float val; } ds_pair_t;
+
+/* A batch of `rows` compressed messages, row-major, every member a DEVICE pointer owned by
+ * the caller; members the compressor does not use are NULL.  S = number of scale groups,
+ * W = ceil(d/64), Bq = ceil(d/bucket).  Sizes come from ds_payload_sizes.
+ *   SIGN     sign_words [rows, W]: bit (j & 63) of word (j >> 6) is (v_j < 0), so zero and
+ *            negative zero carry bit 0; bits past d are 0.   scales [rows, S]: mean |v|
+ *            of each group.  Decoded element: bit ? -scale : +scale.
+ *   QSGD     levels [rows, ceil(d/2)]: 4-bit code of element j in byte j >> 1, low nibble
+ *            for even j; sign_words as above; scales [rows, Bq]: L2 norm of each bucket.
+ *            Decoded element: +-(code * (norm / s)).
+ *   TOPK     pairs [rows, k]: exactly k entries, ascending idx; the k largest |v| (order
+ *            of magnitudes = order of the bit patterns with the sign cleared), equal
+ *            magnitudes resolved towards the lower index.  Decoded: val at idx, else 0.
+ *   IDENTITY dense [rows, d]. */
+typedef struct {
+    uint64_t *sign_words;
+    float *scales;
+    uint8_t *levels;
+    ds_pair_t *pairs;
+    float *dense;
+} ds_payload_t;
+
+/* Creates a context on the current device and allocates its scratch memory there.
+ * Errors: NULL, SHAPE (n, d, k out of range), CONFIG (bad enum, offsets, bucket, levels),
+ * DEVICE (allocation failed). */
+ds_status_t ds_create(const ds_config_t *cfg, ds_ctx_t **out);
+
+/* Frees the context's scratch memory.  The caller must have synchronised the streams that
+ * used it.  NULL is accepted. */
+ds_status_t ds_destroy(ds_ctx_t *ctx);
+
+/* Bytes each ds_payload_t member needs for `rows` messages, in struct order
+ * (sign_words, scales, levels, pairs, dense); 0 for unused members. */
+ds_status_t ds_payload_sizes(const ds_ctx_t *ctx, int32_t rows, size_t bytes_out[5]);
+
+/* Worker block of Algorithm 1 for all n workers.
+ *   g      [n, g_row_stride]     gradients, cfg.grad_dtype (bf16 is widened exactly)
+ *   delta  [n, delta_row_stride] worker errors, fp32, read and overwritten
+ *   out    n messages
+ * Strides are in elements and >= d.  Rows that are 16-byte aligned take 128-bit loads;
+ * other rows take an element-wise path with the same results.
+ * QSGD draws its rounding from the stream (seed, step, worker i, element j). */
+ds_status_t ds_worker_compress(ds_ctx_t *ctx, uint64_t step, const void *g,
+                               int64_t g_row_stride, float *delta, int64_t delta_row_stride,
+                               const ds_payload_t *out, void *hip_stream);
+
+/* Parameter-server block of Algorithm 1.
+ *   in       n messages (as written by ds_worker_compress, or by anything that keeps the
+ *            layout above)
+ *   delta_s  [d] server error, fp32, read and overwritten
+ *   out      1 message
+ * The average is the chain acc = delta_s; acc = fma(decode(in_i), 1/n, acc) for
+ * i = 0 .. n-1.  QSGD uses the stream (seed, step, 0xFFFFFFFF, j). */
+ds_status_t ds_server_aggregate_compress(ds_ctx_t *ctx, uint64_t step, const ds_payload_t *in,
+                                         float *delta_s, const ds_payload_t *out,
+                                         void *hip_stream);
+
+/* Model update of Algorithm 1 from the server's message `srv` (1 row), q = decode(srv):
+ *   m == NULL:  x <- fma(-gamma, q, x)
+ *   m != NULL:  m <- fma(beta, m, q) ; x <- fma(-gamma, m, x)     (momentum; the paper's
+ *               experiments use none, this is the workloads' extension)
+ * x, m: [d] fp32, in place. */
+ds_status_t ds_apply_update(ds_ctx_t *ctx, const ds_payload_t *srv, float *x, float *m,
+                            float gamma, float beta, void *hip_stream);
+
+/* Decodes message `row` of a batch of `rows` messages into dense_out [d] (fp32): the
+ * decoder of Q[.] that the server and the update use. */
+ds_status_t ds_decompress(ds_ctx_t *ctx, const ds_payload_t *p, int32_t rows, int32_t row,
+                          float *dense_out, void *hip_stream);
+
+/* Static string for a status code. */
+const char *ds_status_string(ds_status_t s);
+
+/* Library version, "major.minor". */
+const char *ds_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DS_H_ */

@@ -1,0 +1,266 @@
+"""ctypes binding of libds_hip.so -- same names as the C-ABI in include/ds.h.
+
+Marshalling only: tensors' device pointers and the current HIP stream are handed to the
+library; nothing here computes.  There is no CPU fallback: if the library is missing the
+import of a symbol fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+import torch
+
+COMP_IDENTITY, COMP_SIGN, COMP_TOPK, COMP_QSGD = 0, 1, 2, 3
+SCALE_WHOLE, SCALE_SEGMENTS, SCALE_CHUNK = 0, 1, 2
+F32, BF16 = 0, 1
+
+_COMP = {"identity": COMP_IDENTITY, "sign": COMP_SIGN, "topk": COMP_TOPK, "qsgd": COMP_QSGD}
+_MODE = {"whole": SCALE_WHOLE, "segments": SCALE_SEGMENTS, "chunk": SCALE_CHUNK}
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIBNAME = "libds_hip.so"
+
+
+class DsError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(f"{what}: status {code} ({_status_string(code)})")
+
+
+class ds_config_t(C.Structure):
+    _fields_ = [("comp", C.c_int32), ("n", C.c_int32), ("d", C.c_int64), ("grad_dtype", C.c_int32),
+                ("scale_mode", C.c_int32), ("chunk", C.c_int64),
+                ("seg_offsets", C.POINTER(C.c_int64)), ("n_seg", C.c_int32), ("levels", C.c_int32),
+                ("k", C.c_int64), ("bucket", C.c_int32), ("reserved", C.c_int32),
+                ("seed", C.c_uint64)]
+
+
+class ds_payload_t(C.Structure):
+    _fields_ = [("sign_words", C.c_void_p), ("scales", C.c_void_p), ("levels", C.c_void_p),
+                ("pairs", C.c_void_p), ("dense", C.c_void_p)]
+
+
+EXPORTS = ["ds_create", "ds_destroy", "ds_payload_sizes", "ds_worker_compress",
+           "ds_server_aggregate_compress", "ds_apply_update", "ds_decompress", "ds_status_string",
+           "ds_version"]
+
+_lib = None
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, _LIBNAME)
+
+
+def load_library():
+    """Loads libds_hip.so from the package directory; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError(
+            f"{path} is missing: build it with `python -m paper_1905_05957_amd.build` "
+            "(there is no fallback path)")
+    L = C.CDLL(path)
+    vp, i64, i32, u64, f32 = C.c_void_p, C.c_int64, C.c_int32, C.c_uint64, C.c_float
+    L.ds_create.argtypes = [C.POINTER(ds_config_t), C.POINTER(vp)]
+    L.ds_destroy.argtypes = [vp]
+    L.ds_payload_sizes.argtypes = [vp, i32, C.POINTER(C.c_size_t)]
+    L.ds_worker_compress.argtypes = [vp, u64, vp, i64, vp, i64, C.POINTER(ds_payload_t), vp]
+    L.ds_server_aggregate_compress.argtypes = [vp, u64, C.POINTER(ds_payload_t), vp,
+                                               C.POINTER(ds_payload_t), vp]
+    L.ds_apply_update.argtypes = [vp, C.POINTER(ds_payload_t), vp, vp, f32, f32, vp]
+    L.ds_decompress.argtypes = [vp, C.POINTER(ds_payload_t), i32, i32, vp, vp]
+    for name in EXPORTS[:7]:
+        getattr(L, name).restype = C.c_int
+    L.ds_status_string.argtypes = [C.c_int]
+    L.ds_status_string.restype = C.c_char_p
+    L.ds_version.argtypes = []
+    L.ds_version.restype = C.c_char_p
+    _lib = L
+    return L
+
+
+def _status_string(code: int) -> str:
+    try:
+        return load_library().ds_status_string(code).decode()
+    except Exception:  # pragma: no cover
+        return "?"
+
+
+def _check(code: int, what: str):
+    if code != 0:
+        raise DsError(code, what)
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+class Payload:
+    """Device buffers of a batch of compressed messages (torch tensors, caller-owned)."""
+
+    def __init__(self, comp: int, rows: int, d: int, W: int, S: int, k: int, device):
+        self.comp, self.rows, self.d, self.k = comp, rows, d, k
+        self.sign_words = self.scales = self.levels = self.pairs = self.dense = None
+        if comp == COMP_IDENTITY:
+            self.dense = torch.zeros((rows, d), dtype=torch.float32, device=device)
+        elif comp == COMP_SIGN:
+            self.sign_words = torch.zeros((rows, W), dtype=torch.int64, device=device)
+            self.scales = torch.zeros((rows, S), dtype=torch.float32, device=device)
+        elif comp == COMP_TOPK:
+            self.pairs = torch.zeros((rows, k, 2), dtype=torch.int32, device=device)
+        elif comp == COMP_QSGD:
+            self.sign_words = torch.zeros((rows, W), dtype=torch.int64, device=device)
+            self.scales = torch.zeros((rows, S), dtype=torch.float32, device=device)
+            self.levels = torch.zeros((rows, (d + 1) // 2), dtype=torch.uint8, device=device)
+
+    def c_struct(self) -> ds_payload_t:
+        def p(t):
+            return None if t is None else t.data_ptr()
+        return ds_payload_t(p(self.sign_words), p(self.scales), p(self.levels), p(self.pairs),
+                            p(self.dense))
+
+    def tensors(self):
+        return {k: v for k, v in (("sign_words", self.sign_words), ("scales", self.scales),
+                                  ("levels", self.levels), ("pairs", self.pairs),
+                                  ("dense", self.dense)) if v is not None}
+
+    def to_numpy(self) -> dict:
+        """Host copy in the layout the tests compare (top-k pairs split into idx / val)."""
+        out = {}
+        if self.sign_words is not None:
+            out["sign_words"] = self.sign_words.cpu().numpy().view(np.uint64)
+        if self.scales is not None:
+            out["scales"] = self.scales.cpu().numpy()
+        if self.levels is not None:
+            out["levels"] = self.levels.cpu().numpy()
+        if self.pairs is not None:
+            pr = self.pairs.cpu().numpy()
+            out["idx"] = np.ascontiguousarray(pr[:, :, 0])
+            out["val"] = np.ascontiguousarray(pr[:, :, 1]).view(np.float32)
+        if self.dense is not None:
+            out["dense"] = self.dense.cpu().numpy()
+        return out
+
+    def load_numpy(self, host: dict) -> None:
+        """Uploads a host message batch (same layout as to_numpy) into these buffers."""
+        if self.sign_words is not None:
+            self.sign_words.copy_(torch.from_numpy(host["sign_words"].view(np.int64)))
+        if self.scales is not None:
+            self.scales.copy_(torch.from_numpy(host["scales"]))
+        if self.levels is not None:
+            self.levels.copy_(torch.from_numpy(host["levels"]))
+        if self.pairs is not None:
+            pr = np.stack([host["idx"], host["val"].view(np.int32)], axis=-1)
+            self.pairs.copy_(torch.from_numpy(np.ascontiguousarray(pr)))
+        if self.dense is not None:
+            self.dense.copy_(torch.from_numpy(host["dense"]))
+
+
+class Context:
+    """One configured DoubleSqueeze context (ds_ctx_t) on the current device."""
+
+    def __init__(self, comp, n: int, d: int, grad_dtype: str = "f32", scale_mode="whole",
+                 chunk: int = 0, seg_offsets=None, k: int = 0, bucket: int = 512, levels: int = 15,
+                 seed: int = 0):
+        L = load_library()
+        self.comp = _COMP[comp] if isinstance(comp, str) else int(comp)
+        self.n, self.d, self.k = int(n), int(d), int(k)
+        self.grad_dtype = BF16 if grad_dtype in ("bf16", BF16, torch.bfloat16) else F32
+        mode = _MODE[scale_mode] if isinstance(scale_mode, str) else int(scale_mode)
+        cfg = ds_config_t()
+        cfg.comp, cfg.n, cfg.d, cfg.grad_dtype = self.comp, self.n, self.d, self.grad_dtype
+        cfg.scale_mode, cfg.chunk = mode, int(chunk)
+        self._seg = None
+        if seg_offsets is not None:
+            self._seg = np.ascontiguousarray(seg_offsets, dtype=np.int64)
+            cfg.seg_offsets = self._seg.ctypes.data_as(C.POINTER(C.c_int64))
+            cfg.n_seg = len(self._seg) - 1
+        cfg.k, cfg.bucket, cfg.levels, cfg.seed = self.k, int(bucket), int(levels), int(seed)
+        self._h = C.c_void_p()
+        _check(L.ds_create(C.byref(cfg), C.byref(self._h)), "ds_create")
+        sizes = self.payload_sizes(1)
+        self.W = (self.d + 63) // 64
+        self.S = sizes[1] // 4
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            torch.cuda.synchronize()
+            load_library().ds_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):  # pragma: no cover
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def payload_sizes(self, rows: int):
+        out = (C.c_size_t * 5)()
+        _check(load_library().ds_payload_sizes(self._h, rows, out), "ds_payload_sizes")
+        return list(out)
+
+    def alloc_payload(self, rows: int, device="cuda") -> Payload:
+        return Payload(self.comp, rows, self.d, self.W, self.S, self.k, device)
+
+    def worker_compress(self, step: int, g: torch.Tensor, delta: torch.Tensor, out: Payload,
+                        stream=None):
+        s = out.c_struct()
+        _check(load_library().ds_worker_compress(self._h, step, g.data_ptr(), g.stride(0),
+                                                 delta.data_ptr(), delta.stride(0), C.byref(s),
+                                                 _stream_ptr(stream)), "ds_worker_compress")
+
+    def server_aggregate_compress(self, step: int, inp: Payload, delta_s: torch.Tensor,
+                                  out: Payload, stream=None):
+        a, b = inp.c_struct(), out.c_struct()
+        _check(load_library().ds_server_aggregate_compress(self._h, step, C.byref(a),
+                                                           delta_s.data_ptr(), C.byref(b),
+                                                           _stream_ptr(stream)),
+               "ds_server_aggregate_compress")
+
+    def apply_update(self, srv: Payload, x: torch.Tensor, m: Optional[torch.Tensor], gamma: float,
+                     beta: float = 0.0, stream=None):
+        s = srv.c_struct()
+        _check(load_library().ds_apply_update(self._h, C.byref(s), x.data_ptr(),
+                                              None if m is None else m.data_ptr(), gamma, beta,
+                                              _stream_ptr(stream)), "ds_apply_update")
+
+    def decompress(self, p: Payload, row: int, out: torch.Tensor, stream=None):
+        s = p.c_struct()
+        _check(load_library().ds_decompress(self._h, C.byref(s), p.rows, row, out.data_ptr(),
+                                            _stream_ptr(stream)), "ds_decompress")
+
+
+# -- the C names, as plain functions ------------------------------------------------------
+def ds_create(**kw) -> Context:
+    return Context(**kw)
+
+
+def ds_destroy(ctx: Context) -> None:
+    ctx.close()
+
+
+def ds_payload_sizes(ctx: Context, rows: int):
+    return ctx.payload_sizes(rows)
+
+
+def ds_worker_compress(ctx: Context, step, g, delta, out, stream=None):
+    ctx.worker_compress(step, g, delta, out, stream)
+
+
+def ds_server_aggregate_compress(ctx: Context, step, inp, delta_s, out, stream=None):
+    ctx.server_aggregate_compress(step, inp, delta_s, out, stream)
+
+
+def ds_apply_update(ctx: Context, srv, x, m, gamma, beta=0.0, stream=None):
+    ctx.apply_update(srv, x, m, gamma, beta, stream)
+
+
+def ds_decompress(ctx: Context, p, row, out, stream=None):
+    ctx.decompress(p, row, out, stream)

@@ -1,0 +1,249 @@
+// C-ABI of libds_hip.so: argument validation and dispatch to the per-compressor kernels.
+// The three step calls are the three blocks of Algorithm 1 of the DoubleSqueeze paper.
+#include "ds_internal.h"
+
+#include <new>
+
+namespace {
+
+bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+ds_status_t check_payload(const ds_ctx *c, const ds_payload_t *p)
+{
+    if (!p) return DS_ERR_NULL;
+    switch (c->cfg.comp) {
+    case DS_COMP_IDENTITY:
+        if (!p->dense) return DS_ERR_NULL;
+        if (misaligned(p->dense)) return DS_ERR_ALIGN;
+        break;
+    case DS_COMP_SIGN:
+        if (!p->sign_words || !p->scales) return DS_ERR_NULL;
+        if (misaligned(p->sign_words) || misaligned(p->scales)) return DS_ERR_ALIGN;
+        break;
+    case DS_COMP_TOPK:
+        if (!p->pairs) return DS_ERR_NULL;
+        if (misaligned(p->pairs)) return DS_ERR_ALIGN;
+        break;
+    case DS_COMP_QSGD:
+        if (!p->sign_words || !p->scales || !p->levels) return DS_ERR_NULL;
+        if (misaligned(p->sign_words) || misaligned(p->scales) || misaligned(p->levels)) return DS_ERR_ALIGN;
+        break;
+    }
+    return DS_OK;
+}
+
+// Binds the calling thread to the context's device for the duration of a call.
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = true;
+    explicit DeviceGuard(int dev)
+    {
+        if (hipGetDevice(&prev) != hipSuccess) { ok = false; return; }
+        if (prev != dev && hipSetDevice(dev) != hipSuccess) ok = false;
+        dev_ = dev;
+    }
+    ~DeviceGuard()
+    {
+        if (ok && prev != dev_) (void)hipSetDevice(prev);
+    }
+    int dev_ = -1;
+};
+
+}  // namespace
+
+extern "C" {
+
+const char *ds_status_string(ds_status_t s)
+{
+    switch (s) {
+    case DS_OK: return "ok";
+    case DS_ERR_NULL: return "a required pointer is NULL";
+    case DS_ERR_SHAPE: return "shape out of range";
+    case DS_ERR_CONFIG: return "inconsistent configuration";
+    case DS_ERR_ALIGN: return "base pointer not 16-byte aligned";
+    case DS_ERR_UNSUPPORTED: return "not supported";
+    case DS_ERR_DEVICE: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+const char *ds_version(void) { return "0.1"; }
+
+ds_status_t ds_create(const ds_config_t *cfg, ds_ctx_t **out)
+{
+    if (!cfg || !out) return DS_ERR_NULL;
+    *out = nullptr;
+    if (cfg->n < 1 || cfg->n > 65535) return DS_ERR_SHAPE;
+    if (cfg->d < 1 || cfg->d > 0x7FFFFFFFLL) return DS_ERR_SHAPE;
+    if (cfg->grad_dtype != DS_F32 && cfg->grad_dtype != DS_BF16) return DS_ERR_CONFIG;
+    switch (cfg->comp) {
+    case DS_COMP_IDENTITY:
+        break;
+    case DS_COMP_SIGN:
+        if (cfg->scale_mode == DS_SCALE_SEGMENTS) {
+            if (!cfg->seg_offsets) return DS_ERR_NULL;
+            if (cfg->n_seg < 1) return DS_ERR_CONFIG;
+            if (cfg->seg_offsets[0] != 0 || cfg->seg_offsets[cfg->n_seg] != cfg->d) return DS_ERR_CONFIG;
+            for (int32_t s = 0; s < cfg->n_seg; ++s)
+                if (cfg->seg_offsets[s + 1] <= cfg->seg_offsets[s]) return DS_ERR_CONFIG;
+        } else if (cfg->scale_mode == DS_SCALE_CHUNK) {
+            if (cfg->chunk < 1) return DS_ERR_CONFIG;
+        } else if (cfg->scale_mode != DS_SCALE_WHOLE) {
+            return DS_ERR_CONFIG;
+        }
+        break;
+    case DS_COMP_TOPK:
+        if (cfg->k < 1 || cfg->k > cfg->d) return DS_ERR_SHAPE;
+        break;
+    case DS_COMP_QSGD:
+        if (cfg->bucket < 64 || cfg->bucket % 64 != 0) return DS_ERR_CONFIG;
+        if (cfg->levels < 1 || cfg->levels > 15) return DS_ERR_CONFIG;
+        break;
+    default:
+        return DS_ERR_CONFIG;
+    }
+    ds_ctx *c = new (std::nothrow) ds_ctx();
+    if (!c) return DS_ERR_DEVICE;
+    c->cfg = *cfg;  // cfg.seg_offsets (host) is read by ds_sign_init and cleared after it
+    if (hipGetDevice(&c->device) != hipSuccess) { delete c; return DS_ERR_DEVICE; }
+    c->W = (cfg->d + 63) / 64;
+    c->n_tiles = (cfg->d + 2047) / 2048;
+    c->S = 0;
+    c->inv_n = 1.0f / static_cast<float>(cfg->n);
+    c->topk = nullptr;
+    c->sign_tb_mem = nullptr;
+    c->sign_partials = nullptr;
+    ds_status_t rc = DS_OK;
+    if (cfg->comp == DS_COMP_SIGN) {
+        rc = ds_sign_init(c);
+    } else if (cfg->comp == DS_COMP_QSGD) {
+        c->S = (cfg->d + cfg->bucket - 1) / cfg->bucket;
+    } else if (cfg->comp == DS_COMP_TOPK) {
+        rc = ds_topk_init(c);
+    }
+    c->cfg.seg_offsets = nullptr;
+    if (rc != DS_OK) {
+        ds_destroy(c);
+        return rc;
+    }
+    *out = c;
+    return DS_OK;
+}
+
+ds_status_t ds_destroy(ds_ctx_t *c)
+{
+    if (!c) return DS_OK;
+    DeviceGuard guard(c->device);
+    ds_sign_fini(c);
+    ds_topk_fini(c);
+    delete c;
+    return DS_OK;
+}
+
+ds_status_t ds_payload_sizes(const ds_ctx_t *c, int32_t rows, size_t bytes_out[5])
+{
+    if (!c || !bytes_out) return DS_ERR_NULL;
+    if (rows < 1) return DS_ERR_SHAPE;
+    const size_t r = static_cast<size_t>(rows), d = static_cast<size_t>(c->cfg.d);
+    for (int i = 0; i < 5; ++i) bytes_out[i] = 0;
+    switch (c->cfg.comp) {
+    case DS_COMP_IDENTITY:
+        bytes_out[4] = r * d * sizeof(float);
+        break;
+    case DS_COMP_SIGN:
+        bytes_out[0] = r * static_cast<size_t>(c->W) * sizeof(uint64_t);
+        bytes_out[1] = r * static_cast<size_t>(c->S) * sizeof(float);
+        break;
+    case DS_COMP_TOPK:
+        bytes_out[3] = r * static_cast<size_t>(c->cfg.k) * sizeof(ds_pair_t);
+        break;
+    case DS_COMP_QSGD:
+        bytes_out[0] = r * static_cast<size_t>(c->W) * sizeof(uint64_t);
+        bytes_out[1] = r * static_cast<size_t>(c->S) * sizeof(float);
+        bytes_out[2] = r * ((d + 1) / 2);
+        break;
+    }
+    return DS_OK;
+}
+
+ds_status_t ds_worker_compress(ds_ctx_t *c, uint64_t step, const void *g, int64_t g_row_stride, float *delta,
+                               int64_t delta_row_stride, const ds_payload_t *out, void *hip_stream)
+{
+    if (!c || !g || !delta) return DS_ERR_NULL;
+    ds_status_t rc = check_payload(c, out);
+    if (rc != DS_OK) return rc;
+    if (g_row_stride < c->cfg.d || delta_row_stride < c->cfg.d) return DS_ERR_SHAPE;
+    if (misaligned(g) || misaligned(delta)) return DS_ERR_ALIGN;
+    DeviceGuard guard(c->device);
+    if (!guard.ok) return DS_ERR_DEVICE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    switch (c->cfg.comp) {
+    case DS_COMP_IDENTITY: return ds_identity_worker(c, g, g_row_stride, delta, delta_row_stride, out, st);
+    case DS_COMP_SIGN: return ds_sign_worker(c, g, g_row_stride, delta, delta_row_stride, out, st);
+    case DS_COMP_TOPK: return ds_topk_worker(c, g, g_row_stride, delta, delta_row_stride, out, st);
+    case DS_COMP_QSGD: return ds_qsgd_worker(c, step, g, g_row_stride, delta, delta_row_stride, out, st);
+    }
+    return DS_ERR_CONFIG;
+}
+
+ds_status_t ds_server_aggregate_compress(ds_ctx_t *c, uint64_t step, const ds_payload_t *in, float *delta_s,
+                                         const ds_payload_t *out, void *hip_stream)
+{
+    if (!c || !delta_s) return DS_ERR_NULL;
+    ds_status_t rc = check_payload(c, in);
+    if (rc != DS_OK) return rc;
+    rc = check_payload(c, out);
+    if (rc != DS_OK) return rc;
+    if (misaligned(delta_s)) return DS_ERR_ALIGN;
+    DeviceGuard guard(c->device);
+    if (!guard.ok) return DS_ERR_DEVICE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    switch (c->cfg.comp) {
+    case DS_COMP_IDENTITY: return ds_identity_server(c, in, delta_s, out, st);
+    case DS_COMP_SIGN: return ds_sign_server(c, in, delta_s, out, st);
+    case DS_COMP_TOPK: return ds_topk_server(c, in, delta_s, out, st);
+    case DS_COMP_QSGD: return ds_qsgd_server(c, step, in, delta_s, out, st);
+    }
+    return DS_ERR_CONFIG;
+}
+
+ds_status_t ds_apply_update(ds_ctx_t *c, const ds_payload_t *srv, float *x, float *m, float gamma, float beta,
+                            void *hip_stream)
+{
+    if (!c || !x) return DS_ERR_NULL;
+    ds_status_t rc = check_payload(c, srv);
+    if (rc != DS_OK) return rc;
+    if (misaligned(x) || (m && misaligned(m))) return DS_ERR_ALIGN;
+    DeviceGuard guard(c->device);
+    if (!guard.ok) return DS_ERR_DEVICE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    switch (c->cfg.comp) {
+    case DS_COMP_IDENTITY: return ds_identity_update(c, srv, x, m, gamma, beta, st);
+    case DS_COMP_SIGN: return ds_sign_update(c, srv, x, m, gamma, beta, st);
+    case DS_COMP_TOPK: return ds_topk_update(c, srv, x, m, gamma, beta, st);
+    case DS_COMP_QSGD: return ds_qsgd_update(c, srv, x, m, gamma, beta, st);
+    }
+    return DS_ERR_CONFIG;
+}
+
+ds_status_t ds_decompress(ds_ctx_t *c, const ds_payload_t *p, int32_t rows, int32_t row, float *dense_out,
+                          void *hip_stream)
+{
+    if (!c || !dense_out) return DS_ERR_NULL;
+    ds_status_t rc = check_payload(c, p);
+    if (rc != DS_OK) return rc;
+    if (rows < 1 || row < 0 || row >= rows) return DS_ERR_SHAPE;
+    if (misaligned(dense_out)) return DS_ERR_ALIGN;
+    DeviceGuard guard(c->device);
+    if (!guard.ok) return DS_ERR_DEVICE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    switch (c->cfg.comp) {
+    case DS_COMP_IDENTITY: return ds_identity_decode(c, p, row, dense_out, st);
+    case DS_COMP_SIGN: return ds_sign_decode(c, p, row, dense_out, st);
+    case DS_COMP_TOPK: return ds_topk_decode(c, p, row, dense_out, st);
+    case DS_COMP_QSGD: return ds_qsgd_decode(c, p, row, dense_out, st);
+    }
+    return DS_ERR_CONFIG;
+}
+
+}  // extern "C"

@@ -1,0 +1,168 @@
+// Device-side helpers shared by the gfx950 kernels of the DoubleSqueeze step.
+//
+// Tile geometry used by every dense kernel: a workgroup of 256 threads (4 wavefronts of
+// 64 lanes) owns a tile of 2048 consecutive elements that starts at a multiple of 2048.
+// Thread t touches, for r = 0, 1, the four consecutive elements
+//     tile_base + r*1024 + 4*t + {0,1,2,3}
+// so that one wavefront instruction moves 64 x 16 B = 1 KiB of contiguous fp32 data
+// (128-bit loads), and a wavefront's 256 elements per r are exactly four 64-bit words of
+// the sign plane.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ds {
+
+constexpr int kBlock = 256;
+constexpr int kTile = 2048;
+constexpr int kHalf = 1024;
+constexpr int kR = 2;
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+__device__ __forceinline__ bool aligned8(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 7u) == 0; }
+
+// Four consecutive fp32 elements e..e+3 of a row, zero where e+c >= lim.
+__device__ __forceinline__ f32x4 ld4(const float *__restrict__ row, int64_t e, int64_t lim, bool vec)
+{
+    if (vec && e + 4 <= lim) return *reinterpret_cast<const f32x4 *>(row + e);
+    f32x4 r = {0.f, 0.f, 0.f, 0.f};
+    if (e < lim) r.x = row[e];
+    if (e + 1 < lim) r.y = row[e + 1];
+    if (e + 2 < lim) r.z = row[e + 2];
+    if (e + 3 < lim) r.w = row[e + 3];
+    return r;
+}
+
+// Same, streaming (read once): bypasses cache retention.
+__device__ __forceinline__ f32x4 ld4_stream(const float *__restrict__ row, int64_t e, int64_t lim, bool vec)
+{
+    if (vec && e + 4 <= lim) return __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(row + e));
+    return ld4(row, e, lim, false);
+}
+
+__device__ __forceinline__ float bf16_widen(uint32_t h) { return __uint_as_float(h << 16); }
+
+// Four consecutive bf16 elements widened exactly to fp32.
+__device__ __forceinline__ f32x4 ld4_bf16(const uint16_t *__restrict__ row, int64_t e, int64_t lim, bool vec)
+{
+    f32x4 r = {0.f, 0.f, 0.f, 0.f};
+    if (vec && e + 4 <= lim) {
+        u32x2 u = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(row + e));
+        r.x = __uint_as_float(u.x << 16);
+        r.y = __uint_as_float(u.x & 0xFFFF0000u);
+        r.z = __uint_as_float(u.y << 16);
+        r.w = __uint_as_float(u.y & 0xFFFF0000u);
+        return r;
+    }
+    if (e < lim) r.x = bf16_widen(row[e]);
+    if (e + 1 < lim) r.y = bf16_widen(row[e + 1]);
+    if (e + 2 < lim) r.z = bf16_widen(row[e + 2]);
+    if (e + 3 < lim) r.w = bf16_widen(row[e + 3]);
+    return r;
+}
+
+__device__ __forceinline__ void st4(float *__restrict__ row, int64_t e, int64_t lim, bool vec, f32x4 v)
+{
+    if (vec && e + 4 <= lim) { *reinterpret_cast<f32x4 *>(row + e) = v; return; }
+    if (e < lim) row[e] = v.x;
+    if (e + 1 < lim) row[e + 1] = v.y;
+    if (e + 2 < lim) row[e + 2] = v.z;
+    if (e + 3 < lim) row[e + 3] = v.w;
+}
+
+// Gradient row of either dtype.
+template <bool BF16>
+__device__ __forceinline__ f32x4 ld4_grad(const void *__restrict__ row, int64_t e, int64_t lim, bool vec)
+{
+    if constexpr (BF16) return ld4_bf16(static_cast<const uint16_t *>(row), e, lim, vec);
+    else return ld4_stream(static_cast<const float *>(row), e, lim, vec);
+}
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+__device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
+
+// Butterfly sum over the 64 lanes; every lane returns the same value, the order is fixed.
+__device__ __forceinline__ double wave_sum(double x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+
+// Sum over the 256 threads of the workgroup in a fixed order; lds4 holds 4 doubles.
+// Every thread returns the total.
+__device__ __forceinline__ double block_sum(double x, double *lds4)
+{
+    double w = wave_sum(x);
+    __syncthreads();                       // protect lds4 from the previous use
+    if (lane_id() == 0) lds4[wave_id()] = w;
+    __syncthreads();
+    return ((lds4[0] + lds4[1]) + lds4[2]) + lds4[3];
+}
+
+// Sign-plane packing by wavefront ballot.  Each lane passes the "negative" flags of its
+// four consecutive elements; the wavefront's 256 elements form 32 bytes of the plane
+// (element j of the wavefront = bit j&7 of byte j>>3).  Lane b < 32 returns byte b; lanes
+// 32..63 return the same bytes again (b & 31).
+__device__ __forceinline__ uint32_t wave_sign_byte(bool n0, bool n1, bool n2, bool n3)
+{
+    const uint64_t m0 = __ballot(n0), m1 = __ballot(n1), m2 = __ballot(n2), m3 = __ballot(n3);
+    const int sh = (lane_id() & 31) * 2;       // byte b covers lanes 2b and 2b+1
+    const uint32_t a0 = static_cast<uint32_t>(m0 >> sh) & 3u;
+    const uint32_t a1 = static_cast<uint32_t>(m1 >> sh) & 3u;
+    const uint32_t a2 = static_cast<uint32_t>(m2 >> sh) & 3u;
+    const uint32_t a3 = static_cast<uint32_t>(m3 >> sh) & 3u;
+    return (a0 & 1u) | ((a1 & 1u) << 1) | ((a2 & 1u) << 2) | ((a3 & 1u) << 3) |
+           ((a0 >> 1) << 4) | ((a1 >> 1) << 5) | ((a2 >> 1) << 6) | ((a3 >> 1) << 7);
+}
+
+// Writes the wavefront's 32 sign bytes for the 256 elements starting at element `first`
+// (a multiple of 256) of a row.  Only bytes whose first element is below `bit_lim` are
+// written; bit_lim is a multiple of 64: the end of the caller's chunk, or 64*ceil(d/64) at
+// the end of the row so that the pad bits of the last word are written as zero.
+__device__ __forceinline__ void store_sign_bytes(uint64_t *__restrict__ words_row, int64_t first,
+                                                 int64_t bit_lim, uint32_t byte)
+{
+    const int b = lane_id();
+    if (b < 32 && first + 8 * b < bit_lim)
+        reinterpret_cast<uint8_t *>(words_row)[(first >> 3) + b] = static_cast<uint8_t>(byte);
+}
+
+// The four sign bits of elements e..e+3 (e a multiple of 4) read from a sign plane.
+__device__ __forceinline__ uint32_t load_sign_nibble(const uint64_t *__restrict__ words_row, int64_t e)
+{
+    const uint32_t byte = reinterpret_cast<const uint8_t *>(words_row)[e >> 3];
+    return (byte >> (e & 4)) & 15u;
+}
+
+// Philox4x32-10 (Salmon et al., SC'11): ten rounds of two 32x32->64 multiplies.
+__device__ __forceinline__ u32x4 philox4x32_10(u32x4 c, uint32_t k0, uint32_t k1)
+{
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = static_cast<uint64_t>(0xD2511F53u) * c.x;
+        const uint64_t p1 = static_cast<uint64_t>(0xCD9E8D57u) * c.z;
+        u32x4 nx;
+        nx.x = static_cast<uint32_t>(p1 >> 32) ^ c.y ^ k0;
+        nx.y = static_cast<uint32_t>(p1);
+        nx.z = static_cast<uint32_t>(p0 >> 32) ^ c.w ^ k1;
+        nx.w = static_cast<uint32_t>(p0);
+        c = nx;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return c;
+}
+
+}  // namespace ds

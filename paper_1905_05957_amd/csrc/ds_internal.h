@@ -1,0 +1,89 @@
+// Host-side internals of libds_hip.so: the context and the per-compressor launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/ds.h"
+
+// Tables that map the fixed 2048-element tiles onto the scale groups of the 1-bit
+// compressor when a group does not fit one workgroup (whole vector, arbitrary segments,
+// odd chunk sizes).  A "piece" is a maximal run of elements inside one tile and one group;
+// pieces are numbered in element order, so piece p spans [piece_start[p], piece_start[p+1]).
+struct ds_sign_tables {
+    const int32_t *tile_piece_first;  // [n_tiles + 1]
+    const int64_t *piece_start;       // [n_pieces + 1]
+    const int32_t *piece_seg;         // [n_pieces]
+    const int32_t *seg_piece_first;   // [S + 1]
+    const int64_t *seg_off;           // [S + 1]
+    int32_t n_pieces;
+    int32_t n_seg;
+};
+
+struct ds_topk_scratch;  // defined in topk.hip
+
+struct ds_ctx {
+    ds_config_t cfg;
+    int device;
+    int64_t W;        // sign words per row
+    int64_t S;        // scale groups per row (SIGN) / buckets per row (QSGD)
+    int64_t n_tiles;  // ceil(d / 2048)
+    float inv_n;
+    // SIGN
+    bool sign_fused;  // every group is one chunk handled by one workgroup
+    ds_sign_tables sign_tb;
+    void *sign_tb_mem;     // one device allocation behind sign_tb
+    double *sign_partials; // [n, n_pieces] partial sums of |v|
+    // TOPK
+    ds_topk_scratch *topk;
+};
+
+#define DS_HIP_TRY(expr)                                 \
+    do {                                                 \
+        hipError_t e_ = (expr);                          \
+        if (e_ != hipSuccess) return DS_ERR_DEVICE;      \
+    } while (0)
+
+static inline ds_status_t ds_launch_status()
+{
+    return hipGetLastError() == hipSuccess ? DS_OK : DS_ERR_DEVICE;
+}
+
+// identity.hip
+ds_status_t ds_identity_worker(ds_ctx *c, const void *g, int64_t gs, float *delta, int64_t dstr,
+                               const ds_payload_t *out, hipStream_t st);
+ds_status_t ds_identity_server(ds_ctx *c, const ds_payload_t *in, float *delta_s,
+                               const ds_payload_t *out, hipStream_t st);
+ds_status_t ds_identity_update(ds_ctx *c, const ds_payload_t *srv, float *x, float *m, float gamma,
+                               float beta, hipStream_t st);
+ds_status_t ds_identity_decode(ds_ctx *c, const ds_payload_t *p, int32_t row, float *out, hipStream_t st);
+
+// sign.hip
+ds_status_t ds_sign_init(ds_ctx *c);
+void ds_sign_fini(ds_ctx *c);
+ds_status_t ds_sign_worker(ds_ctx *c, const void *g, int64_t gs, float *delta, int64_t dstr,
+                           const ds_payload_t *out, hipStream_t st);
+ds_status_t ds_sign_server(ds_ctx *c, const ds_payload_t *in, float *delta_s,
+                           const ds_payload_t *out, hipStream_t st);
+ds_status_t ds_sign_update(ds_ctx *c, const ds_payload_t *srv, float *x, float *m, float gamma,
+                           float beta, hipStream_t st);
+ds_status_t ds_sign_decode(ds_ctx *c, const ds_payload_t *p, int32_t row, float *out, hipStream_t st);
+
+// qsgd.hip
+ds_status_t ds_qsgd_worker(ds_ctx *c, uint64_t step, const void *g, int64_t gs, float *delta,
+                           int64_t dstr, const ds_payload_t *out, hipStream_t st);
+ds_status_t ds_qsgd_server(ds_ctx *c, uint64_t step, const ds_payload_t *in, float *delta_s,
+                           const ds_payload_t *out, hipStream_t st);
+ds_status_t ds_qsgd_update(ds_ctx *c, const ds_payload_t *srv, float *x, float *m, float gamma,
+                           float beta, hipStream_t st);
+ds_status_t ds_qsgd_decode(ds_ctx *c, const ds_payload_t *p, int32_t row, float *out, hipStream_t st);
+
+// topk.hip
+ds_status_t ds_topk_init(ds_ctx *c);
+void ds_topk_fini(ds_ctx *c);
+ds_status_t ds_topk_worker(ds_ctx *c, const void *g, int64_t gs, float *delta, int64_t dstr,
+                           const ds_payload_t *out, hipStream_t st);
+ds_status_t ds_topk_server(ds_ctx *c, const ds_payload_t *in, float *delta_s,
+                           const ds_payload_t *out, hipStream_t st);
+ds_status_t ds_topk_update(ds_ctx *c, const ds_payload_t *srv, float *x, float *m, float gamma,
+                           float beta, hipStream_t st);
+ds_status_t ds_topk_decode(ds_ctx *c, const ds_payload_t *p, int32_t row, float *out, hipStream_t st);

@@ -1,0 +1,581 @@
+// 1-bit compressor kernels (Section 3.2 "1-Bit Quantization", Section 5.1 "1-bit
+// compression" of the DoubleSqueeze paper) for the three calls of Algorithm 1.
+//
+// A message is a sign plane (bit = v < 0) plus one scale per group, scale = mean |v| of
+// the group, so that the decoded group has the l1 magnitude of v.
+//
+// Two routes:
+//  * fused (groups are chunks of <= 2048 elements, a multiple of 64): one workgroup holds
+//    a whole chunk in registers, so v = g + delta, sum |v|, the sign bits and
+//    delta' = v - Q[v] happen in ONE pass over HBM.
+//  * general (whole vector, arbitrary segments, other chunk sizes): the scale needs a sum
+//    over more than one workgroup, so pass 1 writes v into the delta buffer together with
+//    the sign bits and fp64 partial sums, a small kernel reduces them in a fixed order,
+//    and pass 2 turns v into delta' = v - Q[v].
+//
+// Sums of |v| are accumulated in fp64 and rounded once, in an order that depends only on
+// the shape, so results are bit-reproducible run to run.
+#include "ds_device.h"
+#include "ds_internal.h"
+
+#include <vector>
+
+using namespace ds;
+
+namespace {
+
+// ---------------------------------------------------------------------------------------
+// sources of the vector v that is being compressed
+// ---------------------------------------------------------------------------------------
+
+// Worker: v = g + delta  (Algorithm 1, "Compute the error-compensated stochastic gradient").
+template <bool BF16>
+struct WorkerSrc {
+    const void *g;
+    int64_t g_stride;
+    const float *delta;
+    int64_t delta_stride;
+
+    __device__ __forceinline__ const void *grow(int row) const
+    {
+        if constexpr (BF16) return static_cast<const uint16_t *>(g) + row * g_stride;
+        else return static_cast<const float *>(g) + row * g_stride;
+    }
+};
+
+// Server with one scale per chunk: v = delta_s + (1/n) sum_i Q[v_i], taken as the chain
+// acc = fma(q_i, 1/n, acc) over workers in ascending order (Algorithm 1, "Average all
+// gradients received from workers").
+struct ServerArgs {
+    const uint64_t *words_in;  // [n, W]
+    const float *scales_in;    // [n, S]
+    int32_t n;
+    int64_t W, S;
+    float inv_n;
+};
+
+__device__ __forceinline__ f32x4 chain4(f32x4 a, uint32_t nib, float s, float inv_n)
+{
+    a.x = __fmaf_rn((nib & 1u) ? -s : s, inv_n, a.x);
+    a.y = __fmaf_rn((nib & 2u) ? -s : s, inv_n, a.y);
+    a.z = __fmaf_rn((nib & 4u) ? -s : s, inv_n, a.z);
+    a.w = __fmaf_rn((nib & 8u) ? -s : s, inv_n, a.w);
+    return a;
+}
+
+__device__ __forceinline__ f32x4 zero_past(f32x4 v, int64_t e, int64_t lim)
+{
+    if (e + 0 >= lim) v.x = 0.f;
+    if (e + 1 >= lim) v.y = 0.f;
+    if (e + 2 >= lim) v.z = 0.f;
+    if (e + 3 >= lim) v.w = 0.f;
+    return v;
+}
+
+__device__ __forceinline__ double abs_sum4(f32x4 v)
+{
+    return ((static_cast<double>(fabsf(v.x)) + static_cast<double>(fabsf(v.y))) +
+            static_cast<double>(fabsf(v.z))) + static_cast<double>(fabsf(v.w));
+}
+
+// delta' = v - Q[v] with Q[v]_j = (v_j < 0) ? -scale : +scale
+__device__ __forceinline__ f32x4 sign_error4(f32x4 v, float s)
+{
+    f32x4 o;
+    o.x = v.x - ((v.x < 0.f) ? -s : s);
+    o.y = v.y - ((v.y < 0.f) ? -s : s);
+    o.z = v.z - ((v.z < 0.f) ? -s : s);
+    o.w = v.w - ((v.w < 0.f) ? -s : s);
+    return o;
+}
+
+// ---------------------------------------------------------------------------------------
+// fused route: one workgroup per chunk
+// ---------------------------------------------------------------------------------------
+// Common tail: scale from the held values, sign plane, error, stores.
+__device__ __forceinline__ void fused_finish(f32x4 (&v)[kR], int64_t base, int64_t lim, int64_t len,
+                                             float *__restrict__ err_row, bool err_vec,
+                                             uint64_t *__restrict__ words_row, int64_t bit_lim,
+                                             float *__restrict__ scale_out, double *lds4)
+{
+    double part = 0.0;
+#pragma unroll
+    for (int r = 0; r < kR; ++r) part += abs_sum4(v[r]);
+    const double total = block_sum(part, lds4);
+    const float scale = static_cast<float>(total / static_cast<double>(len));
+    if (threadIdx.x == 0) *scale_out = scale;
+#pragma unroll
+    for (int r = 0; r < kR; ++r) {
+        const int64_t wave_first = base + r * kHalf + wave_id() * 256;
+        const uint32_t byte = wave_sign_byte(v[r].x < 0.f, v[r].y < 0.f, v[r].z < 0.f, v[r].w < 0.f);
+        store_sign_bytes(words_row, wave_first, bit_lim, byte);
+        const int64_t e = base + r * kHalf + threadIdx.x * 4;
+        if (e < lim) st4(err_row, e, lim, err_vec, sign_error4(v[r], scale));
+    }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kBlock) void k_sign_chunk_worker(WorkerSrc<BF16> src, float *delta,
+                                                              int64_t d, int64_t chunk,
+                                                              uint64_t *words, int64_t W,
+                                                              float *scales, int64_t S)
+{
+    __shared__ double lds4[4];
+    const int row = blockIdx.y;
+    const int64_t ci = blockIdx.x;
+    const int64_t base = ci * chunk;
+    const int64_t lim = (base + chunk < d) ? base + chunk : d;
+    const void *grow = src.grow(row);
+    float *drow = delta + row * src.delta_stride;
+    const bool gvec = BF16 ? aligned8(grow) : aligned16(grow);
+    const bool dvec = aligned16(drow);
+    f32x4 v[kR];
+#pragma unroll
+    for (int r = 0; r < kR; ++r) {
+        const int64_t e = base + r * kHalf + threadIdx.x * 4;
+        v[r] = ld4_grad<BF16>(grow, e, lim, gvec) + ld4(drow, e, lim, dvec);
+    }
+    fused_finish(v, base, lim, lim - base, drow, dvec, words + row * W, (lim == d) ? W * 64 : lim,
+                 scales + row * S + ci, lds4);
+}
+
+__global__ __launch_bounds__(kBlock) void k_sign_chunk_server(ServerArgs a, float *delta_s, int64_t d,
+                                                              int64_t chunk, uint64_t *words_out,
+                                                              float *scales_out)
+{
+    __shared__ double lds4[4];
+    const int64_t ci = blockIdx.x;
+    const int64_t base = ci * chunk;
+    const int64_t lim = (base + chunk < d) ? base + chunk : d;
+    const bool dvec = aligned16(delta_s);
+    f32x4 v[kR];
+#pragma unroll
+    for (int r = 0; r < kR; ++r) {
+        const int64_t e = base + r * kHalf + threadIdx.x * 4;
+        v[r] = ld4(delta_s, e, lim, dvec);
+    }
+    for (int i = 0; i < a.n; ++i) {
+        const float s = a.scales_in[i * a.S + ci];
+        const uint64_t *wrow = a.words_in + i * a.W;
+#pragma unroll
+        for (int r = 0; r < kR; ++r) {
+            const int64_t e = base + r * kHalf + threadIdx.x * 4;
+            if (e < lim) v[r] = chain4(v[r], load_sign_nibble(wrow, e), s, a.inv_n);
+        }
+    }
+    // components past lim must stay zero: they count in the sum of |v|
+#pragma unroll
+    for (int r = 0; r < kR; ++r) v[r] = zero_past(v[r], base + r * kHalf + threadIdx.x * 4, lim);
+    fused_finish(v, base, lim, lim - base, delta_s, dvec, words_out, (lim == d) ? a.W * 64 : lim,
+                 scales_out + ci, lds4);
+}
+
+// x update from the server's message (Algorithm 1, "Update the local model"), optionally
+// through a momentum buffer.  One thread per 4 elements; OUT = write decoded q only.
+template <bool MOM, bool DECODE_ONLY>
+__global__ __launch_bounds__(kBlock) void k_sign_chunk_update(const uint64_t *__restrict__ words,
+                                                              const float *__restrict__ scales,
+                                                              int64_t chunk, float *x, float *m,
+                                                              int64_t d, float gamma, float beta)
+{
+    const int64_t e = (static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x) * 4;
+    if (e >= d) return;
+    const bool xvec = aligned16(x);
+    // chunk is a multiple of 4 on this route, so the four elements share a chunk;
+    // e < 2^31, so the chunk index is a 32-bit division
+    const float s = scales[static_cast<uint32_t>(e) / static_cast<uint32_t>(chunk)];
+    const uint32_t nib = load_sign_nibble(words, e);
+    f32x4 q = {(nib & 1u) ? -s : s, (nib & 2u) ? -s : s, (nib & 4u) ? -s : s, (nib & 8u) ? -s : s};
+    if constexpr (DECODE_ONLY) {
+        st4(x, e, d, xvec, q);
+    } else {
+        f32x4 xv = ld4(x, e, d, xvec);
+        if constexpr (MOM) {
+            const bool mvec = aligned16(m);
+            f32x4 mv = ld4(m, e, d, mvec);
+            mv.x = __fmaf_rn(beta, mv.x, q.x); mv.y = __fmaf_rn(beta, mv.y, q.y);
+            mv.z = __fmaf_rn(beta, mv.z, q.z); mv.w = __fmaf_rn(beta, mv.w, q.w);
+            st4(m, e, d, mvec, mv);
+            q = mv;
+        }
+        xv.x = __fmaf_rn(-gamma, q.x, xv.x); xv.y = __fmaf_rn(-gamma, q.y, xv.y);
+        xv.z = __fmaf_rn(-gamma, q.z, xv.z); xv.w = __fmaf_rn(-gamma, q.w, xv.w);
+        st4(x, e, d, xvec, xv);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// general route: tiles x pieces
+// ---------------------------------------------------------------------------------------
+// Group of element e, given the pieces [p0, p1) of its tile.
+__device__ __forceinline__ int32_t seg_of(const ds_sign_tables &tb, int32_t p0, int32_t p1, int64_t e)
+{
+    int32_t p = p0;
+    while (p + 1 < p1 && tb.piece_start[p + 1] <= e) ++p;
+    return tb.piece_seg[p];
+}
+
+__device__ __forceinline__ double masked_abs(float x, int64_t e, int64_t lo, int64_t hi)
+{
+    return (e >= lo && e < hi) ? static_cast<double>(fabsf(x)) : 0.0;
+}
+
+// Pass-1 tail: store v, sign bits, per-piece partial sums of |v|.
+__device__ __forceinline__ void pass1_finish(f32x4 (&v)[kR], int64_t base, int64_t d,
+                                             float *__restrict__ vrow, bool vvec,
+                                             uint64_t *__restrict__ words_row, int64_t bit_lim,
+                                             const ds_sign_tables &tb, int32_t p0, int32_t p1,
+                                             double *__restrict__ partial_row, double *lds4)
+{
+#pragma unroll
+    for (int r = 0; r < kR; ++r) {
+        const int64_t e = base + r * kHalf + threadIdx.x * 4;
+        if (e < d) st4(vrow, e, d, vvec, v[r]);
+        const int64_t wave_first = base + r * kHalf + wave_id() * 256;
+        const uint32_t byte = wave_sign_byte(v[r].x < 0.f, v[r].y < 0.f, v[r].z < 0.f, v[r].w < 0.f);
+        store_sign_bytes(words_row, wave_first, bit_lim, byte);
+    }
+    if (p1 - p0 == 1) {
+        double part = 0.0;
+#pragma unroll
+        for (int r = 0; r < kR; ++r) part += abs_sum4(v[r]);   // elements past d are zero
+        const double total = block_sum(part, lds4);
+        if (threadIdx.x == 0) partial_row[p0] = total;
+    } else {
+        for (int32_t p = p0; p < p1; ++p) {
+            const int64_t lo = tb.piece_start[p], hi = tb.piece_start[p + 1];
+            double part = 0.0;
+#pragma unroll
+            for (int r = 0; r < kR; ++r) {
+                const int64_t e = base + r * kHalf + threadIdx.x * 4;
+                part += ((masked_abs(v[r].x, e, lo, hi) + masked_abs(v[r].y, e + 1, lo, hi)) +
+                         masked_abs(v[r].z, e + 2, lo, hi)) + masked_abs(v[r].w, e + 3, lo, hi);
+            }
+            const double total = block_sum(part, lds4);
+            if (threadIdx.x == 0) partial_row[p] = total;
+        }
+    }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kBlock) void k_sign_pass1_worker(WorkerSrc<BF16> src, float *delta,
+                                                              int64_t d, uint64_t *words, int64_t W,
+                                                              ds_sign_tables tb, double *partials)
+{
+    __shared__ double lds4[4];
+    const int row = blockIdx.y;
+    const int64_t tile = blockIdx.x;
+    const int64_t base = tile * kTile;
+    const void *grow = src.grow(row);
+    float *drow = delta + row * src.delta_stride;
+    const bool gvec = BF16 ? aligned8(grow) : aligned16(grow);
+    const bool dvec = aligned16(drow);
+    f32x4 v[kR];
+#pragma unroll
+    for (int r = 0; r < kR; ++r) {
+        const int64_t e = base + r * kHalf + threadIdx.x * 4;
+        v[r] = ld4_grad<BF16>(grow, e, d, gvec) + ld4(drow, e, d, dvec);
+    }
+    pass1_finish(v, base, d, drow, dvec, words + row * W, W * 64, tb, tb.tile_piece_first[tile],
+                 tb.tile_piece_first[tile + 1], partials + static_cast<int64_t>(row) * tb.n_pieces, lds4);
+}
+
+__global__ __launch_bounds__(kBlock) void k_sign_pass1_server(ServerArgs a, float *delta_s, int64_t d,
+                                                              uint64_t *words_out, ds_sign_tables tb,
+                                                              double *partials)
+{
+    __shared__ double lds4[4];
+    const int64_t tile = blockIdx.x;
+    const int64_t base = tile * kTile;
+    const bool dvec = aligned16(delta_s);
+    const int32_t p0 = tb.tile_piece_first[tile], p1 = tb.tile_piece_first[tile + 1];
+    f32x4 v[kR];
+    int32_t seg[kR][4];
+#pragma unroll
+    for (int r = 0; r < kR; ++r) {
+        const int64_t e = base + r * kHalf + threadIdx.x * 4;
+        v[r] = ld4(delta_s, e, d, dvec);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) seg[r][c] = (e + c < d) ? seg_of(tb, p0, p1, e + c) : 0;
+    }
+    for (int i = 0; i < a.n; ++i) {
+        const uint64_t *wrow = a.words_in + i * a.W;
+        const float *srow = a.scales_in + i * a.S;
+#pragma unroll
+        for (int r = 0; r < kR; ++r) {
+            const int64_t e = base + r * kHalf + threadIdx.x * 4;
+            if (e < d) {
+                const uint32_t nib = load_sign_nibble(wrow, e);
+                const float s0 = srow[seg[r][0]], s1 = srow[seg[r][1]], s2 = srow[seg[r][2]], s3 = srow[seg[r][3]];
+                if (e + 0 < d) v[r].x = __fmaf_rn((nib & 1u) ? -s0 : s0, a.inv_n, v[r].x);
+                if (e + 1 < d) v[r].y = __fmaf_rn((nib & 2u) ? -s1 : s1, a.inv_n, v[r].y);
+                if (e + 2 < d) v[r].z = __fmaf_rn((nib & 4u) ? -s2 : s2, a.inv_n, v[r].z);
+                if (e + 3 < d) v[r].w = __fmaf_rn((nib & 8u) ? -s3 : s3, a.inv_n, v[r].w);
+            }
+        }
+    }
+    pass1_finish(v, base, d, delta_s, dvec, words_out, a.W * 64, tb, p0, p1, partials, lds4);
+}
+
+// scale[row][s] = (float)( sum of the group's partials / |group| ), fixed order.
+__global__ __launch_bounds__(kBlock) void k_sign_reduce(const double *__restrict__ partials,
+                                                        ds_sign_tables tb, float *scales, int64_t S)
+{
+    __shared__ double lds[kBlock];
+    const int32_t s = blockIdx.x;
+    const int row = blockIdx.y;
+    const double *prow = partials + static_cast<int64_t>(row) * tb.n_pieces;
+    const int32_t p0 = tb.seg_piece_first[s], p1 = tb.seg_piece_first[s + 1];
+    double acc = 0.0;
+    for (int32_t p = p0 + threadIdx.x; p < p1; p += kBlock) acc += prow[p];
+    lds[threadIdx.x] = acc;
+    __syncthreads();
+    for (int o = kBlock / 2; o > 0; o >>= 1) {
+        if (threadIdx.x < o) lds[threadIdx.x] += lds[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const double len = static_cast<double>(tb.seg_off[s + 1] - tb.seg_off[s]);
+        scales[row * S + s] = static_cast<float>(lds[0] / len);
+    }
+}
+
+// Pass 2: the buffer holds v; overwrite with delta' = v - Q[v].
+__global__ __launch_bounds__(kBlock) void k_sign_pass2(float *buf, int64_t stride, int64_t d,
+                                                       const float *__restrict__ scales, int64_t S,
+                                                       ds_sign_tables tb)
+{
+    const int row = blockIdx.y;
+    const int64_t tile = blockIdx.x;
+    const int64_t base = tile * kTile;
+    float *brow = buf + row * stride;
+    const float *srow = scales + row * S;
+    const bool vec = aligned16(brow);
+    const int32_t p0 = tb.tile_piece_first[tile], p1 = tb.tile_piece_first[tile + 1];
+#pragma unroll
+    for (int r = 0; r < kR; ++r) {
+        const int64_t e = base + r * kHalf + threadIdx.x * 4;
+        if (e >= d) continue;
+        f32x4 v = ld4(brow, e, d, vec);
+        if (p1 - p0 == 1) {
+            v = sign_error4(v, srow[tb.piece_seg[p0]]);
+        } else {
+            float s[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) s[c] = (e + c < d) ? srow[seg_of(tb, p0, p1, e + c)] : 0.f;
+            v.x = v.x - ((v.x < 0.f) ? -s[0] : s[0]);
+            v.y = v.y - ((v.y < 0.f) ? -s[1] : s[1]);
+            v.z = v.z - ((v.z < 0.f) ? -s[2] : s[2]);
+            v.w = v.w - ((v.w < 0.f) ? -s[3] : s[3]);
+        }
+        st4(brow, e, d, vec, v);
+    }
+}
+
+template <bool MOM, bool DECODE_ONLY>
+__global__ __launch_bounds__(kBlock) void k_sign_update(const uint64_t *__restrict__ words,
+                                                        const float *__restrict__ scales,
+                                                        ds_sign_tables tb, float *x, float *m,
+                                                        int64_t d, float gamma, float beta)
+{
+    const int64_t tile = blockIdx.x;
+    const int64_t base = tile * kTile;
+    const bool xvec = aligned16(x);
+    const int32_t p0 = tb.tile_piece_first[tile], p1 = tb.tile_piece_first[tile + 1];
+#pragma unroll
+    for (int r = 0; r < kR; ++r) {
+        const int64_t e = base + r * kHalf + threadIdx.x * 4;
+        if (e >= d) continue;
+        const uint32_t nib = load_sign_nibble(words, e);
+        float q[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const float s = (e + c < d) ? scales[seg_of(tb, p0, p1, e + c)] : 0.f;
+            q[c] = ((nib >> c) & 1u) ? -s : s;
+        }
+        if constexpr (DECODE_ONLY) {
+            st4(x, e, d, xvec, f32x4{q[0], q[1], q[2], q[3]});
+        } else {
+            f32x4 xv = ld4(x, e, d, xvec);
+            if constexpr (MOM) {
+                const bool mvec = aligned16(m);
+                f32x4 mv = ld4(m, e, d, mvec);
+                mv.x = __fmaf_rn(beta, mv.x, q[0]); mv.y = __fmaf_rn(beta, mv.y, q[1]);
+                mv.z = __fmaf_rn(beta, mv.z, q[2]); mv.w = __fmaf_rn(beta, mv.w, q[3]);
+                st4(m, e, d, mvec, mv);
+                q[0] = mv.x; q[1] = mv.y; q[2] = mv.z; q[3] = mv.w;
+            }
+            xv.x = __fmaf_rn(-gamma, q[0], xv.x); xv.y = __fmaf_rn(-gamma, q[1], xv.y);
+            xv.z = __fmaf_rn(-gamma, q[2], xv.z); xv.w = __fmaf_rn(-gamma, q[3], xv.w);
+            st4(x, e, d, xvec, xv);
+        }
+    }
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------
+ds_status_t ds_sign_init(ds_ctx *c)
+{
+    const ds_config_t &cfg = c->cfg;
+    const int64_t d = cfg.d;
+    c->sign_fused = false;
+    c->sign_tb_mem = nullptr;
+    c->sign_partials = nullptr;
+    std::vector<int64_t> seg_off;
+    if (cfg.scale_mode == DS_SCALE_WHOLE) {
+        seg_off = {0, d};
+    } else if (cfg.scale_mode == DS_SCALE_SEGMENTS) {
+        seg_off.assign(cfg.seg_offsets, cfg.seg_offsets + cfg.n_seg + 1);
+    } else {
+        if (cfg.chunk % 64 == 0 && cfg.chunk >= 256 && cfg.chunk <= kTile) {
+            c->sign_fused = true;
+            c->S = (d + cfg.chunk - 1) / cfg.chunk;
+            return DS_OK;
+        }
+        for (int64_t o = 0; o < d; o += cfg.chunk) seg_off.push_back(o);
+        seg_off.push_back(d);
+    }
+    const int64_t S = static_cast<int64_t>(seg_off.size()) - 1;
+    c->S = S;
+    const int64_t n_tiles = c->n_tiles;
+    std::vector<int32_t> tile_piece_first(n_tiles + 1), piece_seg, seg_piece_first(S + 1);
+    std::vector<int64_t> piece_start;
+    int64_t s = 0;
+    for (int64_t t = 0; t < n_tiles; ++t) {
+        const int64_t lo = t * kTile, hi = (lo + kTile < d) ? lo + kTile : d;
+        tile_piece_first[t] = static_cast<int32_t>(piece_start.size());
+        int64_t pos = lo;
+        while (pos < hi) {
+            while (seg_off[s + 1] <= pos) ++s;
+            if (pos == seg_off[s]) seg_piece_first[s] = static_cast<int32_t>(piece_start.size());
+            piece_start.push_back(pos);
+            piece_seg.push_back(static_cast<int32_t>(s));
+            pos = (seg_off[s + 1] < hi) ? seg_off[s + 1] : hi;
+        }
+    }
+    const int64_t n_pieces = static_cast<int64_t>(piece_seg.size());
+    if (n_pieces > 0x7FFFFFFF) return DS_ERR_SHAPE;
+    tile_piece_first[n_tiles] = static_cast<int32_t>(n_pieces);
+    seg_piece_first[S] = static_cast<int32_t>(n_pieces);
+    piece_start.push_back(d);
+
+    // one allocation: int64 arrays first (8-byte aligned), then the int32 arrays
+    const size_t b_ps = sizeof(int64_t) * (n_pieces + 1), b_so = sizeof(int64_t) * (S + 1);
+    const size_t b_tpf = sizeof(int32_t) * (n_tiles + 1), b_pseg = sizeof(int32_t) * n_pieces;
+    const size_t b_spf = sizeof(int32_t) * (S + 1);
+    char *mem = nullptr;
+    DS_HIP_TRY(hipMalloc(&mem, b_ps + b_so + b_tpf + b_pseg + b_spf));
+    c->sign_tb_mem = mem;
+    char *p = mem;
+    auto put = [&](const void *src, size_t bytes) -> const void * {
+        const void *at = p;
+        if (bytes) (void)hipMemcpy(p, src, bytes, hipMemcpyHostToDevice);
+        p += bytes;
+        return at;
+    };
+    c->sign_tb.piece_start = static_cast<const int64_t *>(put(piece_start.data(), b_ps));
+    c->sign_tb.seg_off = static_cast<const int64_t *>(put(seg_off.data(), b_so));
+    c->sign_tb.tile_piece_first = static_cast<const int32_t *>(put(tile_piece_first.data(), b_tpf));
+    c->sign_tb.piece_seg = static_cast<const int32_t *>(put(piece_seg.data(), b_pseg));
+    c->sign_tb.seg_piece_first = static_cast<const int32_t *>(put(seg_piece_first.data(), b_spf));
+    c->sign_tb.n_pieces = static_cast<int32_t>(n_pieces);
+    c->sign_tb.n_seg = static_cast<int32_t>(S);
+    if (hipGetLastError() != hipSuccess) return DS_ERR_DEVICE;
+    DS_HIP_TRY(hipMalloc(&c->sign_partials, sizeof(double) * n_pieces * static_cast<size_t>(cfg.n)));
+    return DS_OK;
+}
+
+void ds_sign_fini(ds_ctx *c)
+{
+    if (c->sign_tb_mem) (void)hipFree(c->sign_tb_mem);
+    if (c->sign_partials) (void)hipFree(c->sign_partials);
+    c->sign_tb_mem = nullptr;
+    c->sign_partials = nullptr;
+}
+
+ds_status_t ds_sign_worker(ds_ctx *c, const void *g, int64_t gs, float *delta, int64_t dstr,
+                           const ds_payload_t *out, hipStream_t st)
+{
+    const ds_config_t &cfg = c->cfg;
+    const bool bf16 = cfg.grad_dtype == DS_BF16;
+    if (c->sign_fused) {
+        dim3 grid(static_cast<unsigned>(c->S), static_cast<unsigned>(cfg.n));
+        if (bf16) {
+            WorkerSrc<true> src{g, gs, delta, dstr};
+            k_sign_chunk_worker<true><<<grid, kBlock, 0, st>>>(src, delta, cfg.d, cfg.chunk, out->sign_words,
+                                                               c->W, out->scales, c->S);
+        } else {
+            WorkerSrc<false> src{g, gs, delta, dstr};
+            k_sign_chunk_worker<false><<<grid, kBlock, 0, st>>>(src, delta, cfg.d, cfg.chunk, out->sign_words,
+                                                                c->W, out->scales, c->S);
+        }
+        return ds_launch_status();
+    }
+    dim3 grid(static_cast<unsigned>(c->n_tiles), static_cast<unsigned>(cfg.n));
+    if (bf16) {
+        WorkerSrc<true> src{g, gs, delta, dstr};
+        k_sign_pass1_worker<true><<<grid, kBlock, 0, st>>>(src, delta, cfg.d, out->sign_words, c->W, c->sign_tb,
+                                                           c->sign_partials);
+    } else {
+        WorkerSrc<false> src{g, gs, delta, dstr};
+        k_sign_pass1_worker<false><<<grid, kBlock, 0, st>>>(src, delta, cfg.d, out->sign_words, c->W, c->sign_tb,
+                                                            c->sign_partials);
+    }
+    k_sign_reduce<<<dim3(static_cast<unsigned>(c->S), static_cast<unsigned>(cfg.n)), kBlock, 0, st>>>(
+        c->sign_partials, c->sign_tb, out->scales, c->S);
+    k_sign_pass2<<<grid, kBlock, 0, st>>>(delta, dstr, cfg.d, out->scales, c->S, c->sign_tb);
+    return ds_launch_status();
+}
+
+ds_status_t ds_sign_server(ds_ctx *c, const ds_payload_t *in, float *delta_s, const ds_payload_t *out,
+                           hipStream_t st)
+{
+    const ds_config_t &cfg = c->cfg;
+    ServerArgs a{in->sign_words, in->scales, cfg.n, c->W, c->S, c->inv_n};
+    if (c->sign_fused) {
+        k_sign_chunk_server<<<dim3(static_cast<unsigned>(c->S)), kBlock, 0, st>>>(
+            a, delta_s, cfg.d, cfg.chunk, out->sign_words, out->scales);
+        return ds_launch_status();
+    }
+    dim3 grid(static_cast<unsigned>(c->n_tiles));
+    k_sign_pass1_server<<<grid, kBlock, 0, st>>>(a, delta_s, cfg.d, out->sign_words, c->sign_tb, c->sign_partials);
+    k_sign_reduce<<<dim3(static_cast<unsigned>(c->S), 1), kBlock, 0, st>>>(c->sign_partials, c->sign_tb,
+                                                                          out->scales, c->S);
+    k_sign_pass2<<<grid, kBlock, 0, st>>>(delta_s, cfg.d, cfg.d, out->scales, c->S, c->sign_tb);
+    return ds_launch_status();
+}
+
+template <bool DECODE_ONLY>
+static ds_status_t sign_update_impl(ds_ctx *c, const uint64_t *words, const float *scales, float *x, float *m,
+                                    float gamma, float beta, hipStream_t st)
+{
+    const ds_config_t &cfg = c->cfg;
+    if (c->sign_fused) {
+        const unsigned blocks = static_cast<unsigned>((cfg.d + kBlock * 4 - 1) / (kBlock * 4));
+        if (m && !DECODE_ONLY)
+            k_sign_chunk_update<true, false><<<blocks, kBlock, 0, st>>>(words, scales, cfg.chunk, x, m, cfg.d, gamma, beta);
+        else
+            k_sign_chunk_update<false, DECODE_ONLY><<<blocks, kBlock, 0, st>>>(words, scales, cfg.chunk, x, m, cfg.d, gamma, beta);
+    } else {
+        const unsigned blocks = static_cast<unsigned>(c->n_tiles);
+        if (m && !DECODE_ONLY)
+            k_sign_update<true, false><<<blocks, kBlock, 0, st>>>(words, scales, c->sign_tb, x, m, cfg.d, gamma, beta);
+        else
+            k_sign_update<false, DECODE_ONLY><<<blocks, kBlock, 0, st>>>(words, scales, c->sign_tb, x, m, cfg.d, gamma, beta);
+    }
+    return ds_launch_status();
+}
+
+ds_status_t ds_sign_update(ds_ctx *c, const ds_payload_t *srv, float *x, float *m, float gamma, float beta,
+                           hipStream_t st)
+{
+    return sign_update_impl<false>(c, srv->sign_words, srv->scales, x, m, gamma, beta, st);
+}
+
+ds_status_t ds_sign_decode(ds_ctx *c, const ds_payload_t *p, int32_t row, float *out, hipStream_t st)
+{
+    return sign_update_impl<true>(c, p->sign_words + row * c->W, p->scales + row * c->S, out, nullptr, 0.f, 0.f, st);
+}

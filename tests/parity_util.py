@@ -1,0 +1,130 @@
+"""Shared helpers of the GPU parity tests: build both sides from one Workload, run one
+DoubleSqueeze step on each from identical state, compare to the stated bar.
+
+Bar (per call, on identical inputs):
+  sign planes, level codes, top-k indices ........ bit-exact (pad bits included)
+  scales / bucket norms ........................... |a-b| <= 1e-6 |b|
+  delta, delta_s, x, m ............................ max|a-b| <= 1e-6 max|b| per row
+  top-k values .................................... equal as floats
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle as O
+import paper_1905_05957_amd as P
+
+REL = 1e-6
+
+
+def oracle_config(wl) -> O.Config:
+    comp = {"identity": O.IDENTITY, "sign": O.SIGN, "topk": O.TOPK, "qsgd": O.QSGD}[wl.comp]
+    return O.Config(comp, n=wl.n, d=wl.d, grad_bf16=(wl.grad_dtype == "bf16"),
+                    group_off=wl.group_offsets() if wl.comp == "sign" else None,
+                    k=wl.k, bucket=wl.bucket, levels=wl.levels, seed=wl.seed)
+
+
+def gpu_context(wl) -> P.Context:
+    return P.Context(wl.comp, wl.n, wl.d, grad_dtype=wl.grad_dtype, scale_mode=wl.scale_mode,
+                     chunk=wl.chunk,
+                     seg_offsets=wl.seg_offsets if wl.scale_mode == "segments" else None,
+                     k=wl.k, bucket=wl.bucket, levels=wl.levels, seed=wl.seed)
+
+
+def host_grad(g: torch.Tensor) -> np.ndarray:
+    """Contiguous host copy in the oracle's input format (bf16 -> uint16 bit patterns)."""
+    g = g.contiguous()
+    if g.dtype == torch.bfloat16:
+        return g.view(torch.int16).cpu().numpy().view(np.uint16)
+    return g.cpu().numpy()
+
+
+def assert_close_rows(a: np.ndarray, b: np.ndarray, what: str, rel: float = REL):
+    a2 = a.reshape(-1, a.shape[-1]) if a.ndim > 1 else a[None]
+    b2 = b.reshape(-1, b.shape[-1]) if b.ndim > 1 else b[None]
+    assert a2.shape == b2.shape, (what, a2.shape, b2.shape)
+    for r in range(a2.shape[0]):
+        ref = np.abs(b2[r]).max() if b2.shape[1] else 0.0
+        err = np.abs(a2[r].astype(np.float64) - b2[r].astype(np.float64)).max() if b2.shape[1] else 0.0
+        assert err <= rel * ref, f"{what} row {r}: max err {err:.3e} > {rel:g} * {ref:.3e}"
+
+
+def assert_payload_equal(gpu: dict, ref: dict, what: str):
+    assert set(gpu) == set(ref), (what, set(gpu), set(ref))
+    for key in ref:
+        a, b = gpu[key], ref[key]
+        assert a.shape == b.shape, (what, key, a.shape, b.shape)
+        if key in ("sign_words", "levels", "idx"):
+            if not np.array_equal(a, b):
+                bad = np.argwhere(a != b)
+                raise AssertionError(f"{what}.{key}: {len(bad)} mismatches, first at {bad[0]}: "
+                                     f"gpu {a[tuple(bad[0])]} ref {b[tuple(bad[0])]}")
+        elif key == "scales":
+            err = np.abs(a.astype(np.float64) - b.astype(np.float64))
+            assert np.all(err <= REL * np.abs(b)), f"{what}.scales: max rel err {np.max(err / np.maximum(np.abs(b), 1e-300)):.3e}"
+        elif key == "val":
+            assert np.array_equal(a, b), f"{what}.val differs"      # by value: -0 == +0
+        elif key == "dense":
+            assert_close_rows(a, b, f"{what}.dense")
+    return True
+
+
+class Pair:
+    """GPU state + the means to run one compared step."""
+
+    def __init__(self, wl, device):
+        self.wl, self.dev = wl, device
+        self.ctx = gpu_context(wl)
+        self.cfg = oracle_config(wl)
+        self.delta = wl.initial_delta(device)
+        self.delta_s = torch.zeros(wl.d, dtype=torch.float32, device=device)
+        self.x = wl.initial_x(device)
+        self.m = torch.zeros(wl.d, dtype=torch.float32, device=device) if wl.beta is not None else None
+        self.pw = self.ctx.alloc_payload(wl.n, device)
+        self.ps = self.ctx.alloc_payload(1, device)
+
+    def gpu_step(self, t: int, g: torch.Tensor):
+        self.ctx.worker_compress(t, g, self.delta, self.pw)
+        self.ctx.server_aggregate_compress(t, self.pw, self.delta_s, self.ps)
+        self.ctx.apply_update(self.ps, self.x, self.m, self.wl.gamma,
+                              0.0 if self.wl.beta is None else self.wl.beta)
+
+    def compared_step(self, t: int, g: torch.Tensor, tag: str = ""):
+        """One step on the GPU and, call by call from the same inputs, on the oracle."""
+        wl, cfg = self.wl, self.cfg
+        tag = f"{wl.name}{tag} t={t}"
+        # ---- worker ----
+        h_delta = self.delta.cpu().numpy().copy()
+        h_g = host_grad(g)
+        self.ctx.worker_compress(t, g, self.delta, self.pw)
+        ref_pw = O.worker_compress(cfg, t, h_g, h_delta)
+        gpu_pw = self.pw.to_numpy()
+        assert_payload_equal(gpu_pw, ref_pw, tag + " worker payload")
+        assert_close_rows(self.delta.cpu().numpy(), h_delta, tag + " delta")
+        # ---- server (the oracle is fed the GPU's worker messages) ----
+        h_ds = self.delta_s.cpu().numpy().copy()
+        self.ctx.server_aggregate_compress(t, self.pw, self.delta_s, self.ps)
+        ref_ps = O.server_aggregate_compress(cfg, t, gpu_pw, h_ds)
+        gpu_ps = self.ps.to_numpy()
+        assert_payload_equal(gpu_ps, ref_ps, tag + " server payload")
+        assert_close_rows(self.delta_s.cpu().numpy(), h_ds, tag + " delta_s")
+        # ---- update (the oracle is fed the GPU's server message) ----
+        h_x = self.x.cpu().numpy().copy()
+        h_m = None if self.m is None else self.m.cpu().numpy().copy()
+        beta = 0.0 if wl.beta is None else wl.beta
+        self.ctx.apply_update(self.ps, self.x, self.m, wl.gamma, beta)
+        O.apply_update(cfg, gpu_ps, h_x, h_m, wl.gamma, beta)
+        assert_close_rows(self.x.cpu().numpy(), h_x, tag + " x")
+        if h_m is not None:
+            assert_close_rows(self.m.cpu().numpy(), h_m, tag + " m")
+        # ---- the decoder the server uses ----
+        dec = torch.empty(wl.d, dtype=torch.float32, device=self.dev)
+        self.ctx.decompress(self.ps, 0, dec)
+        assert_close_rows(dec.cpu().numpy(), O.decode(cfg, gpu_ps, 0), tag + " decode(server)")
+        row = wl.n - 1
+        self.ctx.decompress(self.pw, row, dec)
+        assert_close_rows(dec.cpu().numpy(), O.decode(cfg, gpu_pw, row), tag + " decode(worker)")
+
+    def close(self):
+        self.ctx.close()
