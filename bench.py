@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Throughput of the DoubleSqueeze step on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic gradients:
+ds_worker_compress (n workers) + ds_server_aggregate_compress + ds_apply_update, i.e. one
+iteration of Algorithm 1 of the paper without the gradient computation and the two sends.
+Inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` = gradient elements (n*d) per second of the headline
+workload; `roofline` prices the dominant kernel (the worker pass) in algorithmic HBM bytes
+against the 8 TB/s peak, timed live with HIP events on the launch stream; `cpu_baseline` is
+the CPU oracle timed on this host on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(wl, S: int) -> dict:
+    """HBM bytes the method must move per step at the three-call boundary: read g and
+    delta once, write delta once, write/read every message once, read/write x (and m) once."""
+    n, d = wl.n, wl.d
+    gb = 2 if wl.grad_dtype == "bf16" else 4
+    W8 = 8 * ((d + 63) // 64)
+    if wl.comp == "sign":
+        msg = W8 + 4 * S
+    elif wl.comp == "qsgd":
+        msg = W8 + 4 * S + (d + 1) // 2
+    elif wl.comp == "topk":
+        msg = 8 * wl.k
+    else:
+        msg = 4 * d
+    worker = n * (d * (gb + 4 + 4) + msg)
+    server = n * msg + d * 8 + msg
+    if wl.comp == "topk":
+        # the server still reads and writes its dense error once; the update touches k entries
+        update = msg + 8 * wl.k * (2 if wl.beta is not None else 1)
+    else:
+        update = msg + d * (16 if wl.beta is not None else 8)
+    return {"worker": worker, "server": server, "update": update, "total": worker + server + update}
+
+
+def make_workload(name: str):
+    import ds_workloads as W
+    return {"c2": W.c2, "c3": W.c3, "c4": W.c4, "c5": W.c5}[name]()
+
+
+def run_gpu(wl, steps: int, warmup: int, sets: int = 2):
+    import torch
+    import paper_1905_05957_amd as P
+
+    dev = torch.device("cuda:0")
+    ctx = P.Context(wl.comp, wl.n, wl.d, grad_dtype=wl.grad_dtype, scale_mode=wl.scale_mode,
+                    chunk=wl.chunk, seg_offsets=wl.seg_offsets if wl.scale_mode == "segments" else None,
+                    k=wl.k, bucket=wl.bucket, levels=wl.levels, seed=wl.seed)
+    grads = [wl.gradients(s, dev) for s in range(sets)]
+    delta = wl.initial_delta(dev)
+    delta_s = torch.zeros(wl.d, dtype=torch.float32, device=dev)
+    x = wl.initial_x(dev)
+    m = torch.zeros(wl.d, dtype=torch.float32, device=dev) if wl.beta is not None else None
+    pw, ps = ctx.alloc_payload(wl.n, dev), ctx.alloc_payload(1, dev)
+    beta = 0.0 if wl.beta is None else wl.beta
+    stream = torch.cuda.current_stream()
+
+    def step(t, ev=None):
+        g = grads[t % sets]
+        if ev is not None:
+            ev[0].record(stream)
+        ctx.worker_compress(t, g, delta, pw)
+        if ev is not None:
+            ev[1].record(stream)
+        ctx.server_aggregate_compress(t, pw, delta_s, ps)
+        if ev is not None:
+            ev[2].record(stream)
+        ctx.apply_update(ps, x, m, wl.gamma, beta)
+        if ev is not None:
+            ev[3].record(stream)
+
+    for t in range(warmup):
+        step(t)
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(steps):
+        step(warmup + t, evs[t])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    stage = [0.0, 0.0, 0.0]
+    for ev in evs:
+        for s in range(3):
+            stage[s] += ev[s].elapsed_time(ev[s + 1])
+    stage_ms = [v / steps for v in stage]
+    S = ctx.S
+    ctx.close()
+    return {"ms_per_step": wall * 1e3 / steps, "stage_ms": stage_ms, "S": S}
+
+
+def run_oracle_sample(wl, target_elems: int):
+    """The CPU oracle, as it stands, on the first d' elements of every row (d' chosen so that
+    n*d' is about target_elems, cut at a scale-group / bucket boundary); one full step."""
+    import numpy as np
+    import torch
+    import dataclasses
+    import oracle as O
+
+    dq = max(1, min(wl.d, target_elems // wl.n))
+    unit = {"sign": wl.chunk if wl.scale_mode == "chunk" else 64, "qsgd": wl.bucket}.get(wl.comp, 64)
+    dq = max(unit, (dq // unit) * unit)
+    dq = min(dq, wl.d)
+    sub = dataclasses.replace(wl, d=dq, k=max(1, wl.k * dq // wl.d) if wl.k else 0)
+    if wl.seg_offsets is not None:
+        off = wl.seg_offsets[wl.seg_offsets < dq]
+        sub.seg_offsets = np.concatenate([off, [dq]]).astype(np.int64)
+        sub.seg_sigma = wl.seg_sigma[: len(off)]
+    comp = {"identity": O.IDENTITY, "sign": O.SIGN, "topk": O.TOPK, "qsgd": O.QSGD}[sub.comp]
+    cfg = O.Config(comp, n=sub.n, d=dq, grad_bf16=(sub.grad_dtype == "bf16"),
+                   group_off=sub.group_offsets() if sub.comp == "sign" else None, k=sub.k,
+                   bucket=sub.bucket, levels=sub.levels, seed=sub.seed)
+    g = sub.gradients(0, "cpu")
+    hg = g.view(torch.int16).numpy().view(np.uint16) if g.dtype == torch.bfloat16 else g.numpy()
+    delta = sub.initial_delta("cpu").numpy()
+    delta_s = np.zeros(dq, np.float32)
+    x = sub.initial_x("cpu").numpy()
+    m = np.zeros(dq, np.float32) if sub.beta is not None else None
+    O.lib()
+    t0 = time.perf_counter()
+    pw = O.worker_compress(cfg, 0, hg, delta)
+    ps = O.server_aggregate_compress(cfg, 0, pw, delta_s)
+    O.apply_update(cfg, ps, x, m, sub.gamma, 0.0 if sub.beta is None else sub.beta)
+    dt = time.perf_counter() - t0
+    return {"value": sub.n * dq / dt, "unit": "gradient elements/s", "cores": 1, "kind": "oracle",
+            "sample": f"one full step on the first {dq} of {wl.d} elements of all {wl.n} rows "
+                      f"({dt:.1f} s, single thread)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c5", choices=["c2", "c3", "c4", "c5"])
+    ap.add_argument("--others", default="c2,c3,c4", help="further workloads reported in the same line ('' = none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-elems", type=int, default=400_000_000)
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (n workers are rows of one tensor); "
+              "--gpus above 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+
+    def measure(name, steps, warmup):
+        wl = make_workload(name)
+        r = run_gpu(wl, steps, warmup)
+        ab = algorithmic_bytes(wl, r["S"])
+        ms = r["ms_per_step"]
+        wk_ms = r["stage_ms"][0]
+        out = {
+            "workload": wl.name, "n": wl.n, "d": wl.d, "ms_per_step": ms,
+            "value": wl.n * wl.d / (ms * 1e-3),
+            "stage_ms": {"worker": r["stage_ms"][0], "server": r["stage_ms"][1], "update": r["stage_ms"][2]},
+            "algorithmic_bytes_per_step": ab["total"],
+            "step_hbm_GBs": ab["total"] / (ms * 1e-3) / 1e9,
+            "step_frac_of_peak": ab["total"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "roofline": {"bound": "hbm", "kernel": "worker pass (ds_worker_compress)",
+                         "achieved": ab["worker"] / (wk_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": ab["worker"] / (wk_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None},
+        }
+        return wl, out
+
+    wl, head = measure(a.workload, a.steps, a.warmup)
+    others = []
+    for name in [s for s in a.others.split(",") if s and s != a.workload]:
+        try:
+            _, o = measure(name, max(5, a.steps // 2), max(2, a.warmup // 2))
+            others.append(o)
+        except Exception as e:  # a workload whose compressor is not built yet
+            others.append({"workload": name, "error": str(e)})
+        torch.cuda.empty_cache()
+
+    line = {
+        "metric": "DoubleSqueeze step: gradient elements/s (n*d)", "value": head["value"],
+        "unit": "gradient elements/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": head["workload"], "n_workers": wl.n, "d": wl.d,
+                   "grad_dtype": wl.grad_dtype, "compressor": wl.comp},
+        "stage_ms": head["stage_ms"],
+        "algorithmic_bytes_per_step": head["algorithmic_bytes_per_step"],
+        "step_hbm_GBs": head["step_hbm_GBs"], "step_frac_of_peak": head["step_frac_of_peak"],
+        "roofline": head["roofline"],
+        "other_workloads": others,
+    }
+    if not a.no_cpu_baseline:
+        line["cpu_baseline"] = run_oracle_sample(wl, a.cpu_elems)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -93,25 +93,18 @@ __device__ __forceinline__ f32x4 sign_error4(f32x4 v, float s)
 // fused route: one workgroup per chunk
 // ---------------------------------------------------------------------------------------
 // Common tail: scale from the held values, sign plane, error, stores.
-__device__ __forceinline__ void fused_finish(f32x4 (&v)[kR], int64_t base, int64_t lim, int64_t len,
+__device__ __forceinline__ void fused_finish(f32x4 v, int64_t base, int64_t lim,
                                              float *__restrict__ err_row, bool err_vec,
                                              uint64_t *__restrict__ words_row, int64_t bit_lim,
-                                             float *__restrict__ scale_out, double *lds4)
+                                             float *__restrict__ scale_out, double *lds)
 {
-    double part = 0.0;
-#pragma unroll
-    for (int r = 0; r < kR; ++r) part += abs_sum4(v[r]);
-    const double total = block_sum(part, lds4);
-    const float scale = static_cast<float>(total / static_cast<double>(len));
+    const uint32_t byte = wave_sign_byte(v.x < 0.f, v.y < 0.f, v.z < 0.f, v.w < 0.f);
+    store_sign_bytes(words_row, base + wave_id() * 256, bit_lim, byte);
+    const double total = block_sum(abs_sum4(v), lds, false);
+    const float scale = static_cast<float>(total / static_cast<double>(lim - base));
     if (threadIdx.x == 0) *scale_out = scale;
-#pragma unroll
-    for (int r = 0; r < kR; ++r) {
-        const int64_t wave_first = base + r * kHalf + wave_id() * 256;
-        const uint32_t byte = wave_sign_byte(v[r].x < 0.f, v[r].y < 0.f, v[r].z < 0.f, v[r].w < 0.f);
-        store_sign_bytes(words_row, wave_first, bit_lim, byte);
-        const int64_t e = base + r * kHalf + threadIdx.x * 4;
-        if (e < lim) st4(err_row, e, lim, err_vec, sign_error4(v[r], scale));
-    }
+    const int64_t e = base + threadIdx.x * 4;
+    if (e < lim) st4(err_row, e, lim, err_vec, sign_error4(v, scale));
 }
 
 template <bool BF16>
@@ -120,7 +113,7 @@ __global__ __launch_bounds__(kBlock) void k_sign_chunk_worker(WorkerSrc<BF16> sr
                                                               uint64_t *words, int64_t W,
                                                               float *scales, int64_t S)
 {
-    __shared__ double lds4[4];
+    __shared__ double lds[kWaves];
     const int row = blockIdx.y;
     const int64_t ci = blockIdx.x;
     const int64_t base = ci * chunk;
@@ -129,49 +122,59 @@ __global__ __launch_bounds__(kBlock) void k_sign_chunk_worker(WorkerSrc<BF16> sr
     float *drow = delta + row * src.delta_stride;
     const bool gvec = BF16 ? aligned8(grow) : aligned16(grow);
     const bool dvec = aligned16(drow);
-    f32x4 v[kR];
-#pragma unroll
-    for (int r = 0; r < kR; ++r) {
-        const int64_t e = base + r * kHalf + threadIdx.x * 4;
-        v[r] = ld4_grad<BF16>(grow, e, lim, gvec) + ld4(drow, e, lim, dvec);
-    }
-    fused_finish(v, base, lim, lim - base, drow, dvec, words + row * W, (lim == d) ? W * 64 : lim,
-                 scales + row * S + ci, lds4);
+    const int64_t e = base + threadIdx.x * 4;
+    const f32x4 v = ld4_grad<BF16>(grow, e, lim, gvec) + ld4(drow, e, lim, dvec);
+    fused_finish(v, base, lim, drow, dvec, words + row * W, (lim == d) ? W * 64 : lim,
+                 scales + row * S + ci, lds);
 }
 
 __global__ __launch_bounds__(kBlock) void k_sign_chunk_server(ServerArgs a, float *delta_s, int64_t d,
                                                               int64_t chunk, uint64_t *words_out,
                                                               float *scales_out)
 {
-    __shared__ double lds4[4];
+    __shared__ double lds[kWaves];
     const int64_t ci = blockIdx.x;
     const int64_t base = ci * chunk;
     const int64_t lim = (base + chunk < d) ? base + chunk : d;
     const bool dvec = aligned16(delta_s);
-    f32x4 v[kR];
-#pragma unroll
-    for (int r = 0; r < kR; ++r) {
-        const int64_t e = base + r * kHalf + threadIdx.x * 4;
-        v[r] = ld4(delta_s, e, lim, dvec);
-    }
-    for (int i = 0; i < a.n; ++i) {
-        const float s = a.scales_in[i * a.S + ci];
-        const uint64_t *wrow = a.words_in + i * a.W;
-#pragma unroll
-        for (int r = 0; r < kR; ++r) {
-            const int64_t e = base + r * kHalf + threadIdx.x * 4;
-            if (e < lim) v[r] = chain4(v[r], load_sign_nibble(wrow, e), s, a.inv_n);
-        }
+    const int64_t e = base + threadIdx.x * 4;
+    f32x4 v = ld4(delta_s, e, lim, dvec);
+    if (e < lim) {
+        for (int i = 0; i < a.n; ++i)
+            v = chain4(v, load_sign_nibble(a.words_in + i * a.W, e), a.scales_in[i * a.S + ci], a.inv_n);
     }
     // components past lim must stay zero: they count in the sum of |v|
-#pragma unroll
-    for (int r = 0; r < kR; ++r) v[r] = zero_past(v[r], base + r * kHalf + threadIdx.x * 4, lim);
-    fused_finish(v, base, lim, lim - base, delta_s, dvec, words_out, (lim == d) ? a.W * 64 : lim,
-                 scales_out + ci, lds4);
+    v = zero_past(v, e, lim);
+    fused_finish(v, base, lim, delta_s, dvec, words_out, (lim == d) ? a.W * 64 : lim, scales_out + ci, lds);
 }
 
-// x update from the server's message (Algorithm 1, "Update the local model"), optionally
-// through a momentum buffer.  One thread per 4 elements; OUT = write decoded q only.
+__device__ __forceinline__ f32x4 fma4(float a, f32x4 b, f32x4 c)
+{
+    return f32x4{__fmaf_rn(a, b.x, c.x), __fmaf_rn(a, b.y, c.y), __fmaf_rn(a, b.z, c.z), __fmaf_rn(a, b.w, c.w)};
+}
+
+// Tail shared by every update kernel (Algorithm 1, "Update the local model"), q = decoded
+// server message for elements e..e+3:
+//   DECODE_ONLY: x <- q ;  plain: x <- fma(-gamma, q, x) ;
+//   MOM: m <- fma(beta, m, q), x <- fma(-gamma, m, x).
+template <bool MOM, bool DECODE_ONLY>
+__device__ __forceinline__ void apply_q4(f32x4 q, int64_t e, int64_t d, float *x, float *m, float gamma, float beta)
+{
+    const bool xvec = aligned16(x);
+    if constexpr (DECODE_ONLY) {
+        st4(x, e, d, xvec, q);
+    } else {
+        const f32x4 xv = ld4(x, e, d, xvec);
+        if constexpr (MOM) {
+            const bool mvec = aligned16(m);
+            q = fma4(beta, ld4(m, e, d, mvec), q);
+            st4(m, e, d, mvec, q);
+        }
+        st4(x, e, d, xvec, fma4(-gamma, q, xv));
+    }
+}
+
+// One thread per 4 elements.
 template <bool MOM, bool DECODE_ONLY>
 __global__ __launch_bounds__(kBlock) void k_sign_chunk_update(const uint64_t *__restrict__ words,
                                                               const float *__restrict__ scales,
@@ -180,28 +183,12 @@ __global__ __launch_bounds__(kBlock) void k_sign_chunk_update(const uint64_t *__
 {
     const int64_t e = (static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x) * 4;
     if (e >= d) return;
-    const bool xvec = aligned16(x);
     // chunk is a multiple of 4 on this route, so the four elements share a chunk;
     // e < 2^31, so the chunk index is a 32-bit division
     const float s = scales[static_cast<uint32_t>(e) / static_cast<uint32_t>(chunk)];
     const uint32_t nib = load_sign_nibble(words, e);
-    f32x4 q = {(nib & 1u) ? -s : s, (nib & 2u) ? -s : s, (nib & 4u) ? -s : s, (nib & 8u) ? -s : s};
-    if constexpr (DECODE_ONLY) {
-        st4(x, e, d, xvec, q);
-    } else {
-        f32x4 xv = ld4(x, e, d, xvec);
-        if constexpr (MOM) {
-            const bool mvec = aligned16(m);
-            f32x4 mv = ld4(m, e, d, mvec);
-            mv.x = __fmaf_rn(beta, mv.x, q.x); mv.y = __fmaf_rn(beta, mv.y, q.y);
-            mv.z = __fmaf_rn(beta, mv.z, q.z); mv.w = __fmaf_rn(beta, mv.w, q.w);
-            st4(m, e, d, mvec, mv);
-            q = mv;
-        }
-        xv.x = __fmaf_rn(-gamma, q.x, xv.x); xv.y = __fmaf_rn(-gamma, q.y, xv.y);
-        xv.z = __fmaf_rn(-gamma, q.z, xv.z); xv.w = __fmaf_rn(-gamma, q.w, xv.w);
-        st4(x, e, d, xvec, xv);
-    }
+    const f32x4 q = {(nib & 1u) ? -s : s, (nib & 2u) ? -s : s, (nib & 4u) ? -s : s, (nib & 8u) ? -s : s};
+    apply_q4<MOM, DECODE_ONLY>(q, e, d, x, m, gamma, beta);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -221,37 +208,25 @@ __device__ __forceinline__ double masked_abs(float x, int64_t e, int64_t lo, int
 }
 
 // Pass-1 tail: store v, sign bits, per-piece partial sums of |v|.
-__device__ __forceinline__ void pass1_finish(f32x4 (&v)[kR], int64_t base, int64_t d,
+__device__ __forceinline__ void pass1_finish(f32x4 v, int64_t base, int64_t d,
                                              float *__restrict__ vrow, bool vvec,
                                              uint64_t *__restrict__ words_row, int64_t bit_lim,
                                              const ds_sign_tables &tb, int32_t p0, int32_t p1,
-                                             double *__restrict__ partial_row, double *lds4)
+                                             double *__restrict__ partial_row, double *lds)
 {
-#pragma unroll
-    for (int r = 0; r < kR; ++r) {
-        const int64_t e = base + r * kHalf + threadIdx.x * 4;
-        if (e < d) st4(vrow, e, d, vvec, v[r]);
-        const int64_t wave_first = base + r * kHalf + wave_id() * 256;
-        const uint32_t byte = wave_sign_byte(v[r].x < 0.f, v[r].y < 0.f, v[r].z < 0.f, v[r].w < 0.f);
-        store_sign_bytes(words_row, wave_first, bit_lim, byte);
-    }
+    const int64_t e = base + threadIdx.x * 4;
+    if (e < d) st4(vrow, e, d, vvec, v);
+    const uint32_t byte = wave_sign_byte(v.x < 0.f, v.y < 0.f, v.z < 0.f, v.w < 0.f);
+    store_sign_bytes(words_row, base + wave_id() * 256, bit_lim, byte);
     if (p1 - p0 == 1) {
-        double part = 0.0;
-#pragma unroll
-        for (int r = 0; r < kR; ++r) part += abs_sum4(v[r]);   // elements past d are zero
-        const double total = block_sum(part, lds4);
+        const double total = block_sum(abs_sum4(v), lds, false);   // elements past d are zero
         if (threadIdx.x == 0) partial_row[p0] = total;
     } else {
         for (int32_t p = p0; p < p1; ++p) {
             const int64_t lo = tb.piece_start[p], hi = tb.piece_start[p + 1];
-            double part = 0.0;
-#pragma unroll
-            for (int r = 0; r < kR; ++r) {
-                const int64_t e = base + r * kHalf + threadIdx.x * 4;
-                part += ((masked_abs(v[r].x, e, lo, hi) + masked_abs(v[r].y, e + 1, lo, hi)) +
-                         masked_abs(v[r].z, e + 2, lo, hi)) + masked_abs(v[r].w, e + 3, lo, hi);
-            }
-            const double total = block_sum(part, lds4);
+            const double part = ((masked_abs(v.x, e, lo, hi) + masked_abs(v.y, e + 1, lo, hi)) +
+                                 masked_abs(v.z, e + 2, lo, hi)) + masked_abs(v.w, e + 3, lo, hi);
+            const double total = block_sum(part, lds, true);
             if (threadIdx.x == 0) partial_row[p] = total;
         }
     }
@@ -262,7 +237,7 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass1_worker(WorkerSrc<BF16> sr
                                                               int64_t d, uint64_t *words, int64_t W,
                                                               ds_sign_tables tb, double *partials)
 {
-    __shared__ double lds4[4];
+    __shared__ double lds[kWaves];
     const int row = blockIdx.y;
     const int64_t tile = blockIdx.x;
     const int64_t base = tile * kTile;
@@ -270,51 +245,39 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass1_worker(WorkerSrc<BF16> sr
     float *drow = delta + row * src.delta_stride;
     const bool gvec = BF16 ? aligned8(grow) : aligned16(grow);
     const bool dvec = aligned16(drow);
-    f32x4 v[kR];
-#pragma unroll
-    for (int r = 0; r < kR; ++r) {
-        const int64_t e = base + r * kHalf + threadIdx.x * 4;
-        v[r] = ld4_grad<BF16>(grow, e, d, gvec) + ld4(drow, e, d, dvec);
-    }
+    const int64_t e = base + threadIdx.x * 4;
+    const f32x4 v = ld4_grad<BF16>(grow, e, d, gvec) + ld4(drow, e, d, dvec);
     pass1_finish(v, base, d, drow, dvec, words + row * W, W * 64, tb, tb.tile_piece_first[tile],
-                 tb.tile_piece_first[tile + 1], partials + static_cast<int64_t>(row) * tb.n_pieces, lds4);
+                 tb.tile_piece_first[tile + 1], partials + static_cast<int64_t>(row) * tb.n_pieces, lds);
 }
 
 __global__ __launch_bounds__(kBlock) void k_sign_pass1_server(ServerArgs a, float *delta_s, int64_t d,
                                                               uint64_t *words_out, ds_sign_tables tb,
                                                               double *partials)
 {
-    __shared__ double lds4[4];
+    __shared__ double lds[kWaves];
     const int64_t tile = blockIdx.x;
     const int64_t base = tile * kTile;
     const bool dvec = aligned16(delta_s);
     const int32_t p0 = tb.tile_piece_first[tile], p1 = tb.tile_piece_first[tile + 1];
-    f32x4 v[kR];
-    int32_t seg[kR][4];
+    const int64_t e = base + threadIdx.x * 4;
+    f32x4 v = ld4(delta_s, e, d, dvec);
+    if (e < d) {
+        int32_t seg[4];
 #pragma unroll
-    for (int r = 0; r < kR; ++r) {
-        const int64_t e = base + r * kHalf + threadIdx.x * 4;
-        v[r] = ld4(delta_s, e, d, dvec);
-#pragma unroll
-        for (int c = 0; c < 4; ++c) seg[r][c] = (e + c < d) ? seg_of(tb, p0, p1, e + c) : 0;
-    }
-    for (int i = 0; i < a.n; ++i) {
-        const uint64_t *wrow = a.words_in + i * a.W;
-        const float *srow = a.scales_in + i * a.S;
-#pragma unroll
-        for (int r = 0; r < kR; ++r) {
-            const int64_t e = base + r * kHalf + threadIdx.x * 4;
-            if (e < d) {
-                const uint32_t nib = load_sign_nibble(wrow, e);
-                const float s0 = srow[seg[r][0]], s1 = srow[seg[r][1]], s2 = srow[seg[r][2]], s3 = srow[seg[r][3]];
-                if (e + 0 < d) v[r].x = __fmaf_rn((nib & 1u) ? -s0 : s0, a.inv_n, v[r].x);
-                if (e + 1 < d) v[r].y = __fmaf_rn((nib & 2u) ? -s1 : s1, a.inv_n, v[r].y);
-                if (e + 2 < d) v[r].z = __fmaf_rn((nib & 4u) ? -s2 : s2, a.inv_n, v[r].z);
-                if (e + 3 < d) v[r].w = __fmaf_rn((nib & 8u) ? -s3 : s3, a.inv_n, v[r].w);
-            }
+        for (int c = 0; c < 4; ++c) seg[c] = (e + c < d) ? seg_of(tb, p0, p1, e + c) : 0;
+        for (int i = 0; i < a.n; ++i) {
+            const float *srow = a.scales_in + i * a.S;
+            const uint32_t nib = load_sign_nibble(a.words_in + i * a.W, e);
+            const float s0 = srow[seg[0]], s1 = srow[seg[1]], s2 = srow[seg[2]], s3 = srow[seg[3]];
+            v.x = __fmaf_rn((nib & 1u) ? -s0 : s0, a.inv_n, v.x);
+            v.y = __fmaf_rn((nib & 2u) ? -s1 : s1, a.inv_n, v.y);
+            v.z = __fmaf_rn((nib & 4u) ? -s2 : s2, a.inv_n, v.z);
+            v.w = __fmaf_rn((nib & 8u) ? -s3 : s3, a.inv_n, v.w);
         }
     }
-    pass1_finish(v, base, d, delta_s, dvec, words_out, a.W * 64, tb, p0, p1, partials, lds4);
+    v = zero_past(v, e, d);
+    pass1_finish(v, base, d, delta_s, dvec, words_out, a.W * 64, tb, p0, p1, partials, lds);
 }
 
 // scale[row][s] = (float)( sum of the group's partials / |group| ), fixed order.
@@ -347,29 +310,25 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass2(float *buf, int64_t strid
 {
     const int row = blockIdx.y;
     const int64_t tile = blockIdx.x;
-    const int64_t base = tile * kTile;
     float *brow = buf + row * stride;
     const float *srow = scales + row * S;
     const bool vec = aligned16(brow);
     const int32_t p0 = tb.tile_piece_first[tile], p1 = tb.tile_piece_first[tile + 1];
+    const int64_t e = tile * kTile + threadIdx.x * 4;
+    if (e >= d) return;
+    f32x4 v = ld4(brow, e, d, vec);
+    if (p1 - p0 == 1) {
+        v = sign_error4(v, srow[tb.piece_seg[p0]]);
+    } else {
+        float s[4];
 #pragma unroll
-    for (int r = 0; r < kR; ++r) {
-        const int64_t e = base + r * kHalf + threadIdx.x * 4;
-        if (e >= d) continue;
-        f32x4 v = ld4(brow, e, d, vec);
-        if (p1 - p0 == 1) {
-            v = sign_error4(v, srow[tb.piece_seg[p0]]);
-        } else {
-            float s[4];
-#pragma unroll
-            for (int c = 0; c < 4; ++c) s[c] = (e + c < d) ? srow[seg_of(tb, p0, p1, e + c)] : 0.f;
-            v.x = v.x - ((v.x < 0.f) ? -s[0] : s[0]);
-            v.y = v.y - ((v.y < 0.f) ? -s[1] : s[1]);
-            v.z = v.z - ((v.z < 0.f) ? -s[2] : s[2]);
-            v.w = v.w - ((v.w < 0.f) ? -s[3] : s[3]);
-        }
-        st4(brow, e, d, vec, v);
+        for (int c = 0; c < 4; ++c) s[c] = (e + c < d) ? srow[seg_of(tb, p0, p1, e + c)] : 0.f;
+        v.x = v.x - ((v.x < 0.f) ? -s[0] : s[0]);
+        v.y = v.y - ((v.y < 0.f) ? -s[1] : s[1]);
+        v.z = v.z - ((v.z < 0.f) ? -s[2] : s[2]);
+        v.w = v.w - ((v.w < 0.f) ? -s[3] : s[3]);
     }
+    st4(brow, e, d, vec, v);
 }
 
 template <bool MOM, bool DECODE_ONLY>
@@ -379,37 +338,17 @@ __global__ __launch_bounds__(kBlock) void k_sign_update(const uint64_t *__restri
                                                         int64_t d, float gamma, float beta)
 {
     const int64_t tile = blockIdx.x;
-    const int64_t base = tile * kTile;
-    const bool xvec = aligned16(x);
     const int32_t p0 = tb.tile_piece_first[tile], p1 = tb.tile_piece_first[tile + 1];
+    const int64_t e = tile * kTile + threadIdx.x * 4;
+    if (e >= d) return;
+    const uint32_t nib = load_sign_nibble(words, e);
+    float q[4];
 #pragma unroll
-    for (int r = 0; r < kR; ++r) {
-        const int64_t e = base + r * kHalf + threadIdx.x * 4;
-        if (e >= d) continue;
-        const uint32_t nib = load_sign_nibble(words, e);
-        float q[4];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const float s = (e + c < d) ? scales[seg_of(tb, p0, p1, e + c)] : 0.f;
-            q[c] = ((nib >> c) & 1u) ? -s : s;
-        }
-        if constexpr (DECODE_ONLY) {
-            st4(x, e, d, xvec, f32x4{q[0], q[1], q[2], q[3]});
-        } else {
-            f32x4 xv = ld4(x, e, d, xvec);
-            if constexpr (MOM) {
-                const bool mvec = aligned16(m);
-                f32x4 mv = ld4(m, e, d, mvec);
-                mv.x = __fmaf_rn(beta, mv.x, q[0]); mv.y = __fmaf_rn(beta, mv.y, q[1]);
-                mv.z = __fmaf_rn(beta, mv.z, q[2]); mv.w = __fmaf_rn(beta, mv.w, q[3]);
-                st4(m, e, d, mvec, mv);
-                q[0] = mv.x; q[1] = mv.y; q[2] = mv.z; q[3] = mv.w;
-            }
-            xv.x = __fmaf_rn(-gamma, q[0], xv.x); xv.y = __fmaf_rn(-gamma, q[1], xv.y);
-            xv.z = __fmaf_rn(-gamma, q[2], xv.z); xv.w = __fmaf_rn(-gamma, q[3], xv.w);
-            st4(x, e, d, xvec, xv);
-        }
+    for (int c = 0; c < 4; ++c) {
+        const float s = (e + c < d) ? scales[seg_of(tb, p0, p1, e + c)] : 0.f;
+        q[c] = ((nib >> c) & 1u) ? -s : s;
     }
+    apply_q4<MOM, DECODE_ONLY>(f32x4{q[0], q[1], q[2], q[3]}, e, d, x, m, gamma, beta);
 }
 
 }  // namespace
@@ -430,7 +369,7 @@ ds_status_t ds_sign_init(ds_ctx *c)
     } else if (cfg.scale_mode == DS_SCALE_SEGMENTS) {
         seg_off.assign(cfg.seg_offsets, cfg.seg_offsets + cfg.n_seg + 1);
     } else {
-        if (cfg.chunk % 64 == 0 && cfg.chunk >= 256 && cfg.chunk <= kTile) {
+        if (cfg.chunk % 64 == 0 && cfg.chunk >= 512 && cfg.chunk <= kTile) {
             c->sign_fused = true;
             c->S = (d + cfg.chunk - 1) / cfg.chunk;
             return DS_OK;
