@@ -170,4 +170,40 @@ __device__ __forceinline__ u32x4 philox4x32_10(u32x4 c, uint32_t k0, uint32_t k1
     return c;
 }
 
+// Zeroes the components of e..e+3 that lie at or past lim.
+__device__ __forceinline__ f32x4 zero_past(f32x4 v, int64_t e, int64_t lim)
+{
+    if (e + 0 >= lim) v.x = 0.f;
+    if (e + 1 >= lim) v.y = 0.f;
+    if (e + 2 >= lim) v.z = 0.f;
+    if (e + 3 >= lim) v.w = 0.f;
+    return v;
+}
+
+__device__ __forceinline__ f32x4 fma4(float a, f32x4 b, f32x4 c)
+{
+    return f32x4{__fmaf_rn(a, b.x, c.x), __fmaf_rn(a, b.y, c.y), __fmaf_rn(a, b.z, c.z), __fmaf_rn(a, b.w, c.w)};
+}
+
+// Tail shared by every update kernel (Algorithm 1, "Update the local model"), q = decoded
+// server message for elements e..e+3:
+//   DECODE_ONLY: x <- q ;  plain: x <- fma(-gamma, q, x) ;
+//   MOM: m <- fma(beta, m, q), x <- fma(-gamma, m, x).
+template <bool MOM, bool DECODE_ONLY>
+__device__ __forceinline__ void apply_q4(f32x4 q, int64_t e, int64_t d, float *x, float *m, float gamma, float beta)
+{
+    const bool xvec = aligned16(x);
+    if constexpr (DECODE_ONLY) {
+        st4(x, e, d, xvec, q);
+    } else {
+        const f32x4 xv = ld4(x, e, d, xvec);
+        if constexpr (MOM) {
+            const bool mvec = aligned16(m);
+            q = fma4(beta, ld4(m, e, d, mvec), q);
+            st4(m, e, d, mvec, q);
+        }
+        st4(x, e, d, xvec, fma4(-gamma, q, xv));
+    }
+}
+
 }  // namespace ds

@@ -1,5 +1,267 @@
+// Randomised quantisation kernels (Section 3.2 "Randomized Quantization" of the
+// DoubleSqueeze paper: a value between two neighbouring representable points goes to the
+// upper one with probability proportional to its distance from the lower one, which is
+// unbiased), in the bucketed QSGD form: per bucket an L2 norm, s uniform levels
+// {0..s} * norm/s as 4-bit codes, the sign in a separate bit plane.
+//
+// Rounding draws come from Philox4x32-10 with counter (j >> 2, 0, stream, lo32(step)) and
+// key (lo32(seed), hi32(seed) ^ hi32(step)): one block serves the four consecutive elements
+// a thread owns, word c for element 4*(j>>2) + c.  stream = worker index, 0xFFFFFFFF on
+// the server.
+//
+// Buckets are powers of two from 64 to 2048 elements, so a 2048-element tile holds whole
+// buckets and a bucket is a fixed group of lanes: sum v^2 (fp64, exact products) by a
+// segmented butterfly inside a wavefront and, for buckets above 256 elements, a fixed-order
+// combine of wavefront sums through LDS.  One pass over HBM: v = g + delta, norm, codes,
+// sign bits and delta' = v - Q[v] all from registers.
+#include "ds_device.h"
 #include "ds_internal.h"
-ds_status_t ds_qsgd_worker(ds_ctx *, uint64_t, const void *, int64_t, float *, int64_t, const ds_payload_t *, hipStream_t) { return DS_ERR_UNSUPPORTED; }
-ds_status_t ds_qsgd_server(ds_ctx *, uint64_t, const ds_payload_t *, float *, const ds_payload_t *, hipStream_t) { return DS_ERR_UNSUPPORTED; }
-ds_status_t ds_qsgd_update(ds_ctx *, const ds_payload_t *, float *, float *, float, float, hipStream_t) { return DS_ERR_UNSUPPORTED; }
-ds_status_t ds_qsgd_decode(ds_ctx *, const ds_payload_t *, int32_t, float *, hipStream_t) { return DS_ERR_UNSUPPORTED; }
+
+using namespace ds;
+
+namespace {
+
+constexpr uint32_t kServerStream = 0xFFFFFFFFu;
+constexpr int kUnitGroup = 64;  // workers whose decode units are staged in LDS at a time
+
+struct QParams {
+    int64_t d;
+    int32_t bucket;       // elements per bucket, power of two in [64, 2048]
+    int32_t bshift;       // log2(bucket)
+    int32_t s;            // levels
+    uint32_t key0, key1;  // Philox key (step's high word folded in)
+    uint32_t step_lo;
+    int64_t W, Bq;
+};
+
+// Sum of x over the lanes of this thread's bucket; every lane of the bucket returns it.
+// lds: kWaves doubles.
+__device__ __forceinline__ double bucket_sum(double x, int lanes_per_bucket, double *lds)
+{
+    if (lanes_per_bucket <= 64) {
+        for (int o = lanes_per_bucket >> 1; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+        return x;
+    }
+    const double w = wave_sum(x);
+    if (lane_id() == 0) lds[wave_id()] = w;
+    __syncthreads();
+    const int wpb = lanes_per_bucket >> 6;            // wavefronts per bucket
+    const int first = (wave_id() / wpb) * wpb;
+    double t = lds[first];
+    for (int i = 1; i < wpb; ++i) t += lds[first + i];
+    return t;
+}
+
+// Quantise the four values a thread holds; returns the decoded values q (so the caller can
+// form v - q) and writes codes, sign bits and the bucket norm.
+__device__ __forceinline__ f32x4 quantise4(f32x4 v, int64_t e, uint32_t stream, const QParams &P,
+                                           uint8_t *__restrict__ levels_row, uint64_t *__restrict__ words_row,
+                                           float *__restrict__ norms_row, double *lds)
+{
+    const int lpb = P.bucket >> 2;
+    const double ss = ((static_cast<double>(v.x) * static_cast<double>(v.x) +
+                        static_cast<double>(v.y) * static_cast<double>(v.y)) +
+                       static_cast<double>(v.z) * static_cast<double>(v.z)) +
+                      static_cast<double>(v.w) * static_cast<double>(v.w);
+    const float norm = static_cast<float>(sqrt(bucket_sum(ss, lpb, lds)));
+    const bool live = e < P.d;
+    if (live && (threadIdx.x & (lpb - 1)) == 0) norms_row[e >> P.bshift] = norm;
+
+    uint32_t code[4] = {0u, 0u, 0u, 0u};
+    if (live && norm > 0.f) {
+        const float inv = __fdiv_rn(static_cast<float>(P.s), norm);
+        const uint32_t blk = static_cast<uint32_t>(e >> 2);
+        const u32x4 rnd = philox4x32_10(u32x4{blk, 0u, stream, P.step_lo}, P.key0, P.key1);
+        const float vv[4] = {v.x, v.y, v.z, v.w};
+        const uint32_t rr[4] = {rnd.x, rnd.y, rnd.z, rnd.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const float r = fabsf(vv[c]) * inv;
+            const float fl = floorf(r);
+            const float p = r - fl;
+            const float u = static_cast<float>(rr[c] >> 8) * 0x1p-24f;
+            int k = static_cast<int>(fl) + ((u < p) ? 1 : 0);
+            k = (k > P.s) ? P.s : k;
+            code[c] = static_cast<uint32_t>(k);
+        }
+    }
+    // 4-bit codes: element j in byte j >> 1, low nibble for even j
+    if (live) {
+        const uint32_t packed = code[0] | (code[1] << 4) | (code[2] << 8) | (code[3] << 12);
+        uint8_t *dst = levels_row + (e >> 1);
+        if (e + 4 <= P.d && (reinterpret_cast<uintptr_t>(dst) & 1u) == 0) {
+            *reinterpret_cast<uint16_t *>(dst) = static_cast<uint16_t>(packed);
+        } else {
+            dst[0] = static_cast<uint8_t>(packed);
+            if (e + 2 < P.d) dst[1] = static_cast<uint8_t>(packed >> 8);
+        }
+    }
+    const uint32_t byte = wave_sign_byte(v.x < 0.f, v.y < 0.f, v.z < 0.f, v.w < 0.f);
+    store_sign_bytes(words_row, (e >> 8) << 8, P.W * 64, byte);
+    // decoded message: +-(code * norm/s)
+    const float unit = __fdiv_rn(norm, static_cast<float>(P.s));
+    f32x4 q;
+    q.x = static_cast<float>(code[0]) * unit; q.x = (v.x < 0.f) ? -q.x : q.x;
+    q.y = static_cast<float>(code[1]) * unit; q.y = (v.y < 0.f) ? -q.y : q.y;
+    q.z = static_cast<float>(code[2]) * unit; q.z = (v.z < 0.f) ? -q.z : q.z;
+    q.w = static_cast<float>(code[3]) * unit; q.w = (v.w < 0.f) ? -q.w : q.w;
+    return q;
+}
+
+// The four 4-bit codes of elements e..e+3 (e a multiple of 4, e < d).
+__device__ __forceinline__ uint32_t load_codes4(const uint8_t *__restrict__ levels_row, int64_t e, int64_t d)
+{
+    const uint8_t *src = levels_row + (e >> 1);
+    if (e + 4 <= d && (reinterpret_cast<uintptr_t>(src) & 1u) == 0) return *reinterpret_cast<const uint16_t *>(src);
+    uint32_t r = src[0];
+    if (e + 2 < d) r |= static_cast<uint32_t>(src[1]) << 8;
+    return r;
+}
+
+__device__ __forceinline__ f32x4 decode4(uint32_t codes, uint32_t nib, float unit)
+{
+    f32x4 q;
+    q.x = static_cast<float>(codes & 15u) * unit;          q.x = (nib & 1u) ? -q.x : q.x;
+    q.y = static_cast<float>((codes >> 4) & 15u) * unit;   q.y = (nib & 2u) ? -q.y : q.y;
+    q.z = static_cast<float>((codes >> 8) & 15u) * unit;   q.z = (nib & 4u) ? -q.z : q.z;
+    q.w = static_cast<float>((codes >> 12) & 15u) * unit;  q.w = (nib & 8u) ? -q.w : q.w;
+    return q;
+}
+
+// Worker block of Algorithm 1 with Q = randomised quantisation.
+template <bool BF16>
+__global__ __launch_bounds__(kBlock) void k_qsgd_worker(const void *g, int64_t gs, float *delta, int64_t dstr,
+                                                        QParams P, uint8_t *levels, uint64_t *words, float *norms)
+{
+    __shared__ double lds[kWaves];
+    const int row = blockIdx.y;
+    const int64_t e = static_cast<int64_t>(blockIdx.x) * kTile + threadIdx.x * 4;
+    const void *grow = BF16 ? static_cast<const void *>(static_cast<const uint16_t *>(g) + row * gs)
+                            : static_cast<const void *>(static_cast<const float *>(g) + row * gs);
+    float *drow = delta + row * dstr;
+    const bool gvec = BF16 ? aligned8(grow) : aligned16(grow);
+    const bool dvec = aligned16(drow);
+    const f32x4 v = ld4_grad<BF16>(grow, e, P.d, gvec) + ld4(drow, e, P.d, dvec);
+    const f32x4 q = quantise4(v, e, static_cast<uint32_t>(row), P, levels + row * ((P.d + 1) / 2),
+                              words + row * P.W, norms + row * P.Bq, lds);
+    if (e < P.d) st4(drow, e, P.d, dvec, v - q);
+}
+
+// Parameter-server block: v = delta_s + (1/n) sum_i decode(msg_i) as the fma chain over
+// workers in ascending order, then the same quantiser on the server's stream.
+__global__ __launch_bounds__(kBlock) void k_qsgd_server(const uint8_t *levels_in, const uint64_t *words_in,
+                                                        const float *norms_in, int n, float inv_n, float *delta_s,
+                                                        QParams P, uint8_t *levels_out, uint64_t *words_out,
+                                                        float *norms_out)
+{
+    __shared__ double lds[kWaves];
+    __shared__ float units[kUnitGroup * (kTile / 64)];
+    const int64_t tile_base = static_cast<int64_t>(blockIdx.x) * kTile;
+    const int64_t e = tile_base + threadIdx.x * 4;
+    const bool dvec = aligned16(delta_s);
+    const int bpt = kTile >> P.bshift;                      // buckets per tile
+    const int64_t b0 = tile_base >> P.bshift;
+    const int my_b = (threadIdx.x * 4) >> P.bshift;
+    const int64_t lev_stride = (P.d + 1) / 2;
+    f32x4 a = ld4(delta_s, e, P.d, dvec);
+    for (int i0 = 0; i0 < n; i0 += kUnitGroup) {
+        const int cnt = (n - i0 < kUnitGroup) ? n - i0 : kUnitGroup;
+        __syncthreads();
+        for (int t = threadIdx.x; t < cnt * bpt; t += kBlock) {
+            const int i = t / bpt, b = t - i * bpt;
+            const int64_t B = b0 + b;
+            units[t] = (B < P.Bq) ? __fdiv_rn(norms_in[(i0 + i) * P.Bq + B], static_cast<float>(P.s)) : 0.f;
+        }
+        __syncthreads();
+        if (e < P.d) {
+            for (int i = 0; i < cnt; ++i) {
+                const int64_t w = i0 + i;
+                const uint32_t codes = load_codes4(levels_in + w * lev_stride, e, P.d);
+                const uint32_t nib = load_sign_nibble(words_in + w * P.W, e);
+                const f32x4 q = decode4(codes, nib, units[i * bpt + my_b]);
+                a = fma4(inv_n, q, a);   // fma(q, 1/n, acc): the product commutes
+            }
+        }
+    }
+    a = zero_past(a, e, P.d);
+    const f32x4 q = quantise4(a, e, kServerStream, P, levels_out, words_out, norms_out, lds);
+    if (e < P.d) st4(delta_s, e, P.d, dvec, a - q);
+}
+
+template <bool MOM, bool DECODE_ONLY>
+__global__ __launch_bounds__(kBlock) void k_qsgd_update(const uint8_t *levels, const uint64_t *words,
+                                                        const float *norms, QParams P, float *x, float *m,
+                                                        float gamma, float beta)
+{
+    const int64_t e = static_cast<int64_t>(blockIdx.x) * kTile + threadIdx.x * 4;
+    if (e >= P.d) return;
+    const float unit = __fdiv_rn(norms[e >> P.bshift], static_cast<float>(P.s));
+    const f32x4 q = decode4(load_codes4(levels, e, P.d), load_sign_nibble(words, e), unit);
+    apply_q4<MOM, DECODE_ONLY>(zero_past(q, e, P.d), e, P.d, x, m, gamma, beta);
+}
+
+bool bucket_ok(int32_t b) { return b >= 64 && b <= kTile && (b & (b - 1)) == 0; }
+
+QParams make_params(const ds_ctx *c, uint64_t step)
+{
+    QParams P;
+    P.d = c->cfg.d;
+    P.bucket = c->cfg.bucket;
+    P.bshift = 0;
+    while ((1 << P.bshift) < P.bucket) ++P.bshift;
+    P.s = c->cfg.levels;
+    P.key0 = static_cast<uint32_t>(c->cfg.seed);
+    P.key1 = static_cast<uint32_t>(c->cfg.seed >> 32) ^ static_cast<uint32_t>(step >> 32);
+    P.step_lo = static_cast<uint32_t>(step);
+    P.W = c->W;
+    P.Bq = c->S;
+    return P;
+}
+
+}  // namespace
+
+ds_status_t ds_qsgd_worker(ds_ctx *c, uint64_t step, const void *g, int64_t gs, float *delta, int64_t dstr,
+                           const ds_payload_t *out, hipStream_t st)
+{
+    if (!bucket_ok(c->cfg.bucket)) return DS_ERR_UNSUPPORTED;
+    const QParams P = make_params(c, step);
+    dim3 grid(static_cast<unsigned>(c->n_tiles), static_cast<unsigned>(c->cfg.n));
+    if (c->cfg.grad_dtype == DS_BF16)
+        k_qsgd_worker<true><<<grid, kBlock, 0, st>>>(g, gs, delta, dstr, P, out->levels, out->sign_words, out->scales);
+    else
+        k_qsgd_worker<false><<<grid, kBlock, 0, st>>>(g, gs, delta, dstr, P, out->levels, out->sign_words, out->scales);
+    return ds_launch_status();
+}
+
+ds_status_t ds_qsgd_server(ds_ctx *c, uint64_t step, const ds_payload_t *in, float *delta_s,
+                           const ds_payload_t *out, hipStream_t st)
+{
+    if (!bucket_ok(c->cfg.bucket)) return DS_ERR_UNSUPPORTED;
+    const QParams P = make_params(c, step);
+    k_qsgd_server<<<static_cast<unsigned>(c->n_tiles), kBlock, 0, st>>>(in->levels, in->sign_words, in->scales,
+                                                                       c->cfg.n, c->inv_n, delta_s, P, out->levels,
+                                                                       out->sign_words, out->scales);
+    return ds_launch_status();
+}
+
+ds_status_t ds_qsgd_update(ds_ctx *c, const ds_payload_t *srv, float *x, float *m, float gamma, float beta,
+                           hipStream_t st)
+{
+    if (!bucket_ok(c->cfg.bucket)) return DS_ERR_UNSUPPORTED;
+    const QParams P = make_params(c, 0);
+    const unsigned blocks = static_cast<unsigned>(c->n_tiles);
+    if (m)
+        k_qsgd_update<true, false><<<blocks, kBlock, 0, st>>>(srv->levels, srv->sign_words, srv->scales, P, x, m, gamma, beta);
+    else
+        k_qsgd_update<false, false><<<blocks, kBlock, 0, st>>>(srv->levels, srv->sign_words, srv->scales, P, x, m, gamma, beta);
+    return ds_launch_status();
+}
+
+ds_status_t ds_qsgd_decode(ds_ctx *c, const ds_payload_t *p, int32_t row, float *out, hipStream_t st)
+{
+    if (!bucket_ok(c->cfg.bucket)) return DS_ERR_UNSUPPORTED;
+    const QParams P = make_params(c, 0);
+    k_qsgd_update<false, true><<<static_cast<unsigned>(c->n_tiles), kBlock, 0, st>>>(
+        p->levels + row * ((P.d + 1) / 2), p->sign_words + row * P.W, p->scales + row * P.Bq, P, out, nullptr, 0.f, 0.f);
+    return ds_launch_status();
+}
