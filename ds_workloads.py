@@ -123,7 +123,9 @@ class Workload:
                 row = z / torch.sqrt(chi2 / 3.0) * sig
             elif self.dist == "laplace_outliers":
                 u = torch.rand(self.d, generator=gen, device=dev, dtype=torch.float32) - 0.5
-                lap = -self.sigma * torch.sign(u) * torch.log1p(-2.0 * u.abs())
+                # |u| < 1/2 strictly, so the draw stays finite
+                a2 = (2.0 * u.abs()).clamp_(max=1.0 - 2.0 ** -24)
+                lap = -self.sigma * torch.sign(u) * torch.log1p(-a2)
                 hit = torch.rand(self.d, generator=gen, device=dev, dtype=torch.float32) < 1e-3
                 row = torch.where(hit, lap * 100.0, lap)
             elif self.dist == "levels8":

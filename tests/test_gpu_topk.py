@@ -1,0 +1,77 @@
+"""GPU parity: top-k sparsification against the CPU oracle.  Index sets must be bit-exact
+(ties towards the lower index, ascending order), values equal, error buffers within 1e-6."""
+import numpy as np
+import pytest
+import torch
+
+import ds_workloads as W
+from parity_util import Pair
+
+pytestmark = pytest.mark.gpu
+
+
+def _wl(d, n=3, k=None, **kw):
+    base = dict(name=f"topk_d{d}", comp="topk", n=n, d=d, k=(max(1, d // 100) if k is None else k),
+                dist="laplace_outliers", sigma=1e-3, gamma=0.05)
+    base.update(kw)
+    return W.Workload(**base)
+
+
+def _run(wl, device, steps=2, sets=2, grads=None):
+    pair = Pair(wl, device)
+    try:
+        gs = grads if grads is not None else [wl.gradients(s, device) for s in range(sets)]
+        for t in range(steps):
+            pair.compared_step(t, gs[t % len(gs)])
+    finally:
+        pair.close()
+
+
+@pytest.mark.parametrize("d,k", [(1, 1), (7, 3), (2048, 20), (2049, 2049), (5 * 2048 + 37, 1), (5 * 2048 + 37, 103),
+                                 (100_003, 1000), (100_003, 100_003), (40_000, 39_999)])
+def test_topk_shapes(gpu_device, d, k):
+    _run(_wl(d, k=k), gpu_device)
+
+
+def test_topk_all_zero_and_all_equal(gpu_device):
+    d, n, k = 3 * 2048 + 5, 2, 77
+    wl = _wl(d, n=n, k=k)
+    zero = torch.zeros((n, d), device=gpu_device)
+    _run(wl, gpu_device, steps=2, grads=[zero])           # keys all 0: indices 0..k-1
+    same = torch.full((n, d), -0.5, device=gpu_device)
+    same[1] = 0.25
+    _run(wl, gpu_device, steps=2, grads=[same])
+    pair = Pair(wl, gpu_device)
+    try:
+        pair.gpu_step(0, zero)
+        assert pair.pw.to_numpy()["idx"].tolist() == [list(range(k))] * n
+    finally:
+        pair.close()
+
+
+def test_topk_tie_heavy_levels(gpu_device):
+    # magnitudes from 8 distinct values only: the threshold bin holds d/8 exact ties
+    _run(W.c3_ties(d=1 << 20, n=4), gpu_device, steps=2)
+
+
+def test_topk_pm_pairs_and_denormals(gpu_device):
+    d, n = 20_000, 2
+    wl = _wl(d, n=n, k=500)
+    r = np.random.default_rng(0)
+    base = np.repeat(r.standard_normal(d // 2), 2) * np.tile([1.0, -1.0], d // 2)
+    g = np.stack([base, base[::-1] * 1e-42]).astype(np.float32)    # second row: denormals
+    _run(wl, gpu_device, steps=2, grads=[torch.from_numpy(g).to(gpu_device)])
+
+
+def test_topk_c3_scaled(gpu_device):
+    wl = W.c3(d=25_557_032 // 16, n=8)
+    _run(wl, gpu_device, steps=3)
+
+
+def test_topk_bf16_momentum(gpu_device):
+    _run(_wl(30_011, n=4, k=300, grad_dtype="bf16", beta=0.9, gamma=0.1), gpu_device, steps=3)
+
+
+def test_topk_unaligned_rows(gpu_device):
+    wl = _wl(10_002, n=3, k=100)       # d mod 4 = 2: rows 1, 2 start 8-byte aligned only
+    _run(wl, gpu_device, steps=2)
