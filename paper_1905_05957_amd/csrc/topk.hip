@@ -4,22 +4,27 @@
 // resolved towards the lower index.
 //
 // Selection is exact and deterministic: a radix select on the 31-bit magnitude pattern
-// key = bits(v) & 0x7FFFFFFF, 12 + 11 + 8 bits.
-//   pass 1   (dense)  v = g + delta is written into the delta buffer and histogrammed on
-//                     the top 12 key bits (LDS histogram per persistent workgroup).
-//   pick 1            the bin b1 that holds the k-th largest key.
-//   compact  (dense)  every element with key >= b1 << 19 becomes a candidate
-//                     (index, value), written tile by tile into a compact list; elements of
-//                     bin b1 are histogrammed on the next 11 bits.
-//   pick 2, hist 3, pick 3   work on the candidate list only (about k entries) and end with
-//                     the exact threshold key T and the number of ties at T to keep.
-//   count / scan / emit      per tile, in tile order: entries above T plus the first ties
-//                     by index, written at their scanned offsets, so the output is sorted
-//                     by index with no sort; kept positions of the error buffer are zeroed
-//                     (delta = v - Q[v] is 0 there and v elsewhere).
-// The candidate order inside a tile is index order (ballot + prefix count), tiles are
-// placed by an atomic counter but addressed through a per-tile table, so the result does
-// not depend on scheduling.
+// key = bits(v) & 0x7FFFFFFF in 12 + 11 + 8 bits, arranged so that the dense vector is
+// looked at ONCE:
+//   sample     256 evenly spread 256-element subtiles of v are histogrammed (12 key bits);
+//              the bin holding the sample's r-th largest key, r about 1.5 k |sample| / d,
+//              is a lower bound lo_bin for the k-th key's bin with overwhelming probability.
+//   pass 1     (dense, the one HBM pass) v is formed and written into the error buffer;
+//              every element with key >= lo_bin << 19 becomes a candidate (index, value).
+//              Each wavefront compacts the candidates of its own 256-element subtile, in
+//              index order, into that subtile's fixed slot region: no shared counters, no
+//              LDS, no barriers.
+//   hist 1..3  over the candidates only (about 1.5 k of them): 12, 11, 8 key bits, each
+//              followed by a pick of the bin that holds the k-th key -> exact threshold key
+//              T and the number of ties at T to keep.
+//   verify     if the candidates number fewer than k (the sample misjudged), the row falls
+//              back to the exact two-look route: dense 12-bit histogram of the stored v,
+//              pick, dense compaction.  Those kernels exit at once for rows that need none.
+//   count / scan / emit   per 16384-element group, in order: entries above T plus the first
+//              ties by index are written at scanned offsets, so the output is sorted by
+//              index without a sort; kept positions of the error buffer are zeroed
+//              (delta = v - Q[v] is 0 there and v elsewhere).
+// Nothing depends on scheduling order, so results are bit-reproducible.
 #include "ds_device.h"
 #include "ds_internal.h"
 
@@ -29,16 +34,21 @@ using namespace ds;
 
 namespace {
 
+constexpr int kSub = 256;                  // elements per subtile = one wavefront of the dense pass
+constexpr int kGroupSubs = 64;             // subtiles per group = one wavefront of the candidate passes
+constexpr int kGroup = kSub * kGroupSubs;  // 16384 elements
 constexpr int kH1 = 4096, kH2 = 2048, kH3 = 256;
-constexpr int kHistRow = kH1 + kH2 + kH3;
-constexpr int kTilesPerBlock = kWaves;  // wave-per-tile kernels
+constexpr int kOffSample = 0, kOffH1 = kH1, kOffH2 = 2 * kH1, kOffH3 = 2 * kH1 + kH2, kOffH1F = 2 * kH1 + kH2 + kH3;
+constexpr int kHistRow = 3 * kH1 + kH2 + kH3;
+constexpr int kSampleSubs = 256;           // subtiles sampled per row
+constexpr uint32_t kNone = 0xFFFFFFFFu;
 
 struct Sel {
-    uint32_t b1, k1;   // top-12-bit bin of the k-th key; entries still needed from it
-    uint32_t b2, k2;   // next 11 bits; entries still needed from that sub-bin
-    uint32_t T, k3;    // threshold key; ties at T to keep (lowest indices first)
-    uint32_t n_cand;   // candidates = elements with key >= b1 << 19
-    uint32_t alloc;    // running allocation in the candidate list
+    uint32_t lo_bin;    // candidates are the elements whose top-12-bit bin is >= lo_bin
+    uint32_t fallback;  // 1: too few candidates, the row takes the two-look route
+    uint32_t b1, k1;    // top-12-bit bin of the k-th key; entries still needed from it
+    uint32_t b2, k2;    // next 11 bits; entries still needed from that sub-bin
+    uint32_t T, k3;     // threshold key; ties at T to keep (lowest indices first)
 };
 
 __device__ __forceinline__ uint32_t key_of(float v) { return __float_as_uint(v) & 0x7FFFFFFFu; }
@@ -52,62 +62,95 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t m)
 }  // namespace
 
 struct ds_topk_scratch {
-    uint32_t *hist;      // [rows][kHistRow]
-    Sel *sel;            // [rows]
-    u32x2 *cand;         // [rows][d]  (index, value bits)
-    uint32_t *tile_off;  // [rows][n_tiles] start of the tile's candidates
-    uint32_t *tile_cnt;  // [rows][n_tiles] number of candidates
-    uint32_t *tile_gt;   // [rows][n_tiles] candidates with key > T
-    uint32_t *tile_eq;   // [rows][n_tiles] candidates with key == T
-    uint32_t *tile_eqb;  // [rows][n_tiles] ties at T in earlier tiles
-    uint32_t *tile_out;  // [rows][n_tiles] first output slot of the tile
+    uint32_t *hist;       // [rows][kHistRow]
+    Sel *sel;             // [rows]
+    u32x2 *slots;         // [rows][n_sub * 256] candidate (index, value bits), per subtile region
+    uint32_t *sub_cnt;    // [rows][sub_pad]  candidates per subtile
+    uint32_t *grp_gt;     // [rows][n_groups] candidates with key > T
+    uint32_t *grp_eq;     // [rows][n_groups] candidates with key == T
+    uint32_t *grp_eqb;    // [rows][n_groups] ties at T in earlier groups
+    uint32_t *grp_out;    // [rows][n_groups] first output slot of the group
+    uint32_t *sub_start;  // [n][n_sub + 1]   server: first entry of each worker's message per subtile
+    int64_t n_sub, sub_pad, n_groups;
     int rows;
 };
 
 namespace {
 
+// ---------------------------------------------------------------------------------------
+// sources of v, one f32x4 per lane, one 256-element subtile per wavefront
+// ---------------------------------------------------------------------------------------
+template <bool BF16>
+struct WorkerV {   // v = g + delta
+    const void *g;
+    int64_t gs;
+    const float *delta;
+    int64_t dstr;
+    __device__ __forceinline__ f32x4 load(int row, int64_t e, int64_t d, float *) const
+    {
+        const void *grow = BF16 ? static_cast<const void *>(static_cast<const uint16_t *>(g) + row * gs)
+                                : static_cast<const void *>(static_cast<const float *>(g) + row * gs);
+        const float *drow = delta + row * dstr;
+        return ld4_grad<BF16>(grow, e, d, BF16 ? aligned8(grow) : aligned16(grow)) + ld4(drow, e, d, aligned16(drow));
+    }
+};
+
+struct BufferV {   // v already stored
+    const float *buf;
+    int64_t stride;
+    __device__ __forceinline__ f32x4 load(int row, int64_t e, int64_t d, float *) const
+    {
+        const float *brow = buf + row * stride;
+        return ld4(brow, e, d, aligned16(brow));
+    }
+};
+
+// Server: v = delta_s + (1/n) sum_i Q[v_i] for sparse messages, as the chain
+// acc = fma(val, 1/n, acc) over workers in ascending order.  The wavefront keeps its subtile
+// in a private LDS strip; a message lists an index once, so the lanes of one worker never
+// collide, and the wavefront's LDS operations retire in program order, which keeps the
+// workers' order.
+struct ServerV {
+    const u32x2 *pairs_in;      // [n][k]
+    const uint32_t *sub_start;  // [n][n_sub + 1]
+    const float *delta_s;
+    int64_t k, n_sub;
+    int32_t n;
+    float inv_n;
+    __device__ __forceinline__ f32x4 load(int, int64_t e, int64_t d, float *strip) const
+    {
+        const int lane = lane_id();
+        const f32x4 a = ld4(delta_s, e, d, aligned16(delta_s));
+        strip[lane * 4 + 0] = a.x; strip[lane * 4 + 1] = a.y; strip[lane * 4 + 2] = a.z; strip[lane * 4 + 3] = a.w;
+        const int64_t sub = e >> 8;
+        const uint32_t base = static_cast<uint32_t>(sub << 8);
+        for (int i = 0; i < n; ++i) {
+            const uint32_t s0 = sub_start[i * (n_sub + 1) + sub];
+            uint32_t s1 = sub_start[i * (n_sub + 1) + sub + 1];
+            if (s1 > static_cast<uint32_t>(k)) s1 = static_cast<uint32_t>(k);
+            const u32x2 *p = pairs_in + i * k;
+            __builtin_amdgcn_wave_barrier();
+            for (uint32_t j = s0 + lane; j < s1; j += 64) {
+                const u32x2 pr = p[j];
+                const uint32_t rel = pr.x - base;
+                if (rel < static_cast<uint32_t>(kSub)) strip[rel] = __fmaf_rn(__uint_as_float(pr.y), inv_n, strip[rel]);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+        return f32x4{strip[lane * 4 + 0], strip[lane * 4 + 1], strip[lane * 4 + 2], strip[lane * 4 + 3]};
+    }
+};
+
+// ---------------------------------------------------------------------------------------
+// small kernels
+// ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void k_topk_zero(uint32_t *hist, Sel *sel, int rows)
 {
     const int total = rows * kHistRow;
     for (int i = blockIdx.x * kBlock + threadIdx.x; i < total; i += gridDim.x * kBlock) hist[i] = 0u;
-    if (blockIdx.x == 0 && threadIdx.x < rows) sel[threadIdx.x].alloc = 0u;
     if (blockIdx.x == 0)
-        for (int r = threadIdx.x + kBlock; r < rows; r += kBlock) sel[r].alloc = 0u;
-}
-
-__device__ __forceinline__ void hist4(uint32_t *h, f32x4 v, int64_t e, int64_t d)
-{
-    if (e + 0 < d) atomicAdd(&h[key_of(v.x) >> 19], 1u);
-    if (e + 1 < d) atomicAdd(&h[key_of(v.y) >> 19], 1u);
-    if (e + 2 < d) atomicAdd(&h[key_of(v.z) >> 19], 1u);
-    if (e + 3 < d) atomicAdd(&h[key_of(v.w) >> 19], 1u);
-}
-
-// Pass 1, worker: v = g + delta -> delta buffer, 12-bit histogram.  Persistent workgroups.
-template <bool BF16>
-__global__ __launch_bounds__(kBlock) void k_topk_pass1_worker(const void *g, int64_t gs, float *delta, int64_t dstr,
-                                                              int64_t d, int64_t n_tiles, uint32_t *hist)
-{
-    __shared__ uint32_t h[kH1];
-    const int row = blockIdx.y;
-    for (int i = threadIdx.x; i < kH1; i += kBlock) h[i] = 0u;
-    __syncthreads();
-    const void *grow = BF16 ? static_cast<const void *>(static_cast<const uint16_t *>(g) + row * gs)
-                            : static_cast<const void *>(static_cast<const float *>(g) + row * gs);
-    float *drow = delta + row * dstr;
-    const bool gvec = BF16 ? aligned8(grow) : aligned16(grow);
-    const bool dvec = aligned16(drow);
-    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const int64_t e = tile * kTile + threadIdx.x * 4;
-        if (e >= d) continue;
-        const f32x4 v = ld4_grad<BF16>(grow, e, d, gvec) + ld4(drow, e, d, dvec);
-        st4(drow, e, d, dvec, v);
-        hist4(h, v, e, d);
-    }
-    __syncthreads();
-    uint32_t *hrow = hist + static_cast<int64_t>(row) * kHistRow;
-    for (int i = threadIdx.x; i < kH1; i += kBlock)
-        if (h[i]) atomicAdd(&hrow[i], h[i]);
+        for (int r = threadIdx.x; r < rows; r += kBlock) sel[r] = Sel{0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
 }
 
 // First position in idx-sorted pairs[0..k) whose index is >= target.
@@ -116,76 +159,62 @@ __device__ __forceinline__ int64_t lower_bound_idx(const u32x2 *__restrict__ pai
     int64_t lo = 0, hi = k;
     while (lo < hi) {
         const int64_t mid = (lo + hi) >> 1;
-        if (static_cast<int64_t>(static_cast<int32_t>(pairs[mid].x)) < target) lo = mid + 1;
+        if (static_cast<int64_t>(pairs[mid].x) < target) lo = mid + 1;
         else hi = mid;
     }
     return lo;
 }
 
-// Adds, in worker order, the entries of every worker's message that fall into the tile
-// [base, base + 2048) onto the tile held in LDS: tilev[j] = fma(val, 1/n, tilev[j]).
-// A message lists each index once, so one worker's entries never collide; workers are
-// separated by barriers, which keeps the chain order of the server's average.
-__device__ __forceinline__ void scatter_messages(float *tilev, int64_t *lo_sh, int64_t *hi_sh,
-                                                 const u32x2 *__restrict__ pairs_in, int n, int64_t k,
-                                                 float inv_n, int64_t base)
+// Server: sub_start[i][s] = first entry of worker i's message with index >= 256 s
+// (a binary search per subtile boundary: the cost does not depend on how k relates to d).
+__global__ __launch_bounds__(kBlock) void k_topk_sub_starts(const u32x2 *pairs_in, int64_t k, int64_t n_sub,
+                                                            uint32_t *sub_start)
 {
-    for (int i0 = 0; i0 < n; i0 += kBlock) {
-        const int cnt = (n - i0 < kBlock) ? n - i0 : kBlock;
-        __syncthreads();
-        if (static_cast<int>(threadIdx.x) < cnt) {
-            const u32x2 *p = pairs_in + static_cast<int64_t>(i0 + threadIdx.x) * k;
-            lo_sh[threadIdx.x] = lower_bound_idx(p, k, base);
-            hi_sh[threadIdx.x] = lower_bound_idx(p, k, base + kTile);
-        }
-        __syncthreads();
-        for (int i = 0; i < cnt; ++i) {
-            const u32x2 *p = pairs_in + static_cast<int64_t>(i0 + i) * k;
-            for (int64_t j = lo_sh[i] + threadIdx.x; j < hi_sh[i]; j += kBlock) {
-                const u32x2 pr = p[j];
-                const uint32_t rel = pr.x - static_cast<uint32_t>(base);
-                if (rel < static_cast<uint32_t>(kTile)) tilev[rel] = __fmaf_rn(__uint_as_float(pr.y), inv_n, tilev[rel]);
-            }
-            __syncthreads();
-        }
-    }
+    const int i = blockIdx.y;
+    const int64_t s = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (s > n_sub) return;
+    sub_start[i * (n_sub + 1) + s] = static_cast<uint32_t>(lower_bound_idx(pairs_in + i * k, k, s * kSub));
 }
 
-// Pass 1, server: v = delta_s + (1/n) sum_i Q[v_i] for sparse messages, written into the
-// delta_s buffer, 12-bit histogram.
-__global__ __launch_bounds__(kBlock) void k_topk_pass1_server(const u32x2 *pairs_in, int n, int64_t k, float inv_n,
-                                                              float *delta_s, int64_t d, int64_t n_tiles,
-                                                              uint32_t *hist)
+__device__ __forceinline__ int64_t sample_subtile(int64_t j, int64_t ns, int64_t n_sub)
+{
+    // evenly spread, with a small hashed jitter inside each stride
+    const int64_t lo = (j * n_sub) / ns, hi = ((j + 1) * n_sub) / ns;
+    const int64_t span = hi - lo;
+    const uint32_t h = static_cast<uint32_t>(j) * 2654435761u;
+    return lo + ((span > 1) ? static_cast<int64_t>((h >> 8) % static_cast<uint32_t>(span)) : 0);
+}
+
+// 12-bit histogram of v over the sampled subtiles.
+template <class Src>
+__global__ __launch_bounds__(kBlock) void k_topk_sample(Src src, int64_t d, int64_t n_sub, int64_t ns, uint32_t *hist)
 {
     __shared__ uint32_t h[kH1];
-    __shared__ float tilev[kTile];
-    __shared__ int64_t lo_sh[kBlock], hi_sh[kBlock];
+    __shared__ float strips[kWaves][kSub];
+    const int row = blockIdx.y;
     for (int i = threadIdx.x; i < kH1; i += kBlock) h[i] = 0u;
-    const bool dvec = aligned16(delta_s);
-    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const int64_t base = tile * kTile;
-        const int64_t e = base + threadIdx.x * 4;
-        const f32x4 a = ld4(delta_s, e, d, dvec);
-        tilev[threadIdx.x * 4 + 0] = a.x; tilev[threadIdx.x * 4 + 1] = a.y;
-        tilev[threadIdx.x * 4 + 2] = a.z; tilev[threadIdx.x * 4 + 3] = a.w;
-        scatter_messages(tilev, lo_sh, hi_sh, pairs_in, n, k, inv_n, base);
-        const f32x4 v = {tilev[threadIdx.x * 4 + 0], tilev[threadIdx.x * 4 + 1], tilev[threadIdx.x * 4 + 2],
-                         tilev[threadIdx.x * 4 + 3]};
-        if (e < d) {
-            st4(delta_s, e, d, dvec, v);
-            hist4(h, v, e, d);
-        }
+    __syncthreads();
+    const int64_t j = static_cast<int64_t>(blockIdx.x) * kWaves + wave_id();
+    if (j < ns) {
+        const int64_t e = sample_subtile(j, ns, n_sub) * kSub + lane_id() * 4;
+        const f32x4 v = src.load(row, e, d, strips[wave_id()]);
+        if (e + 0 < d) atomicAdd(&h[key_of(v.x) >> 19], 1u);
+        if (e + 1 < d) atomicAdd(&h[key_of(v.y) >> 19], 1u);
+        if (e + 2 < d) atomicAdd(&h[key_of(v.z) >> 19], 1u);
+        if (e + 3 < d) atomicAdd(&h[key_of(v.w) >> 19], 1u);
     }
     __syncthreads();
+    uint32_t *hrow = hist + static_cast<int64_t>(row) * kHistRow + kOffSample;
     for (int i = threadIdx.x; i < kH1; i += kBlock)
-        if (h[i]) atomicAdd(&hist[i], h[i]);
+        if (h[i]) atomicAdd(&hrow[i], h[i]);
 }
 
-// Largest bin b of hist[0..NB) with  sum_{bins >= b} >= need ;  rem = need - sum_{bins > b},
-// ge = sum_{bins >= b}.  One workgroup; the thread that owns b writes the three outputs.
+// Largest bin b of hist[0..NB) with  sum_{bins >= b} >= need ;  rem = need - sum_{bins > b}.
+// One workgroup; the thread that owns b writes the outputs (untouched if the histogram
+// holds fewer than `need` keys).
 template <int NB>
 __device__ __forceinline__ void pick_bin(const uint32_t *__restrict__ hist, uint32_t need, uint32_t *part,
-                                         uint32_t *b_out, uint32_t *rem_out, uint32_t *ge_out)
+                                         uint32_t *b_out, uint32_t *rem_out)
 {
     constexpr int PER = (NB >= kBlock) ? NB / kBlock : 1;
     const int t = threadIdx.x;
@@ -214,155 +243,239 @@ __device__ __forceinline__ void pick_bin(const uint32_t *__restrict__ hist, uint
             if (running >= need && above < need) {
                 *b_out = static_cast<uint32_t>(t * PER + j);
                 *rem_out = need - above;
-                *ge_out = running;
             }
         }
     }
 }
 
+// LEVEL 0: sample -> lo_bin.  1: candidates' 12-bit histogram -> b1, k1 or fallback.
+// 2: -> b2, k2.  3: -> T, k3.  4: fallback rows only, dense 12-bit histogram -> b1, k1.
 template <int LEVEL>
-__global__ __launch_bounds__(kBlock) void k_topk_pick(const uint32_t *hist, Sel *sel, uint32_t k)
+__global__ __launch_bounds__(kBlock) void k_topk_pick(const uint32_t *hist, Sel *sel, uint32_t need0)
 {
     __shared__ uint32_t part[kBlock];
-    __shared__ uint32_t out[3];
+    __shared__ uint32_t out[2];
     const int row = blockIdx.x;
     const uint32_t *hrow = hist + static_cast<int64_t>(row) * kHistRow;
     Sel *s = sel + row;
-    if (LEVEL == 1) pick_bin<kH1>(hrow, k, part, &out[0], &out[1], &out[2]);
-    if (LEVEL == 2) pick_bin<kH2>(hrow + kH1, s->k1, part, &out[0], &out[1], &out[2]);
-    if (LEVEL == 3) pick_bin<kH3>(hrow + kH1 + kH2, s->k2, part, &out[0], &out[1], &out[2]);
+    if (LEVEL == 4 && !s->fallback) return;
+    if (threadIdx.x == 0) { out[0] = kNone; out[1] = 0u; }
+    __syncthreads();
+    if (LEVEL == 0) pick_bin<kH1>(hrow + kOffSample, need0, part, &out[0], &out[1]);
+    if (LEVEL == 1) pick_bin<kH1>(hrow + kOffH1, need0, part, &out[0], &out[1]);
+    if (LEVEL == 2) pick_bin<kH2>(hrow + kOffH2, s->k1, part, &out[0], &out[1]);
+    if (LEVEL == 3) pick_bin<kH3>(hrow + kOffH3, s->k2, part, &out[0], &out[1]);
+    if (LEVEL == 4) pick_bin<kH1>(hrow + kOffH1F, need0, part, &out[0], &out[1]);
     __syncthreads();
     if (threadIdx.x == 0) {
-        if (LEVEL == 1) { s->b1 = out[0]; s->k1 = out[1]; s->n_cand = out[2]; }
+        if (LEVEL == 0) s->lo_bin = (out[0] == kNone) ? 0u : out[0];
+        if (LEVEL == 1) {
+            if (out[0] == kNone) s->fallback = 1u;
+            else { s->b1 = out[0]; s->k1 = out[1]; }
+        }
         if (LEVEL == 2) { s->b2 = out[0]; s->k2 = out[1]; }
         if (LEVEL == 3) { s->T = (s->b1 << 19) | (s->b2 << 8) | out[0]; s->k3 = out[1]; }
+        if (LEVEL == 4) { s->b1 = out[0]; s->k1 = out[1]; }
     }
 }
 
-// Dense look 2: candidates (key >= b1 << 19) of one tile, in index order, appended to the
-// row's candidate list; 11-bit histogram of the elements of bin b1.
-__global__ __launch_bounds__(kBlock) void k_topk_compact(const float *buf, int64_t stride, int64_t d, int64_t n_tiles,
-                                                         Sel *sel, uint32_t *hist, u32x2 *cand, uint32_t *tile_off,
-                                                         uint32_t *tile_cnt)
+// ---------------------------------------------------------------------------------------
+// the dense pass
+// ---------------------------------------------------------------------------------------
+// FALLBACK = false: v from src, stored into buf, candidates with bin >= lo_bin.
+// FALLBACK = true : rows flagged for the two-look route only; v is read back from buf,
+//                   candidates with bin >= b1.
+template <class Src, bool FALLBACK>
+__global__ __launch_bounds__(kBlock) void k_topk_pass1(Src src, float *buf, int64_t stride, int64_t d, int64_t n_sub,
+                                                       const Sel *sel, u32x2 *slots, uint32_t *sub_cnt, int64_t sub_pad)
 {
-    __shared__ uint32_t h2[kH2];
-    __shared__ uint32_t wtot[kWaves];
-    __shared__ uint32_t base_sh;
+    __shared__ float strips[FALLBACK ? 1 : kWaves][FALLBACK ? 1 : kSub];
     const int row = blockIdx.y;
-    const int64_t tile = blockIdx.x;
-    const float *brow = buf + row * stride;
-    const int64_t e = tile * kTile + threadIdx.x * 4;
-    for (int i = threadIdx.x; i < kH2; i += kBlock) h2[i] = 0u;
-    const uint32_t b1 = sel[row].b1;
-    const uint32_t lo_key = b1 << 19;
-    const f32x4 v = ld4(brow, e, d, aligned16(brow));
-    const uint32_t key[4] = {key_of(v.x), key_of(v.y), key_of(v.z), key_of(v.w)};
+    if (FALLBACK && !sel[row].fallback) return;
+    const int64_t e = static_cast<int64_t>(blockIdx.x) * kTile + threadIdx.x * 4;
+    const int64_t sub = e >> 8;
+    if (sub >= n_sub) return;                       // whole wavefront
+    const f32x4 v = src.load(row, e, d, FALLBACK ? nullptr : strips[wave_id()]);
+    if (!FALLBACK && e < d) {
+        float *brow = buf + row * stride;
+        st4(brow, e, d, aligned16(brow), v);
+    }
+    const uint32_t lo_key = (FALLBACK ? sel[row].b1 : sel[row].lo_bin) << 19;
     const uint32_t bits[4] = {__float_as_uint(v.x), __float_as_uint(v.y), __float_as_uint(v.z), __float_as_uint(v.w)};
     bool f[4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) f[c] = (e + c < d) && key[c] >= lo_key;
+    for (int c = 0; c < 4; ++c) f[c] = (e + c < d) && (bits[c] & 0x7FFFFFFFu) >= lo_key;
     const uint64_t m0 = __ballot(f[0]), m1 = __ballot(f[1]), m2 = __ballot(f[2]), m3 = __ballot(f[3]);
     const uint32_t before = lanes_below(m0) + lanes_below(m1) + lanes_below(m2) + lanes_below(m3);
-    const uint32_t wave_total = __popcll(m0) + __popcll(m1) + __popcll(m2) + __popcll(m3);
-    if (lane_id() == 0) wtot[wave_id()] = wave_total;
-    __syncthreads();
-#pragma unroll
-    for (int c = 0; c < 4; ++c)
-        if (f[c] && (key[c] >> 19) == b1) atomicAdd(&h2[(key[c] >> 8) & (kH2 - 1)], 1u);
-    uint32_t wave_off = 0, tile_total = 0;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-        if (w < wave_id()) wave_off += wtot[w];
-        tile_total += wtot[w];
-    }
-    if (threadIdx.x == 0) {
-        const uint32_t b = tile_total ? atomicAdd(&sel[row].alloc, tile_total) : 0u;
-        base_sh = b;
-        tile_off[row * n_tiles + tile] = b;
-        tile_cnt[row * n_tiles + tile] = tile_total;
-    }
-    __syncthreads();
-    u32x2 *out = cand + static_cast<int64_t>(row) * d + base_sh + wave_off + before;
+    u32x2 *out = slots + (static_cast<int64_t>(row) * n_sub + sub) * kSub + before;
     uint32_t r = 0;
 #pragma unroll
     for (int c = 0; c < 4; ++c)
         if (f[c]) out[r++] = u32x2{static_cast<uint32_t>(e + c), bits[c]};
-    uint32_t *h2g = hist + static_cast<int64_t>(row) * kHistRow + kH1;
-    for (int i = threadIdx.x; i < kH2; i += kBlock)
-        if (h2[i]) atomicAdd(&h2g[i], h2[i]);
+    if (lane_id() == 0)
+        sub_cnt[row * sub_pad + sub] = __popcll(m0) + __popcll(m1) + __popcll(m2) + __popcll(m3);
 }
 
-// Histogram of the low 8 key bits of the candidates that share the 23-bit prefix (b1, b2).
-__global__ __launch_bounds__(kBlock) void k_topk_hist3(const u32x2 *cand, int64_t d, const Sel *sel, uint32_t *hist)
+// Fallback rows: dense 12-bit histogram of the stored v.  Persistent workgroups.
+__global__ __launch_bounds__(kBlock) void k_topk_fallback_hist(const float *buf, int64_t stride, int64_t d,
+                                                               int64_t n_tiles, const Sel *sel, uint32_t *hist)
 {
-    __shared__ uint32_t h3[kH3];
+    __shared__ uint32_t h[kH1];
     const int row = blockIdx.y;
-    if (threadIdx.x < kH3) h3[threadIdx.x] = 0u;
+    if (!sel[row].fallback) return;
+    for (int i = threadIdx.x; i < kH1; i += kBlock) h[i] = 0u;
     __syncthreads();
-    const Sel s = sel[row];
-    const uint32_t prefix = (s.b1 << 11) | s.b2;
-    const u32x2 *crow = cand + static_cast<int64_t>(row) * d;
-    for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < s.n_cand; i += gridDim.x * kBlock) {
-        const uint32_t key = crow[i].y & 0x7FFFFFFFu;
-        if ((key >> 8) == prefix) atomicAdd(&h3[key & 255u], 1u);
+    const float *brow = buf + row * stride;
+    const bool vec = aligned16(brow);
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int64_t e = tile * kTile + threadIdx.x * 4;
+        if (e >= d) continue;
+        const f32x4 v = ld4(brow, e, d, vec);
+        if (e + 0 < d) atomicAdd(&h[key_of(v.x) >> 19], 1u);
+        if (e + 1 < d) atomicAdd(&h[key_of(v.y) >> 19], 1u);
+        if (e + 2 < d) atomicAdd(&h[key_of(v.z) >> 19], 1u);
+        if (e + 3 < d) atomicAdd(&h[key_of(v.w) >> 19], 1u);
     }
     __syncthreads();
-    uint32_t *h3g = hist + static_cast<int64_t>(row) * kHistRow + kH1 + kH2;
-    if (threadIdx.x < kH3 && h3[threadIdx.x]) atomicAdd(&h3g[threadIdx.x], h3[threadIdx.x]);
+    uint32_t *hrow = hist + static_cast<int64_t>(row) * kHistRow + kOffH1F;
+    for (int i = threadIdx.x; i < kH1; i += kBlock)
+        if (h[i]) atomicAdd(&hrow[i], h[i]);
 }
 
-// One wavefront per tile: how many of its candidates lie above T, how many tie with T.
-__global__ __launch_bounds__(kBlock) void k_topk_tile_count(const u32x2 *cand, int64_t d, const Sel *sel,
-                                                            const uint32_t *tile_off, const uint32_t *tile_cnt,
-                                                            int64_t n_tiles, uint32_t *tile_gt, uint32_t *tile_eq)
+// ---------------------------------------------------------------------------------------
+// candidate passes: one wavefront walks the candidates of one group (64 subtiles) in order
+// ---------------------------------------------------------------------------------------
+struct GroupWalk {
+    uint32_t c;      // this lane's subtile count
+    uint32_t P;      // inclusive prefix over lanes
+    uint32_t total;
+};
+
+__device__ __forceinline__ GroupWalk group_begin(const uint32_t *__restrict__ cnt_row, int64_t g, int64_t n_sub)
+{
+    GroupWalk w;
+    const int lane = lane_id();
+    const int64_t sub = g * kGroupSubs + lane;
+    w.c = (sub < n_sub) ? cnt_row[sub] : 0u;
+    uint32_t p = w.c;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t up = __shfl_up(p, o, 64);
+        if (lane >= o) p += up;
+    }
+    w.P = p;
+    w.total = __shfl(p, 63, 64);
+    return w;
+}
+
+// Candidate number i (in index order) of the group; all lanes must call.
+__device__ __forceinline__ u32x2 group_fetch(const GroupWalk &w, const u32x2 *__restrict__ slots_row, int64_t g,
+                                             uint32_t i, bool valid)
+{
+    int lo = 0, hi = 63;                          // first lane s with P_s > i
+#pragma unroll
+    for (int step = 0; step < 6; ++step) {
+        const int mid = (lo + hi) >> 1;
+        const uint32_t pm = __shfl(w.P, mid, 64);
+        if (pm > i) hi = mid; else lo = mid + 1;
+    }
+    const uint32_t ps = __shfl(w.P, lo, 64), cs = __shfl(w.c, lo, 64);
+    u32x2 pr = {0u, 0u};
+    if (valid) pr = slots_row[(g * kGroupSubs + lo) * kSub + (i - (ps - cs))];
+    return pr;
+}
+
+// LEVEL 1: 12-bit histogram of all candidates.  2: next 11 bits of those in bin b1.
+// 3: low 8 bits of those with prefix (b1, b2).  One group per wavefront.
+template <int LEVEL>
+__global__ __launch_bounds__(kBlock) void k_topk_cand_hist(const u32x2 *slots, const uint32_t *sub_cnt, int64_t n_sub,
+                                                           int64_t sub_pad, int64_t n_groups, const Sel *sel,
+                                                           uint32_t *hist)
+{
+    constexpr int NB = (LEVEL == 1) ? kH1 : (LEVEL == 2) ? kH2 : kH3;
+    constexpr int OFF = (LEVEL == 1) ? kOffH1 : (LEVEL == 2) ? kOffH2 : kOffH3;
+    __shared__ uint32_t h[NB];
+    const int row = blockIdx.y;
+    const Sel s = sel[row];
+    for (int i = threadIdx.x; i < NB; i += kBlock) h[i] = 0u;
+    __syncthreads();
+    const int64_t g = static_cast<int64_t>(blockIdx.x) * kWaves + wave_id();
+    if (g < n_groups) {
+        const GroupWalk w = group_begin(sub_cnt + row * sub_pad, g, n_sub);
+        const u32x2 *srow = slots + static_cast<int64_t>(row) * n_sub * kSub;
+        const uint32_t prefix = (s.b1 << 11) | s.b2;
+        for (uint32_t i0 = 0; i0 < w.total; i0 += 64) {
+            const uint32_t i = i0 + lane_id();
+            const bool valid = i < w.total;
+            const uint32_t key = group_fetch(w, srow, g, valid ? i : 0u, valid).y & 0x7FFFFFFFu;
+            if (!valid) continue;
+            if (LEVEL == 1) atomicAdd(&h[key >> 19], 1u);
+            if (LEVEL == 2 && (key >> 19) == s.b1) atomicAdd(&h[(key >> 8) & (kH2 - 1)], 1u);
+            if (LEVEL == 3 && (key >> 8) == prefix) atomicAdd(&h[key & 255u], 1u);
+        }
+    }
+    __syncthreads();
+    uint32_t *hrow = hist + static_cast<int64_t>(row) * kHistRow + OFF;
+    for (int i = threadIdx.x; i < NB; i += kBlock)
+        if (h[i]) atomicAdd(&hrow[i], h[i]);
+}
+
+// Per group: candidates above T, candidates tying with T.
+__global__ __launch_bounds__(kBlock) void k_topk_count(const u32x2 *slots, const uint32_t *sub_cnt, int64_t n_sub,
+                                                       int64_t sub_pad, int64_t n_groups, const Sel *sel,
+                                                       uint32_t *grp_gt, uint32_t *grp_eq)
 {
     const int row = blockIdx.y;
-    const int64_t tile = static_cast<int64_t>(blockIdx.x) * kTilesPerBlock + wave_id();
-    if (tile >= n_tiles) return;
+    const int64_t g = static_cast<int64_t>(blockIdx.x) * kWaves + wave_id();
+    if (g >= n_groups) return;
     const uint32_t T = sel[row].T;
-    const u32x2 *c = cand + static_cast<int64_t>(row) * d + tile_off[row * n_tiles + tile];
-    const uint32_t cnt = tile_cnt[row * n_tiles + tile];
+    const GroupWalk w = group_begin(sub_cnt + row * sub_pad, g, n_sub);
+    const u32x2 *srow = slots + static_cast<int64_t>(row) * n_sub * kSub;
     uint32_t gt = 0, eq = 0;
-    for (uint32_t i = lane_id(); i < cnt; i += 64) {
-        const uint32_t key = c[i].y & 0x7FFFFFFFu;
-        gt += key > T;
-        eq += key == T;
+    for (uint32_t i0 = 0; i0 < w.total; i0 += 64) {
+        const uint32_t i = i0 + lane_id();
+        const bool valid = i < w.total;
+        const uint32_t key = group_fetch(w, srow, g, valid ? i : 0u, valid).y & 0x7FFFFFFFu;
+        gt += valid && key > T;
+        eq += valid && key == T;
     }
     gt = wave_sum_u32(gt);
     eq = wave_sum_u32(eq);
     if (lane_id() == 0) {
-        tile_gt[row * n_tiles + tile] = gt;
-        tile_eq[row * n_tiles + tile] = eq;
+        grp_gt[row * n_groups + g] = gt;
+        grp_eq[row * n_groups + g] = eq;
     }
 }
 
-// Exclusive scan over the workgroup of one value per thread (Hillis-Steele in LDS).
+// Exclusive scan over the workgroup of one value per thread; tmp holds kWaves values.
 __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t x, uint32_t *tmp)
 {
-    const int t = threadIdx.x;
-    __syncthreads();
-    tmp[t] = x;
-    __syncthreads();
-    for (int off = 1; off < kBlock; off <<= 1) {
-        const uint32_t add = (t >= off) ? tmp[t - off] : 0u;
-        __syncthreads();
-        tmp[t] += add;
-        __syncthreads();
+    const int lane = lane_id();
+    uint32_t p = x;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t up = __shfl_up(p, o, 64);
+        if (lane >= o) p += up;
     }
-    return tmp[t] - x;
+    __syncthreads();
+    if (lane == 63) tmp[wave_id()] = p;
+    __syncthreads();
+    uint32_t before = 0;
+    for (int w = 0; w < wave_id(); ++w) before += tmp[w];
+    return before + p - x;
 }
 
-// Per row, in tile order: ties seen before each tile, and each tile's first output slot.
-__global__ __launch_bounds__(kBlock) void k_topk_scan(const Sel *sel, int64_t n_tiles, const uint32_t *tile_gt,
-                                                      const uint32_t *tile_eq, uint32_t *tile_eqb, uint32_t *tile_out)
+// Per row, in group order: ties seen before each group, and each group's first output slot.
+__global__ __launch_bounds__(kBlock) void k_topk_scan(const Sel *sel, int64_t n_groups, const uint32_t *grp_gt,
+                                                      const uint32_t *grp_eq, uint32_t *grp_eqb, uint32_t *grp_out)
 {
-    __shared__ uint32_t tmp[kBlock];
+    __shared__ uint32_t tmp[kWaves];
     const int row = blockIdx.x;
     const uint32_t k3 = sel[row].k3;
-    const int64_t per = (n_tiles + kBlock - 1) / kBlock;
-    const int64_t t0 = threadIdx.x * per, t1 = (t0 + per < n_tiles) ? t0 + per : n_tiles;
-    const uint32_t *gt = tile_gt + row * n_tiles, *eq = tile_eq + row * n_tiles;
-    uint32_t *eqb = tile_eqb + row * n_tiles, *out = tile_out + row * n_tiles;
+    const int64_t per = (n_groups + kBlock - 1) / kBlock;
+    const int64_t t0 = threadIdx.x * per, t1 = (t0 + per < n_groups) ? t0 + per : n_groups;
+    const uint32_t *gt = grp_gt + row * n_groups, *eq = grp_eq + row * n_groups;
+    uint32_t *eqb = grp_eqb + row * n_groups, *out = grp_out + row * n_groups;
     uint32_t s = 0;
     for (int64_t t = t0; t < t1; ++t) s += eq[t];
     uint32_t run = block_exclusive_scan(s, tmp);
@@ -381,29 +494,27 @@ __global__ __launch_bounds__(kBlock) void k_topk_scan(const Sel *sel, int64_t n_
     }
 }
 
-// One wavefront per tile: write the kept entries in index order and zero them in the
-// error buffer (delta = v - Q[v]).
-__global__ __launch_bounds__(kBlock) void k_topk_emit(const u32x2 *cand, int64_t d, const Sel *sel,
-                                                      const uint32_t *tile_off, const uint32_t *tile_cnt,
-                                                      const uint32_t *tile_eqb, const uint32_t *tile_out,
-                                                      int64_t n_tiles, int64_t k, u32x2 *pairs, float *buf,
-                                                      int64_t stride)
+// Per group: write the kept entries in index order and zero them in the error buffer
+// (delta = v - Q[v]).
+__global__ __launch_bounds__(kBlock) void k_topk_emit(const u32x2 *slots, const uint32_t *sub_cnt, int64_t n_sub,
+                                                      int64_t sub_pad, int64_t n_groups, const Sel *sel,
+                                                      const uint32_t *grp_eqb, const uint32_t *grp_out, int64_t k,
+                                                      u32x2 *pairs, float *buf, int64_t stride)
 {
     const int row = blockIdx.y;
-    const int64_t tile = static_cast<int64_t>(blockIdx.x) * kTilesPerBlock + wave_id();
-    if (tile >= n_tiles) return;
+    const int64_t g = static_cast<int64_t>(blockIdx.x) * kWaves + wave_id();
+    if (g >= n_groups) return;
     const Sel s = sel[row];
-    const u32x2 *c = cand + static_cast<int64_t>(row) * d + tile_off[row * n_tiles + tile];
-    const uint32_t cnt = tile_cnt[row * n_tiles + tile];
-    uint32_t eq_seen = tile_eqb[row * n_tiles + tile];
-    uint32_t out = tile_out[row * n_tiles + tile];
+    const GroupWalk w = group_begin(sub_cnt + row * sub_pad, g, n_sub);
+    const u32x2 *srow = slots + static_cast<int64_t>(row) * n_sub * kSub;
+    uint32_t eq_seen = grp_eqb[row * n_groups + g];
+    uint32_t out = grp_out[row * n_groups + g];
     u32x2 *prow = pairs + static_cast<int64_t>(row) * k;
     float *brow = buf + row * stride;
-    for (uint32_t i0 = 0; i0 < cnt; i0 += 64) {
+    for (uint32_t i0 = 0; i0 < w.total; i0 += 64) {
         const uint32_t i = i0 + lane_id();
-        const bool valid = i < cnt;
-        u32x2 pr = {0u, 0u};
-        if (valid) pr = c[i];
+        const bool valid = i < w.total;
+        const u32x2 pr = group_fetch(w, srow, g, valid ? i : 0u, valid);
         const uint32_t key = pr.y & 0x7FFFFFFFu;
         const bool is_eq = valid && key == s.T;
         const uint64_t eq_mask = __ballot(is_eq);
@@ -419,7 +530,10 @@ __global__ __launch_bounds__(kBlock) void k_topk_emit(const u32x2 *cand, int64_t
     }
 }
 
-// x <- fma(-gamma, val, x) at the kept indices (Algorithm 1, model update, sparse message).
+// ---------------------------------------------------------------------------------------
+// consumers of a sparse message
+// ---------------------------------------------------------------------------------------
+// x <- fma(-gamma, val, x) at the kept indices (Algorithm 1, model update).
 __global__ __launch_bounds__(kBlock) void k_topk_update_sparse(const u32x2 *pairs, int64_t k, float *x, int64_t d,
                                                                float gamma)
 {
@@ -436,36 +550,23 @@ __global__ __launch_bounds__(kBlock) void k_topk_dense_apply(const u32x2 *pairs,
                                                              int64_t d, float gamma, float beta)
 {
     __shared__ float tilev[kTile];
-    __shared__ int64_t lo_sh[kBlock], hi_sh[kBlock];
+    __shared__ int64_t range[2];
     const int64_t base = static_cast<int64_t>(blockIdx.x) * kTile;
     const int64_t e = base + threadIdx.x * 4;
 #pragma unroll
     for (int c = 0; c < 4; ++c) tilev[threadIdx.x * 4 + c] = 0.f;
-    scatter_messages(tilev, lo_sh, hi_sh, pairs, 1, k, 1.0f, base);
+    if (threadIdx.x < 2) range[threadIdx.x] = lower_bound_idx(pairs, k, base + threadIdx.x * kTile);
+    __syncthreads();
+    for (int64_t j = range[0] + threadIdx.x; j < range[1]; j += kBlock) {
+        const u32x2 pr = pairs[j];
+        const uint32_t rel = pr.x - static_cast<uint32_t>(base);
+        if (rel < static_cast<uint32_t>(kTile)) tilev[rel] = __uint_as_float(pr.y);
+    }
+    __syncthreads();
     if (e >= d) return;
     const f32x4 q = {tilev[threadIdx.x * 4 + 0], tilev[threadIdx.x * 4 + 1], tilev[threadIdx.x * 4 + 2],
                      tilev[threadIdx.x * 4 + 3]};
     apply_q4<MOM, DECODE_ONLY>(q, e, d, x, m, gamma, beta);
-}
-
-// selection pipeline shared by worker (rows = n) and server (rows = 1), after pass 1
-ds_status_t select_and_emit(ds_ctx *c, int rows, float *buf, int64_t stride, u32x2 *pairs, hipStream_t st)
-{
-    ds_topk_scratch *t = c->topk;
-    const int64_t d = c->cfg.d, n_tiles = c->n_tiles, k = c->cfg.k;
-    const unsigned tile_blocks = static_cast<unsigned>((n_tiles + kTilesPerBlock - 1) / kTilesPerBlock);
-    k_topk_pick<1><<<rows, kBlock, 0, st>>>(t->hist, t->sel, static_cast<uint32_t>(k));
-    k_topk_compact<<<dim3(static_cast<unsigned>(n_tiles), rows), kBlock, 0, st>>>(buf, stride, d, n_tiles, t->sel, t->hist,
-                                                                                 t->cand, t->tile_off, t->tile_cnt);
-    k_topk_pick<2><<<rows, kBlock, 0, st>>>(t->hist, t->sel, 0u);
-    k_topk_hist3<<<dim3(64, rows), kBlock, 0, st>>>(t->cand, d, t->sel, t->hist);
-    k_topk_pick<3><<<rows, kBlock, 0, st>>>(t->hist, t->sel, 0u);
-    k_topk_tile_count<<<dim3(tile_blocks, rows), kBlock, 0, st>>>(t->cand, d, t->sel, t->tile_off, t->tile_cnt, n_tiles,
-                                                                 t->tile_gt, t->tile_eq);
-    k_topk_scan<<<rows, kBlock, 0, st>>>(t->sel, n_tiles, t->tile_gt, t->tile_eq, t->tile_eqb, t->tile_out);
-    k_topk_emit<<<dim3(tile_blocks, rows), kBlock, 0, st>>>(t->cand, d, t->sel, t->tile_off, t->tile_cnt, t->tile_eqb,
-                                                           t->tile_out, n_tiles, k, pairs, buf, stride);
-    return ds_launch_status();
 }
 
 unsigned persistent_blocks(int64_t n_tiles, int rows)
@@ -476,6 +577,44 @@ unsigned persistent_blocks(int64_t n_tiles, int rows)
     return static_cast<unsigned>(per_row);
 }
 
+// sample -> dense pass -> refinement -> ordered emission, for `rows` vectors
+template <class Src>
+ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t stride, u32x2 *pairs, hipStream_t st)
+{
+    ds_topk_scratch *t = c->topk;
+    const int64_t d = c->cfg.d, k = c->cfg.k, n_sub = t->n_sub, sub_pad = t->sub_pad, n_groups = t->n_groups;
+    const int64_t ns = (n_sub < kSampleSubs) ? n_sub : kSampleSubs;
+    // sample rank: 1.5 x the expected number of top-k members in the sample, plus slack
+    const double sample_elems = static_cast<double>((ns * kSub < d) ? ns * kSub : d);
+    double r = 1.5 * static_cast<double>(k) * sample_elems / static_cast<double>(d) + 16.0;
+    if (r > 4.0e9) r = 4.0e9;
+    const uint32_t rank = static_cast<uint32_t>(r);
+    const unsigned grp_blocks = static_cast<unsigned>((n_groups + kWaves - 1) / kWaves);
+    const dim3 dense(static_cast<unsigned>(c->n_tiles), rows), cand(grp_blocks, rows);
+    const BufferV bsrc{buf, stride};
+
+    k_topk_sample<Src><<<dim3(static_cast<unsigned>((ns + kWaves - 1) / kWaves), rows), kBlock, 0, st>>>(src, d, n_sub, ns, t->hist);
+    k_topk_pick<0><<<rows, kBlock, 0, st>>>(t->hist, t->sel, rank);
+    k_topk_pass1<Src, false><<<dense, kBlock, 0, st>>>(src, buf, stride, d, n_sub, t->sel, t->slots, t->sub_cnt, sub_pad);
+    k_topk_cand_hist<1><<<cand, kBlock, 0, st>>>(t->slots, t->sub_cnt, n_sub, sub_pad, n_groups, t->sel, t->hist);
+    k_topk_pick<1><<<rows, kBlock, 0, st>>>(t->hist, t->sel, static_cast<uint32_t>(k));
+    // two-look route for rows whose sample misjudged; no-ops otherwise
+    k_topk_fallback_hist<<<dim3(persistent_blocks(c->n_tiles, rows), rows), kBlock, 0, st>>>(buf, stride, d, c->n_tiles,
+                                                                                            t->sel, t->hist);
+    k_topk_pick<4><<<rows, kBlock, 0, st>>>(t->hist, t->sel, static_cast<uint32_t>(k));
+    k_topk_pass1<BufferV, true><<<dense, kBlock, 0, st>>>(bsrc, buf, stride, d, n_sub, t->sel, t->slots, t->sub_cnt, sub_pad);
+    // refinement on the candidates
+    k_topk_cand_hist<2><<<cand, kBlock, 0, st>>>(t->slots, t->sub_cnt, n_sub, sub_pad, n_groups, t->sel, t->hist);
+    k_topk_pick<2><<<rows, kBlock, 0, st>>>(t->hist, t->sel, 0u);
+    k_topk_cand_hist<3><<<cand, kBlock, 0, st>>>(t->slots, t->sub_cnt, n_sub, sub_pad, n_groups, t->sel, t->hist);
+    k_topk_pick<3><<<rows, kBlock, 0, st>>>(t->hist, t->sel, 0u);
+    k_topk_count<<<cand, kBlock, 0, st>>>(t->slots, t->sub_cnt, n_sub, sub_pad, n_groups, t->sel, t->grp_gt, t->grp_eq);
+    k_topk_scan<<<rows, kBlock, 0, st>>>(t->sel, n_groups, t->grp_gt, t->grp_eq, t->grp_eqb, t->grp_out);
+    k_topk_emit<<<cand, kBlock, 0, st>>>(t->slots, t->sub_cnt, n_sub, sub_pad, n_groups, t->sel, t->grp_eqb, t->grp_out, k,
+                                         pairs, buf, stride);
+    return ds_launch_status();
+}
+
 }  // namespace
 
 ds_status_t ds_topk_init(ds_ctx *c)
@@ -484,14 +623,19 @@ ds_status_t ds_topk_init(ds_ctx *c)
     if (!t) return DS_ERR_DEVICE;
     *t = ds_topk_scratch{};
     c->topk = t;
-    const size_t rows = static_cast<size_t>(c->cfg.n), nt = static_cast<size_t>(c->n_tiles);
+    const size_t rows = static_cast<size_t>(c->cfg.n);
     t->rows = c->cfg.n;
+    t->n_sub = (c->cfg.d + kSub - 1) / kSub;
+    t->n_groups = (t->n_sub + kGroupSubs - 1) / kGroupSubs;
+    t->sub_pad = t->n_groups * kGroupSubs;
     DS_HIP_TRY(hipMalloc(&t->hist, rows * kHistRow * sizeof(uint32_t)));
     DS_HIP_TRY(hipMalloc(&t->sel, rows * sizeof(Sel)));
-    DS_HIP_TRY(hipMalloc(&t->cand, rows * static_cast<size_t>(c->cfg.d) * sizeof(u32x2)));
-    uint32_t **tabs[6] = {&t->tile_off, &t->tile_cnt, &t->tile_gt, &t->tile_eq, &t->tile_eqb, &t->tile_out};
-    for (auto tab : tabs) DS_HIP_TRY(hipMalloc(tab, rows * nt * sizeof(uint32_t)));
-    DS_HIP_TRY(hipMemset(t->sel, 0, rows * sizeof(Sel)));
+    DS_HIP_TRY(hipMalloc(&t->slots, rows * static_cast<size_t>(t->n_sub) * kSub * sizeof(u32x2)));
+    DS_HIP_TRY(hipMalloc(&t->sub_cnt, rows * static_cast<size_t>(t->sub_pad) * sizeof(uint32_t)));
+    uint32_t **tabs[4] = {&t->grp_gt, &t->grp_eq, &t->grp_eqb, &t->grp_out};
+    for (auto tab : tabs) DS_HIP_TRY(hipMalloc(tab, rows * static_cast<size_t>(t->n_groups) * sizeof(uint32_t)));
+    DS_HIP_TRY(hipMalloc(&t->sub_start, rows * static_cast<size_t>(t->n_sub + 1) * sizeof(uint32_t)));
+    DS_HIP_TRY(hipMemset(t->sub_cnt, 0, rows * static_cast<size_t>(t->sub_pad) * sizeof(uint32_t)));
     return DS_OK;
 }
 
@@ -499,7 +643,7 @@ void ds_topk_fini(ds_ctx *c)
 {
     ds_topk_scratch *t = c->topk;
     if (!t) return;
-    void *ptrs[9] = {t->hist, t->sel, t->cand, t->tile_off, t->tile_cnt, t->tile_gt, t->tile_eq, t->tile_eqb, t->tile_out};
+    void *ptrs[9] = {t->hist, t->sel, t->slots, t->sub_cnt, t->grp_gt, t->grp_eq, t->grp_eqb, t->grp_out, t->sub_start};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     delete t;
@@ -511,22 +655,22 @@ ds_status_t ds_topk_worker(ds_ctx *c, const void *g, int64_t gs, float *delta, i
 {
     ds_topk_scratch *t = c->topk;
     const int rows = c->cfg.n;
+    u32x2 *pairs = reinterpret_cast<u32x2 *>(out->pairs);
     k_topk_zero<<<8, kBlock, 0, st>>>(t->hist, t->sel, rows);
-    dim3 grid(persistent_blocks(c->n_tiles, rows), rows);
-    if (c->cfg.grad_dtype == DS_BF16)
-        k_topk_pass1_worker<true><<<grid, kBlock, 0, st>>>(g, gs, delta, dstr, c->cfg.d, c->n_tiles, t->hist);
-    else
-        k_topk_pass1_worker<false><<<grid, kBlock, 0, st>>>(g, gs, delta, dstr, c->cfg.d, c->n_tiles, t->hist);
-    return select_and_emit(c, rows, delta, dstr, reinterpret_cast<u32x2 *>(out->pairs), st);
+    if (c->cfg.grad_dtype == DS_BF16) return run_select(c, rows, WorkerV<true>{g, gs, delta, dstr}, delta, dstr, pairs, st);
+    return run_select(c, rows, WorkerV<false>{g, gs, delta, dstr}, delta, dstr, pairs, st);
 }
 
 ds_status_t ds_topk_server(ds_ctx *c, const ds_payload_t *in, float *delta_s, const ds_payload_t *out, hipStream_t st)
 {
     ds_topk_scratch *t = c->topk;
+    const u32x2 *pairs_in = reinterpret_cast<const u32x2 *>(in->pairs);
+    const int64_t k = c->cfg.k;
     k_topk_zero<<<8, kBlock, 0, st>>>(t->hist, t->sel, 1);
-    k_topk_pass1_server<<<persistent_blocks(c->n_tiles, 1), kBlock, 0, st>>>(
-        reinterpret_cast<const u32x2 *>(in->pairs), c->cfg.n, c->cfg.k, c->inv_n, delta_s, c->cfg.d, c->n_tiles, t->hist);
-    return select_and_emit(c, 1, delta_s, c->cfg.d, reinterpret_cast<u32x2 *>(out->pairs), st);
+    k_topk_sub_starts<<<dim3(static_cast<unsigned>((t->n_sub + 1 + kBlock - 1) / kBlock), c->cfg.n), kBlock, 0, st>>>(
+        pairs_in, k, t->n_sub, t->sub_start);
+    const ServerV src{pairs_in, t->sub_start, delta_s, k, t->n_sub, c->cfg.n, c->inv_n};
+    return run_select(c, 1, src, delta_s, c->cfg.d, reinterpret_cast<u32x2 *>(out->pairs), st);
 }
 
 ds_status_t ds_topk_update(ds_ctx *c, const ds_payload_t *srv, float *x, float *m, float gamma, float beta, hipStream_t st)

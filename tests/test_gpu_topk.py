@@ -75,3 +75,29 @@ def test_topk_bf16_momentum(gpu_device):
 def test_topk_unaligned_rows(gpu_device):
     wl = _wl(10_002, n=3, k=100)       # d mod 4 = 2: rows 1, 2 start 8-byte aligned only
     _run(wl, gpu_device, steps=2)
+
+
+def _sampled_subtiles(n_sub, ns=256):
+    """The subtiles the selection kernel samples (evenly spread with a hashed jitter); kept in
+    step with the kernel only to build an adversarial input for its verify-and-fall-back."""
+    out = []
+    for j in range(ns):
+        lo, hi = (j * n_sub) // ns, ((j + 1) * n_sub) // ns
+        span = hi - lo
+        h = (j * 2654435761) & 0xFFFFFFFF
+        out.append(lo + ((h >> 8) % span if span > 1 else 0))
+    return out
+
+
+def test_topk_sample_misjudges_and_falls_back(gpu_device):
+    # large values exactly where the sampler looks, small ones elsewhere, k above the number
+    # of large values: the sampled lower bound is too high and the exact route must take over
+    d, n = 1 << 20, 2
+    k = d // 10
+    g = (torch.rand((n, d), device=gpu_device) * 1e-3 + 1e-4)
+    g = g * (torch.randint(0, 2, (n, d), device=gpu_device) * 2 - 1)
+    for s in _sampled_subtiles(d // 256):
+        g[:, s * 256:(s + 1) * 256] = 1.0
+    assert int((g[0].abs() >= 1.0).sum()) < k
+    wl = _wl(d, n=n, k=k)
+    _run(wl, gpu_device, steps=2, grads=[g])
