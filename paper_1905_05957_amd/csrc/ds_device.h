@@ -117,31 +117,38 @@ __device__ __forceinline__ double block_sum(double x, double *lds, bool guard = 
 }
 
 // Sign-plane packing by wavefront ballot.  Each lane passes the "negative" flags of its
-// four consecutive elements; the wavefront's 256 elements form 32 bytes of the plane
-// (element j of the wavefront = bit j&7 of byte j>>3).  Lane b < 32 returns byte b; lanes
-// 32..63 return the same bytes again (b & 31).
-__device__ __forceinline__ uint32_t wave_sign_byte(bool n0, bool n1, bool n2, bool n3)
+// four consecutive elements; the wavefront's 256 elements form eight 32-bit words of the
+// plane (element j of the wavefront = bit j & 31 of word j >> 5).  Lane q < 8 returns word q
+// (it covers lanes 8q .. 8q+7); lanes 8..63 return the words again (q & 7).
+__device__ __forceinline__ uint32_t spread4(uint32_t x)   // bit i of the low byte -> bit 4 i
 {
-    const uint64_t m0 = __ballot(n0), m1 = __ballot(n1), m2 = __ballot(n2), m3 = __ballot(n3);
-    const int sh = (lane_id() & 31) * 2;       // byte b covers lanes 2b and 2b+1
-    const uint32_t a0 = static_cast<uint32_t>(m0 >> sh) & 3u;
-    const uint32_t a1 = static_cast<uint32_t>(m1 >> sh) & 3u;
-    const uint32_t a2 = static_cast<uint32_t>(m2 >> sh) & 3u;
-    const uint32_t a3 = static_cast<uint32_t>(m3 >> sh) & 3u;
-    return (a0 & 1u) | ((a1 & 1u) << 1) | ((a2 & 1u) << 2) | ((a3 & 1u) << 3) |
-           ((a0 >> 1) << 4) | ((a1 >> 1) << 5) | ((a2 >> 1) << 6) | ((a3 >> 1) << 7);
+    x = (x | (x << 12)) & 0x000F000Fu;
+    x = (x | (x << 6)) & 0x03030303u;
+    x = (x | (x << 3)) & 0x11111111u;
+    return x;
 }
 
-// Writes the wavefront's 32 sign bytes for the 256 elements starting at element `first`
-// (a multiple of 256) of a row.  Only bytes whose first element is below `bit_lim` are
+__device__ __forceinline__ uint32_t wave_sign_word(bool n0, bool n1, bool n2, bool n3)
+{
+    const uint64_t m0 = __ballot(n0), m1 = __ballot(n1), m2 = __ballot(n2), m3 = __ballot(n3);
+    const int sh = (lane_id() & 7) * 8;
+    const uint32_t x0 = static_cast<uint32_t>(m0 >> sh) & 0xFFu, x1 = static_cast<uint32_t>(m1 >> sh) & 0xFFu;
+    const uint32_t x2 = static_cast<uint32_t>(m2 >> sh) & 0xFFu, x3 = static_cast<uint32_t>(m3 >> sh) & 0xFFu;
+    return spread4(x0) | (spread4(x1) << 1) | (spread4(x2) << 2) | (spread4(x3) << 3);
+}
+
+// Writes the wavefront's eight sign words for the 256 elements starting at element `first`
+// (a multiple of 256) of a row.  Only words whose first element is below `bit_lim` are
 // written; bit_lim is a multiple of 64: the end of the caller's chunk, or 64*ceil(d/64) at
 // the end of the row so that the pad bits of the last word are written as zero.
-__device__ __forceinline__ void store_sign_bytes(uint64_t *__restrict__ words_row, int64_t first,
-                                                 int64_t bit_lim, uint32_t byte)
+// Streaming stores: on MI355X the small side stream of sign words costs 9 % of the worker
+// pass with ordinary stores and half of that with non-temporal ones.
+__device__ __forceinline__ void store_sign_words(uint64_t *__restrict__ words_row, int64_t first,
+                                                 int64_t bit_lim, uint32_t word)
 {
-    const int b = lane_id();
-    if (b < 32 && first + 8 * b < bit_lim)
-        reinterpret_cast<uint8_t *>(words_row)[(first >> 3) + b] = static_cast<uint8_t>(byte);
+    const int q = lane_id();
+    if (q < 8 && first + 32 * q < bit_lim)
+        __builtin_nontemporal_store(word, reinterpret_cast<uint32_t *>(words_row) + (first >> 5) + q);
 }
 
 // The four sign bits of elements e..e+3 (e a multiple of 4) read from a sign plane.

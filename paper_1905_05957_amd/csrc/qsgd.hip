@@ -96,8 +96,8 @@ __device__ __forceinline__ f32x4 quantise4(f32x4 v, int64_t e, uint32_t stream, 
             if (e + 2 < P.d) dst[1] = static_cast<uint8_t>(packed >> 8);
         }
     }
-    const uint32_t byte = wave_sign_byte(v.x < 0.f, v.y < 0.f, v.z < 0.f, v.w < 0.f);
-    store_sign_bytes(words_row, (e >> 8) << 8, P.W * 64, byte);
+    const uint32_t sword = wave_sign_word(v.x < 0.f, v.y < 0.f, v.z < 0.f, v.w < 0.f);
+    store_sign_words(words_row, (e >> 8) << 8, P.W * 64, sword);
     // decoded message: +-(code * norm/s)
     const float unit = __fdiv_rn(norm, static_cast<float>(P.s));
     f32x4 q;

@@ -18,6 +18,7 @@
 #include "ds_device.h"
 #include "ds_internal.h"
 
+#include <cstdlib>
 #include <vector>
 
 using namespace ds;
@@ -89,8 +90,8 @@ __device__ __forceinline__ void fused_finish(f32x4 v, int64_t base, int64_t lim,
                                              uint64_t *__restrict__ words_row, int64_t bit_lim,
                                              float *__restrict__ scale_out, double *lds)
 {
-    const uint32_t byte = wave_sign_byte(v.x < 0.f, v.y < 0.f, v.z < 0.f, v.w < 0.f);
-    store_sign_bytes(words_row, base + wave_id() * 256, bit_lim, byte);
+    const uint32_t sword = wave_sign_word(v.x < 0.f, v.y < 0.f, v.z < 0.f, v.w < 0.f);
+    store_sign_words(words_row, base + wave_id() * 256, bit_lim, sword);
     const double total = block_sum(abs_sum4(v), lds, false);
     const float scale = static_cast<float>(total / static_cast<double>(lim - base));
     if (threadIdx.x == 0) *scale_out = scale;
@@ -119,24 +120,58 @@ __global__ __launch_bounds__(kBlock) void k_sign_chunk_worker(WorkerSrc<BF16> sr
                  scales + row * S + ci, lds);
 }
 
+template <int CPW>   // chunks per workgroup: independent chunks, more bytes in flight per thread
 __global__ __launch_bounds__(kBlock) void k_sign_chunk_server(ServerArgs a, float *delta_s, int64_t d,
                                                               int64_t chunk, uint64_t *words_out,
                                                               float *scales_out)
 {
-    __shared__ double lds[kWaves];
-    const int64_t ci = blockIdx.x;
-    const int64_t base = ci * chunk;
-    const int64_t lim = (base + chunk < d) ? base + chunk : d;
+    __shared__ double lds[CPW][kWaves];
     const bool dvec = aligned16(delta_s);
-    const int64_t e = base + threadIdx.x * 4;
-    f32x4 v = ld4(delta_s, e, lim, dvec);
-    if (e < lim) {
-        for (int i = 0; i < a.n; ++i)
-            v = chain4(v, load_sign_nibble(a.words_in + i * a.W, e), a.scales_in[i * a.S + ci], a.inv_n);
+    const int lane = lane_id();
+    f32x4 v[CPW];
+    int64_t base[CPW], lim[CPW];
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) {
+        const int64_t ci = static_cast<int64_t>(blockIdx.x) * CPW + c;
+        base[c] = ci * chunk;
+        lim[c] = (base[c] + chunk < d) ? base[c] + chunk : d;     // base >= d: empty chunk, lim < base
+        v[c] = ld4(delta_s, base[c] + threadIdx.x * 4, lim[c], dvec);
     }
-    // components past lim must stay zero: they count in the sum of |v|
-    v = zero_past(v, e, lim);
-    fused_finish(v, base, lim, delta_s, dvec, words_out, (lim == d) ? a.W * 64 : lim, scales_out + ci, lds);
+    // The wavefront's 256 elements are 32 bytes of each worker's sign plane.  Eight workers at
+    // a time: lane L loads 32-bit word (L & 7) of worker (L >> 3), one load instruction for
+    // all of them; the nibble a lane needs for worker i then sits in lane 8 i + (L >> 3).
+    for (int i0 = 0; i0 < a.n; i0 += 8) {
+        const int nb = (a.n - i0 < 8) ? a.n - i0 : 8;
+        const int wi = lane >> 3;
+        uint32_t word[CPW];
+        float sc[CPW];
+#pragma unroll
+        for (int c = 0; c < CPW; ++c) {
+            const int64_t ci = static_cast<int64_t>(blockIdx.x) * CPW + c;
+            const int64_t wave_first = base[c] + wave_id() * 256;
+            word[c] = 0u;
+            if (wi < nb && wave_first + 32 * (lane & 7) < a.W * 64)
+                word[c] = reinterpret_cast<const uint32_t *>(a.words_in + (i0 + wi) * a.W)[(wave_first >> 5) + (lane & 7)];
+            sc[c] = (lane < nb && base[c] < d) ? a.scales_in[(i0 + lane) * a.S + ci] : 0.f;
+        }
+        for (int i = 0; i < nb; ++i) {
+#pragma unroll
+            for (int c = 0; c < CPW; ++c) {
+                const uint32_t w = __shfl(word[c], i * 8 + (lane >> 3), 64);
+                const float s = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sc[c]), i));
+                if (base[c] + threadIdx.x * 4 < lim[c]) v[c] = chain4(v[c], (w >> (4 * (lane & 7))) & 15u, s, a.inv_n);
+            }
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) {
+        const int64_t ci = static_cast<int64_t>(blockIdx.x) * CPW + c;
+        // components past lim must stay zero: they count in the sum of |v|
+        v[c] = zero_past(v[c], base[c] + threadIdx.x * 4, lim[c]);
+        if (base[c] < d)   // uniform over the workgroup
+            fused_finish(v[c], base[c], lim[c], delta_s, dvec, words_out, (lim[c] == d) ? a.W * 64 : lim[c],
+                         scales_out + ci, lds[c]);
+    }
 }
 
 // One thread per 4 elements.
@@ -181,8 +216,8 @@ __device__ __forceinline__ void pass1_finish(f32x4 v, int64_t base, int64_t d,
 {
     const int64_t e = base + threadIdx.x * 4;
     if (e < d) st4(vrow, e, d, vvec, v);
-    const uint32_t byte = wave_sign_byte(v.x < 0.f, v.y < 0.f, v.z < 0.f, v.w < 0.f);
-    store_sign_bytes(words_row, base + wave_id() * 256, bit_lim, byte);
+    const uint32_t sword = wave_sign_word(v.x < 0.f, v.y < 0.f, v.z < 0.f, v.w < 0.f);
+    store_sign_words(words_row, base + wave_id() * 256, bit_lim, sword);
     if (p1 - p0 == 1) {
         const double total = block_sum(abs_sum4(v), lds, false);   // elements past d are zero
         if (threadIdx.x == 0) partial_row[p0] = total;
@@ -440,8 +475,16 @@ ds_status_t ds_sign_server(ds_ctx *c, const ds_payload_t *in, float *delta_s, co
     const ds_config_t &cfg = c->cfg;
     ServerArgs a{in->sign_words, in->scales, cfg.n, c->W, c->S, c->inv_n};
     if (c->sign_fused) {
-        k_sign_chunk_server<<<dim3(static_cast<unsigned>(c->S)), kBlock, 0, st>>>(
-            a, delta_s, cfg.d, cfg.chunk, out->sign_words, out->scales);
+        static const int cpw = getenv("DS_SERVER_CPW") ? atoi(getenv("DS_SERVER_CPW")) : 2;
+        if (cpw == 2)
+            k_sign_chunk_server<2><<<dim3(static_cast<unsigned>((c->S + 1) / 2)), kBlock, 0, st>>>(
+                a, delta_s, cfg.d, cfg.chunk, out->sign_words, out->scales);
+        else if (cpw == 4)
+            k_sign_chunk_server<4><<<dim3(static_cast<unsigned>((c->S + 3) / 4)), kBlock, 0, st>>>(
+                a, delta_s, cfg.d, cfg.chunk, out->sign_words, out->scales);
+        else
+            k_sign_chunk_server<1><<<dim3(static_cast<unsigned>(c->S)), kBlock, 0, st>>>(
+                a, delta_s, cfg.d, cfg.chunk, out->sign_words, out->scales);
         return ds_launch_status();
     }
     dim3 grid(static_cast<unsigned>(c->n_tiles));
