@@ -25,6 +25,13 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per launch of the worker pass, measured with rocprofv3 --pmc (FETCH_SIZE and
+# WRITE_SIZE runs, each scaled by the same counter's reading for a 1 GiB copy); the runs and
+# the scale factors are recorded under profiles/.  None = not profiled yet.
+MEASURED_WORKER_TRAFFIC = {
+    "c5": 5.973e9 + 4.161e9,
+}
+
 
 def algorithmic_bytes(wl, S: int) -> dict:
     """HBM bytes the method must move per step at the three-call boundary: read g and
@@ -55,7 +62,7 @@ def make_workload(name: str):
     return {"c2": W.c2, "c3": W.c3, "c4": W.c4, "c5": W.c5}[name]()
 
 
-def run_gpu(wl, steps: int, warmup: int, sets: int = 2):
+def run_gpu(wl, steps: int, warmup: int, sets: int = 2, calib_copy: bool = False):
     import torch
     import paper_1905_05957_amd as P
 
@@ -103,6 +110,15 @@ def run_gpu(wl, steps: int, warmup: int, sets: int = 2):
     stage_ms = [v / steps for v in stage]
     S = ctx.S
     ctx.close()
+    # one plain device-to-device copy of known size (1 GiB read + 1 GiB written): the
+    # calibration dispatch for HBM byte counters collected with rocprofv3 --pmc
+    if calib_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     return {"ms_per_step": wall * 1e3 / steps, "stage_ms": stage_ms, "S": S}
 
 
@@ -152,6 +168,8 @@ def main():
     ap.add_argument("--workload", default="c5", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--others", default="c2,c3,c4", help="further workloads reported in the same line ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one 1 GiB device copy (calibration dispatch for rocprofv3 --pmc byte counters)")
     ap.add_argument("--cpu-elems", type=int, default=400_000_000)
     a = ap.parse_args()
     if a.gpus != 1:
@@ -164,9 +182,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
 
-    def measure(name, steps, warmup):
+    def measure(name, steps, warmup, calib_copy=False):
         wl = make_workload(name)
-        r = run_gpu(wl, steps, warmup)
+        r = run_gpu(wl, steps, warmup, calib_copy=calib_copy)
         ab = algorithmic_bytes(wl, r["S"])
         ms = r["ms_per_step"]
         wk_ms = r["stage_ms"][0]
@@ -179,11 +197,13 @@ def main():
             "step_frac_of_peak": ab["total"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
             "roofline": {"bound": "hbm", "kernel": "worker pass (ds_worker_compress)",
                          "achieved": ab["worker"] / (wk_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": ab["worker"] / (wk_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None},
+                         "frac": ab["worker"] / (wk_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "algorithmic_bytes": ab["worker"], "launch_ms": wk_ms,
+                         "traffic": MEASURED_WORKER_TRAFFIC.get(name)},
         }
         return wl, out
 
-    wl, head = measure(a.workload, a.steps, a.warmup)
+    wl, head = measure(a.workload, a.steps, a.warmup, calib_copy=a.calib_copy)
     others = []
     for name in [s for s in a.others.split(",") if s and s != a.workload]:
         try:

@@ -18,7 +18,6 @@
 #include "ds_device.h"
 #include "ds_internal.h"
 
-#include <cstdlib>
 #include <vector>
 
 using namespace ds;
@@ -475,16 +474,10 @@ ds_status_t ds_sign_server(ds_ctx *c, const ds_payload_t *in, float *delta_s, co
     const ds_config_t &cfg = c->cfg;
     ServerArgs a{in->sign_words, in->scales, cfg.n, c->W, c->S, c->inv_n};
     if (c->sign_fused) {
-        static const int cpw = getenv("DS_SERVER_CPW") ? atoi(getenv("DS_SERVER_CPW")) : 2;
-        if (cpw == 2)
-            k_sign_chunk_server<2><<<dim3(static_cast<unsigned>((c->S + 1) / 2)), kBlock, 0, st>>>(
-                a, delta_s, cfg.d, cfg.chunk, out->sign_words, out->scales);
-        else if (cpw == 4)
-            k_sign_chunk_server<4><<<dim3(static_cast<unsigned>((c->S + 3) / 4)), kBlock, 0, st>>>(
-                a, delta_s, cfg.d, cfg.chunk, out->sign_words, out->scales);
-        else
-            k_sign_chunk_server<1><<<dim3(static_cast<unsigned>(c->S)), kBlock, 0, st>>>(
-                a, delta_s, cfg.d, cfg.chunk, out->sign_words, out->scales);
+        // two chunks per workgroup: more bytes in flight per thread (measured 271 us against
+        // 292 us with one and 285 us with four on the 124 M-element workload)
+        k_sign_chunk_server<2><<<dim3(static_cast<unsigned>((c->S + 1) / 2)), kBlock, 0, st>>>(
+            a, delta_s, cfg.d, cfg.chunk, out->sign_words, out->scales);
         return ds_launch_status();
     }
     dim3 grid(static_cast<unsigned>(c->n_tiles));
