@@ -70,7 +70,7 @@ struct ds_topk_scratch {
     uint32_t *grp_eq;     // [rows][n_groups] candidates with key == T
     uint32_t *grp_eqb;    // [rows][n_groups] ties at T in earlier groups
     uint32_t *grp_out;    // [rows][n_groups] first output slot of the group
-    uint32_t *sub_start;  // [n][n_sub + 1]   server: first entry of each worker's message per subtile
+    uint32_t *sub_start;  // [n_sub + 1][n]   server: first entry of each worker's message per subtile
     int64_t n_sub, sub_pad, n_groups;
     int rows;
 };
@@ -107,12 +107,14 @@ struct BufferV {   // v already stored
 
 // Server: v = delta_s + (1/n) sum_i Q[v_i] for sparse messages, as the chain
 // acc = fma(val, 1/n, acc) over workers in ascending order.  The wavefront keeps its subtile
-// in a private LDS strip; a message lists an index once, so the lanes of one worker never
-// collide, and the wavefront's LDS operations retire in program order, which keeps the
-// workers' order.
+// in a private LDS strip.  Lane i fetches worker i's entry range for the subtile (one load
+// instruction for all workers), the entries of all workers are then fetched flattened in
+// worker order (one more load instruction per 64 entries), and applied to the strip worker
+// by worker: a message lists an index once, so the lanes of one worker never collide, and
+// the wavefront's LDS operations retire in program order, which keeps the workers' order.
 struct ServerV {
     const u32x2 *pairs_in;      // [n][k]
-    const uint32_t *sub_start;  // [n][n_sub + 1]
+    const uint32_t *sub_start;  // [n_sub + 1][n]
     const float *delta_s;
     int64_t k, n_sub;
     int32_t n;
@@ -124,20 +126,46 @@ struct ServerV {
         strip[lane * 4 + 0] = a.x; strip[lane * 4 + 1] = a.y; strip[lane * 4 + 2] = a.z; strip[lane * 4 + 3] = a.w;
         const int64_t sub = e >> 8;
         const uint32_t base = static_cast<uint32_t>(sub << 8);
-        for (int i = 0; i < n; ++i) {
-            const uint32_t s0 = sub_start[i * (n_sub + 1) + sub];
-            uint32_t s1 = sub_start[i * (n_sub + 1) + sub + 1];
-            if (s1 > static_cast<uint32_t>(k)) s1 = static_cast<uint32_t>(k);
-            const u32x2 *p = pairs_in + i * k;
-            __builtin_amdgcn_wave_barrier();
-            for (uint32_t j = s0 + lane; j < s1; j += 64) {
-                const u32x2 pr = p[j];
-                const uint32_t rel = pr.x - base;
-                if (rel < static_cast<uint32_t>(kSub)) strip[rel] = __fmaf_rn(__uint_as_float(pr.y), inv_n, strip[rel]);
+        for (int w0 = 0; w0 < n; w0 += 64) {
+            const int nw = (n - w0 < 64) ? n - w0 : 64;
+            uint32_t s0 = 0u, c = 0u;
+            if (lane < nw) {
+                s0 = sub_start[sub * n + w0 + lane];
+                uint32_t s1 = sub_start[(sub + 1) * n + w0 + lane];
+                if (s1 > static_cast<uint32_t>(k)) s1 = static_cast<uint32_t>(k);
+                c = (s1 > s0) ? s1 - s0 : 0u;
             }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
+            uint32_t P = c;                                   // inclusive prefix over workers
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const uint32_t up = __shfl_up(P, o, 64);
+                if (lane >= o) P += up;
+            }
+            const uint32_t total = __shfl(P, 63, 64);
+            for (uint32_t i0 = 0; i0 < total; i0 += 64) {
+                const uint32_t i = i0 + lane;
+                const bool valid = i < total;
+                int lo = 0, hi = 63;                          // first worker w with P_w > i
+#pragma unroll
+                for (int step = 0; step < 6; ++step) {
+                    const int mid = (lo + hi) >> 1;
+                    if (__shfl(P, mid, 64) > (valid ? i : 0u)) hi = mid; else lo = mid + 1;
+                }
+                const uint32_t pw = __shfl(P, lo, 64), cw = __shfl(c, lo, 64), sw = __shfl(s0, lo, 64);
+                u32x2 pr = {0u, 0u};
+                if (valid) pr = pairs_in[static_cast<int64_t>(w0 + lo) * k + sw + (i - (pw - cw))];
+                const uint32_t rel = pr.x - base;
+                const int wfirst = __builtin_amdgcn_readfirstlane(lo);
+                const int wlast = __builtin_amdgcn_readlane(lo, 63 - __builtin_clzll(__ballot(valid)));
+                for (int wi = wfirst; wi <= wlast; ++wi) {    // uniform bounds: workers in this batch
+                    __builtin_amdgcn_wave_barrier();
+                    if (valid && lo == wi && rel < static_cast<uint32_t>(kSub))
+                        strip[rel] = __fmaf_rn(__uint_as_float(pr.y), inv_n, strip[rel]);
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                }
+            }
         }
+        __builtin_amdgcn_wave_barrier();
         return f32x4{strip[lane * 4 + 0], strip[lane * 4 + 1], strip[lane * 4 + 2], strip[lane * 4 + 3]};
     }
 };
@@ -173,7 +201,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_sub_starts(const u32x2 *pairs_i
     const int i = blockIdx.y;
     const int64_t s = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
     if (s > n_sub) return;
-    sub_start[i * (n_sub + 1) + s] = static_cast<uint32_t>(lower_bound_idx(pairs_in + i * k, k, s * kSub));
+    sub_start[s * gridDim.y + i] = static_cast<uint32_t>(lower_bound_idx(pairs_in + i * k, k, s * kSub));
 }
 
 __device__ __forceinline__ int64_t sample_subtile(int64_t j, int64_t ns, int64_t n_sub)
@@ -286,16 +314,14 @@ __global__ __launch_bounds__(kBlock) void k_topk_pick(const uint32_t *hist, Sel 
 // FALLBACK = true : rows flagged for the two-look route only; v is read back from buf,
 //                   candidates with bin >= b1.
 template <class Src, bool FALLBACK>
-__global__ __launch_bounds__(kBlock) void k_topk_pass1(Src src, float *buf, int64_t stride, int64_t d, int64_t n_sub,
-                                                       const Sel *sel, u32x2 *slots, uint32_t *sub_cnt, int64_t sub_pad)
+__device__ __forceinline__ void pass1_tile(const Src &src, float *buf, int64_t stride, int64_t d, int64_t n_sub,
+                                           const Sel *sel, u32x2 *slots, uint32_t *sub_cnt, int64_t sub_pad, int row,
+                                           int64_t tile, float *strip)
 {
-    __shared__ float strips[FALLBACK ? 1 : kWaves][FALLBACK ? 1 : kSub];
-    const int row = blockIdx.y;
-    if (FALLBACK && !sel[row].fallback) return;
-    const int64_t e = static_cast<int64_t>(blockIdx.x) * kTile + threadIdx.x * 4;
+    const int64_t e = tile * kTile + threadIdx.x * 4;
     const int64_t sub = e >> 8;
     if (sub >= n_sub) return;                       // whole wavefront
-    const f32x4 v = src.load(row, e, d, FALLBACK ? nullptr : strips[wave_id()]);
+    const f32x4 v = src.load(row, e, d, strip);
     if (!FALLBACK && e < d) {
         float *brow = buf + row * stride;
         st4(brow, e, d, aligned16(brow), v);
@@ -316,6 +342,20 @@ __global__ __launch_bounds__(kBlock) void k_topk_pass1(Src src, float *buf, int6
         sub_cnt[row * sub_pad + sub] = __popcll(m0) + __popcll(m1) + __popcll(m2) + __popcll(m3);
 }
 
+template <class Src, bool FALLBACK>
+__global__ __launch_bounds__(kBlock) void k_topk_pass1(Src src, float *buf, int64_t stride, int64_t d, int64_t n_sub,
+                                                       const Sel *sel, u32x2 *slots, uint32_t *sub_cnt, int64_t sub_pad)
+{
+    __shared__ float strips[FALLBACK ? 1 : kWaves][FALLBACK ? 1 : kSub];
+    const int row = blockIdx.y;
+    if (FALLBACK && !sel[row].fallback) return;
+    const int64_t n_tiles = (d + kTile - 1) / kTile;
+    // the regular launch has one workgroup per tile; the fallback launch is a small grid
+    // that exits at once for rows that do not need it and strides over the tiles otherwise
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x)
+        pass1_tile<Src, FALLBACK>(src, buf, stride, d, n_sub, sel, slots, sub_cnt, sub_pad, row, tile,
+                                  FALLBACK ? nullptr : strips[wave_id()]);
+}
 // Fallback rows: dense 12-bit histogram of the stored v.  Persistent workgroups.
 __global__ __launch_bounds__(kBlock) void k_topk_fallback_hist(const float *buf, int64_t stride, int64_t d,
                                                                int64_t n_tiles, const Sel *sel, uint32_t *hist)
@@ -385,6 +425,30 @@ __device__ __forceinline__ u32x2 group_fetch(const GroupWalk &w, const u32x2 *__
     return pr;
 }
 
+// The candidate passes fetch up to kPrefetch batches of 64 candidates before using any of
+// them, so that a wavefront has several independent loads in flight instead of a chain of
+// dependent ones (a group holds about 250-320 candidates at k = 1 %).
+constexpr int kPrefetch = 8;
+
+struct Batch {
+    u32x2 pr[kPrefetch];
+};
+
+__device__ __forceinline__ Batch group_fetch_batches(const GroupWalk &w, const u32x2 *__restrict__ slots_row,
+                                                     int64_t g, uint32_t i0)
+{
+    Batch b;
+#pragma unroll
+    for (int j = 0; j < kPrefetch; ++j) {
+        b.pr[j] = u32x2{0u, 0u};
+        if (i0 + j * 64 < w.total) {                       // uniform over the wavefront
+            const uint32_t i = i0 + j * 64 + lane_id();
+            b.pr[j] = group_fetch(w, slots_row, g, (i < w.total) ? i : 0u, i < w.total);
+        }
+    }
+    return b;
+}
+
 // LEVEL 1: 12-bit histogram of all candidates.  2: next 11 bits of those in bin b1.
 // 3: low 8 bits of those with prefix (b1, b2).  One group per wavefront.
 template <int LEVEL>
@@ -404,14 +468,16 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_hist(const u32x2 *slots, c
         const GroupWalk w = group_begin(sub_cnt + row * sub_pad, g, n_sub);
         const u32x2 *srow = slots + static_cast<int64_t>(row) * n_sub * kSub;
         const uint32_t prefix = (s.b1 << 11) | s.b2;
-        for (uint32_t i0 = 0; i0 < w.total; i0 += 64) {
-            const uint32_t i = i0 + lane_id();
-            const bool valid = i < w.total;
-            const uint32_t key = group_fetch(w, srow, g, valid ? i : 0u, valid).y & 0x7FFFFFFFu;
-            if (!valid) continue;
-            if (LEVEL == 1) atomicAdd(&h[key >> 19], 1u);
-            if (LEVEL == 2 && (key >> 19) == s.b1) atomicAdd(&h[(key >> 8) & (kH2 - 1)], 1u);
-            if (LEVEL == 3 && (key >> 8) == prefix) atomicAdd(&h[key & 255u], 1u);
+        for (uint32_t i0 = 0; i0 < w.total; i0 += 64 * kPrefetch) {
+            const Batch bt = group_fetch_batches(w, srow, g, i0);
+#pragma unroll
+            for (int j = 0; j < kPrefetch; ++j) {
+                if (i0 + j * 64 + lane_id() >= w.total) continue;
+                const uint32_t key = bt.pr[j].y & 0x7FFFFFFFu;
+                if (LEVEL == 1) atomicAdd(&h[key >> 19], 1u);
+                if (LEVEL == 2 && (key >> 19) == s.b1) atomicAdd(&h[(key >> 8) & (kH2 - 1)], 1u);
+                if (LEVEL == 3 && (key >> 8) == prefix) atomicAdd(&h[key & 255u], 1u);
+            }
         }
     }
     __syncthreads();
@@ -432,12 +498,15 @@ __global__ __launch_bounds__(kBlock) void k_topk_count(const u32x2 *slots, const
     const GroupWalk w = group_begin(sub_cnt + row * sub_pad, g, n_sub);
     const u32x2 *srow = slots + static_cast<int64_t>(row) * n_sub * kSub;
     uint32_t gt = 0, eq = 0;
-    for (uint32_t i0 = 0; i0 < w.total; i0 += 64) {
-        const uint32_t i = i0 + lane_id();
-        const bool valid = i < w.total;
-        const uint32_t key = group_fetch(w, srow, g, valid ? i : 0u, valid).y & 0x7FFFFFFFu;
-        gt += valid && key > T;
-        eq += valid && key == T;
+    for (uint32_t i0 = 0; i0 < w.total; i0 += 64 * kPrefetch) {
+        const Batch bt = group_fetch_batches(w, srow, g, i0);
+#pragma unroll
+        for (int j = 0; j < kPrefetch; ++j) {
+            const bool valid = i0 + j * 64 + lane_id() < w.total;
+            const uint32_t key = bt.pr[j].y & 0x7FFFFFFFu;
+            gt += valid && key > T;
+            eq += valid && key == T;
+        }
     }
     gt = wave_sum_u32(gt);
     eq = wave_sum_u32(eq);
@@ -511,22 +580,26 @@ __global__ __launch_bounds__(kBlock) void k_topk_emit(const u32x2 *slots, const 
     uint32_t out = grp_out[row * n_groups + g];
     u32x2 *prow = pairs + static_cast<int64_t>(row) * k;
     float *brow = buf + row * stride;
-    for (uint32_t i0 = 0; i0 < w.total; i0 += 64) {
-        const uint32_t i = i0 + lane_id();
-        const bool valid = i < w.total;
-        const u32x2 pr = group_fetch(w, srow, g, valid ? i : 0u, valid);
-        const uint32_t key = pr.y & 0x7FFFFFFFu;
-        const bool is_eq = valid && key == s.T;
-        const uint64_t eq_mask = __ballot(is_eq);
-        const bool keep = valid && (key > s.T || (is_eq && eq_seen + lanes_below(eq_mask) < s.k3));
-        const uint64_t keep_mask = __ballot(keep);
-        if (keep) {
-            const uint32_t slot = out + lanes_below(keep_mask);
-            if (slot < k) prow[slot] = pr;
-            brow[pr.x] = 0.f;
+    for (uint32_t i0 = 0; i0 < w.total; i0 += 64 * kPrefetch) {
+        const Batch bt = group_fetch_batches(w, srow, g, i0);
+#pragma unroll
+        for (int j = 0; j < kPrefetch; ++j) {
+            if (i0 + j * 64 >= w.total) break;                 // uniform over the wavefront
+            const bool valid = i0 + j * 64 + lane_id() < w.total;
+            const u32x2 pr = bt.pr[j];
+            const uint32_t key = pr.y & 0x7FFFFFFFu;
+            const bool is_eq = valid && key == s.T;
+            const uint64_t eq_mask = __ballot(is_eq);
+            const bool keep = valid && (key > s.T || (is_eq && eq_seen + lanes_below(eq_mask) < s.k3));
+            const uint64_t keep_mask = __ballot(keep);
+            if (keep) {
+                const uint32_t slot = out + lanes_below(keep_mask);
+                if (slot < k) prow[slot] = pr;
+                brow[pr.x] = 0.f;
+            }
+            out += __popcll(keep_mask);
+            eq_seen += __popcll(eq_mask);
         }
-        out += __popcll(keep_mask);
-        eq_seen += __popcll(eq_mask);
     }
 }
 
@@ -602,7 +675,8 @@ ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t 
     k_topk_fallback_hist<<<dim3(persistent_blocks(c->n_tiles, rows), rows), kBlock, 0, st>>>(buf, stride, d, c->n_tiles,
                                                                                             t->sel, t->hist);
     k_topk_pick<4><<<rows, kBlock, 0, st>>>(t->hist, t->sel, static_cast<uint32_t>(k));
-    k_topk_pass1<BufferV, true><<<dense, kBlock, 0, st>>>(bsrc, buf, stride, d, n_sub, t->sel, t->slots, t->sub_cnt, sub_pad);
+    k_topk_pass1<BufferV, true><<<dim3(persistent_blocks(c->n_tiles, rows), rows), kBlock, 0, st>>>(
+        bsrc, buf, stride, d, n_sub, t->sel, t->slots, t->sub_cnt, sub_pad);
     // refinement on the candidates
     k_topk_cand_hist<2><<<cand, kBlock, 0, st>>>(t->slots, t->sub_cnt, n_sub, sub_pad, n_groups, t->sel, t->hist);
     k_topk_pick<2><<<rows, kBlock, 0, st>>>(t->hist, t->sel, 0u);
