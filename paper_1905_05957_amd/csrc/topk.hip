@@ -42,6 +42,8 @@ constexpr int kOffSample = 0, kOffH1 = kH1, kOffH2 = 2 * kH1, kOffH3 = 2 * kH1 +
 constexpr int kHistRow = 3 * kH1 + kH2 + kH3;
 constexpr int kSampleSubs = 256;           // subtiles sampled per row
 constexpr uint32_t kNone = 0xFFFFFFFFu;
+constexpr int kStages = 4;                 // arrival counters per row: sample, candidate histogram, fallback histogram, count
+enum { kStageSample = 0, kStageHist = 1, kStageFallback = 2, kStageCount = 3 };
 
 struct Sel {
     uint32_t lo_bin;    // candidates are the elements whose top-12-bit bin is >= lo_bin
@@ -62,7 +64,8 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t m)
 }  // namespace
 
 struct ds_topk_scratch {
-    uint32_t *hist;       // [rows][kHistRow]
+    uint32_t *hist;       // [2][rows][kHistRow]: the call in flight uses one half and zeroes the other
+    uint32_t *done;       // [rows][kStages] arrival counters of the "last workgroup finishes the row" steps
     Sel *sel;             // [rows]
     u32x2 *slots;         // [rows][n_sub * 256] candidate (index, value bits), per subtile region
     uint32_t *sub_cnt;    // [rows][sub_pad]  candidates per subtile
@@ -73,6 +76,7 @@ struct ds_topk_scratch {
     uint32_t *sub_start;  // [n_sub + 1][n]   server: first entry of each worker's message per subtile
     int64_t n_sub, sub_pad, n_groups;
     int rows;
+    int parity;           // which half of hist the next call uses
 };
 
 namespace {
@@ -173,12 +177,37 @@ struct ServerV {
 // ---------------------------------------------------------------------------------------
 // small kernels
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void k_topk_zero(uint32_t *hist, Sel *sel, int rows)
+// "The last workgroup finishes the row": data that workgroups of one kernel hand to the last
+// of them travels only through device-scope atomics (atomicAdd into histograms, dev_store /
+// dev_load below), which are performed at the device's coherence point, so no cache
+// write-back or invalidation is needed -- an agent-scope fence per workgroup costs a full L2
+// write-back on this GPU and tripled the step time when tried.
+__device__ __forceinline__ void dev_store(uint32_t *p, uint32_t v)
 {
-    const int total = rows * kHistRow;
-    for (int i = blockIdx.x * kBlock + threadIdx.x; i < total; i += gridDim.x * kBlock) hist[i] = 0u;
-    if (blockIdx.x == 0)
-        for (int r = threadIdx.x; r < rows; r += kBlock) sel[r] = Sel{0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t dev_load(const uint32_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// True in exactly one workgroup of those that call it with the same counter: the last of
+// `expected` to arrive.  Every wavefront first waits until its own outstanding atomics have
+// been performed (workgroup-scope release = wait for the memory counters), the barrier
+// collects the wavefronts, then one device-scope increment announces the workgroup.  The
+// counter is left at zero for its next use.  All threads of the workgroup must call.
+__device__ __forceinline__ bool last_workgroup(uint32_t *counter, uint32_t expected, uint32_t *flag_sh)
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t prev = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool last = prev + 1u == expected;
+        if (last) dev_store(counter, 0u);
+        *flag_sh = last ? 1u : 0u;
+    }
+    __syncthreads();
+    return *flag_sh != 0u;
 }
 
 // First position in idx-sorted pairs[0..k) whose index is >= target.
@@ -204,39 +233,6 @@ __global__ __launch_bounds__(kBlock) void k_topk_sub_starts(const u32x2 *pairs_i
     sub_start[s * gridDim.y + i] = static_cast<uint32_t>(lower_bound_idx(pairs_in + i * k, k, s * kSub));
 }
 
-__device__ __forceinline__ int64_t sample_subtile(int64_t j, int64_t ns, int64_t n_sub)
-{
-    // evenly spread, with a small hashed jitter inside each stride
-    const int64_t lo = (j * n_sub) / ns, hi = ((j + 1) * n_sub) / ns;
-    const int64_t span = hi - lo;
-    const uint32_t h = static_cast<uint32_t>(j) * 2654435761u;
-    return lo + ((span > 1) ? static_cast<int64_t>((h >> 8) % static_cast<uint32_t>(span)) : 0);
-}
-
-// 12-bit histogram of v over the sampled subtiles.
-template <class Src>
-__global__ __launch_bounds__(kBlock) void k_topk_sample(Src src, int64_t d, int64_t n_sub, int64_t ns, uint32_t *hist)
-{
-    __shared__ uint32_t h[kH1];
-    __shared__ float strips[kWaves][kSub];
-    const int row = blockIdx.y;
-    for (int i = threadIdx.x; i < kH1; i += kBlock) h[i] = 0u;
-    __syncthreads();
-    const int64_t j = static_cast<int64_t>(blockIdx.x) * kWaves + wave_id();
-    if (j < ns) {
-        const int64_t e = sample_subtile(j, ns, n_sub) * kSub + lane_id() * 4;
-        const f32x4 v = src.load(row, e, d, strips[wave_id()]);
-        if (e + 0 < d) atomicAdd(&h[key_of(v.x) >> 19], 1u);
-        if (e + 1 < d) atomicAdd(&h[key_of(v.y) >> 19], 1u);
-        if (e + 2 < d) atomicAdd(&h[key_of(v.z) >> 19], 1u);
-        if (e + 3 < d) atomicAdd(&h[key_of(v.w) >> 19], 1u);
-    }
-    __syncthreads();
-    uint32_t *hrow = hist + static_cast<int64_t>(row) * kHistRow + kOffSample;
-    for (int i = threadIdx.x; i < kH1; i += kBlock)
-        if (h[i]) atomicAdd(&hrow[i], h[i]);
-}
-
 // Largest bin b of hist[0..NB) with  sum_{bins >= b} >= need ;  rem = need - sum_{bins > b}.
 // One workgroup; the thread that owns b writes the outputs (untouched if the histogram
 // holds fewer than `need` keys).
@@ -251,7 +247,7 @@ __device__ __forceinline__ void pick_bin(const uint32_t *__restrict__ hist, uint
     uint32_t sum = 0;
 #pragma unroll
     for (int j = 0; j < PER; ++j) {
-        local[j] = active ? hist[t * PER + j] : 0u;
+        local[j] = active ? dev_load(&hist[t * PER + j]) : 0u;
         sum += local[j];
     }
     part[t] = sum;
@@ -276,17 +272,12 @@ __device__ __forceinline__ void pick_bin(const uint32_t *__restrict__ hist, uint
     }
 }
 
+// Run by one whole workgroup per row.
 // LEVEL 0: sample -> lo_bin.  1: candidates' 12-bit histogram -> b1, k1 or fallback.
-// 2: -> b2, k2.  3: -> T, k3.  4: fallback rows only, dense 12-bit histogram -> b1, k1.
+// 2: -> b2, k2.  3: -> T, k3.  4: dense 12-bit histogram of a fallback row -> b1, k1.
 template <int LEVEL>
-__global__ __launch_bounds__(kBlock) void k_topk_pick(const uint32_t *hist, Sel *sel, uint32_t need0)
+__device__ __forceinline__ void pick_level(const uint32_t *hrow, Sel *s, uint32_t need0, uint32_t *part, uint32_t *out)
 {
-    __shared__ uint32_t part[kBlock];
-    __shared__ uint32_t out[2];
-    const int row = blockIdx.x;
-    const uint32_t *hrow = hist + static_cast<int64_t>(row) * kHistRow;
-    Sel *s = sel + row;
-    if (LEVEL == 4 && !s->fallback) return;
     if (threadIdx.x == 0) { out[0] = kNone; out[1] = 0u; }
     __syncthreads();
     if (LEVEL == 0) pick_bin<kH1>(hrow + kOffSample, need0, part, &out[0], &out[1]);
@@ -298,13 +289,50 @@ __global__ __launch_bounds__(kBlock) void k_topk_pick(const uint32_t *hist, Sel 
     if (threadIdx.x == 0) {
         if (LEVEL == 0) s->lo_bin = (out[0] == kNone) ? 0u : out[0];
         if (LEVEL == 1) {
-            if (out[0] == kNone) s->fallback = 1u;
-            else { s->b1 = out[0]; s->k1 = out[1]; }
+            s->fallback = (out[0] == kNone) ? 1u : 0u;
+            if (out[0] != kNone) { s->b1 = out[0]; s->k1 = out[1]; }
         }
         if (LEVEL == 2) { s->b2 = out[0]; s->k2 = out[1]; }
         if (LEVEL == 3) { s->T = (s->b1 << 19) | (s->b2 << 8) | out[0]; s->k3 = out[1]; }
         if (LEVEL == 4) { s->b1 = out[0]; s->k1 = out[1]; }
     }
+}
+
+__device__ __forceinline__ int64_t sample_subtile(int64_t j, int64_t ns, int64_t n_sub)
+{
+    // evenly spread, with a small hashed jitter inside each stride
+    const int64_t lo = (j * n_sub) / ns, hi = ((j + 1) * n_sub) / ns;
+    const int64_t span = hi - lo;
+    const uint32_t h = static_cast<uint32_t>(j) * 2654435761u;
+    return lo + ((span > 1) ? static_cast<int64_t>((h >> 8) % static_cast<uint32_t>(span)) : 0);
+}
+
+// 12-bit histogram of v over the sampled subtiles.
+template <class Src>
+__global__ __launch_bounds__(kBlock) void k_topk_sample(Src src, int64_t d, int64_t n_sub, int64_t ns, uint32_t *hist,
+                                                        Sel *sel, uint32_t *done, uint32_t rank)
+{
+    __shared__ uint32_t h[kH1];
+    __shared__ uint32_t part[kBlock], out[2], flag;
+    __shared__ float strips[kWaves][kSub];
+    const int row = blockIdx.y;
+    for (int i = threadIdx.x; i < kH1; i += kBlock) h[i] = 0u;
+    __syncthreads();
+    const int64_t j = static_cast<int64_t>(blockIdx.x) * kWaves + wave_id();
+    if (j < ns) {
+        const int64_t e = sample_subtile(j, ns, n_sub) * kSub + lane_id() * 4;
+        const f32x4 v = src.load(row, e, d, strips[wave_id()]);
+        if (e + 0 < d) atomicAdd(&h[key_of(v.x) >> 19], 1u);
+        if (e + 1 < d) atomicAdd(&h[key_of(v.y) >> 19], 1u);
+        if (e + 2 < d) atomicAdd(&h[key_of(v.z) >> 19], 1u);
+        if (e + 3 < d) atomicAdd(&h[key_of(v.w) >> 19], 1u);
+    }
+    __syncthreads();
+    uint32_t *hrow = hist + static_cast<int64_t>(row) * kHistRow;
+    for (int i = threadIdx.x; i < kH1; i += kBlock)
+        if (h[i]) atomicAdd(&hrow[kOffSample + i], h[i]);
+    if (last_workgroup(done + row * kStages + kStageSample, gridDim.x, &flag))
+        pick_level<0>(hrow, sel + row, rank, part, out);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -358,9 +386,11 @@ __global__ __launch_bounds__(kBlock) void k_topk_pass1(Src src, float *buf, int6
 }
 // Fallback rows: dense 12-bit histogram of the stored v.  Persistent workgroups.
 __global__ __launch_bounds__(kBlock) void k_topk_fallback_hist(const float *buf, int64_t stride, int64_t d,
-                                                               int64_t n_tiles, const Sel *sel, uint32_t *hist)
+                                                               int64_t n_tiles, Sel *sel, uint32_t *hist,
+                                                               uint32_t *done, uint32_t k)
 {
     __shared__ uint32_t h[kH1];
+    __shared__ uint32_t part[kBlock], out[2], flag;
     const int row = blockIdx.y;
     if (!sel[row].fallback) return;
     for (int i = threadIdx.x; i < kH1; i += kBlock) h[i] = 0u;
@@ -377,9 +407,11 @@ __global__ __launch_bounds__(kBlock) void k_topk_fallback_hist(const float *buf,
         if (e + 3 < d) atomicAdd(&h[key_of(v.w) >> 19], 1u);
     }
     __syncthreads();
-    uint32_t *hrow = hist + static_cast<int64_t>(row) * kHistRow + kOffH1F;
+    uint32_t *hrow = hist + static_cast<int64_t>(row) * kHistRow;
     for (int i = threadIdx.x; i < kH1; i += kBlock)
-        if (h[i]) atomicAdd(&hrow[i], h[i]);
+        if (h[i]) atomicAdd(&hrow[kOffH1F + i], h[i]);
+    if (last_workgroup(done + row * kStages + kStageFallback, gridDim.x, &flag))
+        pick_level<4>(hrow, sel + row, k, part, out);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -453,12 +485,13 @@ __device__ __forceinline__ Batch group_fetch_batches(const GroupWalk &w, const u
 // 3: low 8 bits of those with prefix (b1, b2).  One group per wavefront.
 template <int LEVEL>
 __global__ __launch_bounds__(kBlock) void k_topk_cand_hist(const u32x2 *slots, const uint32_t *sub_cnt, int64_t n_sub,
-                                                           int64_t sub_pad, int64_t n_groups, const Sel *sel,
-                                                           uint32_t *hist)
+                                                           int64_t sub_pad, int64_t n_groups, Sel *sel,
+                                                           uint32_t *hist, uint32_t *done, uint32_t k)
 {
     constexpr int NB = (LEVEL == 1) ? kH1 : (LEVEL == 2) ? kH2 : kH3;
     constexpr int OFF = (LEVEL == 1) ? kOffH1 : (LEVEL == 2) ? kOffH2 : kOffH3;
     __shared__ uint32_t h[NB];
+    __shared__ uint32_t part[kBlock], out[2], flag;
     const int row = blockIdx.y;
     const Sel s = sel[row];
     for (int i = threadIdx.x; i < NB; i += kBlock) h[i] = 0u;
@@ -481,39 +514,11 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_hist(const u32x2 *slots, c
         }
     }
     __syncthreads();
-    uint32_t *hrow = hist + static_cast<int64_t>(row) * kHistRow + OFF;
+    uint32_t *hrow = hist + static_cast<int64_t>(row) * kHistRow;
     for (int i = threadIdx.x; i < NB; i += kBlock)
-        if (h[i]) atomicAdd(&hrow[i], h[i]);
-}
-
-// Per group: candidates above T, candidates tying with T.
-__global__ __launch_bounds__(kBlock) void k_topk_count(const u32x2 *slots, const uint32_t *sub_cnt, int64_t n_sub,
-                                                       int64_t sub_pad, int64_t n_groups, const Sel *sel,
-                                                       uint32_t *grp_gt, uint32_t *grp_eq)
-{
-    const int row = blockIdx.y;
-    const int64_t g = static_cast<int64_t>(blockIdx.x) * kWaves + wave_id();
-    if (g >= n_groups) return;
-    const uint32_t T = sel[row].T;
-    const GroupWalk w = group_begin(sub_cnt + row * sub_pad, g, n_sub);
-    const u32x2 *srow = slots + static_cast<int64_t>(row) * n_sub * kSub;
-    uint32_t gt = 0, eq = 0;
-    for (uint32_t i0 = 0; i0 < w.total; i0 += 64 * kPrefetch) {
-        const Batch bt = group_fetch_batches(w, srow, g, i0);
-#pragma unroll
-        for (int j = 0; j < kPrefetch; ++j) {
-            const bool valid = i0 + j * 64 + lane_id() < w.total;
-            const uint32_t key = bt.pr[j].y & 0x7FFFFFFFu;
-            gt += valid && key > T;
-            eq += valid && key == T;
-        }
-    }
-    gt = wave_sum_u32(gt);
-    eq = wave_sum_u32(eq);
-    if (lane_id() == 0) {
-        grp_gt[row * n_groups + g] = gt;
-        grp_eq[row * n_groups + g] = eq;
-    }
+        if (h[i]) atomicAdd(&hrow[OFF + i], h[i]);
+    if (last_workgroup(done + row * kStages + kStageHist, gridDim.x, &flag))
+        pick_level<LEVEL>(hrow, sel + row, k, part, out);
 }
 
 // Exclusive scan over the workgroup of one value per thread; tmp holds kWaves values.
@@ -535,32 +540,74 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t x, uint32_t *t
 }
 
 // Per row, in group order: ties seen before each group, and each group's first output slot.
-__global__ __launch_bounds__(kBlock) void k_topk_scan(const Sel *sel, int64_t n_groups, const uint32_t *grp_gt,
-                                                      const uint32_t *grp_eq, uint32_t *grp_eqb, uint32_t *grp_out)
+// Run by one whole workgroup.
+__device__ __forceinline__ void scan_row(int row, const Sel *sel, int64_t n_groups, const uint32_t *grp_gt,
+                                         const uint32_t *grp_eq, uint32_t *grp_eqb, uint32_t *grp_out, uint32_t *tmp)
 {
-    __shared__ uint32_t tmp[kWaves];
-    const int row = blockIdx.x;
     const uint32_t k3 = sel[row].k3;
     const int64_t per = (n_groups + kBlock - 1) / kBlock;
     const int64_t t0 = threadIdx.x * per, t1 = (t0 + per < n_groups) ? t0 + per : n_groups;
     const uint32_t *gt = grp_gt + row * n_groups, *eq = grp_eq + row * n_groups;
     uint32_t *eqb = grp_eqb + row * n_groups, *out = grp_out + row * n_groups;
     uint32_t s = 0;
-    for (int64_t t = t0; t < t1; ++t) s += eq[t];
+    for (int64_t t = t0; t < t1; ++t) s += dev_load(&eq[t]);
     uint32_t run = block_exclusive_scan(s, tmp);
     uint32_t sel_sum = 0;
     for (int64_t t = t0; t < t1; ++t) {
+        const uint32_t e_t = dev_load(&eq[t]), g_t = dev_load(&gt[t]);
         eqb[t] = run;
         const uint32_t left = (k3 > run) ? k3 - run : 0u;
-        sel_sum += gt[t] + ((eq[t] < left) ? eq[t] : left);
-        run += eq[t];
+        sel_sum += g_t + ((e_t < left) ? e_t : left);
+        run += e_t;
     }
     uint32_t o = block_exclusive_scan(sel_sum, tmp);
     for (int64_t t = t0; t < t1; ++t) {
+        const uint32_t e_t = dev_load(&eq[t]), g_t = dev_load(&gt[t]);
         out[t] = o;
         const uint32_t left = (k3 > eqb[t]) ? k3 - eqb[t] : 0u;
-        o += gt[t] + ((eq[t] < left) ? eq[t] : left);
+        o += g_t + ((e_t < left) ? e_t : left);
     }
+}
+
+// Per group: candidates above T, candidates tying with T; the last workgroup of the row
+// then scans the groups.  The kernel also zeroes the histogram half that the NEXT call will
+// use (`zero`, `zero_words`), which replaces a separate clearing launch.
+__global__ __launch_bounds__(kBlock) void k_topk_count(const u32x2 *slots, const uint32_t *sub_cnt, int64_t n_sub,
+                                                       int64_t sub_pad, int64_t n_groups, const Sel *sel,
+                                                       uint32_t *grp_gt, uint32_t *grp_eq, uint32_t *grp_eqb,
+                                                       uint32_t *grp_out, uint32_t *done, uint32_t *zero,
+                                                       int64_t zero_words)
+{
+    __shared__ uint32_t tmp[kWaves], flag;
+    const int row = blockIdx.y;
+    const int64_t wg = static_cast<int64_t>(blockIdx.y) * gridDim.x + blockIdx.x;
+    for (int64_t i = wg * kBlock + threadIdx.x; i < zero_words; i += static_cast<int64_t>(gridDim.x) * gridDim.y * kBlock)
+        zero[i] = 0u;
+    const int64_t g = static_cast<int64_t>(blockIdx.x) * kWaves + wave_id();
+    if (g < n_groups) {
+        const uint32_t T = sel[row].T;
+        const GroupWalk w = group_begin(sub_cnt + row * sub_pad, g, n_sub);
+        const u32x2 *srow = slots + static_cast<int64_t>(row) * n_sub * kSub;
+        uint32_t gt = 0, eq = 0;
+        for (uint32_t i0 = 0; i0 < w.total; i0 += 64 * kPrefetch) {
+            const Batch bt = group_fetch_batches(w, srow, g, i0);
+#pragma unroll
+            for (int j = 0; j < kPrefetch; ++j) {
+                const bool valid = i0 + j * 64 + lane_id() < w.total;
+                const uint32_t key = bt.pr[j].y & 0x7FFFFFFFu;
+                gt += valid && key > T;
+                eq += valid && key == T;
+            }
+        }
+        gt = wave_sum_u32(gt);
+        eq = wave_sum_u32(eq);
+        if (lane_id() == 0) {
+            dev_store(&grp_gt[row * n_groups + g], gt);
+            dev_store(&grp_eq[row * n_groups + g], eq);
+        }
+    }
+    if (last_workgroup(done + row * kStages + kStageCount, gridDim.x, &flag))
+        scan_row(row, sel, n_groups, grp_gt, grp_eq, grp_eqb, grp_out, tmp);
 }
 
 // Per group: write the kept entries in index order and zero them in the error buffer
@@ -666,24 +713,26 @@ ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t 
     const dim3 dense(static_cast<unsigned>(c->n_tiles), rows), cand(grp_blocks, rows);
     const BufferV bsrc{buf, stride};
 
-    k_topk_sample<Src><<<dim3(static_cast<unsigned>((ns + kWaves - 1) / kWaves), rows), kBlock, 0, st>>>(src, d, n_sub, ns, t->hist);
-    k_topk_pick<0><<<rows, kBlock, 0, st>>>(t->hist, t->sel, rank);
+    uint32_t *hist = t->hist + static_cast<int64_t>(t->parity) * t->rows * kHistRow;
+    uint32_t *hist_next = t->hist + static_cast<int64_t>(t->parity ^ 1) * t->rows * kHistRow;
+    t->parity ^= 1;
+    const uint32_t k32 = static_cast<uint32_t>(k);
+
+    k_topk_sample<Src><<<dim3(static_cast<unsigned>((ns + kWaves - 1) / kWaves), rows), kBlock, 0, st>>>(
+        src, d, n_sub, ns, hist, t->sel, t->done, rank);
     k_topk_pass1<Src, false><<<dense, kBlock, 0, st>>>(src, buf, stride, d, n_sub, t->sel, t->slots, t->sub_cnt, sub_pad);
-    k_topk_cand_hist<1><<<cand, kBlock, 0, st>>>(t->slots, t->sub_cnt, n_sub, sub_pad, n_groups, t->sel, t->hist);
-    k_topk_pick<1><<<rows, kBlock, 0, st>>>(t->hist, t->sel, static_cast<uint32_t>(k));
-    // two-look route for rows whose sample misjudged; no-ops otherwise
+    k_topk_cand_hist<1><<<cand, kBlock, 0, st>>>(t->slots, t->sub_cnt, n_sub, sub_pad, n_groups, t->sel, hist, t->done, k32);
+    // two-look route for rows whose sample misjudged; both launches exit at once otherwise
     k_topk_fallback_hist<<<dim3(persistent_blocks(c->n_tiles, rows), rows), kBlock, 0, st>>>(buf, stride, d, c->n_tiles,
-                                                                                            t->sel, t->hist);
-    k_topk_pick<4><<<rows, kBlock, 0, st>>>(t->hist, t->sel, static_cast<uint32_t>(k));
+                                                                                            t->sel, hist, t->done, k32);
     k_topk_pass1<BufferV, true><<<dim3(persistent_blocks(c->n_tiles, rows), rows), kBlock, 0, st>>>(
         bsrc, buf, stride, d, n_sub, t->sel, t->slots, t->sub_cnt, sub_pad);
     // refinement on the candidates
-    k_topk_cand_hist<2><<<cand, kBlock, 0, st>>>(t->slots, t->sub_cnt, n_sub, sub_pad, n_groups, t->sel, t->hist);
-    k_topk_pick<2><<<rows, kBlock, 0, st>>>(t->hist, t->sel, 0u);
-    k_topk_cand_hist<3><<<cand, kBlock, 0, st>>>(t->slots, t->sub_cnt, n_sub, sub_pad, n_groups, t->sel, t->hist);
-    k_topk_pick<3><<<rows, kBlock, 0, st>>>(t->hist, t->sel, 0u);
-    k_topk_count<<<cand, kBlock, 0, st>>>(t->slots, t->sub_cnt, n_sub, sub_pad, n_groups, t->sel, t->grp_gt, t->grp_eq);
-    k_topk_scan<<<rows, kBlock, 0, st>>>(t->sel, n_groups, t->grp_gt, t->grp_eq, t->grp_eqb, t->grp_out);
+    k_topk_cand_hist<2><<<cand, kBlock, 0, st>>>(t->slots, t->sub_cnt, n_sub, sub_pad, n_groups, t->sel, hist, t->done, k32);
+    k_topk_cand_hist<3><<<cand, kBlock, 0, st>>>(t->slots, t->sub_cnt, n_sub, sub_pad, n_groups, t->sel, hist, t->done, k32);
+    k_topk_count<<<cand, kBlock, 0, st>>>(t->slots, t->sub_cnt, n_sub, sub_pad, n_groups, t->sel, t->grp_gt, t->grp_eq,
+                                          t->grp_eqb, t->grp_out, t->done, hist_next,
+                                          static_cast<int64_t>(t->rows) * kHistRow);
     k_topk_emit<<<cand, kBlock, 0, st>>>(t->slots, t->sub_cnt, n_sub, sub_pad, n_groups, t->sel, t->grp_eqb, t->grp_out, k,
                                          pairs, buf, stride);
     return ds_launch_status();
@@ -702,7 +751,11 @@ ds_status_t ds_topk_init(ds_ctx *c)
     t->n_sub = (c->cfg.d + kSub - 1) / kSub;
     t->n_groups = (t->n_sub + kGroupSubs - 1) / kGroupSubs;
     t->sub_pad = t->n_groups * kGroupSubs;
-    DS_HIP_TRY(hipMalloc(&t->hist, rows * kHistRow * sizeof(uint32_t)));
+    DS_HIP_TRY(hipMalloc(&t->hist, 2 * rows * kHistRow * sizeof(uint32_t)));
+    DS_HIP_TRY(hipMemset(t->hist, 0, 2 * rows * kHistRow * sizeof(uint32_t)));
+    DS_HIP_TRY(hipMalloc(&t->done, rows * kStages * sizeof(uint32_t)));
+    DS_HIP_TRY(hipMemset(t->done, 0, rows * kStages * sizeof(uint32_t)));
+    t->parity = 0;
     DS_HIP_TRY(hipMalloc(&t->sel, rows * sizeof(Sel)));
     DS_HIP_TRY(hipMalloc(&t->slots, rows * static_cast<size_t>(t->n_sub) * kSub * sizeof(u32x2)));
     DS_HIP_TRY(hipMalloc(&t->sub_cnt, rows * static_cast<size_t>(t->sub_pad) * sizeof(uint32_t)));
@@ -717,7 +770,7 @@ void ds_topk_fini(ds_ctx *c)
 {
     ds_topk_scratch *t = c->topk;
     if (!t) return;
-    void *ptrs[9] = {t->hist, t->sel, t->slots, t->sub_cnt, t->grp_gt, t->grp_eq, t->grp_eqb, t->grp_out, t->sub_start};
+    void *ptrs[10] = {t->done, t->hist, t->sel, t->slots, t->sub_cnt, t->grp_gt, t->grp_eq, t->grp_eqb, t->grp_out, t->sub_start};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     delete t;
@@ -727,10 +780,8 @@ void ds_topk_fini(ds_ctx *c)
 ds_status_t ds_topk_worker(ds_ctx *c, const void *g, int64_t gs, float *delta, int64_t dstr, const ds_payload_t *out,
                            hipStream_t st)
 {
-    ds_topk_scratch *t = c->topk;
     const int rows = c->cfg.n;
     u32x2 *pairs = reinterpret_cast<u32x2 *>(out->pairs);
-    k_topk_zero<<<8, kBlock, 0, st>>>(t->hist, t->sel, rows);
     if (c->cfg.grad_dtype == DS_BF16) return run_select(c, rows, WorkerV<true>{g, gs, delta, dstr}, delta, dstr, pairs, st);
     return run_select(c, rows, WorkerV<false>{g, gs, delta, dstr}, delta, dstr, pairs, st);
 }
@@ -740,7 +791,6 @@ ds_status_t ds_topk_server(ds_ctx *c, const ds_payload_t *in, float *delta_s, co
     ds_topk_scratch *t = c->topk;
     const u32x2 *pairs_in = reinterpret_cast<const u32x2 *>(in->pairs);
     const int64_t k = c->cfg.k;
-    k_topk_zero<<<8, kBlock, 0, st>>>(t->hist, t->sel, 1);
     k_topk_sub_starts<<<dim3(static_cast<unsigned>((t->n_sub + 1 + kBlock - 1) / kBlock), c->cfg.n), kBlock, 0, st>>>(
         pairs_in, k, t->n_sub, t->sub_start);
     const ServerV src{pairs_in, t->sub_start, delta_s, k, t->n_sub, c->cfg.n, c->inv_n};
