@@ -35,8 +35,9 @@ using namespace ds;
 namespace {
 
 constexpr int kSub = 256;                  // elements per subtile = one wavefront of the dense pass
-constexpr int kGroupSubs = 64;             // subtiles per group = one wavefront of the candidate passes
-constexpr int kGroup = kSub * kGroupSubs;  // 16384 elements
+constexpr int kReg = kTile;                // elements per candidate region = one workgroup of the dense pass
+constexpr int kGroupRegs = 8;              // regions per group = one wavefront of the candidate passes
+constexpr int kGroup = kReg * kGroupRegs;  // 16384 elements
 constexpr int kH1 = 4096, kH2 = 2048, kH3 = 256;
 constexpr int kOffSample = 0, kOffH1 = kH1, kOffH2 = 2 * kH1, kOffH3 = 2 * kH1 + kH2, kOffH1F = 2 * kH1 + kH2 + kH3;
 constexpr int kHistRow = 3 * kH1 + kH2 + kH3;
@@ -67,14 +68,15 @@ struct ds_topk_scratch {
     uint32_t *hist;       // [2][rows][kHistRow]: the call in flight uses one half and zeroes the other
     uint32_t *done;       // [rows][kStages] arrival counters of the "last workgroup finishes the row" steps
     Sel *sel;             // [rows]
-    u32x2 *slots;         // [rows][n_sub * 256] candidate (index, value bits), per subtile region
-    uint32_t *sub_cnt;    // [rows][sub_pad]  candidates per subtile
+    u32x2 *slots;         // [rows][n_reg * 2048] candidate (index, value bits), one region per 2048-element tile
+    uint32_t *reg_cnt;    // [rows][reg_pad]  candidates per region
     uint32_t *grp_gt;     // [rows][n_groups] candidates with key > T
     uint32_t *grp_eq;     // [rows][n_groups] candidates with key == T
     uint32_t *grp_eqb;    // [rows][n_groups] ties at T in earlier groups
     uint32_t *grp_out;    // [rows][n_groups] first output slot of the group
     uint32_t *sub_start;  // [n_sub + 1][n]   server: first entry of each worker's message per subtile
-    int64_t n_sub, sub_pad, n_groups;
+    int64_t n_sub;        // 256-element subtiles per row (sampling, server ranges)
+    int64_t n_reg, reg_pad, n_groups;
     int rows;
     int parity;           // which half of hist the next call uses
 };
@@ -343,13 +345,12 @@ __global__ __launch_bounds__(kBlock) void k_topk_sample(Src src, int64_t d, int6
 //                   candidates with bin >= b1.
 template <class Src, bool FALLBACK>
 __device__ __forceinline__ void pass1_tile(const Src &src, float *buf, int64_t stride, int64_t d, int64_t n_sub,
-                                           const Sel *sel, u32x2 *slots, uint32_t *sub_cnt, int64_t sub_pad, int row,
-                                           int64_t tile, float *strip)
+                                           const Sel *sel, u32x2 *slots, uint32_t *reg_cnt, int64_t n_reg,
+                                           int64_t reg_pad, int row, int64_t tile, float *strip, uint32_t *wtot)
 {
     const int64_t e = tile * kTile + threadIdx.x * 4;
-    const int64_t sub = e >> 8;
-    if (sub >= n_sub) return;                       // whole wavefront
-    const f32x4 v = src.load(row, e, d, strip);
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if ((e >> 8) < n_sub) v = src.load(row, e, d, strip);        // whole wavefronts
     if (!FALLBACK && e < d) {
         float *brow = buf + row * stride;
         st4(brow, e, d, aligned16(brow), v);
@@ -359,31 +360,43 @@ __device__ __forceinline__ void pass1_tile(const Src &src, float *buf, int64_t s
     bool f[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) f[c] = (e + c < d) && (bits[c] & 0x7FFFFFFFu) >= lo_key;
+    // index-ordered compaction over the workgroup: ballots inside a wavefront, wavefront
+    // totals through LDS
     const uint64_t m0 = __ballot(f[0]), m1 = __ballot(f[1]), m2 = __ballot(f[2]), m3 = __ballot(f[3]);
     const uint32_t before = lanes_below(m0) + lanes_below(m1) + lanes_below(m2) + lanes_below(m3);
-    u32x2 *out = slots + (static_cast<int64_t>(row) * n_sub + sub) * kSub + before;
+    __syncthreads();                                  // wtot may still be read (persistent launch)
+    if (lane_id() == 0) wtot[wave_id()] = __popcll(m0) + __popcll(m1) + __popcll(m2) + __popcll(m3);
+    __syncthreads();
+    uint32_t wave_off = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        if (w < wave_id()) wave_off += wtot[w];
+        total += wtot[w];
+    }
+    u32x2 *out = slots + (static_cast<int64_t>(row) * n_reg + tile) * kReg + wave_off + before;
     uint32_t r = 0;
 #pragma unroll
     for (int c = 0; c < 4; ++c)
         if (f[c]) out[r++] = u32x2{static_cast<uint32_t>(e + c), bits[c]};
-    if (lane_id() == 0)
-        sub_cnt[row * sub_pad + sub] = __popcll(m0) + __popcll(m1) + __popcll(m2) + __popcll(m3);
+    if (threadIdx.x == 0) reg_cnt[row * reg_pad + tile] = total;
 }
 
 template <class Src, bool FALLBACK>
 __global__ __launch_bounds__(kBlock) void k_topk_pass1(Src src, float *buf, int64_t stride, int64_t d, int64_t n_sub,
-                                                       const Sel *sel, u32x2 *slots, uint32_t *sub_cnt, int64_t sub_pad)
+                                                       const Sel *sel, u32x2 *slots, uint32_t *reg_cnt, int64_t n_reg,
+                                                       int64_t reg_pad)
 {
     __shared__ float strips[FALLBACK ? 1 : kWaves][FALLBACK ? 1 : kSub];
+    __shared__ uint32_t wtot[kWaves];
     const int row = blockIdx.y;
     if (FALLBACK && !sel[row].fallback) return;
-    const int64_t n_tiles = (d + kTile - 1) / kTile;
     // the regular launch has one workgroup per tile; the fallback launch is a small grid
     // that exits at once for rows that do not need it and strides over the tiles otherwise
-    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x)
-        pass1_tile<Src, FALLBACK>(src, buf, stride, d, n_sub, sel, slots, sub_cnt, sub_pad, row, tile,
-                                  FALLBACK ? nullptr : strips[wave_id()]);
+    for (int64_t tile = blockIdx.x; tile < n_reg; tile += gridDim.x)
+        pass1_tile<Src, FALLBACK>(src, buf, stride, d, n_sub, sel, slots, reg_cnt, n_reg, reg_pad, row, tile,
+                                  FALLBACK ? nullptr : strips[wave_id()], wtot);
 }
+
 // Fallback rows: dense 12-bit histogram of the stored v.  Persistent workgroups.
 __global__ __launch_bounds__(kBlock) void k_topk_fallback_hist(const float *buf, int64_t stride, int64_t d,
                                                                int64_t n_tiles, Sel *sel, uint32_t *hist,
@@ -418,25 +431,25 @@ __global__ __launch_bounds__(kBlock) void k_topk_fallback_hist(const float *buf,
 // candidate passes: one wavefront walks the candidates of one group (64 subtiles) in order
 // ---------------------------------------------------------------------------------------
 struct GroupWalk {
-    uint32_t c;      // this lane's subtile count
+    uint32_t c;      // lane r < kGroupRegs: candidate count of region r of the group
     uint32_t P;      // inclusive prefix over lanes
     uint32_t total;
 };
 
-__device__ __forceinline__ GroupWalk group_begin(const uint32_t *__restrict__ cnt_row, int64_t g, int64_t n_sub)
+__device__ __forceinline__ GroupWalk group_begin(const uint32_t *__restrict__ cnt_row, int64_t g, int64_t n_reg)
 {
     GroupWalk w;
     const int lane = lane_id();
-    const int64_t sub = g * kGroupSubs + lane;
-    w.c = (sub < n_sub) ? cnt_row[sub] : 0u;
+    const int64_t reg = g * kGroupRegs + lane;
+    w.c = (lane < kGroupRegs && reg < n_reg) ? cnt_row[reg] : 0u;
     uint32_t p = w.c;
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
+    for (int o = 1; o < kGroupRegs; o <<= 1) {
         const uint32_t up = __shfl_up(p, o, 64);
         if (lane >= o) p += up;
     }
     w.P = p;
-    w.total = __shfl(p, 63, 64);
+    w.total = __shfl(p, kGroupRegs - 1, 64);
     return w;
 }
 
@@ -444,22 +457,22 @@ __device__ __forceinline__ GroupWalk group_begin(const uint32_t *__restrict__ cn
 __device__ __forceinline__ u32x2 group_fetch(const GroupWalk &w, const u32x2 *__restrict__ slots_row, int64_t g,
                                              uint32_t i, bool valid)
 {
-    int lo = 0, hi = 63;                          // first lane s with P_s > i
+    int lo = 0, hi = kGroupRegs - 1;              // first region r with P_r > i
 #pragma unroll
-    for (int step = 0; step < 6; ++step) {
+    for (int step = 0; step < 3; ++step) {
         const int mid = (lo + hi) >> 1;
         const uint32_t pm = __shfl(w.P, mid, 64);
         if (pm > i) hi = mid; else lo = mid + 1;
     }
     const uint32_t ps = __shfl(w.P, lo, 64), cs = __shfl(w.c, lo, 64);
     u32x2 pr = {0u, 0u};
-    if (valid) pr = slots_row[(g * kGroupSubs + lo) * kSub + (i - (ps - cs))];
+    if (valid) pr = slots_row[(g * kGroupRegs + lo) * kReg + (i - (ps - cs))];
     return pr;
 }
 
 // The candidate passes fetch up to kPrefetch batches of 64 candidates before using any of
 // them, so that a wavefront has several independent loads in flight instead of a chain of
-// dependent ones (a group holds about 250-320 candidates at k = 1 %).
+// dependent ones (a group of 8 regions holds about 250-320 candidates at k = 1 %).
 constexpr int kPrefetch = 8;
 
 struct Batch {
@@ -484,8 +497,8 @@ __device__ __forceinline__ Batch group_fetch_batches(const GroupWalk &w, const u
 // LEVEL 1: 12-bit histogram of all candidates.  2: next 11 bits of those in bin b1.
 // 3: low 8 bits of those with prefix (b1, b2).  One group per wavefront.
 template <int LEVEL>
-__global__ __launch_bounds__(kBlock) void k_topk_cand_hist(const u32x2 *slots, const uint32_t *sub_cnt, int64_t n_sub,
-                                                           int64_t sub_pad, int64_t n_groups, Sel *sel,
+__global__ __launch_bounds__(kBlock) void k_topk_cand_hist(const u32x2 *slots, const uint32_t *reg_cnt, int64_t n_reg,
+                                                           int64_t reg_pad, int64_t n_groups, Sel *sel,
                                                            uint32_t *hist, uint32_t *done, uint32_t k)
 {
     constexpr int NB = (LEVEL == 1) ? kH1 : (LEVEL == 2) ? kH2 : kH3;
@@ -498,8 +511,8 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_hist(const u32x2 *slots, c
     __syncthreads();
     const int64_t g = static_cast<int64_t>(blockIdx.x) * kWaves + wave_id();
     if (g < n_groups) {
-        const GroupWalk w = group_begin(sub_cnt + row * sub_pad, g, n_sub);
-        const u32x2 *srow = slots + static_cast<int64_t>(row) * n_sub * kSub;
+        const GroupWalk w = group_begin(reg_cnt + row * reg_pad, g, n_reg);
+        const u32x2 *srow = slots + static_cast<int64_t>(row) * n_reg * kReg;
         const uint32_t prefix = (s.b1 << 11) | s.b2;
         for (uint32_t i0 = 0; i0 < w.total; i0 += 64 * kPrefetch) {
             const Batch bt = group_fetch_batches(w, srow, g, i0);
@@ -572,8 +585,8 @@ __device__ __forceinline__ void scan_row(int row, const Sel *sel, int64_t n_grou
 // Per group: candidates above T, candidates tying with T; the last workgroup of the row
 // then scans the groups.  The kernel also zeroes the histogram half that the NEXT call will
 // use (`zero`, `zero_words`), which replaces a separate clearing launch.
-__global__ __launch_bounds__(kBlock) void k_topk_count(const u32x2 *slots, const uint32_t *sub_cnt, int64_t n_sub,
-                                                       int64_t sub_pad, int64_t n_groups, const Sel *sel,
+__global__ __launch_bounds__(kBlock) void k_topk_count(const u32x2 *slots, const uint32_t *reg_cnt, int64_t n_reg,
+                                                       int64_t reg_pad, int64_t n_groups, const Sel *sel,
                                                        uint32_t *grp_gt, uint32_t *grp_eq, uint32_t *grp_eqb,
                                                        uint32_t *grp_out, uint32_t *done, uint32_t *zero,
                                                        int64_t zero_words)
@@ -586,8 +599,8 @@ __global__ __launch_bounds__(kBlock) void k_topk_count(const u32x2 *slots, const
     const int64_t g = static_cast<int64_t>(blockIdx.x) * kWaves + wave_id();
     if (g < n_groups) {
         const uint32_t T = sel[row].T;
-        const GroupWalk w = group_begin(sub_cnt + row * sub_pad, g, n_sub);
-        const u32x2 *srow = slots + static_cast<int64_t>(row) * n_sub * kSub;
+        const GroupWalk w = group_begin(reg_cnt + row * reg_pad, g, n_reg);
+        const u32x2 *srow = slots + static_cast<int64_t>(row) * n_reg * kReg;
         uint32_t gt = 0, eq = 0;
         for (uint32_t i0 = 0; i0 < w.total; i0 += 64 * kPrefetch) {
             const Batch bt = group_fetch_batches(w, srow, g, i0);
@@ -612,8 +625,8 @@ __global__ __launch_bounds__(kBlock) void k_topk_count(const u32x2 *slots, const
 
 // Per group: write the kept entries in index order and zero them in the error buffer
 // (delta = v - Q[v]).
-__global__ __launch_bounds__(kBlock) void k_topk_emit(const u32x2 *slots, const uint32_t *sub_cnt, int64_t n_sub,
-                                                      int64_t sub_pad, int64_t n_groups, const Sel *sel,
+__global__ __launch_bounds__(kBlock) void k_topk_emit(const u32x2 *slots, const uint32_t *reg_cnt, int64_t n_reg,
+                                                      int64_t reg_pad, int64_t n_groups, const Sel *sel,
                                                       const uint32_t *grp_eqb, const uint32_t *grp_out, int64_t k,
                                                       u32x2 *pairs, float *buf, int64_t stride)
 {
@@ -621,8 +634,8 @@ __global__ __launch_bounds__(kBlock) void k_topk_emit(const u32x2 *slots, const 
     const int64_t g = static_cast<int64_t>(blockIdx.x) * kWaves + wave_id();
     if (g >= n_groups) return;
     const Sel s = sel[row];
-    const GroupWalk w = group_begin(sub_cnt + row * sub_pad, g, n_sub);
-    const u32x2 *srow = slots + static_cast<int64_t>(row) * n_sub * kSub;
+    const GroupWalk w = group_begin(reg_cnt + row * reg_pad, g, n_reg);
+    const u32x2 *srow = slots + static_cast<int64_t>(row) * n_reg * kReg;
     uint32_t eq_seen = grp_eqb[row * n_groups + g];
     uint32_t out = grp_out[row * n_groups + g];
     u32x2 *prow = pairs + static_cast<int64_t>(row) * k;
@@ -702,7 +715,7 @@ template <class Src>
 ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t stride, u32x2 *pairs, hipStream_t st)
 {
     ds_topk_scratch *t = c->topk;
-    const int64_t d = c->cfg.d, k = c->cfg.k, n_sub = t->n_sub, sub_pad = t->sub_pad, n_groups = t->n_groups;
+    const int64_t d = c->cfg.d, k = c->cfg.k, n_sub = t->n_sub, n_reg = t->n_reg, reg_pad = t->reg_pad, n_groups = t->n_groups;
     const int64_t ns = (n_sub < kSampleSubs) ? n_sub : kSampleSubs;
     // sample rank: 1.5 x the expected number of top-k members in the sample, plus slack
     const double sample_elems = static_cast<double>((ns * kSub < d) ? ns * kSub : d);
@@ -720,20 +733,20 @@ ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t 
 
     k_topk_sample<Src><<<dim3(static_cast<unsigned>((ns + kWaves - 1) / kWaves), rows), kBlock, 0, st>>>(
         src, d, n_sub, ns, hist, t->sel, t->done, rank);
-    k_topk_pass1<Src, false><<<dense, kBlock, 0, st>>>(src, buf, stride, d, n_sub, t->sel, t->slots, t->sub_cnt, sub_pad);
-    k_topk_cand_hist<1><<<cand, kBlock, 0, st>>>(t->slots, t->sub_cnt, n_sub, sub_pad, n_groups, t->sel, hist, t->done, k32);
+    k_topk_pass1<Src, false><<<dense, kBlock, 0, st>>>(src, buf, stride, d, n_sub, t->sel, t->slots, t->reg_cnt, n_reg, reg_pad);
+    k_topk_cand_hist<1><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32);
     // two-look route for rows whose sample misjudged; both launches exit at once otherwise
     k_topk_fallback_hist<<<dim3(persistent_blocks(c->n_tiles, rows), rows), kBlock, 0, st>>>(buf, stride, d, c->n_tiles,
                                                                                             t->sel, hist, t->done, k32);
     k_topk_pass1<BufferV, true><<<dim3(persistent_blocks(c->n_tiles, rows), rows), kBlock, 0, st>>>(
-        bsrc, buf, stride, d, n_sub, t->sel, t->slots, t->sub_cnt, sub_pad);
+        bsrc, buf, stride, d, n_sub, t->sel, t->slots, t->reg_cnt, n_reg, reg_pad);
     // refinement on the candidates
-    k_topk_cand_hist<2><<<cand, kBlock, 0, st>>>(t->slots, t->sub_cnt, n_sub, sub_pad, n_groups, t->sel, hist, t->done, k32);
-    k_topk_cand_hist<3><<<cand, kBlock, 0, st>>>(t->slots, t->sub_cnt, n_sub, sub_pad, n_groups, t->sel, hist, t->done, k32);
-    k_topk_count<<<cand, kBlock, 0, st>>>(t->slots, t->sub_cnt, n_sub, sub_pad, n_groups, t->sel, t->grp_gt, t->grp_eq,
+    k_topk_cand_hist<2><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32);
+    k_topk_cand_hist<3><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32);
+    k_topk_count<<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, t->grp_gt, t->grp_eq,
                                           t->grp_eqb, t->grp_out, t->done, hist_next,
                                           static_cast<int64_t>(t->rows) * kHistRow);
-    k_topk_emit<<<cand, kBlock, 0, st>>>(t->slots, t->sub_cnt, n_sub, sub_pad, n_groups, t->sel, t->grp_eqb, t->grp_out, k,
+    k_topk_emit<<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, t->grp_eqb, t->grp_out, k,
                                          pairs, buf, stride);
     return ds_launch_status();
 }
@@ -749,20 +762,21 @@ ds_status_t ds_topk_init(ds_ctx *c)
     const size_t rows = static_cast<size_t>(c->cfg.n);
     t->rows = c->cfg.n;
     t->n_sub = (c->cfg.d + kSub - 1) / kSub;
-    t->n_groups = (t->n_sub + kGroupSubs - 1) / kGroupSubs;
-    t->sub_pad = t->n_groups * kGroupSubs;
+    t->n_reg = c->n_tiles;
+    t->n_groups = (t->n_reg + kGroupRegs - 1) / kGroupRegs;
+    t->reg_pad = t->n_groups * kGroupRegs;
     DS_HIP_TRY(hipMalloc(&t->hist, 2 * rows * kHistRow * sizeof(uint32_t)));
     DS_HIP_TRY(hipMemset(t->hist, 0, 2 * rows * kHistRow * sizeof(uint32_t)));
     DS_HIP_TRY(hipMalloc(&t->done, rows * kStages * sizeof(uint32_t)));
     DS_HIP_TRY(hipMemset(t->done, 0, rows * kStages * sizeof(uint32_t)));
     t->parity = 0;
     DS_HIP_TRY(hipMalloc(&t->sel, rows * sizeof(Sel)));
-    DS_HIP_TRY(hipMalloc(&t->slots, rows * static_cast<size_t>(t->n_sub) * kSub * sizeof(u32x2)));
-    DS_HIP_TRY(hipMalloc(&t->sub_cnt, rows * static_cast<size_t>(t->sub_pad) * sizeof(uint32_t)));
+    DS_HIP_TRY(hipMalloc(&t->slots, rows * static_cast<size_t>(t->n_reg) * kReg * sizeof(u32x2)));
+    DS_HIP_TRY(hipMalloc(&t->reg_cnt, rows * static_cast<size_t>(t->reg_pad) * sizeof(uint32_t)));
     uint32_t **tabs[4] = {&t->grp_gt, &t->grp_eq, &t->grp_eqb, &t->grp_out};
     for (auto tab : tabs) DS_HIP_TRY(hipMalloc(tab, rows * static_cast<size_t>(t->n_groups) * sizeof(uint32_t)));
     DS_HIP_TRY(hipMalloc(&t->sub_start, rows * static_cast<size_t>(t->n_sub + 1) * sizeof(uint32_t)));
-    DS_HIP_TRY(hipMemset(t->sub_cnt, 0, rows * static_cast<size_t>(t->sub_pad) * sizeof(uint32_t)));
+    DS_HIP_TRY(hipMemset(t->reg_cnt, 0, rows * static_cast<size_t>(t->reg_pad) * sizeof(uint32_t)));
     return DS_OK;
 }
 
@@ -770,7 +784,7 @@ void ds_topk_fini(ds_ctx *c)
 {
     ds_topk_scratch *t = c->topk;
     if (!t) return;
-    void *ptrs[10] = {t->done, t->hist, t->sel, t->slots, t->sub_cnt, t->grp_gt, t->grp_eq, t->grp_eqb, t->grp_out, t->sub_start};
+    void *ptrs[10] = {t->done, t->hist, t->sel, t->slots, t->reg_cnt, t->grp_gt, t->grp_eq, t->grp_eqb, t->grp_out, t->sub_start};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     delete t;
