@@ -655,7 +655,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_emit(const u32x2 *slots, const 
             if (keep) {
                 const uint32_t slot = out + lanes_below(keep_mask);
                 if (slot < k) prow[slot] = pr;
-                brow[pr.x] = 0.f;
+                __builtin_nontemporal_store(0.f, brow + pr.x);
             }
             out += __popcll(keep_mask);
             eq_seen += __popcll(eq_mask);
