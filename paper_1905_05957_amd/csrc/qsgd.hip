@@ -173,7 +173,40 @@ __global__ __launch_bounds__(kBlock) void k_qsgd_server(const uint8_t *levels_in
             units[t] = (B < P.Bq) ? __fdiv_rn(norms_in[(i0 + i) * P.Bq + B], static_cast<float>(P.s)) : 0.f;
         }
         __syncthreads();
-        if (e < P.d) {
+        // Messages of the wavefront's 256 elements: 128 bytes of codes and 32 bytes of sign
+        // bits per worker.  Fast route (whole wavefront in range, 4-byte aligned code rows):
+        // eight workers at a time, one 32-bit load fetches the sign words of all eight
+        // (lane L: word L & 7 of worker L >> 3) and four 32-bit loads fetch the codes of two
+        // workers each (lane L: word L & 31 of worker L >> 5); ds_bpermute then hands every
+        // lane its own nibble and 16-bit code group.  Other wavefronts load per lane.
+        const int lane = lane_id();
+        const int64_t wave_first = tile_base + wave_id() * 256;
+        const bool fast = (wave_first + 256 <= P.d) && ((lev_stride & 3) == 0) &&
+                          ((reinterpret_cast<uintptr_t>(levels_in) & 3u) == 0);
+        if (fast) {
+            for (int j0 = 0; j0 < cnt; j0 += 8) {
+                const int nb = (cnt - j0 < 8) ? cnt - j0 : 8;
+                uint32_t sw = 0u;
+                if ((lane >> 3) < nb)
+                    sw = reinterpret_cast<const uint32_t *>(words_in + (i0 + j0 + (lane >> 3)) * P.W)[(wave_first >> 5) + (lane & 7)];
+                uint32_t cw[4];
+#pragma unroll
+                for (int p2 = 0; p2 < 4; ++p2) {
+                    const int wk = 2 * p2 + (lane >> 5);
+                    cw[p2] = 0u;
+                    if (wk < nb)
+                        cw[p2] = reinterpret_cast<const uint32_t *>(levels_in + (i0 + j0 + wk) * lev_stride + (wave_first >> 1))[lane & 31];
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    if (j >= nb) break;                      // uniform
+                    const uint32_t nib = (__shfl(sw, j * 8 + (lane >> 3), 64) >> (4 * (lane & 7))) & 15u;
+                    const uint32_t c32 = __shfl(cw[j >> 1], (j & 1) * 32 + (lane >> 1), 64);
+                    const uint32_t codes = (c32 >> (16 * (lane & 1))) & 0xFFFFu;
+                    a = fma4(inv_n, decode4(codes, nib, units[(j0 + j) * bpt + my_b]), a);
+                }
+            }
+        } else if (e < P.d) {
             for (int i = 0; i < cnt; ++i) {
                 const int64_t w = i0 + i;
                 const uint32_t codes = load_codes4(levels_in + w * lev_stride, e, P.d);
