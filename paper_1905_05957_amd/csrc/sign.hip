@@ -261,7 +261,25 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass1_server(ServerArgs a, floa
     const int32_t p0 = tb.tile_piece_first[tile], p1 = tb.tile_piece_first[tile + 1];
     const int64_t e = base + threadIdx.x * 4;
     f32x4 v = ld4(delta_s, e, d, dvec);
-    if (e < d) {
+    const int lane = lane_id();
+    const int64_t wave_first = base + wave_id() * 256;
+    if (p1 - p0 == 1) {
+        // the whole tile lies in one scale group: same batched loads as the chunk route
+        // (lane L: sign word L & 7 of worker L >> 3; lane i: scale of worker i)
+        const int32_t sg = tb.piece_seg[p0];
+        for (int i0 = 0; i0 < a.n; i0 += 8) {
+            const int nb = (a.n - i0 < 8) ? a.n - i0 : 8;
+            uint32_t word = 0u;
+            if ((lane >> 3) < nb && wave_first + 32 * (lane & 7) < a.W * 64)
+                word = reinterpret_cast<const uint32_t *>(a.words_in + (i0 + (lane >> 3)) * a.W)[(wave_first >> 5) + (lane & 7)];
+            const float sc = (lane < nb) ? a.scales_in[(i0 + lane) * a.S + sg] : 0.f;
+            for (int i = 0; i < nb; ++i) {
+                const uint32_t w = __shfl(word, i * 8 + (lane >> 3), 64);
+                const float sv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sc), i));
+                if (e < d) v = chain4(v, (w >> (4 * (lane & 7))) & 15u, sv, a.inv_n);
+            }
+        }
+    } else if (e < d) {
         int32_t seg[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) seg[c] = (e + c < d) ? seg_of(tb, p0, p1, e + c) : 0;
@@ -307,8 +325,11 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass2(float *buf, int64_t strid
                                                        const float *__restrict__ scales, int64_t S,
                                                        ds_sign_tables tb)
 {
-    const int row = blockIdx.y;
-    const int64_t tile = blockIdx.x;
+    // Pass 2 walks the rows and tiles in the opposite order to pass 1: what pass 1 wrote last
+    // is still in the 256 MB memory-side cache, so those reads (and the v lines they
+    // overwrite) never reach HBM.
+    const int row = gridDim.y - 1 - blockIdx.y;
+    const int64_t tile = gridDim.x - 1 - blockIdx.x;
     float *brow = buf + row * stride;
     const float *srow = scales + row * S;
     const bool vec = aligned16(brow);
