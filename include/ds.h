@@ -86,7 +86,8 @@ typedef struct {
     int32_t n_seg;
     int32_t levels;           /* QSGD: s, number of non-zero levels, 1 .. 15 */
     int64_t k;                /* TOPK: entries kept per vector, 1 .. d */
-    int32_t bucket;           /* QSGD: elements per bucket, a multiple of 64 */
+    int32_t bucket;           /* QSGD: elements per bucket, a multiple of 64 (built: the powers of
+                                 two 64 .. 2048; other multiples give DS_ERR_UNSUPPORTED) */
     int32_t reserved;
     uint64_t seed;            /* QSGD: Philox key */
 } ds_config_t;
@@ -119,7 +120,7 @@ typedef struct {
 
 /* Creates a context on the current device and allocates its scratch memory there.
  * Errors: NULL, SHAPE (n, d, k out of range), CONFIG (bad enum, offsets, bucket, levels),
- * DEVICE (allocation failed). */
+ * UNSUPPORTED (bucket not a power of two up to 2048), DEVICE (allocation failed). */
 ds_status_t ds_create(const ds_config_t *cfg, ds_ctx_t **out);
 
 /* Frees the context's scratch memory.  The caller must have synchronised the streams that

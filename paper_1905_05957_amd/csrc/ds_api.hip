@@ -98,6 +98,7 @@ ds_status_t ds_create(const ds_config_t *cfg, ds_ctx_t **out)
     case DS_COMP_QSGD:
         if (cfg->bucket < 64 || cfg->bucket % 64 != 0) return DS_ERR_CONFIG;
         if (cfg->levels < 1 || cfg->levels > 15) return DS_ERR_CONFIG;
+        if (cfg->bucket > 2048 || (cfg->bucket & (cfg->bucket - 1)) != 0) return DS_ERR_UNSUPPORTED;
         break;
     default:
         return DS_ERR_CONFIG;
