@@ -29,7 +29,10 @@ HBM_PEAK_GBS = 8000.0
 # WRITE_SIZE runs, each scaled by the same counter's reading for a 1 GiB copy); the runs and
 # the scale factors are recorded under profiles/.  None = not profiled yet.
 MEASURED_WORKER_TRAFFIC = {
-    "c5": 5.973e9 + 4.161e9,
+    "c5": 5.9729e9 + 4.1613e9,   # k_sign_chunk_worker
+    "c4": 3.3100e9 + 1.9392e9,   # k_qsgd_worker
+    "c3": 2.7916e9,              # all kernels of the worker call (dense pass 2.5074e9)
+    "c2": 1.8343e9,              # pass 1 + pass 2
 }
 
 
