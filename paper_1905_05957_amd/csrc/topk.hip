@@ -20,7 +20,7 @@
 //   verify     if the candidates number fewer than k (the sample misjudged), the row falls
 //              back to the exact two-look route: dense 12-bit histogram of the stored v,
 //              pick, dense compaction.  Those kernels exit at once for rows that need none.
-//   count / scan / emit   per 16384-element group, in order: entries above T plus the first
+//   count / scan / emit   per 32768-element group, in order: entries above T plus the first
 //              ties by index are written at scanned offsets, so the output is sorted by
 //              index without a sort; kept positions of the error buffer are zeroed
 //              (delta = v - Q[v] is 0 there and v elsewhere).
@@ -36,8 +36,8 @@ namespace {
 
 constexpr int kSub = 256;                  // elements per subtile = one wavefront of the dense pass
 constexpr int kReg = kTile;                // elements per candidate region = one workgroup of the dense pass
-constexpr int kGroupRegs = 8;              // regions per group = one wavefront of the candidate passes
-constexpr int kGroup = kReg * kGroupRegs;  // 16384 elements
+constexpr int kGroupRegs = 16;             // regions per group = one wavefront of the candidate passes
+constexpr int kGroup = kReg * kGroupRegs;  // 32768 elements
 constexpr int kH1 = 4096, kH2 = 2048, kH3 = 256;
 constexpr int kOffSample = 0, kOffH1 = kH1, kOffH2 = 2 * kH1, kOffH3 = 2 * kH1 + kH2, kOffH1F = 2 * kH1 + kH2 + kH3;
 constexpr int kHistRow = 3 * kH1 + kH2 + kH3;
@@ -459,7 +459,7 @@ __device__ __forceinline__ u32x2 group_fetch(const GroupWalk &w, const u32x2 *__
 {
     int lo = 0, hi = kGroupRegs - 1;              // first region r with P_r > i
 #pragma unroll
-    for (int step = 0; step < 3; ++step) {
+    for (int step = 0; step < 4; ++step) {
         const int mid = (lo + hi) >> 1;
         const uint32_t pm = __shfl(w.P, mid, 64);
         if (pm > i) hi = mid; else lo = mid + 1;
@@ -473,7 +473,7 @@ __device__ __forceinline__ u32x2 group_fetch(const GroupWalk &w, const u32x2 *__
 // The candidate passes fetch up to kPrefetch batches of 64 candidates before using any of
 // them, so that a wavefront has several independent loads in flight instead of a chain of
 // dependent ones (a group of 8 regions holds about 250-320 candidates at k = 1 %).
-constexpr int kPrefetch = 8;
+constexpr int kPrefetch = 10;
 
 struct Batch {
     u32x2 pr[kPrefetch];
