@@ -39,6 +39,10 @@ constexpr int kReg = kTile;                // elements per candidate region = on
 constexpr int kGroupRegs = 16;             // regions per group = one wavefront of the candidate passes
 constexpr int kGroup = kReg * kGroupRegs;  // 32768 elements
 constexpr int kH1 = 4096, kH2 = 2048, kH3 = 256;
+// The candidates' level-1 histogram covers only the 256 top-12-bit bins from lo_bin upwards
+// (16 octaves of magnitude); anything above is clamped into its last bin.  If the k-th key
+// falls into that last bin the row takes the fallback route.
+constexpr int kH1W = 256;
 constexpr int kOffSample = 0, kOffH1 = kH1, kOffH2 = 2 * kH1, kOffH3 = 2 * kH1 + kH2, kOffH1F = 2 * kH1 + kH2 + kH3;
 constexpr int kHistRow = 3 * kH1 + kH2 + kH3;
 constexpr int kSampleSubs = 256;           // subtiles sampled per row
@@ -283,7 +287,7 @@ __device__ __forceinline__ void pick_level(const uint32_t *hrow, Sel *s, uint32_
     if (threadIdx.x == 0) { out[0] = kNone; out[1] = 0u; }
     __syncthreads();
     if (LEVEL == 0) pick_bin<kH1>(hrow + kOffSample, need0, part, &out[0], &out[1]);
-    if (LEVEL == 1) pick_bin<kH1>(hrow + kOffH1, need0, part, &out[0], &out[1]);
+    if (LEVEL == 1) pick_bin<kH1W>(hrow + kOffH1, need0, part, &out[0], &out[1]);
     if (LEVEL == 2) pick_bin<kH2>(hrow + kOffH2, s->k1, part, &out[0], &out[1]);
     if (LEVEL == 3) pick_bin<kH3>(hrow + kOffH3, s->k2, part, &out[0], &out[1]);
     if (LEVEL == 4) pick_bin<kH1>(hrow + kOffH1F, need0, part, &out[0], &out[1]);
@@ -291,8 +295,10 @@ __device__ __forceinline__ void pick_level(const uint32_t *hrow, Sel *s, uint32_
     if (threadIdx.x == 0) {
         if (LEVEL == 0) s->lo_bin = (out[0] == kNone) ? 0u : out[0];
         if (LEVEL == 1) {
-            s->fallback = (out[0] == kNone) ? 1u : 0u;
-            if (out[0] != kNone) { s->b1 = out[0]; s->k1 = out[1]; }
+            // no bin found: fewer than k candidates; last window bin: bins are lumped there
+            const bool bad = out[0] == kNone || (out[0] == kH1W - 1 && s->lo_bin + kH1W - 1 < kH1 - 1);
+            s->fallback = bad ? 1u : 0u;
+            if (!bad) { s->b1 = s->lo_bin + out[0]; s->k1 = out[1]; }
         }
         if (LEVEL == 2) { s->b2 = out[0]; s->k2 = out[1]; }
         if (LEVEL == 3) { s->T = (s->b1 << 19) | (s->b2 << 8) | out[0]; s->k3 = out[1]; }
@@ -501,7 +507,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_hist(const u32x2 *slots, c
                                                            int64_t reg_pad, int64_t n_groups, Sel *sel,
                                                            uint32_t *hist, uint32_t *done, uint32_t k)
 {
-    constexpr int NB = (LEVEL == 1) ? kH1 : (LEVEL == 2) ? kH2 : kH3;
+    constexpr int NB = (LEVEL == 1) ? kH1W : (LEVEL == 2) ? kH2 : kH3;
     constexpr int OFF = (LEVEL == 1) ? kOffH1 : (LEVEL == 2) ? kOffH2 : kOffH3;
     __shared__ uint32_t h[NB];
     __shared__ uint32_t part[kBlock], out[2], flag;
@@ -520,7 +526,10 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_hist(const u32x2 *slots, c
             for (int j = 0; j < kPrefetch; ++j) {
                 if (i0 + j * 64 + lane_id() >= w.total) continue;
                 const uint32_t key = bt.pr[j].y & 0x7FFFFFFFu;
-                if (LEVEL == 1) atomicAdd(&h[key >> 19], 1u);
+                if (LEVEL == 1) {
+                    const uint32_t rel = (key >> 19) - s.lo_bin;      // candidates have bin >= lo_bin
+                    atomicAdd(&h[rel < kH1W ? rel : kH1W - 1], 1u);
+                }
                 if (LEVEL == 2 && (key >> 19) == s.b1) atomicAdd(&h[(key >> 8) & (kH2 - 1)], 1u);
                 if (LEVEL == 3 && (key >> 8) == prefix) atomicAdd(&h[key & 255u], 1u);
             }

@@ -101,3 +101,17 @@ def test_topk_sample_misjudges_and_falls_back(gpu_device):
     assert int((g[0].abs() >= 1.0).sum()) < k
     wl = _wl(d, n=n, k=k)
     _run(wl, gpu_device, steps=2, grads=[g])
+
+
+def test_topk_outliers_far_above_the_bulk(gpu_device):
+    # exactly k huge entries over a bulk 100 octaves smaller: the sampled lower bound sits in
+    # the bulk, the k-th key lies far outside the windowed first-level histogram, and the
+    # exact route must take over
+    d, n, k = 1 << 20, 2, 2000
+    gen = torch.Generator(device=gpu_device)
+    gen.manual_seed(11)
+    g = (1.0 + torch.rand((n, d), device=gpu_device, generator=gen)) * 1e-30
+    for i in range(n):
+        pos = torch.randperm(d, device=gpu_device, generator=gen)[:k]
+        g[i, pos] = (1.0 + torch.rand(k, device=gpu_device, generator=gen)) * (1 if i == 0 else -1)
+    _run(_wl(d, n=n, k=k), gpu_device, steps=2, grads=[g])
