@@ -357,15 +357,18 @@ __device__ __forceinline__ void pass1_tile(const Src &src, float *buf, int64_t s
     const int64_t e = tile * kTile + threadIdx.x * 4;
     f32x4 v = {0.f, 0.f, 0.f, 0.f};
     if ((e >> 8) < n_sub) v = src.load(row, e, d, strip);        // whole wavefronts
-    if (!FALLBACK && e < d) {
-        float *brow = buf + row * stride;
-        st4(brow, e, d, aligned16(brow), v);
-    }
     const uint32_t lo_key = (FALLBACK ? sel[row].b1 : sel[row].lo_bin) << 19;
     const uint32_t bits[4] = {__float_as_uint(v.x), __float_as_uint(v.y), __float_as_uint(v.z), __float_as_uint(v.w)};
     bool f[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) f[c] = (e + c < d) && (bits[c] & 0x7FFFFFFFu) >= lo_key;
+    // The error buffer gets v where the element is no candidate and 0 where it is: most
+    // candidates end up kept (delta = 0 there), so the emit pass only has to put v back at
+    // the few candidates that are not kept instead of zeroing every kept position.
+    if (e < d) {
+        float *brow = buf + row * stride;
+        st4(brow, e, d, aligned16(brow), f32x4{f[0] ? 0.f : v.x, f[1] ? 0.f : v.y, f[2] ? 0.f : v.z, f[3] ? 0.f : v.w});
+    }
     // index-ordered compaction over the workgroup: ballots inside a wavefront, wavefront
     // totals through LDS
     const uint64_t m0 = __ballot(f[0]), m1 = __ballot(f[1]), m2 = __ballot(f[2]), m3 = __ballot(f[3]);
@@ -401,6 +404,21 @@ __global__ __launch_bounds__(kBlock) void k_topk_pass1(Src src, float *buf, int6
     for (int64_t tile = blockIdx.x; tile < n_reg; tile += gridDim.x)
         pass1_tile<Src, FALLBACK>(src, buf, stride, d, n_sub, sel, slots, reg_cnt, n_reg, reg_pad, row, tile,
                                   FALLBACK ? nullptr : strips[wave_id()], wtot);
+}
+
+// Fallback rows: put v back at every candidate position (the dense pass wrote 0 there), so
+// that the two-look route sees the whole of v in the buffer.
+__global__ __launch_bounds__(kBlock) void k_topk_restore(const u32x2 *slots, const uint32_t *reg_cnt, int64_t n_reg,
+                                                         int64_t reg_pad, const Sel *sel, float *buf, int64_t stride)
+{
+    const int row = blockIdx.y;
+    if (!sel[row].fallback) return;
+    float *brow = buf + row * stride;
+    for (int64_t reg = blockIdx.x; reg < n_reg; reg += gridDim.x) {
+        const uint32_t cnt = reg_cnt[row * reg_pad + reg];
+        const u32x2 *src = slots + (static_cast<int64_t>(row) * n_reg + reg) * kReg;
+        for (uint32_t i = threadIdx.x; i < cnt; i += kBlock) brow[src[i].x] = __uint_as_float(src[i].y);
+    }
 }
 
 // Fallback rows: dense 12-bit histogram of the stored v.  Persistent workgroups.
@@ -632,8 +650,9 @@ __global__ __launch_bounds__(kBlock) void k_topk_count(const u32x2 *slots, const
         scan_row(row, sel, n_groups, grp_gt, grp_eq, grp_eqb, grp_out, tmp);
 }
 
-// Per group: write the kept entries in index order and zero them in the error buffer
-// (delta = v - Q[v]).
+// Per group: write the kept entries in index order; the dense pass left 0 at every
+// candidate position of the error buffer, so the candidates that are not kept get v back
+// (delta = v - Q[v] is 0 at kept positions and v elsewhere).
 __global__ __launch_bounds__(kBlock) void k_topk_emit(const u32x2 *slots, const uint32_t *reg_cnt, int64_t n_reg,
                                                       int64_t reg_pad, int64_t n_groups, const Sel *sel,
                                                       const uint32_t *grp_eqb, const uint32_t *grp_out, int64_t k,
@@ -664,7 +683,8 @@ __global__ __launch_bounds__(kBlock) void k_topk_emit(const u32x2 *slots, const 
             if (keep) {
                 const uint32_t slot = out + lanes_below(keep_mask);
                 if (slot < k) prow[slot] = pr;
-                __builtin_nontemporal_store(0.f, brow + pr.x);
+            } else if (valid) {
+                __builtin_nontemporal_store(__uint_as_float(pr.y), brow + pr.x);   // not kept: delta = v
             }
             out += __popcll(keep_mask);
             eq_seen += __popcll(eq_mask);
@@ -745,7 +765,9 @@ ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t 
         src, d, n_sub, ns, hist, t->sel, t->done, rank);
     k_topk_pass1<Src, false><<<dense, kBlock, 0, st>>>(src, buf, stride, d, n_sub, t->sel, t->slots, t->reg_cnt, n_reg, reg_pad);
     k_topk_cand_hist<1><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32);
-    // two-look route for rows whose sample misjudged; both launches exit at once otherwise
+    // two-look route for rows whose sample misjudged; the three launches exit at once otherwise
+    k_topk_restore<<<dim3(persistent_blocks(c->n_tiles, rows), rows), kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad,
+                                                                                      t->sel, buf, stride);
     k_topk_fallback_hist<<<dim3(persistent_blocks(c->n_tiles, rows), rows), kBlock, 0, st>>>(buf, stride, d, c->n_tiles,
                                                                                             t->sel, hist, t->done, k32);
     k_topk_pass1<BufferV, true><<<dim3(persistent_blocks(c->n_tiles, rows), rows), kBlock, 0, st>>>(
