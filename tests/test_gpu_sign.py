@@ -33,7 +33,7 @@ def test_sign_whole_vector(gpu_device, d):
     _run(_sign_wl(d, scale_mode="whole"), gpu_device)
 
 
-@pytest.mark.parametrize("chunk", [2048, 1024, 256, 320, 100, 64, 4096, 7])
+@pytest.mark.parametrize("chunk", [2048, 1024, 1920, 640, 576, 256, 320, 100, 64, 4096, 7])
 @pytest.mark.parametrize("d", [6 * 2048, 5 * 2048 + 1280, 9001])
 def test_sign_chunks(gpu_device, d, chunk):
     _run(_sign_wl(d, scale_mode="chunk", chunk=chunk), gpu_device)
