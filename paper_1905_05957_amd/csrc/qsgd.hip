@@ -56,7 +56,7 @@ __device__ __forceinline__ double bucket_sum(double x, int lanes_per_bucket, dou
 // form v - q) and writes codes, sign bits and the bucket norm.
 __device__ __forceinline__ f32x4 quantise4(f32x4 v, int64_t e, uint32_t stream, const QParams &P,
                                            uint8_t *__restrict__ levels_row, uint64_t *__restrict__ words_row,
-                                           float *__restrict__ norms_row, double *lds)
+                                           float *__restrict__ norms_row, double *lds, uint32_t *sw_lds)
 {
     const int lpb = P.bucket >> 2;
     const double ss = ((static_cast<double>(v.x) * static_cast<double>(v.x) +
@@ -96,8 +96,9 @@ __device__ __forceinline__ f32x4 quantise4(f32x4 v, int64_t e, uint32_t stream, 
             if (e + 2 < P.d) dst[1] = static_cast<uint8_t>(packed >> 8);
         }
     }
-    const uint32_t sword = wave_sign_word(v.x < 0.f, v.y < 0.f, v.z < 0.f, v.w < 0.f);
-    store_sign_words(words_row, (e >> 8) << 8, P.W * 64, sword);
+    stash_sign_words(sw_lds, wave_sign_word(v.x < 0.f, v.y < 0.f, v.z < 0.f, v.w < 0.f));
+    __syncthreads();
+    flush_sign_words(sw_lds, words_row, (e >> 11) << 11, P.W * 64);
     // decoded message: +-(code * norm/s)
     const float unit = __fdiv_rn(norm, static_cast<float>(P.s));
     f32x4 q;
@@ -134,6 +135,7 @@ __global__ __launch_bounds__(kBlock) void k_qsgd_worker(const void *g, int64_t g
                                                         QParams P, uint8_t *levels, uint64_t *words, float *norms)
 {
     __shared__ double lds[kWaves];
+    __shared__ __attribute__((aligned(16))) uint32_t sw_lds[kWaves * 8];
     const int row = blockIdx.y;
     const int64_t e = static_cast<int64_t>(blockIdx.x) * kTile + threadIdx.x * 4;
     const void *grow = BF16 ? static_cast<const void *>(static_cast<const uint16_t *>(g) + row * gs)
@@ -143,7 +145,7 @@ __global__ __launch_bounds__(kBlock) void k_qsgd_worker(const void *g, int64_t g
     const bool dvec = aligned16(drow);
     const f32x4 v = ld4_grad<BF16>(grow, e, P.d, gvec) + ld4(drow, e, P.d, dvec);
     const f32x4 q = quantise4(v, e, static_cast<uint32_t>(row), P, levels + row * ((P.d + 1) / 2),
-                              words + row * P.W, norms + row * P.Bq, lds);
+                              words + row * P.W, norms + row * P.Bq, lds, sw_lds);
     if (e < P.d) st4(drow, e, P.d, dvec, v - q);
 }
 
@@ -155,6 +157,7 @@ __global__ __launch_bounds__(kBlock) void k_qsgd_server(const uint8_t *levels_in
                                                         float *norms_out)
 {
     __shared__ double lds[kWaves];
+    __shared__ __attribute__((aligned(16))) uint32_t sw_lds[kWaves * 8];
     __shared__ float units[kUnitGroup * (kTile / 64)];
     const int64_t tile_base = static_cast<int64_t>(blockIdx.x) * kTile;
     const int64_t e = tile_base + threadIdx.x * 4;
@@ -217,7 +220,7 @@ __global__ __launch_bounds__(kBlock) void k_qsgd_server(const uint8_t *levels_in
         }
     }
     a = zero_past(a, e, P.d);
-    const f32x4 q = quantise4(a, e, kServerStream, P, levels_out, words_out, norms_out, lds);
+    const f32x4 q = quantise4(a, e, kServerStream, P, levels_out, words_out, norms_out, lds, sw_lds);
     if (e < P.d) st4(delta_s, e, P.d, dvec, a - q);
 }
 

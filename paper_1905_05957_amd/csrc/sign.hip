@@ -89,24 +89,12 @@ __device__ __forceinline__ void fused_finish(f32x4 v, int64_t base, int64_t lim,
                                              uint64_t *__restrict__ words_row, int64_t bit_lim,
                                              float *__restrict__ scale_out, double *lds, uint32_t *sw_lds)
 {
-    // The workgroup's 64 sign words (256 bytes) are gathered in LDS and leave as ONE
-    // non-temporal 16 x 16-byte store after the barrier of the reduction: measured 1.66 ms for
-    // the worker pass against 1.69 ms with eight 32-byte stores and 1.77 ms with ordinary stores.
-    const uint32_t sword = wave_sign_word(v.x < 0.f, v.y < 0.f, v.z < 0.f, v.w < 0.f);
-    if (lane_id() < 8) sw_lds[wave_id() * 8 + lane_id()] = sword;
+    // sign words: gathered in LDS, one store per workgroup after the barrier of the reduction
+    stash_sign_words(sw_lds, wave_sign_word(v.x < 0.f, v.y < 0.f, v.z < 0.f, v.w < 0.f));
     const double total = block_sum(abs_sum4(v), lds, false);
     const float scale = static_cast<float>(total / static_cast<double>(lim - base));
     if (threadIdx.x == 0) *scale_out = scale;
-    if (threadIdx.x < 16 && base + 128 * threadIdx.x < bit_lim) {
-        u32x4 *dst = reinterpret_cast<u32x4 *>(reinterpret_cast<uint32_t *>(words_row) + (base >> 5)) + threadIdx.x;
-        const u32x4 w4 = reinterpret_cast<const u32x4 *>(sw_lds)[threadIdx.x];
-        if (base + 128 * (threadIdx.x + 1) <= bit_lim) {
-            __builtin_nontemporal_store(w4, dst);
-        } else {                                  // bit_lim is a multiple of 64: 2 of the 4 words
-            reinterpret_cast<uint32_t *>(dst)[0] = w4.x;
-            reinterpret_cast<uint32_t *>(dst)[1] = w4.y;
-        }
-    }
+    flush_sign_words(sw_lds, words_row, base, bit_lim);
     const int64_t e = base + threadIdx.x * 4;
     if (e < lim) st4(err_row, e, lim, err_vec, sign_error4(v, scale));
 }
@@ -226,16 +214,18 @@ __device__ __forceinline__ void pass1_finish(f32x4 v, int64_t base, int64_t d,
                                              float *__restrict__ vrow, bool vvec,
                                              uint64_t *__restrict__ words_row, int64_t bit_lim,
                                              const ds_sign_tables &tb, int32_t p0, int32_t p1,
-                                             double *__restrict__ partial_row, double *lds)
+                                             double *__restrict__ partial_row, double *lds, uint32_t *sw_lds)
 {
     const int64_t e = base + threadIdx.x * 4;
     if (e < d) st4(vrow, e, d, vvec, v);
-    const uint32_t sword = wave_sign_word(v.x < 0.f, v.y < 0.f, v.z < 0.f, v.w < 0.f);
-    store_sign_words(words_row, base + wave_id() * 256, bit_lim, sword);
+    stash_sign_words(sw_lds, wave_sign_word(v.x < 0.f, v.y < 0.f, v.z < 0.f, v.w < 0.f));
     if (p1 - p0 == 1) {
         const double total = block_sum(abs_sum4(v), lds, false);   // elements past d are zero
         if (threadIdx.x == 0) partial_row[p0] = total;
+        flush_sign_words(sw_lds, words_row, base, bit_lim);
     } else {
+        __syncthreads();
+        flush_sign_words(sw_lds, words_row, base, bit_lim);
         for (int32_t p = p0; p < p1; ++p) {
             const int64_t lo = tb.piece_start[p], hi = tb.piece_start[p + 1];
             const double part = ((masked_abs(v.x, e, lo, hi) + masked_abs(v.y, e + 1, lo, hi)) +
@@ -252,6 +242,7 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass1_worker(WorkerSrc<BF16> sr
                                                               ds_sign_tables tb, double *partials)
 {
     __shared__ double lds[kWaves];
+    __shared__ __attribute__((aligned(16))) uint32_t sw_lds[kWaves * 8];
     const int row = blockIdx.y;
     const int64_t tile = blockIdx.x;
     const int64_t base = tile * kTile;
@@ -262,7 +253,7 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass1_worker(WorkerSrc<BF16> sr
     const int64_t e = base + threadIdx.x * 4;
     const f32x4 v = ld4_grad<BF16>(grow, e, d, gvec) + ld4(drow, e, d, dvec);
     pass1_finish(v, base, d, drow, dvec, words + row * W, W * 64, tb, tb.tile_piece_first[tile],
-                 tb.tile_piece_first[tile + 1], partials + static_cast<int64_t>(row) * tb.n_pieces, lds);
+                 tb.tile_piece_first[tile + 1], partials + static_cast<int64_t>(row) * tb.n_pieces, lds, sw_lds);
 }
 
 __global__ __launch_bounds__(kBlock) void k_sign_pass1_server(ServerArgs a, float *delta_s, int64_t d,
@@ -270,6 +261,7 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass1_server(ServerArgs a, floa
                                                               double *partials)
 {
     __shared__ double lds[kWaves];
+    __shared__ __attribute__((aligned(16))) uint32_t sw_lds[kWaves * 8];
     const int64_t tile = blockIdx.x;
     const int64_t base = tile * kTile;
     const bool dvec = aligned16(delta_s);
@@ -309,7 +301,7 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass1_server(ServerArgs a, floa
         }
     }
     v = zero_past(v, e, d);
-    pass1_finish(v, base, d, delta_s, dvec, words_out, a.W * 64, tb, p0, p1, partials, lds);
+    pass1_finish(v, base, d, delta_s, dvec, words_out, a.W * 64, tb, p0, p1, partials, lds, sw_lds);
 }
 
 // scale[row][s] = (float)( sum of the group's partials / |group| ), fixed order.
