@@ -6,11 +6,13 @@
 // Selection is exact and deterministic: a radix select on the 31-bit magnitude pattern
 // key = bits(v) & 0x7FFFFFFF in 12 + 11 + 8 bits, arranged so that the dense vector is
 // looked at ONCE:
-//   sample     256 evenly spread 256-element subtiles of v are histogrammed (12 key bits);
-//              the bin holding the sample's r-th largest key, r about 1.25 k |sample| / d,
-//              is a lower bound lo_bin for the k-th key's bin with overwhelming probability.
+//   sample     1024 evenly spread 256-element subtiles of v are histogrammed (12 key bits);
+//              the sample's r-th largest key, r about 1.15 k |sample| / d, located inside its
+//              bin by linear interpolation, is a lower bound lo_key for the k-th key with
+//              high probability (error feedback piles values up just below the threshold,
+//              so a whole-bin bound would let in up to twice as many candidates).
 //   pass 1     (dense, the one HBM pass) v is formed and written into the error buffer;
-//              every element with key >= lo_bin << 19 becomes a candidate (index, value).
+//              every element with key >= lo_key becomes a candidate (index, value).
 //              Each wavefront compacts the candidates of its own 256-element subtile, in
 //              index order, into that subtile's fixed slot region: no shared counters, no
 //              LDS, no barriers.
@@ -45,13 +47,14 @@ constexpr int kH1 = 4096, kH2 = 2048, kH3 = 256;
 constexpr int kH1W = 256;
 constexpr int kOffSample = 0, kOffH1 = kH1, kOffH2 = 2 * kH1, kOffH3 = 2 * kH1 + kH2, kOffH1F = 2 * kH1 + kH2 + kH3;
 constexpr int kHistRow = 3 * kH1 + kH2 + kH3;
-constexpr int kSampleSubs = 256;           // subtiles sampled per row
+constexpr int kSampleSubs = 1024;          // subtiles sampled per row
 constexpr uint32_t kNone = 0xFFFFFFFFu;
 constexpr int kStages = 4;                 // arrival counters per row: sample, candidate histogram, fallback histogram, count
 enum { kStageSample = 0, kStageHist = 1, kStageFallback = 2, kStageCount = 3 };
 
 struct Sel {
-    uint32_t lo_bin;    // candidates are the elements whose top-12-bit bin is >= lo_bin
+    uint32_t lo_key;    // candidates are the elements with key >= lo_key
+    uint32_t lo_bin;    // lo_key >> 19
     uint32_t fallback;  // 1: too few candidates, the row takes the two-look route
     uint32_t b1, k1;    // top-12-bit bin of the k-th key; entries still needed from it
     uint32_t b2, k2;    // next 11 bits; entries still needed from that sub-bin
@@ -244,7 +247,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_sub_starts(const u32x2 *pairs_i
 // holds fewer than `need` keys).
 template <int NB>
 __device__ __forceinline__ void pick_bin(const uint32_t *__restrict__ hist, uint32_t need, uint32_t *part,
-                                         uint32_t *b_out, uint32_t *rem_out)
+                                         uint32_t *b_out, uint32_t *rem_out, uint32_t *cnt_out = nullptr)
 {
     constexpr int PER = (NB >= kBlock) ? NB / kBlock : 1;
     const int t = threadIdx.x;
@@ -273,6 +276,7 @@ __device__ __forceinline__ void pick_bin(const uint32_t *__restrict__ hist, uint
             if (running >= need && above < need) {
                 *b_out = static_cast<uint32_t>(t * PER + j);
                 *rem_out = need - above;
+                if (cnt_out) *cnt_out = local[j];
             }
         }
     }
@@ -284,16 +288,26 @@ __device__ __forceinline__ void pick_bin(const uint32_t *__restrict__ hist, uint
 template <int LEVEL>
 __device__ __forceinline__ void pick_level(const uint32_t *hrow, Sel *s, uint32_t need0, uint32_t *part, uint32_t *out)
 {
-    if (threadIdx.x == 0) { out[0] = kNone; out[1] = 0u; }
+    if (threadIdx.x == 0) { out[0] = kNone; out[1] = 0u; out[2] = 1u; }
     __syncthreads();
-    if (LEVEL == 0) pick_bin<kH1>(hrow + kOffSample, need0, part, &out[0], &out[1]);
+    if (LEVEL == 0) pick_bin<kH1>(hrow + kOffSample, need0, part, &out[0], &out[1], &out[2]);
     if (LEVEL == 1) pick_bin<kH1W>(hrow + kOffH1, need0, part, &out[0], &out[1]);
     if (LEVEL == 2) pick_bin<kH2>(hrow + kOffH2, s->k1, part, &out[0], &out[1]);
     if (LEVEL == 3) pick_bin<kH3>(hrow + kOffH3, s->k2, part, &out[0], &out[1]);
     if (LEVEL == 4) pick_bin<kH1>(hrow + kOffH1F, need0, part, &out[0], &out[1]);
     __syncthreads();
     if (threadIdx.x == 0) {
-        if (LEVEL == 0) s->lo_bin = (out[0] == kNone) ? 0u : out[0];
+        if (LEVEL == 0) {
+            // the sample's rank-`need0` key lies in bin out[0], out[1] entries from the bin's top,
+            // of out[2] in the bin: place the bound inside the bin by linear interpolation
+            uint32_t lo = 0u;
+            if (out[0] != kNone) {
+                const float skip = 1.0f - static_cast<float>(out[1]) / static_cast<float>(out[2]);
+                lo = (out[0] << 19) + static_cast<uint32_t>(skip * 524287.0f);
+            }
+            s->lo_key = lo;
+            s->lo_bin = lo >> 19;
+        }
         if (LEVEL == 1) {
             // no bin found: fewer than k candidates; last window bin: bins are lumped there
             const bool bad = out[0] == kNone || (out[0] == kH1W - 1 && s->lo_bin + kH1W - 1 < kH1 - 1);
@@ -321,7 +335,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_sample(Src src, int64_t d, int6
                                                         Sel *sel, uint32_t *done, uint32_t rank)
 {
     __shared__ uint32_t h[kH1];
-    __shared__ uint32_t part[kBlock], out[2], flag;
+    __shared__ uint32_t part[kBlock], out[3], flag;
     __shared__ float strips[kWaves][kSub];
     const int row = blockIdx.y;
     for (int i = threadIdx.x; i < kH1; i += kBlock) h[i] = 0u;
@@ -346,7 +360,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_sample(Src src, int64_t d, int6
 // ---------------------------------------------------------------------------------------
 // the dense pass
 // ---------------------------------------------------------------------------------------
-// FALLBACK = false: v from src, stored into buf, candidates with bin >= lo_bin.
+// FALLBACK = false: v from src, stored into buf, candidates with key >= lo_key.
 // FALLBACK = true : rows flagged for the two-look route only; v is read back from buf,
 //                   candidates with bin >= b1.
 template <class Src, bool FALLBACK>
@@ -357,7 +371,7 @@ __device__ __forceinline__ void pass1_tile(const Src &src, float *buf, int64_t s
     const int64_t e = tile * kTile + threadIdx.x * 4;
     f32x4 v = {0.f, 0.f, 0.f, 0.f};
     if ((e >> 8) < n_sub) v = src.load(row, e, d, strip);        // whole wavefronts
-    const uint32_t lo_key = (FALLBACK ? sel[row].b1 : sel[row].lo_bin) << 19;
+    const uint32_t lo_key = FALLBACK ? (sel[row].b1 << 19) : sel[row].lo_key;
     const uint32_t bits[4] = {__float_as_uint(v.x), __float_as_uint(v.y), __float_as_uint(v.z), __float_as_uint(v.w)};
     bool f[4];
 #pragma unroll
@@ -427,7 +441,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_fallback_hist(const float *buf,
                                                                uint32_t *done, uint32_t k)
 {
     __shared__ uint32_t h[kH1];
-    __shared__ uint32_t part[kBlock], out[2], flag;
+    __shared__ uint32_t part[kBlock], out[3], flag;
     const int row = blockIdx.y;
     if (!sel[row].fallback) return;
     for (int i = threadIdx.x; i < kH1; i += kBlock) h[i] = 0u;
@@ -528,7 +542,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_hist(const u32x2 *slots, c
     constexpr int NB = (LEVEL == 1) ? kH1W : (LEVEL == 2) ? kH2 : kH3;
     constexpr int OFF = (LEVEL == 1) ? kOffH1 : (LEVEL == 2) ? kOffH2 : kOffH3;
     __shared__ uint32_t h[NB];
-    __shared__ uint32_t part[kBlock], out[2], flag;
+    __shared__ uint32_t part[kBlock], out[3], flag;
     const int row = blockIdx.y;
     const Sel s = sel[row];
     for (int i = threadIdx.x; i < NB; i += kBlock) h[i] = 0u;
@@ -746,10 +760,11 @@ ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t 
     ds_topk_scratch *t = c->topk;
     const int64_t d = c->cfg.d, k = c->cfg.k, n_sub = t->n_sub, n_reg = t->n_reg, reg_pad = t->reg_pad, n_groups = t->n_groups;
     const int64_t ns = (n_sub < kSampleSubs) ? n_sub : kSampleSubs;
-    // sample rank: 1.25 x the expected number of top-k members in the sample, plus slack
-    // (k = 1 % of 25.6 M: 655 expected, rank 851, i.e. 7 standard deviations of the count)
+    // sample rank: 1.15 x the expected number of top-k members in the sample, plus slack
+    // (k = 1 % of 25.6 M: 2621 expected in 262144 samples, rank 3046, i.e. 8 standard
+    // deviations of the count; the slack also covers the interpolation inside the bin)
     const double sample_elems = static_cast<double>((ns * kSub < d) ? ns * kSub : d);
-    double r = 1.25 * static_cast<double>(k) * sample_elems / static_cast<double>(d) + 32.0;
+    double r = 1.15 * static_cast<double>(k) * sample_elems / static_cast<double>(d) + 32.0;
     if (r > 4.0e9) r = 4.0e9;
     const uint32_t rank = static_cast<uint32_t>(r);
     const unsigned grp_blocks = static_cast<unsigned>((n_groups + kWaves - 1) / kWaves);
