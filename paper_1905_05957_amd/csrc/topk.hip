@@ -6,11 +6,13 @@
 // Selection is exact and deterministic: a radix select on the 31-bit magnitude pattern
 // key = bits(v) & 0x7FFFFFFF in 12 + 11 + 8 bits, arranged so that the dense vector is
 // looked at ONCE:
-//   sample     1024 evenly spread 256-element subtiles of v are histogrammed (12 key bits);
-//              the sample's r-th largest key, r about 1.15 k |sample| / d, located inside its
-//              bin by linear interpolation, is a lower bound lo_key for the k-th key with
-//              high probability (error feedback piles values up just below the threshold,
-//              so a whole-bin bound would let in up to twice as many candidates).
+//   sample     512 evenly spread 256-element subtiles of v are histogrammed: 12 key bits,
+//              and 20 key bits inside a one-octave window around the threshold key of the
+//              previous call (kept per row in the context; the result never depends on it).
+//              The sample's r-th largest key, r about 1.15 k |sample| / d, is a lower bound
+//              lo_key for the k-th key with overwhelming probability.  The fine window
+//              matters: error feedback piles values up just below the threshold, and a
+//              12-bit bin edge would let in up to twice as many candidates.
 //   pass 1     (dense, the one HBM pass) v is formed and written into the error buffer;
 //              every element with key >= lo_key becomes a candidate (index, value).
 //              Each wavefront compacts the candidates of its own 256-element subtile, in
@@ -46,8 +48,10 @@ constexpr int kH1 = 4096, kH2 = 2048, kH3 = 256;
 // falls into that last bin the row takes the fallback route.
 constexpr int kH1W = 256;
 constexpr int kOffSample = 0, kOffH1 = kH1, kOffH2 = 2 * kH1, kOffH3 = 2 * kH1 + kH2, kOffH1F = 2 * kH1 + kH2 + kH3;
-constexpr int kHistRow = 3 * kH1 + kH2 + kH3;
-constexpr int kSampleSubs = 1024;          // subtiles sampled per row
+constexpr int kOffFine = 3 * kH1 + kH2 + kH3;   // sample, 16 bins x 256 sub-bins around the previous threshold
+constexpr int kFineBins = 16;                   // 12-bit bins covered by the fine window (one octave)
+constexpr int kHistRow = 4 * kH1 + kH2 + kH3;
+constexpr int kSampleSubs = 512;           // subtiles sampled per row
 constexpr uint32_t kNone = 0xFFFFFFFFu;
 constexpr int kStages = 4;                 // arrival counters per row: sample, candidate histogram, fallback histogram, count
 enum { kStageSample = 0, kStageHist = 1, kStageFallback = 2, kStageCount = 3 };
@@ -73,6 +77,7 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t m)
 
 struct ds_topk_scratch {
     uint32_t *hist;       // [2][rows][kHistRow]: the call in flight uses one half and zeroes the other
+    uint32_t *prev_T;     // [rows + 1] threshold key of the previous call per worker row, and of the server
     uint32_t *done;       // [rows][kStages] arrival counters of the "last workgroup finishes the row" steps
     Sel *sel;             // [rows]
     u32x2 *slots;         // [rows][n_reg * 2048] candidate (index, value bits), one region per 2048-element tile
@@ -286,25 +291,20 @@ __device__ __forceinline__ void pick_bin(const uint32_t *__restrict__ hist, uint
 // LEVEL 0: sample -> lo_bin.  1: candidates' 12-bit histogram -> b1, k1 or fallback.
 // 2: -> b2, k2.  3: -> T, k3.  4: dense 12-bit histogram of a fallback row -> b1, k1.
 template <int LEVEL>
-__device__ __forceinline__ void pick_level(const uint32_t *hrow, Sel *s, uint32_t need0, uint32_t *part, uint32_t *out)
+__device__ __forceinline__ void pick_level(const uint32_t *hrow, Sel *s, uint32_t need0, uint32_t *part, uint32_t *out,
+                                           uint32_t *prev_T = nullptr)
 {
-    if (threadIdx.x == 0) { out[0] = kNone; out[1] = 0u; out[2] = 1u; }
+    if (threadIdx.x == 0) { out[0] = kNone; out[1] = 0u; }
     __syncthreads();
-    if (LEVEL == 0) pick_bin<kH1>(hrow + kOffSample, need0, part, &out[0], &out[1], &out[2]);
+    if (LEVEL == 0) pick_bin<kH1>(hrow + kOffSample, need0, part, &out[0], &out[1]);
     if (LEVEL == 1) pick_bin<kH1W>(hrow + kOffH1, need0, part, &out[0], &out[1]);
     if (LEVEL == 2) pick_bin<kH2>(hrow + kOffH2, s->k1, part, &out[0], &out[1]);
     if (LEVEL == 3) pick_bin<kH3>(hrow + kOffH3, s->k2, part, &out[0], &out[1]);
     if (LEVEL == 4) pick_bin<kH1>(hrow + kOffH1F, need0, part, &out[0], &out[1]);
     __syncthreads();
     if (threadIdx.x == 0) {
-        if (LEVEL == 0) {
-            // the sample's rank-`need0` key lies in bin out[0], out[1] entries from the bin's top,
-            // of out[2] in the bin: place the bound inside the bin by linear interpolation
-            uint32_t lo = 0u;
-            if (out[0] != kNone) {
-                const float skip = 1.0f - static_cast<float>(out[1]) / static_cast<float>(out[2]);
-                lo = (out[0] << 19) + static_cast<uint32_t>(skip * 524287.0f);
-            }
+        if (LEVEL == 0) {       // out[0] = bin of the sample's rank-`need0` key (kNone: sample too small)
+            const uint32_t lo = (out[0] == kNone) ? 0u : (out[0] << 19);
             s->lo_key = lo;
             s->lo_bin = lo >> 19;
         }
@@ -315,7 +315,11 @@ __device__ __forceinline__ void pick_level(const uint32_t *hrow, Sel *s, uint32_
             if (!bad) { s->b1 = s->lo_bin + out[0]; s->k1 = out[1]; }
         }
         if (LEVEL == 2) { s->b2 = out[0]; s->k2 = out[1]; }
-        if (LEVEL == 3) { s->T = (s->b1 << 19) | (s->b2 << 8) | out[0]; s->k3 = out[1]; }
+        if (LEVEL == 3) {
+            s->T = (s->b1 << 19) | (s->b2 << 8) | out[0];
+            s->k3 = out[1];
+            *prev_T = s->T;        // centre of the next call's fine sampling window
+        }
         if (LEVEL == 4) { s->b1 = out[0]; s->k1 = out[1]; }
     }
 }
@@ -332,29 +336,51 @@ __device__ __forceinline__ int64_t sample_subtile(int64_t j, int64_t ns, int64_t
 // 12-bit histogram of v over the sampled subtiles.
 template <class Src>
 __global__ __launch_bounds__(kBlock) void k_topk_sample(Src src, int64_t d, int64_t n_sub, int64_t ns, uint32_t *hist,
-                                                        Sel *sel, uint32_t *done, uint32_t rank)
+                                                        Sel *sel, uint32_t *done, uint32_t rank, const uint32_t *prev_T)
 {
-    __shared__ uint32_t h[kH1];
-    __shared__ uint32_t part[kBlock], out[3], flag;
+    __shared__ uint32_t h[kH1];        // 12-bit bins
+    __shared__ uint32_t hf[kH1];       // fine window: kFineBins 12-bit bins x 256 sub-bins (key bits 18..11)
+    __shared__ uint32_t part[kBlock], out[2], flag;
     __shared__ float strips[kWaves][kSub];
     const int row = blockIdx.y;
-    for (int i = threadIdx.x; i < kH1; i += kBlock) h[i] = 0u;
+    for (int i = threadIdx.x; i < kH1; i += kBlock) { h[i] = 0u; hf[i] = 0u; }
     __syncthreads();
+    const uint32_t tb = prev_T[row] >> 19;
+    const uint32_t bw = (tb > kFineBins / 2) ? tb - kFineBins / 2 : 0u;   // first 12-bit bin of the window
     const int64_t j = static_cast<int64_t>(blockIdx.x) * kWaves + wave_id();
     if (j < ns) {
         const int64_t e = sample_subtile(j, ns, n_sub) * kSub + lane_id() * 4;
         const f32x4 v = src.load(row, e, d, strips[wave_id()]);
-        if (e + 0 < d) atomicAdd(&h[key_of(v.x) >> 19], 1u);
-        if (e + 1 < d) atomicAdd(&h[key_of(v.y) >> 19], 1u);
-        if (e + 2 < d) atomicAdd(&h[key_of(v.z) >> 19], 1u);
-        if (e + 3 < d) atomicAdd(&h[key_of(v.w) >> 19], 1u);
+        const uint32_t key[4] = {key_of(v.x), key_of(v.y), key_of(v.z), key_of(v.w)};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (e + c >= d) continue;
+            const uint32_t bin = key[c] >> 19;
+            atomicAdd(&h[bin], 1u);
+            if (bin - bw < static_cast<uint32_t>(kFineBins)) atomicAdd(&hf[((bin - bw) << 8) | ((key[c] >> 11) & 255u)], 1u);
+        }
     }
     __syncthreads();
     uint32_t *hrow = hist + static_cast<int64_t>(row) * kHistRow;
-    for (int i = threadIdx.x; i < kH1; i += kBlock)
+    for (int i = threadIdx.x; i < kH1; i += kBlock) {
         if (h[i]) atomicAdd(&hrow[kOffSample + i], h[i]);
-    if (last_workgroup(done + row * kStages + kStageSample, gridDim.x, &flag))
-        pick_level<0>(hrow, sel + row, rank, part, out);
+        if (hf[i]) atomicAdd(&hrow[kOffFine + i], hf[i]);
+    }
+    if (last_workgroup(done + row * kStages + kStageSample, gridDim.x, &flag)) {
+        Sel *s = sel + row;
+        pick_level<0>(hrow, s, rank, part, out);          // 12-bit bin of the rank-th sample key
+        __syncthreads();
+        const uint32_t b = out[0], rem = out[1];
+        __syncthreads();
+        if (b != kNone && b - bw < static_cast<uint32_t>(kFineBins)) {
+            // refine inside the bin: the sub-bin that holds the key `rem` places from the bin's top
+            if (threadIdx.x == 0) { out[0] = kNone; out[1] = 0u; }
+            __syncthreads();
+            pick_bin<256>(hrow + kOffFine + ((b - bw) << 8), rem, part, &out[0], &out[1]);
+            __syncthreads();
+            if (threadIdx.x == 0 && out[0] != kNone) s->lo_key = (b << 19) | (out[0] << 11);
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -537,7 +563,7 @@ __device__ __forceinline__ Batch group_fetch_batches(const GroupWalk &w, const u
 template <int LEVEL>
 __global__ __launch_bounds__(kBlock) void k_topk_cand_hist(const u32x2 *slots, const uint32_t *reg_cnt, int64_t n_reg,
                                                            int64_t reg_pad, int64_t n_groups, Sel *sel,
-                                                           uint32_t *hist, uint32_t *done, uint32_t k)
+                                                           uint32_t *hist, uint32_t *done, uint32_t k, uint32_t *prev_T)
 {
     constexpr int NB = (LEVEL == 1) ? kH1W : (LEVEL == 2) ? kH2 : kH3;
     constexpr int OFF = (LEVEL == 1) ? kOffH1 : (LEVEL == 2) ? kOffH2 : kOffH3;
@@ -572,7 +598,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_hist(const u32x2 *slots, c
     for (int i = threadIdx.x; i < NB; i += kBlock)
         if (h[i]) atomicAdd(&hrow[OFF + i], h[i]);
     if (last_workgroup(done + row * kStages + kStageHist, gridDim.x, &flag))
-        pick_level<LEVEL>(hrow, sel + row, k, part, out);
+        pick_level<LEVEL>(hrow, sel + row, k, part, out, prev_T + row);
 }
 
 // Exclusive scan over the workgroup of one value per thread; tmp holds kWaves values.
@@ -755,14 +781,15 @@ unsigned persistent_blocks(int64_t n_tiles, int rows)
 
 // sample -> dense pass -> refinement -> ordered emission, for `rows` vectors
 template <class Src>
-ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t stride, u32x2 *pairs, hipStream_t st)
+ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t stride, u32x2 *pairs, hipStream_t st,
+                       uint32_t *prev_T)
 {
     ds_topk_scratch *t = c->topk;
     const int64_t d = c->cfg.d, k = c->cfg.k, n_sub = t->n_sub, n_reg = t->n_reg, reg_pad = t->reg_pad, n_groups = t->n_groups;
     const int64_t ns = (n_sub < kSampleSubs) ? n_sub : kSampleSubs;
     // sample rank: 1.15 x the expected number of top-k members in the sample, plus slack
-    // (k = 1 % of 25.6 M: 2621 expected in 262144 samples, rank 3046, i.e. 8 standard
-    // deviations of the count; the slack also covers the interpolation inside the bin)
+    // (k = 1 % of 25.6 M: 1311 expected in 131072 samples, rank 1539, i.e. 6 standard
+    // deviations of the count)
     const double sample_elems = static_cast<double>((ns * kSub < d) ? ns * kSub : d);
     double r = 1.15 * static_cast<double>(k) * sample_elems / static_cast<double>(d) + 32.0;
     if (r > 4.0e9) r = 4.0e9;
@@ -777,9 +804,9 @@ ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t 
     const uint32_t k32 = static_cast<uint32_t>(k);
 
     k_topk_sample<Src><<<dim3(static_cast<unsigned>((ns + kWaves - 1) / kWaves), rows), kBlock, 0, st>>>(
-        src, d, n_sub, ns, hist, t->sel, t->done, rank);
+        src, d, n_sub, ns, hist, t->sel, t->done, rank, prev_T);
     k_topk_pass1<Src, false><<<dense, kBlock, 0, st>>>(src, buf, stride, d, n_sub, t->sel, t->slots, t->reg_cnt, n_reg, reg_pad);
-    k_topk_cand_hist<1><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32);
+    k_topk_cand_hist<1><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32, prev_T);
     // two-look route for rows whose sample misjudged; the three launches exit at once otherwise
     k_topk_restore<<<dim3(persistent_blocks(c->n_tiles, rows), rows), kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad,
                                                                                       t->sel, buf, stride);
@@ -788,8 +815,8 @@ ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t 
     k_topk_pass1<BufferV, true><<<dim3(persistent_blocks(c->n_tiles, rows), rows), kBlock, 0, st>>>(
         bsrc, buf, stride, d, n_sub, t->sel, t->slots, t->reg_cnt, n_reg, reg_pad);
     // refinement on the candidates
-    k_topk_cand_hist<2><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32);
-    k_topk_cand_hist<3><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32);
+    k_topk_cand_hist<2><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32, prev_T);
+    k_topk_cand_hist<3><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32, prev_T);
     k_topk_count<<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, t->grp_gt, t->grp_eq,
                                           t->grp_eqb, t->grp_out, t->done, hist_next,
                                           static_cast<int64_t>(t->rows) * kHistRow);
@@ -814,6 +841,8 @@ ds_status_t ds_topk_init(ds_ctx *c)
     t->reg_pad = t->n_groups * kGroupRegs;
     DS_HIP_TRY(hipMalloc(&t->hist, 2 * rows * kHistRow * sizeof(uint32_t)));
     DS_HIP_TRY(hipMemset(t->hist, 0, 2 * rows * kHistRow * sizeof(uint32_t)));
+    DS_HIP_TRY(hipMalloc(&t->prev_T, (rows + 1) * sizeof(uint32_t)));
+    DS_HIP_TRY(hipMemset(t->prev_T, 0, (rows + 1) * sizeof(uint32_t)));
     DS_HIP_TRY(hipMalloc(&t->done, rows * kStages * sizeof(uint32_t)));
     DS_HIP_TRY(hipMemset(t->done, 0, rows * kStages * sizeof(uint32_t)));
     t->parity = 0;
@@ -831,7 +860,7 @@ void ds_topk_fini(ds_ctx *c)
 {
     ds_topk_scratch *t = c->topk;
     if (!t) return;
-    void *ptrs[10] = {t->done, t->hist, t->sel, t->slots, t->reg_cnt, t->grp_gt, t->grp_eq, t->grp_eqb, t->grp_out, t->sub_start};
+    void *ptrs[11] = {t->prev_T, t->done, t->hist, t->sel, t->slots, t->reg_cnt, t->grp_gt, t->grp_eq, t->grp_eqb, t->grp_out, t->sub_start};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     delete t;
@@ -843,8 +872,8 @@ ds_status_t ds_topk_worker(ds_ctx *c, const void *g, int64_t gs, float *delta, i
 {
     const int rows = c->cfg.n;
     u32x2 *pairs = reinterpret_cast<u32x2 *>(out->pairs);
-    if (c->cfg.grad_dtype == DS_BF16) return run_select(c, rows, WorkerV<true>{g, gs, delta, dstr}, delta, dstr, pairs, st);
-    return run_select(c, rows, WorkerV<false>{g, gs, delta, dstr}, delta, dstr, pairs, st);
+    if (c->cfg.grad_dtype == DS_BF16) return run_select(c, rows, WorkerV<true>{g, gs, delta, dstr}, delta, dstr, pairs, st, c->topk->prev_T);
+    return run_select(c, rows, WorkerV<false>{g, gs, delta, dstr}, delta, dstr, pairs, st, c->topk->prev_T);
 }
 
 ds_status_t ds_topk_server(ds_ctx *c, const ds_payload_t *in, float *delta_s, const ds_payload_t *out, hipStream_t st)
@@ -855,7 +884,7 @@ ds_status_t ds_topk_server(ds_ctx *c, const ds_payload_t *in, float *delta_s, co
     k_topk_sub_starts<<<dim3(static_cast<unsigned>((t->n_sub + 1 + kBlock - 1) / kBlock), c->cfg.n), kBlock, 0, st>>>(
         pairs_in, k, t->n_sub, t->sub_start);
     const ServerV src{pairs_in, t->sub_start, delta_s, k, t->n_sub, c->cfg.n, c->inv_n};
-    return run_select(c, 1, src, delta_s, c->cfg.d, reinterpret_cast<u32x2 *>(out->pairs), st);
+    return run_select(c, 1, src, delta_s, c->cfg.d, reinterpret_cast<u32x2 *>(out->pairs), st, t->prev_T + t->rows);
 }
 
 ds_status_t ds_topk_update(ds_ctx *c, const ds_payload_t *srv, float *x, float *m, float gamma, float beta, hipStream_t st)
