@@ -206,13 +206,16 @@ __device__ __forceinline__ uint32_t dev_load(const uint32_t *p)
 }
 
 // True in exactly one workgroup of those that call it with the same counter: the last of
-// `expected` to arrive.  Every wavefront first waits until its own outstanding atomics have
-// been performed (workgroup-scope release = wait for the memory counters), the barrier
-// collects the wavefronts, then one device-scope increment announces the workgroup.  The
-// counter is left at zero for its next use.  All threads of the workgroup must call.
+// `expected` to arrive.  Every wavefront first waits until the memory system has acknowledged
+// its own outstanding atomics and stores (an explicit wait on the vector memory counter: a
+// workgroup-scope release fence emits no such wait on this target, and without it the
+// announcement can overtake another wavefront's histogram atomics, which go to other
+// channels), the barrier collects the wavefronts, then one device-scope increment announces
+// the workgroup.  The counter is left at zero for its next use.  All threads of the
+// workgroup must call.
 __device__ __forceinline__ bool last_workgroup(uint32_t *counter, uint32_t expected, uint32_t *flag_sh)
 {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (threadIdx.x == 0) {
         const uint32_t prev = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -264,15 +267,19 @@ __device__ __forceinline__ void pick_bin(const uint32_t *__restrict__ hist, uint
         local[j] = active ? dev_load(&hist[t * PER + j]) : 0u;
         sum += local[j];
     }
-    part[t] = sum;
-    __syncthreads();
-    for (int off = 1; off < kBlock; off <<= 1) {   // inclusive suffix sums of part[]
-        const uint32_t add = (t + off < kBlock) ? part[t + off] : 0u;
-        __syncthreads();
-        part[t] += add;
-        __syncthreads();
+    // suffix sums over the threads: shuffles inside a wavefront, wavefront totals through LDS
+    const int lane = lane_id();
+    uint32_t incl = sum;                                        // sum over lanes >= mine of my wavefront
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t dn = __shfl_down(incl, o, 64);
+        if (lane + o < 64) incl += dn;
     }
-    uint32_t running = (t + 1 < kBlock) ? part[t + 1] : 0u;   // keys in bins above my chunk
+    __syncthreads();                                            // part[] may still be read by an earlier pick
+    if (lane == 0) part[wave_id()] = incl;
+    __syncthreads();
+    uint32_t running = incl - sum;                              // keys in bins above my chunk
+    for (int w = wave_id() + 1; w < kWaves; ++w) running += part[w];
     if (active) {
 #pragma unroll
         for (int j = PER - 1; j >= 0; --j) {
@@ -312,6 +319,7 @@ __device__ __forceinline__ void pick_level(const uint32_t *hrow, Sel *s, uint32_
             // no bin found: fewer than k candidates; last window bin: bins are lumped there
             const bool bad = out[0] == kNone || (out[0] == kH1W - 1 && s->lo_bin + kH1W - 1 < kH1 - 1);
             s->fallback = bad ? 1u : 0u;
+            out[2] = bad ? 1u : 0u;     // for the caller: a plain re-read of *s could hit a stale scalar cache line
             if (!bad) { s->b1 = s->lo_bin + out[0]; s->k1 = out[1]; }
         }
         if (LEVEL == 2) { s->b2 = out[0]; s->k2 = out[1]; }
@@ -446,21 +454,6 @@ __global__ __launch_bounds__(kBlock) void k_topk_pass1(Src src, float *buf, int6
                                   FALLBACK ? nullptr : strips[wave_id()], wtot);
 }
 
-// Fallback rows: put v back at every candidate position (the dense pass wrote 0 there), so
-// that the two-look route sees the whole of v in the buffer.
-__global__ __launch_bounds__(kBlock) void k_topk_restore(const u32x2 *slots, const uint32_t *reg_cnt, int64_t n_reg,
-                                                         int64_t reg_pad, const Sel *sel, float *buf, int64_t stride)
-{
-    const int row = blockIdx.y;
-    if (!sel[row].fallback) return;
-    float *brow = buf + row * stride;
-    for (int64_t reg = blockIdx.x; reg < n_reg; reg += gridDim.x) {
-        const uint32_t cnt = reg_cnt[row * reg_pad + reg];
-        const u32x2 *src = slots + (static_cast<int64_t>(row) * n_reg + reg) * kReg;
-        for (uint32_t i = threadIdx.x; i < cnt; i += kBlock) brow[src[i].x] = __uint_as_float(src[i].y);
-    }
-}
-
 // Fallback rows: dense 12-bit histogram of the stored v.  Persistent workgroups.
 __global__ __launch_bounds__(kBlock) void k_topk_fallback_hist(const float *buf, int64_t stride, int64_t d,
                                                                int64_t n_tiles, Sel *sel, uint32_t *hist,
@@ -558,12 +551,27 @@ __device__ __forceinline__ Batch group_fetch_batches(const GroupWalk &w, const u
     return b;
 }
 
+// Fallback rows: put v back at every candidate position (the dense pass wrote 0 there), so
+// that the two-look route sees the whole of v in the buffer.  Run by one workgroup (the one
+// that detects the fallback); slow, but the route is rare.
+__device__ __forceinline__ void restore_row(const u32x2 *slots, const uint32_t *reg_cnt, int64_t n_reg, int64_t reg_pad,
+                                            int row, float *buf, int64_t stride)
+{
+    float *brow = buf + row * stride;
+    for (int64_t reg = 0; reg < n_reg; ++reg) {
+        const uint32_t cnt = reg_cnt[row * reg_pad + reg];
+        const u32x2 *src = slots + (static_cast<int64_t>(row) * n_reg + reg) * kReg;
+        for (uint32_t i = threadIdx.x; i < cnt; i += kBlock) brow[src[i].x] = __uint_as_float(src[i].y);
+    }
+}
+
 // LEVEL 1: 12-bit histogram of all candidates.  2: next 11 bits of those in bin b1.
 // 3: low 8 bits of those with prefix (b1, b2).  One group per wavefront.
 template <int LEVEL>
 __global__ __launch_bounds__(kBlock) void k_topk_cand_hist(const u32x2 *slots, const uint32_t *reg_cnt, int64_t n_reg,
                                                            int64_t reg_pad, int64_t n_groups, Sel *sel,
-                                                           uint32_t *hist, uint32_t *done, uint32_t k, uint32_t *prev_T)
+                                                           uint32_t *hist, uint32_t *done, uint32_t k, uint32_t *prev_T,
+                                                           float *buf, int64_t stride)
 {
     constexpr int NB = (LEVEL == 1) ? kH1W : (LEVEL == 2) ? kH2 : kH3;
     constexpr int OFF = (LEVEL == 1) ? kOffH1 : (LEVEL == 2) ? kOffH2 : kOffH3;
@@ -597,8 +605,13 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_hist(const u32x2 *slots, c
     uint32_t *hrow = hist + static_cast<int64_t>(row) * kHistRow;
     for (int i = threadIdx.x; i < NB; i += kBlock)
         if (h[i]) atomicAdd(&hrow[OFF + i], h[i]);
-    if (last_workgroup(done + row * kStages + kStageHist, gridDim.x, &flag))
+    if (last_workgroup(done + row * kStages + kStageHist, gridDim.x, &flag)) {
         pick_level<LEVEL>(hrow, sel + row, k, part, out, prev_T + row);
+        if (LEVEL == 1) {
+            __syncthreads();
+            if (out[2]) restore_row(slots, reg_cnt, n_reg, reg_pad, row, buf, stride);
+        }
+    }
 }
 
 // Exclusive scan over the workgroup of one value per thread; tmp holds kWaves values.
@@ -806,17 +819,15 @@ ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t 
     k_topk_sample<Src><<<dim3(static_cast<unsigned>((ns + kWaves - 1) / kWaves), rows), kBlock, 0, st>>>(
         src, d, n_sub, ns, hist, t->sel, t->done, rank, prev_T);
     k_topk_pass1<Src, false><<<dense, kBlock, 0, st>>>(src, buf, stride, d, n_sub, t->sel, t->slots, t->reg_cnt, n_reg, reg_pad);
-    k_topk_cand_hist<1><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32, prev_T);
-    // two-look route for rows whose sample misjudged; the three launches exit at once otherwise
-    k_topk_restore<<<dim3(persistent_blocks(c->n_tiles, rows), rows), kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad,
-                                                                                      t->sel, buf, stride);
+    k_topk_cand_hist<1><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32, prev_T, buf, stride);
+    // two-look route for rows whose sample misjudged; both launches exit at once otherwise
     k_topk_fallback_hist<<<dim3(persistent_blocks(c->n_tiles, rows), rows), kBlock, 0, st>>>(buf, stride, d, c->n_tiles,
                                                                                             t->sel, hist, t->done, k32);
     k_topk_pass1<BufferV, true><<<dim3(persistent_blocks(c->n_tiles, rows), rows), kBlock, 0, st>>>(
         bsrc, buf, stride, d, n_sub, t->sel, t->slots, t->reg_cnt, n_reg, reg_pad);
     // refinement on the candidates
-    k_topk_cand_hist<2><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32, prev_T);
-    k_topk_cand_hist<3><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32, prev_T);
+    k_topk_cand_hist<2><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32, prev_T, buf, stride);
+    k_topk_cand_hist<3><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32, prev_T, buf, stride);
     k_topk_count<<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, t->grp_gt, t->grp_eq,
                                           t->grp_eqb, t->grp_out, t->done, hist_next,
                                           static_cast<int64_t>(t->rows) * kHistRow);
