@@ -74,6 +74,17 @@ typedef enum {
     DS_SCALE_CHUNK = 2      /* fixed-size chunks, last one short */
 } ds_scale_mode_t;
 
+/* ds_config_t::flags.
+ * DS_FLAG_TOPK_MULTI_LAUNCH: TOPK refines its threshold in a chain of small launches instead
+ * of one launch whose workgroups wait for each other.  The results are the same.  The
+ * single launch needs its whole grid resident on the device at once: contexts that may run
+ * TOPK calls concurrently on different streams of one device should set this flag (a single
+ * launch that finds the device shared gives up after a bounded wait, and its context then
+ * returns DS_ERR_DEVICE from every later call).  The environment variable
+ * DS_TOPK_RESIDENT_LIMIT=<workgroups>, read by ds_create, caps the size of the single launch
+ * (default: what the device holds at once; fewer workgroups than rows selects the chain). */
+typedef enum { DS_FLAG_TOPK_MULTI_LAUNCH = 1 } ds_flags_t;
+
 typedef struct {
     int32_t comp;             /* ds_compressor_t */
     int32_t n;                /* workers, >= 1 */
@@ -88,7 +99,7 @@ typedef struct {
     int64_t k;                /* TOPK: entries kept per vector, 1 .. d */
     int32_t bucket;           /* QSGD: elements per bucket, a multiple of 64 (built: the powers of
                                  two 64 .. 2048; other multiples give DS_ERR_UNSUPPORTED) */
-    int32_t reserved;
+    int32_t flags;            /* ds_flags_t bits, 0 for the defaults */
     uint64_t seed;            /* QSGD: Philox key */
 } ds_config_t;
 

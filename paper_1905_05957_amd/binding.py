@@ -16,6 +16,7 @@ import torch
 COMP_IDENTITY, COMP_SIGN, COMP_TOPK, COMP_QSGD = 0, 1, 2, 3
 SCALE_WHOLE, SCALE_SEGMENTS, SCALE_CHUNK = 0, 1, 2
 F32, BF16 = 0, 1
+FLAG_TOPK_MULTI_LAUNCH = 1
 
 _COMP = {"identity": COMP_IDENTITY, "sign": COMP_SIGN, "topk": COMP_TOPK, "qsgd": COMP_QSGD}
 _MODE = {"whole": SCALE_WHOLE, "segments": SCALE_SEGMENTS, "chunk": SCALE_CHUNK}
@@ -34,7 +35,7 @@ class ds_config_t(C.Structure):
     _fields_ = [("comp", C.c_int32), ("n", C.c_int32), ("d", C.c_int64), ("grad_dtype", C.c_int32),
                 ("scale_mode", C.c_int32), ("chunk", C.c_int64),
                 ("seg_offsets", C.POINTER(C.c_int64)), ("n_seg", C.c_int32), ("levels", C.c_int32),
-                ("k", C.c_int64), ("bucket", C.c_int32), ("reserved", C.c_int32),
+                ("k", C.c_int64), ("bucket", C.c_int32), ("flags", C.c_int32),
                 ("seed", C.c_uint64)]
 
 
@@ -168,7 +169,7 @@ class Context:
 
     def __init__(self, comp, n: int, d: int, grad_dtype: str = "f32", scale_mode="whole",
                  chunk: int = 0, seg_offsets=None, k: int = 0, bucket: int = 512, levels: int = 15,
-                 seed: int = 0):
+                 seed: int = 0, flags: int = 0):
         L = load_library()
         self.comp = _COMP[comp] if isinstance(comp, str) else int(comp)
         self.n, self.d, self.k = int(n), int(d), int(k)
@@ -183,6 +184,7 @@ class Context:
             cfg.seg_offsets = self._seg.ctypes.data_as(C.POINTER(C.c_int64))
             cfg.n_seg = len(self._seg) - 1
         cfg.k, cfg.bucket, cfg.levels, cfg.seed = self.k, int(bucket), int(levels), int(seed)
+        cfg.flags = int(flags)
         self._h = C.c_void_p()
         _check(L.ds_create(C.byref(cfg), C.byref(self._h)), "ds_create")
         sizes = self.payload_sizes(1)

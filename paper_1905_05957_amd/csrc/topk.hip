@@ -32,6 +32,7 @@
 #include "ds_device.h"
 #include "ds_internal.h"
 
+#include <cstdlib>
 #include <new>
 
 using namespace ds;
@@ -90,7 +91,12 @@ struct ds_topk_scratch {
     int64_t n_sub;        // 256-element subtiles per row (sampling, server ranges)
     int64_t n_reg, reg_pad, n_groups;
     int rows;
-    int parity;           // which half of hist the next call uses
+    int parity;           // which half of hist / fhist the next call uses
+    // fused refinement route (k_topk_finish)
+    uint32_t *fhist;      // [2][rows][kFRow]
+    char *sync;           // [rows][kSyncStride] arrival counters and published picks
+    uint32_t *abort_host; // pinned host word, raised by a kernel that gave up waiting
+    int64_t capacity;     // workgroups of k_topk_finish the device holds at once; 0: route off
 };
 
 namespace {
@@ -100,6 +106,8 @@ namespace {
 // ---------------------------------------------------------------------------------------
 template <bool BF16>
 struct WorkerV {   // v = g + delta
+    static constexpr int kLdsWords = 1;
+    __device__ __forceinline__ void prepare(float *) const {}
     const void *g;
     int64_t gs;
     const float *delta;
@@ -114,6 +122,8 @@ struct WorkerV {   // v = g + delta
 };
 
 struct BufferV {   // v already stored
+    static constexpr int kLdsWords = 1;
+    __device__ __forceinline__ void prepare(float *) const {}
     const float *buf;
     int64_t stride;
     __device__ __forceinline__ f32x4 load(int row, int64_t e, int64_t d, float *) const
@@ -127,25 +137,36 @@ struct BufferV {   // v already stored
 // acc = fma(val, 1/n, acc) over workers in ascending order.  The wavefront keeps its subtile
 // in a private LDS strip.  Lane i fetches worker i's entry range for the subtile (one load
 // instruction for all workers), the entries of all workers are then fetched flattened in
-// worker order (one more load instruction per 64 entries), and applied to the strip worker
-// by worker: a message lists an index once, so the lanes of one worker never collide, and
-// the wavefront's LDS operations retire in program order, which keeps the workers' order.
+// worker order (one more load instruction per 64 entries) and applied to the strip in
+// rounds: in each round, of the pending entries that hit one element the one in the lowest
+// lane (= the lowest worker: a message lists an index once) claims it through an LDS minimum
+// and is applied.  Most elements are hit once, so a batch takes one or two rounds whatever
+// the number of workers.
 struct ServerV {
+    static constexpr int kLdsWords = 2 * kSub;   // per wavefront: the strip, then one claim tag per element
     const u32x2 *pairs_in;      // [n][k]
     const uint32_t *sub_start;  // [n_sub + 1][n]
     const float *delta_s;
     int64_t k, n_sub;
     int32_t n;
     float inv_n;
+    // once per wavefront, before the first load
+    __device__ __forceinline__ void prepare(float *strip) const
+    {
+        uint32_t *tag = reinterpret_cast<uint32_t *>(strip + kSub);
+        for (int i = lane_id(); i < kSub; i += 64) tag[i] = kNone;
+    }
     __device__ __forceinline__ f32x4 load(int, int64_t e, int64_t d, float *strip) const
     {
         const int lane = lane_id();
+        uint32_t *tag = reinterpret_cast<uint32_t *>(strip + kSub);
         const f32x4 a = ld4(delta_s, e, d, aligned16(delta_s));
         strip[lane * 4 + 0] = a.x; strip[lane * 4 + 1] = a.y; strip[lane * 4 + 2] = a.z; strip[lane * 4 + 3] = a.w;
         const int64_t sub = e >> 8;
         const uint32_t base = static_cast<uint32_t>(sub << 8);
         for (int w0 = 0; w0 < n; w0 += 64) {
             const int nw = (n - w0 < 64) ? n - w0 : 64;
+            const int nsteps = (nw <= 1) ? 0 : 32 - __builtin_clz(static_cast<uint32_t>(nw - 1));   // ceil(log2 nw)
             uint32_t s0 = 0u, c = 0u;
             if (lane < nw) {
                 s0 = sub_start[sub * n + w0 + lane];
@@ -154,18 +175,16 @@ struct ServerV {
                 c = (s1 > s0) ? s1 - s0 : 0u;
             }
             uint32_t P = c;                                   // inclusive prefix over workers
-#pragma unroll
-            for (int o = 1; o < 64; o <<= 1) {
+            for (int o = 1; o < nw; o <<= 1) {
                 const uint32_t up = __shfl_up(P, o, 64);
                 if (lane >= o) P += up;
             }
-            const uint32_t total = __shfl(P, 63, 64);
+            const uint32_t total = __shfl(P, nw - 1, 64);
             for (uint32_t i0 = 0; i0 < total; i0 += 64) {
                 const uint32_t i = i0 + lane;
                 const bool valid = i < total;
-                int lo = 0, hi = 63;                          // first worker w with P_w > i
-#pragma unroll
-                for (int step = 0; step < 6; ++step) {
+                int lo = 0, hi = nw - 1;                      // first worker w with P_w > i
+                for (int step = 0; step < nsteps; ++step) {
                     const int mid = (lo + hi) >> 1;
                     if (__shfl(P, mid, 64) > (valid ? i : 0u)) hi = mid; else lo = mid + 1;
                 }
@@ -173,13 +192,17 @@ struct ServerV {
                 u32x2 pr = {0u, 0u};
                 if (valid) pr = pairs_in[static_cast<int64_t>(w0 + lo) * k + sw + (i - (pw - cw))];
                 const uint32_t rel = pr.x - base;
-                const int wfirst = __builtin_amdgcn_readfirstlane(lo);
-                const int wlast = __builtin_amdgcn_readlane(lo, 63 - __builtin_clzll(__ballot(valid)));
-                for (int wi = wfirst; wi <= wlast; ++wi) {    // uniform bounds: workers in this batch
-                    __builtin_amdgcn_wave_barrier();
-                    if (valid && lo == wi && rel < static_cast<uint32_t>(kSub))
+                bool pending = valid && rel < static_cast<uint32_t>(kSub);
+                while (__ballot(pending)) {
+                    if (pending) atomicMin(&tag[rel], static_cast<uint32_t>(lane));
+                    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+                    const bool win = pending && tag[rel] == static_cast<uint32_t>(lane);
+                    if (win) {
                         strip[rel] = __fmaf_rn(__uint_as_float(pr.y), inv_n, strip[rel]);
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        tag[rel] = kNone;
+                    }
+                    pending = pending && !win;
+                    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
                 }
             }
         }
@@ -248,6 +271,24 @@ __global__ __launch_bounds__(kBlock) void k_topk_sub_starts(const u32x2 *pairs_i
     const int64_t s = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
     if (s > n_sub) return;
     sub_start[s * gridDim.y + i] = static_cast<uint32_t>(lower_bound_idx(pairs_in + i * k, k, s * kSub));
+}
+
+// The same table from the entries' side: entry j of a sorted message is the first one of
+// every subtile s with sub(j-1) < s <= sub(j) (sub = index >> 8; j = k stands for the end).
+// One coalesced pass over the message instead of a search per subtile; the host picks it
+// when the message has an entry in most subtiles, so that the loop below stays short.
+// Indices are clamped, so a malformed message cannot make it write outside the table.
+__global__ __launch_bounds__(kBlock) void k_topk_sub_starts_scan(const u32x2 *pairs_in, int64_t k, int64_t n_sub,
+                                                                 uint32_t *sub_start)
+{
+    const int i = blockIdx.y, n = gridDim.y;
+    const int64_t j = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (j > k) return;
+    const u32x2 *p = pairs_in + i * k;
+    int64_t prev = -1, cur = n_sub;
+    if (j > 0) { prev = p[j - 1].x >> 8; if (prev > n_sub) prev = n_sub; }
+    if (j < k) { cur = p[j].x >> 8; if (cur > n_sub) cur = n_sub; }
+    for (int64_t s = prev + 1; s <= cur; ++s) sub_start[s * n + i] = static_cast<uint32_t>(j);
 }
 
 // Largest bin b of hist[0..NB) with  sum_{bins >= b} >= need ;  rem = need - sum_{bins > b}.
@@ -349,8 +390,9 @@ __global__ __launch_bounds__(kBlock) void k_topk_sample(Src src, int64_t d, int6
     __shared__ uint32_t h[kH1];        // 12-bit bins
     __shared__ uint32_t hf[kH1];       // fine window: kFineBins 12-bit bins x 256 sub-bins (key bits 18..11)
     __shared__ uint32_t part[kBlock], out[2], flag;
-    __shared__ float strips[kWaves][kSub];
+    __shared__ float strips[kWaves][Src::kLdsWords];
     const int row = blockIdx.y;
+    src.prepare(strips[wave_id()]);
     for (int i = threadIdx.x; i < kH1; i += kBlock) { h[i] = 0u; hf[i] = 0u; }
     __syncthreads();
     const uint32_t tb = prev_T[row] >> 19;
@@ -399,13 +441,12 @@ __global__ __launch_bounds__(kBlock) void k_topk_sample(Src src, int64_t d, int6
 //                   candidates with bin >= b1.
 template <class Src, bool FALLBACK>
 __device__ __forceinline__ void pass1_tile(const Src &src, float *buf, int64_t stride, int64_t d, int64_t n_sub,
-                                           const Sel *sel, u32x2 *slots, uint32_t *reg_cnt, int64_t n_reg,
+                                           uint32_t lo_key, u32x2 *slots, uint32_t *reg_cnt, int64_t n_reg,
                                            int64_t reg_pad, int row, int64_t tile, float *strip, uint32_t *wtot)
 {
     const int64_t e = tile * kTile + threadIdx.x * 4;
     f32x4 v = {0.f, 0.f, 0.f, 0.f};
     if ((e >> 8) < n_sub) v = src.load(row, e, d, strip);        // whole wavefronts
-    const uint32_t lo_key = FALLBACK ? (sel[row].b1 << 19) : sel[row].lo_key;
     const uint32_t bits[4] = {__float_as_uint(v.x), __float_as_uint(v.y), __float_as_uint(v.z), __float_as_uint(v.w)};
     bool f[4];
 #pragma unroll
@@ -443,15 +484,17 @@ __global__ __launch_bounds__(kBlock) void k_topk_pass1(Src src, float *buf, int6
                                                        const Sel *sel, u32x2 *slots, uint32_t *reg_cnt, int64_t n_reg,
                                                        int64_t reg_pad)
 {
-    __shared__ float strips[FALLBACK ? 1 : kWaves][FALLBACK ? 1 : kSub];
+    __shared__ float strips[kWaves][Src::kLdsWords];
     __shared__ uint32_t wtot[kWaves];
     const int row = blockIdx.y;
     if (FALLBACK && !sel[row].fallback) return;
+    src.prepare(strips[wave_id()]);
     // the regular launch has one workgroup per tile; the fallback launch is a small grid
     // that exits at once for rows that do not need it and strides over the tiles otherwise
+    const uint32_t lo_key = FALLBACK ? (sel[row].b1 << 19) : sel[row].lo_key;
     for (int64_t tile = blockIdx.x; tile < n_reg; tile += gridDim.x)
-        pass1_tile<Src, FALLBACK>(src, buf, stride, d, n_sub, sel, slots, reg_cnt, n_reg, reg_pad, row, tile,
-                                  FALLBACK ? nullptr : strips[wave_id()], wtot);
+        pass1_tile<Src, FALLBACK>(src, buf, stride, d, n_sub, lo_key, slots, reg_cnt, n_reg, reg_pad, row, tile,
+                                  strips[wave_id()], wtot);
 }
 
 // Fallback rows: dense 12-bit histogram of the stored v.  Persistent workgroups.
@@ -530,7 +573,7 @@ __device__ __forceinline__ u32x2 group_fetch(const GroupWalk &w, const u32x2 *__
 // The candidate passes fetch up to kPrefetch batches of 64 candidates before using any of
 // them, so that a wavefront has several independent loads in flight instead of a chain of
 // dependent ones (a group of 8 regions holds about 250-320 candidates at k = 1 %).
-constexpr int kPrefetch = 10;
+constexpr int kPrefetch = 8;
 
 struct Batch {
     u32x2 pr[kPrefetch];
@@ -703,24 +746,13 @@ __global__ __launch_bounds__(kBlock) void k_topk_count(const u32x2 *slots, const
         scan_row(row, sel, n_groups, grp_gt, grp_eq, grp_eqb, grp_out, tmp);
 }
 
-// Per group: write the kept entries in index order; the dense pass left 0 at every
+// One group: write the kept entries in index order; the dense pass left 0 at every
 // candidate position of the error buffer, so the candidates that are not kept get v back
-// (delta = v - Q[v] is 0 at kept positions and v elsewhere).
-__global__ __launch_bounds__(kBlock) void k_topk_emit(const u32x2 *slots, const uint32_t *reg_cnt, int64_t n_reg,
-                                                      int64_t reg_pad, int64_t n_groups, const Sel *sel,
-                                                      const uint32_t *grp_eqb, const uint32_t *grp_out, int64_t k,
-                                                      u32x2 *pairs, float *buf, int64_t stride)
+// (delta = v - Q[v] is 0 at kept positions and v elsewhere).  eq_seen = ties at T in earlier
+// groups, out = first output slot of the group.  Called by whole wavefronts.
+__device__ __forceinline__ void emit_group(const GroupWalk &w, const u32x2 *__restrict__ srow, int64_t g, uint32_t T,
+                                           uint32_t k3, uint32_t eq_seen, uint32_t out, u32x2 *prow, float *brow, int64_t k)
 {
-    const int row = blockIdx.y;
-    const int64_t g = static_cast<int64_t>(blockIdx.x) * kWaves + wave_id();
-    if (g >= n_groups) return;
-    const Sel s = sel[row];
-    const GroupWalk w = group_begin(reg_cnt + row * reg_pad, g, n_reg);
-    const u32x2 *srow = slots + static_cast<int64_t>(row) * n_reg * kReg;
-    uint32_t eq_seen = grp_eqb[row * n_groups + g];
-    uint32_t out = grp_out[row * n_groups + g];
-    u32x2 *prow = pairs + static_cast<int64_t>(row) * k;
-    float *brow = buf + row * stride;
     for (uint32_t i0 = 0; i0 < w.total; i0 += 64 * kPrefetch) {
         const Batch bt = group_fetch_batches(w, srow, g, i0);
 #pragma unroll
@@ -729,9 +761,9 @@ __global__ __launch_bounds__(kBlock) void k_topk_emit(const u32x2 *slots, const 
             const bool valid = i0 + j * 64 + lane_id() < w.total;
             const u32x2 pr = bt.pr[j];
             const uint32_t key = pr.y & 0x7FFFFFFFu;
-            const bool is_eq = valid && key == s.T;
+            const bool is_eq = valid && key == T;
             const uint64_t eq_mask = __ballot(is_eq);
-            const bool keep = valid && (key > s.T || (is_eq && eq_seen + lanes_below(eq_mask) < s.k3));
+            const bool keep = valid && (key > T || (is_eq && eq_seen + lanes_below(eq_mask) < k3));
             const uint64_t keep_mask = __ballot(keep);
             if (keep) {
                 const uint32_t slot = out + lanes_below(keep_mask);
@@ -742,6 +774,328 @@ __global__ __launch_bounds__(kBlock) void k_topk_emit(const u32x2 *slots, const 
             out += __popcll(keep_mask);
             eq_seen += __popcll(eq_mask);
         }
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_topk_emit(const u32x2 *slots, const uint32_t *reg_cnt, int64_t n_reg,
+                                                      int64_t reg_pad, int64_t n_groups, const Sel *sel,
+                                                      const uint32_t *grp_eqb, const uint32_t *grp_out, int64_t k,
+                                                      u32x2 *pairs, float *buf, int64_t stride)
+{
+    const int row = blockIdx.y;
+    const int64_t g = static_cast<int64_t>(blockIdx.x) * kWaves + wave_id();
+    if (g >= n_groups) return;
+    const Sel s = sel[row];
+    const GroupWalk w = group_begin(reg_cnt + row * reg_pad, g, n_reg);
+    emit_group(w, slots + static_cast<int64_t>(row) * n_reg * kReg, g, s.T, s.k3, grp_eqb[row * n_groups + g],
+               grp_out[row * n_groups + g], pairs + static_cast<int64_t>(row) * k, buf + row * stride, k);
+}
+
+// ---------------------------------------------------------------------------------------
+// fused refinement: everything after the dense pass in one launch
+// ---------------------------------------------------------------------------------------
+// The candidate phases each touch a few MB that sit in the L2 / memory-side cache, so as
+// separate launches they cost mostly dispatch and ramp time.  k_topk_finish runs them in one
+// launch whose workgroups are all resident at once (the host sizes the grid from the
+// occupancy query) and which synchronise per row:
+//   arrive        every wavefront waits for its outstanding atomics, then one device-scope
+//                 increment of the row's counter per workgroup;
+//   publish       the workgroup whose increment completes the round reads the row's
+//                 histogram, picks the bin and publishes (bin, remaining) as one 64-bit
+//                 atomic store (a plain barrier publishes an empty word); the others poll
+//                 that word, which lies in another cache line than the counter so that the
+//                 polls do not queue up in front of the remaining arrivals.  Rows are 256
+//                 bytes apart for the same reason.
+// Every poll loop is bounded: if a round does not complete within kSpinLimit polls (the grid
+// was not resident as a whole after all, e.g. two such launches from different streams took
+// half the device each), the workgroup raises the context's abort word (host memory) and
+// the kernel drains; the context then reports DS_ERR_DEVICE on every later call.
+//
+// Radix levels here are relative to lo_key: level A = 256 bins of 4096 keys from lo_key
+// upwards (the last bin also takes everything beyond), level B = the 12 low bits inside bin
+// A.  The sample's lower bound is known to 20 key bits and the k-th key lies a few per cent
+// above it, so two levels resolve all 31 bits.  A row whose k-th key is not below bin 255
+// (or that has fewer than k candidates) takes the exact two-look route inside the same
+// launch: put v back, dense 12-bit histogram, pick b1, compact again with lo_key = b1 << 19
+// (the k-th key is then less than 2^19 above lo_key), level A again.
+constexpr int kHA = 256, kHB = 4096, kShiftA = 12;
+constexpr int kFOffA = 0, kFOffA2 = kHA, kFOffB = 2 * kHA, kFOffD = 2 * kHA + kHB;
+constexpr int kFRow = 2 * kHA + kHB + kH1;     // words per row of the fused route's histograms
+enum { kResA = 0, kResD = 1, kResA2 = 2, kResB = 3, kResCompact = 4, kResCount = 5, kResSlots = 6 };
+constexpr int kSyncStride = 256;   // bytes of synchronisation memory per row: the counter in the first 128-byte line, the published words in the second
+constexpr uint32_t kSpinLimit = 1u << 22;
+constexpr uint64_t kResValid = 1ull << 63;
+
+struct RowSync {
+    uint32_t *bar;         // arrival counter of the row, 0 between launches
+    uint64_t *res;         // kResSlots published picks of the row, 0 between launches
+    uint32_t *abort_flag;  // host memory
+    uint32_t *sh;          // 3 LDS words
+    uint32_t G;            // workgroups per row
+    uint32_t rounds;       // arrival rounds so far (the same in every workgroup of the row)
+};
+
+__device__ __forceinline__ void raise_abort(uint32_t *abort_flag)
+{
+    __hip_atomic_store(abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+// True in the workgroup whose arrival completes the round.  All threads must call.
+__device__ __forceinline__ bool row_arrive(RowSync &rs)
+{
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    rs.rounds++;
+    if (threadIdx.x == 0) {
+        const uint32_t prev = __hip_atomic_fetch_add(rs.bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        rs.sh[0] = (prev + 1u == rs.rounds * rs.G) ? 1u : 0u;
+    }
+    __syncthreads();
+    const bool last = rs.sh[0] != 0u;
+    __syncthreads();
+    return last;
+}
+
+// rem < 2^31; bin = kNone or < 2^31 - 1
+__device__ __forceinline__ void row_publish(RowSync &rs, int slot, uint32_t bin, uint32_t rem)
+{
+    const uint64_t enc = kResValid | (static_cast<uint64_t>((bin == kNone) ? 0u : bin + 1u) << 32) | rem;
+    __hip_atomic_store(rs.res + slot, enc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ bool row_wait_result(RowSync &rs, int slot, uint32_t *bin, uint32_t *rem)
+{
+    if (threadIdx.x == 0) {
+        uint64_t v = 0;
+        uint32_t ok = 1u;
+        for (uint32_t spins = 0;; ++spins) {
+            v = __hip_atomic_load(rs.res + slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (v & kResValid) break;
+            __builtin_amdgcn_s_sleep(1);
+            if (spins > kSpinLimit) { ok = 0u; raise_abort(rs.abort_flag); break; }
+        }
+        const uint32_t enc = static_cast<uint32_t>(v >> 32) & 0x7FFFFFFFu;
+        rs.sh[0] = ok;
+        rs.sh[1] = enc ? enc - 1u : kNone;
+        rs.sh[2] = static_cast<uint32_t>(v);
+    }
+    __syncthreads();
+    const bool ok = rs.sh[0] != 0u;
+    *bin = rs.sh[1];
+    *rem = rs.sh[2];
+    __syncthreads();
+    return ok;
+}
+
+// A plain barrier over the row's workgroups.  False: gave up.
+__device__ __forceinline__ bool row_barrier(RowSync &rs, int slot)
+{
+    if (row_arrive(rs) && threadIdx.x == 0) row_publish(rs, slot, kNone, 0u);
+    uint32_t b, r;
+    return row_wait_result(rs, slot, &b, &r);
+}
+
+// Run by the workgroup that completed the round.
+template <int NB>
+__device__ __forceinline__ void row_pick_publish(RowSync &rs, int slot, const uint32_t *hist, uint32_t need,
+                                                 uint32_t *part, uint32_t *out)
+{
+    if (threadIdx.x == 0) { out[0] = kNone; out[1] = 0u; }
+    __syncthreads();
+    pick_bin<NB>(hist, need, part, &out[0], &out[1]);
+    __syncthreads();
+    if (threadIdx.x == 0) row_publish(rs, slot, out[0], out[1]);
+}
+
+// f(key) for every candidate of the groups this wavefront owns (the same groups in every
+// phase: group = workgroup * 8 + wavefront, then strided by the row's wavefront count).
+template <class F>
+__device__ __forceinline__ void for_each_candidate(const u32x2 *__restrict__ srow, const uint32_t *__restrict__ cnt_row,
+                                                   int64_t n_reg, int64_t n_groups, uint32_t G, F f)
+{
+    for (int64_t g = static_cast<int64_t>(blockIdx.x) * kWaves + wave_id(); g < n_groups;
+         g += static_cast<int64_t>(G) * kWaves) {
+        const GroupWalk w = group_begin(cnt_row, g, n_reg);
+        for (uint32_t i0 = 0; i0 < w.total; i0 += 64 * kPrefetch) {
+            const Batch bt = group_fetch_batches(w, srow, g, i0);
+#pragma unroll
+            for (int j = 0; j < kPrefetch; ++j)
+                if (i0 + j * 64 + lane_id() < w.total) f(bt.pr[j].y & 0x7FFFFFFFu);
+        }
+    }
+}
+
+__device__ __forceinline__ void flush_hist(const uint32_t *h, uint32_t *gh, int nb)
+{
+    for (int i = threadIdx.x; i < nb; i += kBlock)
+        if (h[i]) atomicAdd(&gh[i], h[i]);
+}
+
+struct FinishArgs {
+    u32x2 *slots;
+    uint32_t *reg_cnt;
+    int64_t n_reg, reg_pad, n_groups, n_sub;
+    const Sel *sel;
+    uint32_t *fhist;       // [rows][kFRow], zero on entry
+    char *sync;            // [rows][kSyncStride] arrival counter and published words, zero on entry
+    uint32_t *abort_flag;
+    uint32_t *grp_gt, *grp_eq;
+    uint32_t *prev_T;
+    float *buf;
+    int64_t stride, d, k;
+    u32x2 *pairs;
+    uint32_t *zero_a, *zero_b;   // histogram halves of the next call, cleared here
+    int64_t zero_a_words, zero_b_words;
+};
+
+__global__ __launch_bounds__(kBlock, 8) void k_topk_finish(FinishArgs a)
+{
+    __shared__ uint32_t h[kHB];
+    __shared__ uint32_t part[kWaves], out[2], sh[3], wtot[kWaves], red[2 * kWaves];
+    const int row = blockIdx.y;
+    const uint32_t G = gridDim.x;
+    RowSync rs{reinterpret_cast<uint32_t *>(a.sync + row * kSyncStride), reinterpret_cast<uint64_t *>(a.sync + row * kSyncStride + 128),
+               a.abort_flag, sh, G, 0u};
+    uint32_t *fh = a.fhist + static_cast<int64_t>(row) * kFRow;
+    u32x2 *srow = a.slots + static_cast<int64_t>(row) * a.n_reg * kReg;
+    uint32_t *cnt_row = a.reg_cnt + row * a.reg_pad;
+    float *brow = a.buf + row * a.stride;
+    const uint32_t k32 = static_cast<uint32_t>(a.k);
+    {
+        const int64_t first = (static_cast<int64_t>(blockIdx.y) * G + blockIdx.x) * kBlock + threadIdx.x;
+        const int64_t step = static_cast<int64_t>(gridDim.y) * G * kBlock;
+        for (int64_t i = first; i < a.zero_a_words; i += step) a.zero_a[i] = 0u;
+        for (int64_t i = first; i < a.zero_b_words; i += step) a.zero_b[i] = 0u;
+    }
+    uint32_t lo_key = a.sel[row].lo_key;
+    uint32_t bA = kNone, kA = 0u;
+
+    auto level_a = [&](uint32_t *gh, int slot) -> bool {
+        for (int i = threadIdx.x; i < kHA; i += kBlock) h[i] = 0u;
+        __syncthreads();
+        for_each_candidate(srow, cnt_row, a.n_reg, a.n_groups, G, [&](uint32_t key) {
+            const uint32_t rel = (key - lo_key) >> kShiftA;
+            atomicAdd(&h[rel < kHA ? rel : kHA - 1], 1u);
+        });
+        __syncthreads();
+        flush_hist(h, gh, kHA);
+        if (row_arrive(rs)) row_pick_publish<kHA>(rs, slot, gh, k32, part, out);
+        return row_wait_result(rs, slot, &bA, &kA);
+    };
+
+    if (!level_a(fh + kFOffA, kResA)) return;
+    if (bA == kNone || bA == kHA - 1) {
+        // exact two-look route.  A workgroup owns the same tiles in all of its steps, so what
+        // it reads back is what it wrote itself.
+        for (int i = threadIdx.x; i < kH1; i += kBlock) h[i] = 0u;
+        __syncthreads();
+        const bool vec = aligned16(brow);
+        for (int64_t tile = blockIdx.x; tile < a.n_reg; tile += G) {
+            const uint32_t cnt = cnt_row[tile];
+            const u32x2 *src = srow + tile * kReg;
+            for (uint32_t i = threadIdx.x; i < cnt; i += kBlock) brow[src[i].x] = __uint_as_float(src[i].y);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            const int64_t e = tile * kTile + threadIdx.x * 4;
+            if (e < a.d) {
+                const f32x4 v = ld4(brow, e, a.d, vec);
+                if (e + 0 < a.d) atomicAdd(&h[key_of(v.x) >> 19], 1u);
+                if (e + 1 < a.d) atomicAdd(&h[key_of(v.y) >> 19], 1u);
+                if (e + 2 < a.d) atomicAdd(&h[key_of(v.z) >> 19], 1u);
+                if (e + 3 < a.d) atomicAdd(&h[key_of(v.w) >> 19], 1u);
+            }
+        }
+        __syncthreads();
+        flush_hist(h, fh + kFOffD, kH1);
+        if (row_arrive(rs)) row_pick_publish<kH1>(rs, kResD, fh + kFOffD, k32, part, out);
+        uint32_t b1, k1;
+        if (!row_wait_result(rs, kResD, &b1, &k1)) return;
+        if (b1 == kNone) { raise_abort(a.abort_flag); return; }       // cannot happen: k <= d
+        lo_key = b1 << 19;
+        const BufferV bsrc{a.buf, a.stride};
+        for (int64_t tile = blockIdx.x; tile < a.n_reg; tile += G)
+            pass1_tile<BufferV, true>(bsrc, a.buf, a.stride, a.d, a.n_sub, lo_key, a.slots, a.reg_cnt, a.n_reg, a.reg_pad,
+                                      row, tile, nullptr, wtot);
+        // the new candidate lists cross workgroups (and their caches) from here on
+        __threadfence();
+        if (!row_barrier(rs, kResCompact)) return;
+        __threadfence();
+        if (!level_a(fh + kFOffA2, kResA2)) return;
+        if (bA == kNone || bA == kHA - 1) { raise_abort(a.abort_flag); return; }   // cannot happen
+    }
+
+    // level B: the 12 low bits inside bin A
+    for (int i = threadIdx.x; i < kHB; i += kBlock) h[i] = 0u;
+    __syncthreads();
+    for_each_candidate(srow, cnt_row, a.n_reg, a.n_groups, G, [&](uint32_t key) {
+        const uint32_t rel = key - lo_key;
+        if ((rel >> kShiftA) == bA) atomicAdd(&h[rel & (kHB - 1)], 1u);
+    });
+    __syncthreads();
+    flush_hist(h, fh + kFOffB, kHB);
+    if (row_arrive(rs)) row_pick_publish<kHB>(rs, kResB, fh + kFOffB, kA, part, out);
+    uint32_t bB, k3;
+    if (!row_wait_result(rs, kResB, &bB, &k3)) return;
+    if (bB == kNone) { raise_abort(a.abort_flag); return; }           // cannot happen
+    const uint32_t T = lo_key + (bA << kShiftA) + bB;
+
+    // per group: candidates above T, candidates tying with T
+    uint32_t *gtr = a.grp_gt + row * a.n_groups, *eqr = a.grp_eq + row * a.n_groups;
+    for (int64_t g = static_cast<int64_t>(blockIdx.x) * kWaves + wave_id(); g < a.n_groups;
+         g += static_cast<int64_t>(G) * kWaves) {
+        const GroupWalk w = group_begin(cnt_row, g, a.n_reg);
+        uint32_t gt = 0, eq = 0;
+        for (uint32_t i0 = 0; i0 < w.total; i0 += 64 * kPrefetch) {
+            const Batch bt = group_fetch_batches(w, srow, g, i0);
+#pragma unroll
+            for (int j = 0; j < kPrefetch; ++j) {
+                const bool valid = i0 + j * 64 + lane_id() < w.total;
+                const uint32_t key = bt.pr[j].y & 0x7FFFFFFFu;
+                gt += valid && key > T;
+                eq += valid && key == T;
+            }
+        }
+        gt = wave_sum_u32(gt);
+        eq = wave_sum_u32(eq);
+        if (lane_id() == 0) {
+            dev_store(&gtr[g], gt);
+            dev_store(&eqr[g], eq);
+        }
+    }
+    if (!row_barrier(rs, kResCount)) return;
+
+    // emit.  Ties are taken in index order, so the ties kept before a group number
+    // min(k3, ties before it): two running sums over the groups give every offset.
+    uint32_t sum_gt = 0, sum_eq = 0;
+    int64_t upto = 0;
+    u32x2 *prow = a.pairs + static_cast<int64_t>(row) * a.k;
+    for (int64_t gb = static_cast<int64_t>(blockIdx.x) * kWaves; gb < a.n_groups; gb += static_cast<int64_t>(G) * kWaves) {
+        uint32_t pg = 0, pe = 0;
+        for (int64_t t = upto + threadIdx.x; t < gb; t += kBlock) {
+            pg += dev_load(&gtr[t]);
+            pe += dev_load(&eqr[t]);
+        }
+        pg = wave_sum_u32(pg);
+        pe = wave_sum_u32(pe);
+        __syncthreads();
+        if (lane_id() == 0) { red[wave_id()] = pg; red[kWaves + wave_id()] = pe; }
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) { sum_gt += red[w]; sum_eq += red[kWaves + w]; }
+        upto = gb;
+        const int64_t g = gb + wave_id();
+        if (g < a.n_groups) {
+            uint32_t wg = 0, we = 0;
+            if (lane_id() < wave_id()) { wg = dev_load(&gtr[gb + lane_id()]); we = dev_load(&eqr[gb + lane_id()]); }
+            const uint32_t gtb = sum_gt + wave_sum_u32(wg), eqb = sum_eq + wave_sum_u32(we);
+            const GroupWalk w = group_begin(cnt_row, g, a.n_reg);
+            emit_group(w, srow, g, T, k3, eqb, gtb + (eqb < k3 ? eqb : k3), prow, brow, a.k);
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) a.prev_T[row] = T;   // centre of the next call's fine sampling window
+    if (row_arrive(rs) && threadIdx.x == 0) {                      // everyone is past every poll: reset for the next launch
+        for (int sl = 0; sl < kResSlots; ++sl) __hip_atomic_store(rs.res + sl, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        dev_store(rs.bar, 0u);
     }
 }
 
@@ -798,6 +1152,7 @@ ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t 
                        uint32_t *prev_T)
 {
     ds_topk_scratch *t = c->topk;
+    if (__atomic_load_n(t->abort_host, __ATOMIC_RELAXED)) return DS_ERR_DEVICE;   // an earlier launch gave up waiting
     const int64_t d = c->cfg.d, k = c->cfg.k, n_sub = t->n_sub, n_reg = t->n_reg, reg_pad = t->reg_pad, n_groups = t->n_groups;
     const int64_t ns = (n_sub < kSampleSubs) ? n_sub : kSampleSubs;
     // sample rank: 1.15 x the expected number of top-k members in the sample, plus slack
@@ -819,6 +1174,23 @@ ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t 
     k_topk_sample<Src><<<dim3(static_cast<unsigned>((ns + kWaves - 1) / kWaves), rows), kBlock, 0, st>>>(
         src, d, n_sub, ns, hist, t->sel, t->done, rank, prev_T);
     k_topk_pass1<Src, false><<<dense, kBlock, 0, st>>>(src, buf, stride, d, n_sub, t->sel, t->slots, t->reg_cnt, n_reg, reg_pad);
+    if (t->capacity >= rows) {
+        // everything after the dense pass in one launch whose workgroups are all resident
+        int64_t G = t->capacity / rows;
+        if (G > grp_blocks) G = grp_blocks;
+        uint32_t *fh = t->fhist + static_cast<int64_t>(t->parity ^ 1) * t->rows * kFRow;        // parity was flipped above
+        uint32_t *fh_next = t->fhist + static_cast<int64_t>(t->parity) * t->rows * kFRow;
+        FinishArgs a;
+        a.slots = t->slots; a.reg_cnt = t->reg_cnt;
+        a.n_reg = n_reg; a.reg_pad = reg_pad; a.n_groups = n_groups; a.n_sub = n_sub;
+        a.sel = t->sel; a.fhist = fh; a.sync = t->sync; a.abort_flag = t->abort_host;
+        a.grp_gt = t->grp_gt; a.grp_eq = t->grp_eq; a.prev_T = prev_T;
+        a.buf = buf; a.stride = stride; a.d = d; a.k = k; a.pairs = pairs;
+        a.zero_a = hist_next; a.zero_a_words = static_cast<int64_t>(t->rows) * kHistRow;
+        a.zero_b = fh_next; a.zero_b_words = static_cast<int64_t>(t->rows) * kFRow;
+        k_topk_finish<<<dim3(static_cast<unsigned>(G), rows), kBlock, 0, st>>>(a);
+        return ds_launch_status();
+    }
     k_topk_cand_hist<1><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32, prev_T, buf, stride);
     // two-look route for rows whose sample misjudged; both launches exit at once otherwise
     k_topk_fallback_hist<<<dim3(persistent_blocks(c->n_tiles, rows), rows), kBlock, 0, st>>>(buf, stride, d, c->n_tiles,
@@ -863,7 +1235,29 @@ ds_status_t ds_topk_init(ds_ctx *c)
     uint32_t **tabs[4] = {&t->grp_gt, &t->grp_eq, &t->grp_eqb, &t->grp_out};
     for (auto tab : tabs) DS_HIP_TRY(hipMalloc(tab, rows * static_cast<size_t>(t->n_groups) * sizeof(uint32_t)));
     DS_HIP_TRY(hipMalloc(&t->sub_start, rows * static_cast<size_t>(t->n_sub + 1) * sizeof(uint32_t)));
+    DS_HIP_TRY(hipMemset(t->sub_start, 0, rows * static_cast<size_t>(t->n_sub + 1) * sizeof(uint32_t)));
     DS_HIP_TRY(hipMemset(t->reg_cnt, 0, rows * static_cast<size_t>(t->reg_pad) * sizeof(uint32_t)));
+    DS_HIP_TRY(hipMalloc(&t->fhist, 2 * rows * kFRow * sizeof(uint32_t)));
+    DS_HIP_TRY(hipMemset(t->fhist, 0, 2 * rows * kFRow * sizeof(uint32_t)));
+    DS_HIP_TRY(hipMalloc(&t->sync, rows * kSyncStride));
+    DS_HIP_TRY(hipMemset(t->sync, 0, rows * kSyncStride));
+    DS_HIP_TRY(hipHostMalloc(reinterpret_cast<void **>(&t->abort_host), sizeof(uint32_t), hipHostMallocDefault));
+    *t->abort_host = 0u;
+    // The fused route needs its whole grid resident: workgroups per compute unit from the
+    // occupancy query times the number of compute units.
+    t->capacity = 0;
+    if (!(c->cfg.flags & DS_FLAG_TOPK_MULTI_LAUNCH)) {
+        int per_cu = 0, cus = 0;
+        DS_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_topk_finish, kBlock, 0));
+        DS_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device));
+        t->capacity = static_cast<int64_t>(per_cu) * cus;
+        // DS_TOPK_RESIDENT_LIMIT caps the workgroups the single launch uses, for devices that
+        // are shared with other work
+        if (const char *lim = getenv("DS_TOPK_RESIDENT_LIMIT")) {
+            const long v = strtol(lim, nullptr, 10);
+            if (v >= 0 && v < t->capacity) t->capacity = v;
+        }
+    }
     return DS_OK;
 }
 
@@ -871,9 +1265,11 @@ void ds_topk_fini(ds_ctx *c)
 {
     ds_topk_scratch *t = c->topk;
     if (!t) return;
-    void *ptrs[11] = {t->prev_T, t->done, t->hist, t->sel, t->slots, t->reg_cnt, t->grp_gt, t->grp_eq, t->grp_eqb, t->grp_out, t->sub_start};
+    void *ptrs[13] = {t->prev_T, t->done, t->hist, t->sel, t->slots, t->reg_cnt, t->grp_gt, t->grp_eq, t->grp_eqb, t->grp_out,
+                      t->sub_start, t->fhist, t->sync};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
+    if (t->abort_host) (void)hipHostFree(t->abort_host);
     delete t;
     c->topk = nullptr;
 }
@@ -892,8 +1288,12 @@ ds_status_t ds_topk_server(ds_ctx *c, const ds_payload_t *in, float *delta_s, co
     ds_topk_scratch *t = c->topk;
     const u32x2 *pairs_in = reinterpret_cast<const u32x2 *>(in->pairs);
     const int64_t k = c->cfg.k;
-    k_topk_sub_starts<<<dim3(static_cast<unsigned>((t->n_sub + 1 + kBlock - 1) / kBlock), c->cfg.n), kBlock, 0, st>>>(
-        pairs_in, k, t->n_sub, t->sub_start);
+    if (k * 4 >= t->n_sub)
+        k_topk_sub_starts_scan<<<dim3(static_cast<unsigned>((k + 1 + kBlock - 1) / kBlock), c->cfg.n), kBlock, 0, st>>>(
+            pairs_in, k, t->n_sub, t->sub_start);
+    else
+        k_topk_sub_starts<<<dim3(static_cast<unsigned>((t->n_sub + 1 + kBlock - 1) / kBlock), c->cfg.n), kBlock, 0, st>>>(
+            pairs_in, k, t->n_sub, t->sub_start);
     const ServerV src{pairs_in, t->sub_start, delta_s, k, t->n_sub, c->cfg.n, c->inv_n};
     return run_select(c, 1, src, delta_s, c->cfg.d, reinterpret_cast<u32x2 *>(out->pairs), st, t->prev_T + t->rows);
 }

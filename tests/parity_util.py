@@ -25,11 +25,16 @@ def oracle_config(wl) -> O.Config:
                     k=wl.k, bucket=wl.bucket, levels=wl.levels, seed=wl.seed)
 
 
+# ds_config_t::flags of the contexts that gpu_context builds; tests that cover both top-k
+# refinement routes set it through the `topk_route` fixture of their module.
+CONTEXT_FLAGS = 0
+
+
 def gpu_context(wl) -> P.Context:
     return P.Context(wl.comp, wl.n, wl.d, grad_dtype=wl.grad_dtype, scale_mode=wl.scale_mode,
                      chunk=wl.chunk,
                      seg_offsets=wl.seg_offsets if wl.scale_mode == "segments" else None,
-                     k=wl.k, bucket=wl.bucket, levels=wl.levels, seed=wl.seed)
+                     k=wl.k, bucket=wl.bucket, levels=wl.levels, seed=wl.seed, flags=CONTEXT_FLAGS)
 
 
 def host_grad(g: torch.Tensor) -> np.ndarray:

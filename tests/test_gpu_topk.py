@@ -5,9 +5,19 @@ import pytest
 import torch
 
 import ds_workloads as W
+import paper_1905_05957_amd as P
+import parity_util
 from parity_util import Pair
 
 pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True, params=["single_launch", "multi_launch"])
+def topk_route(request):
+    """Every test of this module runs on both refinement routes of the library."""
+    parity_util.CONTEXT_FLAGS = P.FLAG_TOPK_MULTI_LAUNCH if request.param == "multi_launch" else 0
+    yield request.param
+    parity_util.CONTEXT_FLAGS = 0
 
 
 def _wl(d, n=3, k=None, **kw):
@@ -31,6 +41,13 @@ def _run(wl, device, steps=2, sets=2, grads=None):
                                  (100_003, 1000), (100_003, 100_003), (40_000, 39_999)])
 def test_topk_shapes(gpu_device, d, k):
     _run(_wl(d, k=k), gpu_device)
+
+
+def test_topk_few_resident_workgroups(gpu_device, monkeypatch):
+    # 2 workgroups per row for 100 groups of 32768 elements: every wavefront of the single
+    # launch walks several groups and the offsets run over several rounds
+    monkeypatch.setenv("DS_TOPK_RESIDENT_LIMIT", "6")
+    _run(_wl(100 * 32768 + 999, n=3), gpu_device, steps=3)
 
 
 def test_topk_all_zero_and_all_equal(gpu_device):
