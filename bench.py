@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_WORKER_TRAFFIC = {
     "c5": 5.9729e9 + 4.1613e9,   # k_sign_chunk_worker
     "c4": 3.3100e9 + 1.9392e9,   # k_qsgd_worker
-    "c3": 2.7916e9,              # all kernels of the worker call (dense pass 2.5074e9)
+    "c3": 2.6375e9,              # all kernels of the worker call (dense pass 2.4962e9)
     "c2": 1.8343e9,              # pass 1 + pass 2
 }
 
