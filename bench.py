@@ -65,14 +65,15 @@ def make_workload(name: str):
     return {"c2": W.c2, "c3": W.c3, "c4": W.c4, "c5": W.c5}[name]()
 
 
-def run_gpu(wl, steps: int, warmup: int, sets: int = 2, calib_copy: bool = False):
+def run_gpu(wl, steps: int, warmup: int, sets: int = 2, calib_copy: bool = False, deferred_error: bool = True):
     import torch
     import paper_1905_05957_amd as P
 
     dev = torch.device("cuda:0")
     ctx = P.Context(wl.comp, wl.n, wl.d, grad_dtype=wl.grad_dtype, scale_mode=wl.scale_mode,
                     chunk=wl.chunk, seg_offsets=wl.seg_offsets if wl.scale_mode == "segments" else None,
-                    k=wl.k, bucket=wl.bucket, levels=wl.levels, seed=wl.seed)
+                    k=wl.k, bucket=wl.bucket, levels=wl.levels, seed=wl.seed,
+                    flags=P.FLAG_DEFERRED_ERROR if deferred_error else 0)
     grads = [wl.gradients(s, dev) for s in range(sets)]
     delta = wl.initial_delta(dev)
     delta_s = torch.zeros(wl.d, dtype=torch.float32, device=dev)
@@ -174,6 +175,9 @@ def main():
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy (calibration dispatch for rocprofv3 --pmc byte counters)")
     ap.add_argument("--cpu-elems", type=int, default=400_000_000)
+    ap.add_argument("--plain-error", action="store_true",
+                    help="keep the error buffers in plain form after every call (sign with scale groups that "
+                         "span workgroups then takes two looks per call; default: DS_FLAG_DEFERRED_ERROR)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU (n workers are rows of one tensor); "
@@ -187,12 +191,13 @@ def main():
 
     def measure(name, steps, warmup, calib_copy=False):
         wl = make_workload(name)
-        r = run_gpu(wl, steps, warmup, calib_copy=calib_copy)
+        r = run_gpu(wl, steps, warmup, calib_copy=calib_copy, deferred_error=not a.plain_error)
         ab = algorithmic_bytes(wl, r["S"])
         ms = r["ms_per_step"]
         wk_ms = r["stage_ms"][0]
         out = {
             "workload": wl.name, "n": wl.n, "d": wl.d, "ms_per_step": ms,
+            "error_state": "plain" if a.plain_error or not (wl.comp == "sign" and wl.scale_mode != "chunk") else "deferred",
             "value": wl.n * wl.d / (ms * 1e-3),
             "stage_ms": {"worker": r["stage_ms"][0], "server": r["stage_ms"][1], "update": r["stage_ms"][2]},
             "algorithmic_bytes_per_step": ab["total"],

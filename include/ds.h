@@ -82,8 +82,20 @@ typedef enum {
  * launch that finds the device shared gives up after a bounded wait, and its context then
  * returns DS_ERR_DEVICE from every later call).  The environment variable
  * DS_TOPK_RESIDENT_LIMIT=<workgroups>, read by ds_create, caps the size of the single launch
- * (default: what the device holds at once; fewer workgroups than rows selects the chain). */
-typedef enum { DS_FLAG_TOPK_MULTI_LAUNCH = 1 } ds_flags_t;
+ * (default: what the device holds at once; fewer workgroups than rows selects the chain).
+ *
+ * DS_FLAG_DEFERRED_ERROR: SIGN with scale groups that span workgroups (whole vector,
+ * arbitrary segments, chunks that are no multiple of 128 or exceed 2048) needs the group
+ * scale before it can store delta = v - Q[v], i.e. a second look at v.  With this flag the
+ * second look is folded into the next call's load: after a call the error buffers hold v, the
+ * context holds that call's scales, and the next ds_worker_compress /
+ * ds_server_aggregate_compress forms delta = v - Q[v] while it reads the buffer (the same
+ * single subtraction, so every message, x, m and the errors themselves are bit-identical to
+ * the plain form).  The caller must pass the same logical buffers to consecutive calls and
+ * call ds_materialize_error before it reads, copies, checkpoints or edits them.  Contexts for
+ * which the flag has no effect (other compressors, chunk scales handled in one pass) ignore
+ * it. */
+typedef enum { DS_FLAG_TOPK_MULTI_LAUNCH = 1, DS_FLAG_DEFERRED_ERROR = 2 } ds_flags_t;
 
 typedef struct {
     int32_t comp;             /* ds_compressor_t */
@@ -176,6 +188,14 @@ ds_status_t ds_apply_update(ds_ctx_t *ctx, const ds_payload_t *srv, float *x, fl
  * decoder of Q[.] that the server and the update use. */
 ds_status_t ds_decompress(ds_ctx_t *ctx, const ds_payload_t *p, int32_t rows, int32_t row,
                           float *dense_out, void *hip_stream);
+
+/* DS_FLAG_DEFERRED_ERROR: rewrites error buffers that are in deferred form (holding v) to
+ * delta = v - Q[v] in place and marks them as plain for the next call.  delta [n,
+ * delta_row_stride] and delta_s [d] are the buffers given to the last ds_worker_compress /
+ * ds_server_aggregate_compress; either may be NULL to leave that side alone.  A no-op
+ * (DS_OK) for buffers already in plain form and for contexts without the flag. */
+ds_status_t ds_materialize_error(ds_ctx_t *ctx, float *delta, int64_t delta_row_stride,
+                                 float *delta_s, void *hip_stream);
 
 /* Static string for a status code. */
 const char *ds_status_string(ds_status_t s);

@@ -17,6 +17,7 @@ COMP_IDENTITY, COMP_SIGN, COMP_TOPK, COMP_QSGD = 0, 1, 2, 3
 SCALE_WHOLE, SCALE_SEGMENTS, SCALE_CHUNK = 0, 1, 2
 F32, BF16 = 0, 1
 FLAG_TOPK_MULTI_LAUNCH = 1
+FLAG_DEFERRED_ERROR = 2
 
 _COMP = {"identity": COMP_IDENTITY, "sign": COMP_SIGN, "topk": COMP_TOPK, "qsgd": COMP_QSGD}
 _MODE = {"whole": SCALE_WHOLE, "segments": SCALE_SEGMENTS, "chunk": SCALE_CHUNK}
@@ -45,8 +46,8 @@ class ds_payload_t(C.Structure):
 
 
 EXPORTS = ["ds_create", "ds_destroy", "ds_payload_sizes", "ds_worker_compress",
-           "ds_server_aggregate_compress", "ds_apply_update", "ds_decompress", "ds_status_string",
-           "ds_version"]
+           "ds_server_aggregate_compress", "ds_apply_update", "ds_decompress", "ds_materialize_error",
+           "ds_status_string", "ds_version"]
 
 _lib = None
 
@@ -75,7 +76,8 @@ def load_library():
                                                C.POINTER(ds_payload_t), vp]
     L.ds_apply_update.argtypes = [vp, C.POINTER(ds_payload_t), vp, vp, f32, f32, vp]
     L.ds_decompress.argtypes = [vp, C.POINTER(ds_payload_t), i32, i32, vp, vp]
-    for name in EXPORTS[:7]:
+    L.ds_materialize_error.argtypes = [vp, vp, i64, vp, vp]
+    for name in EXPORTS[:8]:
         getattr(L, name).restype = C.c_int
     L.ds_status_string.argtypes = [C.c_int]
     L.ds_status_string.restype = C.c_char_p
@@ -233,6 +235,14 @@ class Context:
                                               None if m is None else m.data_ptr(), gamma, beta,
                                               _stream_ptr(stream)), "ds_apply_update")
 
+    def materialize_error(self, delta: Optional[torch.Tensor], delta_s: Optional[torch.Tensor],
+                          stream=None):
+        _check(load_library().ds_materialize_error(
+            self._h, None if delta is None else delta.data_ptr(),
+            0 if delta is None else delta.stride(0),
+            None if delta_s is None else delta_s.data_ptr(), _stream_ptr(stream)),
+            "ds_materialize_error")
+
     def decompress(self, p: Payload, row: int, out: torch.Tensor, stream=None):
         s = p.c_struct()
         _check(load_library().ds_decompress(self._h, C.byref(s), p.rows, row, out.data_ptr(),
@@ -254,6 +264,10 @@ def ds_payload_sizes(ctx: Context, rows: int):
 
 def ds_worker_compress(ctx: Context, step, g, delta, out, stream=None):
     ctx.worker_compress(step, g, delta, out, stream)
+
+
+def ds_materialize_error(ctx: Context, delta, delta_s, stream=None):
+    ctx.materialize_error(delta, delta_s, stream)
 
 
 def ds_server_aggregate_compress(ctx: Context, step, inp, delta_s, out, stream=None):

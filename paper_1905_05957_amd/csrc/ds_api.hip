@@ -247,4 +247,15 @@ ds_status_t ds_decompress(ds_ctx_t *c, const ds_payload_t *p, int32_t rows, int3
     return DS_ERR_CONFIG;
 }
 
+ds_status_t ds_materialize_error(ds_ctx_t *c, float *delta, int64_t delta_row_stride, float *delta_s, void *hip_stream)
+{
+    if (!c) return DS_ERR_NULL;
+    if (delta && delta_row_stride < c->cfg.d) return DS_ERR_SHAPE;
+    if ((delta && misaligned(delta)) || (delta_s && misaligned(delta_s))) return DS_ERR_ALIGN;
+    if (c->cfg.comp != DS_COMP_SIGN) return DS_OK;   // only the sign compressor has a deferred form
+    DeviceGuard guard(c->device);
+    if (!guard.ok) return DS_ERR_DEVICE;
+    return ds_sign_materialize(c, delta, delta_row_stride, delta_s, static_cast<hipStream_t>(hip_stream));
+}
+
 }  // extern "C"

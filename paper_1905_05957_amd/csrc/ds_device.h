@@ -26,10 +26,19 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 __device__ __forceinline__ bool aligned8(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 7u) == 0; }
 
-// Four consecutive fp32 elements e..e+3 of a row, zero where e+c >= lim.
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// Four consecutive fp32 elements e..e+3 of a row, zero where e+c >= lim.  `vec` = the row
+// starts on a 16-byte boundary.  Rows that start on an 8-byte boundary only (contiguous
+// [n, d] with d = 2 mod 4) take two 64-bit accesses instead of four 32-bit ones; e is a
+// multiple of 4, so the row's alignment is that of every access.
 __device__ __forceinline__ f32x4 ld4(const float *__restrict__ row, int64_t e, int64_t lim, bool vec)
 {
     if (vec && e + 4 <= lim) return *reinterpret_cast<const f32x4 *>(row + e);
+    if (!vec && e + 4 <= lim && aligned8(row)) {
+        const f32x2 a = *reinterpret_cast<const f32x2 *>(row + e), b = *reinterpret_cast<const f32x2 *>(row + e + 2);
+        return f32x4{a.x, a.y, b.x, b.y};
+    }
     f32x4 r = {0.f, 0.f, 0.f, 0.f};
     if (e < lim) r.x = row[e];
     if (e + 1 < lim) r.y = row[e + 1];
@@ -42,6 +51,11 @@ __device__ __forceinline__ f32x4 ld4(const float *__restrict__ row, int64_t e, i
 __device__ __forceinline__ f32x4 ld4_stream(const float *__restrict__ row, int64_t e, int64_t lim, bool vec)
 {
     if (vec && e + 4 <= lim) return __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(row + e));
+    if (!vec && e + 4 <= lim && aligned8(row)) {
+        const f32x2 a = __builtin_nontemporal_load(reinterpret_cast<const f32x2 *>(row + e));
+        const f32x2 b = __builtin_nontemporal_load(reinterpret_cast<const f32x2 *>(row + e + 2));
+        return f32x4{a.x, a.y, b.x, b.y};
+    }
     return ld4(row, e, lim, false);
 }
 
@@ -59,6 +73,12 @@ __device__ __forceinline__ f32x4 ld4_bf16(const uint16_t *__restrict__ row, int6
         r.w = __uint_as_float(u.y & 0xFFFF0000u);
         return r;
     }
+    if (!vec && e + 4 <= lim && (reinterpret_cast<uintptr_t>(row) & 3u) == 0) {   // 4-byte aligned row: two 32-bit loads
+        const uint32_t a = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(row + e));
+        const uint32_t b = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(row + e + 2));
+        return f32x4{__uint_as_float(a << 16), __uint_as_float(a & 0xFFFF0000u), __uint_as_float(b << 16),
+                     __uint_as_float(b & 0xFFFF0000u)};
+    }
     if (e < lim) r.x = bf16_widen(row[e]);
     if (e + 1 < lim) r.y = bf16_widen(row[e + 1]);
     if (e + 2 < lim) r.z = bf16_widen(row[e + 2]);
@@ -69,6 +89,11 @@ __device__ __forceinline__ f32x4 ld4_bf16(const uint16_t *__restrict__ row, int6
 __device__ __forceinline__ void st4(float *__restrict__ row, int64_t e, int64_t lim, bool vec, f32x4 v)
 {
     if (vec && e + 4 <= lim) { *reinterpret_cast<f32x4 *>(row + e) = v; return; }
+    if (!vec && e + 4 <= lim && aligned8(row)) {
+        *reinterpret_cast<f32x2 *>(row + e) = f32x2{v.x, v.y};
+        *reinterpret_cast<f32x2 *>(row + e + 2) = f32x2{v.z, v.w};
+        return;
+    }
     if (e < lim) row[e] = v.x;
     if (e + 1 < lim) row[e + 1] = v.y;
     if (e + 2 < lim) row[e + 2] = v.z;

@@ -33,6 +33,11 @@ struct ds_ctx {
     ds_sign_tables sign_tb;
     void *sign_tb_mem;     // one device allocation behind sign_tb
     double *sign_partials; // [n, n_pieces] partial sums of |v|
+    bool sign_defer;       // DS_FLAG_DEFERRED_ERROR on the two-look route
+    bool sign_w_deferred;  // the worker error buffers hold v of the last call, sign_prev_w its scales
+    bool sign_s_deferred;  // the same for the server's buffer and sign_prev_s
+    float *sign_prev_w;    // [n, S]
+    float *sign_prev_s;    // [S]
     // TOPK
     ds_topk_scratch *topk;
 };
@@ -67,6 +72,7 @@ ds_status_t ds_sign_server(ds_ctx *c, const ds_payload_t *in, float *delta_s,
 ds_status_t ds_sign_update(ds_ctx *c, const ds_payload_t *srv, float *x, float *m, float gamma,
                            float beta, hipStream_t st);
 ds_status_t ds_sign_decode(ds_ctx *c, const ds_payload_t *p, int32_t row, float *out, hipStream_t st);
+ds_status_t ds_sign_materialize(ds_ctx *c, float *delta, int64_t dstr, float *delta_s, hipStream_t st);
 
 // qsgd.hip
 ds_status_t ds_qsgd_worker(ds_ctx *c, uint64_t step, const void *g, int64_t gs, float *delta,

@@ -18,6 +18,8 @@
 #include "ds_device.h"
 #include "ds_internal.h"
 
+#include <type_traits>
+
 #include <vector>
 
 using namespace ds;
@@ -209,6 +211,21 @@ __device__ __forceinline__ double masked_abs(float x, int64_t e, int64_t lo, int
     return (e >= lo && e < hi) ? static_cast<double>(fabsf(x)) : 0.0;
 }
 
+// v - Q[v] for the four elements of a thread, with the group scales of its tile's pieces.
+__device__ __forceinline__ f32x4 sign_error_tile(f32x4 v, int64_t e, int64_t d, const float *__restrict__ srow,
+                                                 const ds_sign_tables &tb, int32_t p0, int32_t p1)
+{
+    if (p1 - p0 == 1) return sign_error4(v, srow[tb.piece_seg[p0]]);
+    float s[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) s[c] = (e + c < d) ? srow[seg_of(tb, p0, p1, e + c)] : 0.f;
+    v.x = v.x - ((v.x < 0.f) ? -s[0] : s[0]);
+    v.y = v.y - ((v.y < 0.f) ? -s[1] : s[1]);
+    v.z = v.z - ((v.z < 0.f) ? -s[2] : s[2]);
+    v.w = v.w - ((v.w < 0.f) ? -s[3] : s[3]);
+    return v;
+}
+
 // Pass-1 tail: store v, sign bits, per-piece partial sums of |v|.
 __device__ __forceinline__ void pass1_finish(f32x4 v, int64_t base, int64_t d,
                                              float *__restrict__ vrow, bool vvec,
@@ -236,10 +253,14 @@ __device__ __forceinline__ void pass1_finish(f32x4 v, int64_t base, int64_t d,
     }
 }
 
-template <bool BF16>
+// DEFERRED: the error buffer holds the previous call's v and `prev_scales` that call's group
+// scales; the error delta = v_prev - Q[v_prev] is formed on the fly (the same subtraction
+// pass 2 would have stored), so the buffer is looked at once per call.
+template <bool BF16, bool DEFERRED>
 __global__ __launch_bounds__(kBlock) void k_sign_pass1_worker(WorkerSrc<BF16> src, float *delta,
                                                               int64_t d, uint64_t *words, int64_t W,
-                                                              ds_sign_tables tb, double *partials)
+                                                              ds_sign_tables tb, double *partials,
+                                                              const float *__restrict__ prev_scales, int64_t S)
 {
     __shared__ double lds[kWaves];
     __shared__ __attribute__((aligned(16))) uint32_t sw_lds[kWaves * 8];
@@ -251,14 +272,18 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass1_worker(WorkerSrc<BF16> sr
     const bool gvec = BF16 ? aligned8(grow) : aligned16(grow);
     const bool dvec = aligned16(drow);
     const int64_t e = base + threadIdx.x * 4;
-    const f32x4 v = ld4_grad<BF16>(grow, e, d, gvec) + ld4(drow, e, d, dvec);
-    pass1_finish(v, base, d, drow, dvec, words + row * W, W * 64, tb, tb.tile_piece_first[tile],
-                 tb.tile_piece_first[tile + 1], partials + static_cast<int64_t>(row) * tb.n_pieces, lds, sw_lds);
+    const int32_t p0 = tb.tile_piece_first[tile], p1 = tb.tile_piece_first[tile + 1];
+    f32x4 dl = ld4(drow, e, d, dvec);
+    if (DEFERRED && e < d) dl = zero_past(sign_error_tile(dl, e, d, prev_scales + row * S, tb, p0, p1), e, d);
+    const f32x4 v = ld4_grad<BF16>(grow, e, d, gvec) + dl;
+    pass1_finish(v, base, d, drow, dvec, words + row * W, W * 64, tb, p0, p1,
+                 partials + static_cast<int64_t>(row) * tb.n_pieces, lds, sw_lds);
 }
 
+template <bool DEFERRED>
 __global__ __launch_bounds__(kBlock) void k_sign_pass1_server(ServerArgs a, float *delta_s, int64_t d,
                                                               uint64_t *words_out, ds_sign_tables tb,
-                                                              double *partials)
+                                                              double *partials, const float *__restrict__ prev_scales)
 {
     __shared__ double lds[kWaves];
     __shared__ __attribute__((aligned(16))) uint32_t sw_lds[kWaves * 8];
@@ -268,6 +293,7 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass1_server(ServerArgs a, floa
     const int32_t p0 = tb.tile_piece_first[tile], p1 = tb.tile_piece_first[tile + 1];
     const int64_t e = base + threadIdx.x * 4;
     f32x4 v = ld4(delta_s, e, d, dvec);
+    if (DEFERRED && e < d) v = sign_error_tile(v, e, d, prev_scales, tb, p0, p1);   // past d: cleared below
     const int lane = lane_id();
     const int64_t wave_first = base + wave_id() * 256;
     if (p1 - p0 == 1) {
@@ -305,8 +331,9 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass1_server(ServerArgs a, floa
 }
 
 // scale[row][s] = (float)( sum of the group's partials / |group| ), fixed order.
+// `keep` (may be null): the context's own copy of the scales, for the deferred error form.
 __global__ __launch_bounds__(kBlock) void k_sign_reduce(const double *__restrict__ partials,
-                                                        ds_sign_tables tb, float *scales, int64_t S)
+                                                        ds_sign_tables tb, float *scales, int64_t S, float *keep)
 {
     __shared__ double lds[kBlock];
     const int32_t s = blockIdx.x;
@@ -323,7 +350,9 @@ __global__ __launch_bounds__(kBlock) void k_sign_reduce(const double *__restrict
     }
     if (threadIdx.x == 0) {
         const double len = static_cast<double>(tb.seg_off[s + 1] - tb.seg_off[s]);
-        scales[row * S + s] = static_cast<float>(lds[0] / len);
+        const float sc = static_cast<float>(lds[0] / len);
+        scales[row * S + s] = sc;
+        if (keep) keep[row * S + s] = sc;
     }
 }
 
@@ -343,19 +372,8 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass2(float *buf, int64_t strid
     const int32_t p0 = tb.tile_piece_first[tile], p1 = tb.tile_piece_first[tile + 1];
     const int64_t e = tile * kTile + threadIdx.x * 4;
     if (e >= d) return;
-    f32x4 v = ld4(brow, e, d, vec);
-    if (p1 - p0 == 1) {
-        v = sign_error4(v, srow[tb.piece_seg[p0]]);
-    } else {
-        float s[4];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) s[c] = (e + c < d) ? srow[seg_of(tb, p0, p1, e + c)] : 0.f;
-        v.x = v.x - ((v.x < 0.f) ? -s[0] : s[0]);
-        v.y = v.y - ((v.y < 0.f) ? -s[1] : s[1]);
-        v.z = v.z - ((v.z < 0.f) ? -s[2] : s[2]);
-        v.w = v.w - ((v.w < 0.f) ? -s[3] : s[3]);
-    }
-    st4(brow, e, d, vec, v);
+    const f32x4 v = ld4(brow, e, d, vec);
+    st4(brow, e, d, vec, sign_error_tile(v, e, d, srow, tb, p0, p1));
 }
 
 template <bool MOM, bool DECODE_ONLY>
@@ -388,6 +406,8 @@ ds_status_t ds_sign_init(ds_ctx *c)
     const ds_config_t &cfg = c->cfg;
     const int64_t d = cfg.d;
     c->sign_fused = false;
+    c->sign_defer = c->sign_w_deferred = c->sign_s_deferred = false;
+    c->sign_prev_w = c->sign_prev_s = nullptr;
     c->sign_tb_mem = nullptr;
     c->sign_partials = nullptr;
     std::vector<int64_t> seg_off;
@@ -451,6 +471,11 @@ ds_status_t ds_sign_init(ds_ctx *c)
     c->sign_tb.n_seg = static_cast<int32_t>(S);
     if (hipGetLastError() != hipSuccess) return DS_ERR_DEVICE;
     DS_HIP_TRY(hipMalloc(&c->sign_partials, sizeof(double) * n_pieces * static_cast<size_t>(cfg.n)));
+    if (cfg.flags & DS_FLAG_DEFERRED_ERROR) {
+        c->sign_defer = true;
+        DS_HIP_TRY(hipMalloc(&c->sign_prev_w, sizeof(float) * static_cast<size_t>(S) * cfg.n));
+        DS_HIP_TRY(hipMalloc(&c->sign_prev_s, sizeof(float) * static_cast<size_t>(S)));
+    }
     return DS_OK;
 }
 
@@ -458,6 +483,9 @@ void ds_sign_fini(ds_ctx *c)
 {
     if (c->sign_tb_mem) (void)hipFree(c->sign_tb_mem);
     if (c->sign_partials) (void)hipFree(c->sign_partials);
+    if (c->sign_prev_w) (void)hipFree(c->sign_prev_w);
+    if (c->sign_prev_s) (void)hipFree(c->sign_prev_s);
+    c->sign_prev_w = c->sign_prev_s = nullptr;
     c->sign_tb_mem = nullptr;
     c->sign_partials = nullptr;
 }
@@ -481,18 +509,22 @@ ds_status_t ds_sign_worker(ds_ctx *c, const void *g, int64_t gs, float *delta, i
         return ds_launch_status();
     }
     dim3 grid(static_cast<unsigned>(c->n_tiles), static_cast<unsigned>(cfg.n));
-    if (bf16) {
-        WorkerSrc<true> src{g, gs, delta, dstr};
-        k_sign_pass1_worker<true><<<grid, kBlock, 0, st>>>(src, delta, cfg.d, out->sign_words, c->W, c->sign_tb,
-                                                           c->sign_partials);
-    } else {
-        WorkerSrc<false> src{g, gs, delta, dstr};
-        k_sign_pass1_worker<false><<<grid, kBlock, 0, st>>>(src, delta, cfg.d, out->sign_words, c->W, c->sign_tb,
-                                                            c->sign_partials);
-    }
+    const bool deferred = c->sign_defer && c->sign_w_deferred;
+    auto pass1 = [&](auto bf, auto df) {
+        constexpr bool BF = decltype(bf)::value, DF = decltype(df)::value;
+        WorkerSrc<BF> src{g, gs, delta, dstr};
+        k_sign_pass1_worker<BF, DF><<<grid, kBlock, 0, st>>>(src, delta, cfg.d, out->sign_words, c->W, c->sign_tb,
+                                                             c->sign_partials, c->sign_prev_w, c->S);
+    };
+    if (bf16) { if (deferred) pass1(std::true_type{}, std::true_type{}); else pass1(std::true_type{}, std::false_type{}); }
+    else { if (deferred) pass1(std::false_type{}, std::true_type{}); else pass1(std::false_type{}, std::false_type{}); }
     k_sign_reduce<<<dim3(static_cast<unsigned>(c->S), static_cast<unsigned>(cfg.n)), kBlock, 0, st>>>(
-        c->sign_partials, c->sign_tb, out->scales, c->S);
-    k_sign_pass2<<<grid, kBlock, 0, st>>>(delta, dstr, cfg.d, out->scales, c->S, c->sign_tb);
+        c->sign_partials, c->sign_tb, out->scales, c->S, c->sign_defer ? c->sign_prev_w : nullptr);
+    if (c->sign_defer) {
+        c->sign_w_deferred = true;   // the buffer now holds v; delta = v - Q[v] is applied by the next load
+    } else {
+        k_sign_pass2<<<grid, kBlock, 0, st>>>(delta, dstr, cfg.d, out->scales, c->S, c->sign_tb);
+    }
     return ds_launch_status();
 }
 
@@ -509,10 +541,37 @@ ds_status_t ds_sign_server(ds_ctx *c, const ds_payload_t *in, float *delta_s, co
         return ds_launch_status();
     }
     dim3 grid(static_cast<unsigned>(c->n_tiles));
-    k_sign_pass1_server<<<grid, kBlock, 0, st>>>(a, delta_s, cfg.d, out->sign_words, c->sign_tb, c->sign_partials);
-    k_sign_reduce<<<dim3(static_cast<unsigned>(c->S), 1), kBlock, 0, st>>>(c->sign_partials, c->sign_tb,
-                                                                          out->scales, c->S);
-    k_sign_pass2<<<grid, kBlock, 0, st>>>(delta_s, cfg.d, cfg.d, out->scales, c->S, c->sign_tb);
+    if (c->sign_defer && c->sign_s_deferred)
+        k_sign_pass1_server<true><<<grid, kBlock, 0, st>>>(a, delta_s, cfg.d, out->sign_words, c->sign_tb, c->sign_partials,
+                                                           c->sign_prev_s);
+    else
+        k_sign_pass1_server<false><<<grid, kBlock, 0, st>>>(a, delta_s, cfg.d, out->sign_words, c->sign_tb, c->sign_partials,
+                                                            nullptr);
+    k_sign_reduce<<<dim3(static_cast<unsigned>(c->S), 1), kBlock, 0, st>>>(c->sign_partials, c->sign_tb, out->scales, c->S,
+                                                                          c->sign_defer ? c->sign_prev_s : nullptr);
+    if (c->sign_defer) {
+        c->sign_s_deferred = true;
+    } else {
+        k_sign_pass2<<<grid, kBlock, 0, st>>>(delta_s, cfg.d, cfg.d, out->scales, c->S, c->sign_tb);
+    }
+    return ds_launch_status();
+}
+
+// Deferred error form -> plain form, in place; a no-op for buffers that are in plain form.
+ds_status_t ds_sign_materialize(ds_ctx *c, float *delta, int64_t dstr, float *delta_s, hipStream_t st)
+{
+    const ds_config_t &cfg = c->cfg;
+    if (!c->sign_defer) return DS_OK;
+    if (delta && c->sign_w_deferred) {
+        k_sign_pass2<<<dim3(static_cast<unsigned>(c->n_tiles), static_cast<unsigned>(cfg.n)), kBlock, 0, st>>>(
+            delta, dstr, cfg.d, c->sign_prev_w, c->S, c->sign_tb);
+        c->sign_w_deferred = false;
+    }
+    if (delta_s && c->sign_s_deferred) {
+        k_sign_pass2<<<dim3(static_cast<unsigned>(c->n_tiles)), kBlock, 0, st>>>(delta_s, cfg.d, cfg.d, c->sign_prev_s, c->S,
+                                                                                c->sign_tb);
+        c->sign_s_deferred = false;
+    }
     return ds_launch_status();
 }
 

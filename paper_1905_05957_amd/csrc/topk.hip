@@ -4,8 +4,7 @@
 // resolved towards the lower index.
 //
 // Selection is exact and deterministic: a radix select on the 31-bit magnitude pattern
-// key = bits(v) & 0x7FFFFFFF in 12 + 11 + 8 bits, arranged so that the dense vector is
-// looked at ONCE:
+// key = bits(v) & 0x7FFFFFFF, arranged so that the dense vector is looked at ONCE:
 //   sample     512 evenly spread 256-element subtiles of v are histogrammed: 12 key bits,
 //              and 20 key bits inside a one-octave window around the threshold key of the
 //              previous call (kept per row in the context; the result never depends on it).
@@ -13,22 +12,26 @@
 //              lo_key for the k-th key with overwhelming probability.  The fine window
 //              matters: error feedback piles values up just below the threshold, and a
 //              12-bit bin edge would let in up to twice as many candidates.
-//   pass 1     (dense, the one HBM pass) v is formed and written into the error buffer;
-//              every element with key >= lo_key becomes a candidate (index, value).
-//              Each wavefront compacts the candidates of its own 256-element subtile, in
-//              index order, into that subtile's fixed slot region: no shared counters, no
-//              LDS, no barriers.
-//   hist 1..3  over the candidates only (about 1.5 k of them): 12, 11, 8 key bits, each
-//              followed by a pick of the bin that holds the k-th key -> exact threshold key
-//              T and the number of ties at T to keep.
-//   verify     if the candidates number fewer than k (the sample misjudged), the row falls
-//              back to the exact two-look route: dense 12-bit histogram of the stored v,
-//              pick, dense compaction.  Those kernels exit at once for rows that need none.
-//   count / scan / emit   per 32768-element group, in order: entries above T plus the first
-//              ties by index are written at scanned offsets, so the output is sorted by
-//              index without a sort; kept positions of the error buffer are zeroed
-//              (delta = v - Q[v] is 0 there and v elsewhere).
-// Nothing depends on scheduling order, so results are bit-reproducible.
+//   pass 1     (dense, the one HBM pass) v is formed and written into the error buffer, with
+//              0 at the positions of candidates = elements with key >= lo_key.  A workgroup
+//              compacts the candidates of its 2048-element tile, in index order, into the
+//              tile's fixed slot region (ballots, wavefront totals through LDS): no shared
+//              counters.
+//   refine     over the candidates only (about 1.2 k of them): histograms relative to lo_key,
+//              each followed by a pick of the bin that holds the k-th key -> exact threshold
+//              key T and the number of ties at T to keep; then, per 32768-element group in
+//              order, entries above T plus the first ties by index are written at offsets
+//              from running sums over the groups, so the output is sorted by index without a
+//              sort, and candidates that are not kept get v back in the error buffer
+//              (delta = v - Q[v] is 0 at kept positions and v elsewhere).
+//   verify     if the candidates number fewer than k, or the k-th key lies outside the
+//              histogram window (the sample misjudged), the row takes the exact two-look
+//              route: v restored, dense 12-bit histogram, pick, dense compaction.
+// The refinement exists twice: as ONE launch whose workgroups are all resident and wait for
+// each other per row (k_topk_finish, the default), and as a chain of small launches in which
+// the last workgroup of a row finishes each step (12 + 11 + 8 key bits), for contexts whose
+// calls may overlap on the device.  Nothing depends on scheduling order, so results are
+// bit-reproducible and the two routes agree bit for bit.
 #include "ds_device.h"
 #include "ds_internal.h"
 

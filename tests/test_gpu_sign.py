@@ -131,3 +131,91 @@ def test_same_call_twice_is_bit_identical(gpu_device):
     for k in outs[0][1]:
         assert np.array_equal(outs[0][1][k], outs[1][1][k])
     assert np.array_equal(outs[0][2], outs[1][2]) and np.array_equal(outs[0][3], outs[1][3])
+
+
+# ---------------------------------------------------------------------------------------
+# deferred error form (ds_config_t::flags & DS_FLAG_DEFERRED_ERROR)
+# ---------------------------------------------------------------------------------------
+def _deferred_workloads():
+    many = np.concatenate([[0], np.cumsum(np.random.default_rng(5).integers(1, 3000, 90))]).astype(np.int64)
+    return [
+        W.c2(d=1_117_398, n=4, n_seg=62, lo=64),
+        _sign_wl(3 * 2048 + 37, scale_mode="whole"),
+        _sign_wl(9001, scale_mode="chunk", chunk=320),
+        _sign_wl(int(many[-1]), scale_mode="segments", seg_offsets=many, seg_sigma=np.full(90, 1e-2),
+                 dist="segment_normal", grad_dtype="bf16", beta=0.9),
+    ]
+
+
+@pytest.mark.parametrize("wl", _deferred_workloads(), ids=lambda w: w.name + "_" + w.scale_mode)
+def test_sign_deferred_error_equals_plain_form(gpu_device, wl):
+    """The same steps on a plain and on a deferred context: every message and x (m) must be
+    bit-identical at every step, and so must the errors once materialised -- also when the
+    buffers are materialised in the middle of the run.  The plain form is what the other
+    tests compare with the oracle call by call."""
+    import parity_util
+    import paper_1905_05957_amd as P
+    plain = Pair(wl, gpu_device)
+    parity_util.CONTEXT_FLAGS = P.FLAG_DEFERRED_ERROR
+    try:
+        lazy = Pair(wl, gpu_device)
+    finally:
+        parity_util.CONTEXT_FLAGS = 0
+    try:
+        gs = [wl.gradients(s, gpu_device) for s in range(2)]
+        for t in range(6):
+            plain.gpu_step(t, gs[t % 2])
+            lazy.gpu_step(t, gs[t % 2])
+            for name, a in plain.pw.tensors().items():
+                assert torch.equal(a, lazy.pw.tensors()[name]), f"{wl.name} t={t} worker {name}"
+            for name, a in plain.ps.tensors().items():
+                assert torch.equal(a, lazy.ps.tensors()[name]), f"{wl.name} t={t} server {name}"
+            assert torch.equal(plain.x, lazy.x)
+            if plain.m is not None:
+                assert torch.equal(plain.m, lazy.m)
+            if t == 2:
+                lazy.ctx.materialize_error(lazy.delta, None)          # workers only; the server stays deferred
+                assert torch.equal(plain.delta, lazy.delta)
+                assert not torch.equal(plain.delta_s, lazy.delta_s)   # still holds v, not delta
+            if t == 3:
+                lazy.ctx.materialize_error(None, lazy.delta_s)
+                assert torch.equal(plain.delta_s, lazy.delta_s)
+        lazy.ctx.materialize_error(lazy.delta, lazy.delta_s)
+        assert torch.equal(plain.delta, lazy.delta) and torch.equal(plain.delta_s, lazy.delta_s)
+        lazy.ctx.materialize_error(lazy.delta, lazy.delta_s)          # a second time: nothing left to do
+        assert torch.equal(plain.delta, lazy.delta) and torch.equal(plain.delta_s, lazy.delta_s)
+    finally:
+        plain.close()
+        lazy.close()
+
+
+def test_sign_deferred_error_against_oracle(gpu_device):
+    """Two free-running steps in deferred form against two free-running oracle steps."""
+    import parity_util
+    import paper_1905_05957_amd as P
+    from parity_util import host_grad, oracle_config, assert_payload_equal
+    wl = W.c2(d=300_001, n=3, n_seg=17, lo=64)
+    parity_util.CONTEXT_FLAGS = P.FLAG_DEFERRED_ERROR
+    try:
+        pair = Pair(wl, gpu_device)
+    finally:
+        parity_util.CONTEXT_FLAGS = 0
+    try:
+        cfg = oracle_config(wl)
+        h_delta = pair.delta.cpu().numpy().copy()
+        h_ds = pair.delta_s.cpu().numpy().copy()
+        h_x = pair.x.cpu().numpy().copy()
+        for t in range(2):
+            g = wl.gradients(t, gpu_device)
+            pair.gpu_step(t, g)
+            ref_w = O.worker_compress(cfg, t, host_grad(g), h_delta)
+            ref_s = O.server_aggregate_compress(cfg, t, ref_w, h_ds)
+            O.apply_update(cfg, ref_s, h_x, None, wl.gamma)
+        assert_payload_equal(pair.pw.to_numpy(), ref_w, "deferred worker t=1")
+        assert_payload_equal(pair.ps.to_numpy(), ref_s, "deferred server t=1")
+        pair.ctx.materialize_error(pair.delta, pair.delta_s)
+        assert_close_rows(pair.delta.cpu().numpy(), h_delta, "deferred delta")
+        assert_close_rows(pair.delta_s.cpu().numpy(), h_ds, "deferred delta_s")
+        assert_close_rows(pair.x.cpu().numpy(), h_x, "deferred x")
+    finally:
+        pair.close()
