@@ -100,6 +100,7 @@ struct ds_topk_scratch {
     char *sync;           // [rows][kSyncStride] arrival counters and published picks
     uint32_t *abort_host; // pinned host word, raised by a kernel that gave up waiting
     int64_t capacity;     // workgroups of k_topk_finish the device holds at once; 0: route off
+    uint32_t spin_limit;  // polls a workgroup of k_topk_finish spends on one wait before it gives up
 };
 
 namespace {
@@ -826,7 +827,7 @@ constexpr int kFOffA = 0, kFOffA2 = kHA, kFOffB = 2 * kHA, kFOffD = 2 * kHA + kH
 constexpr int kFRow = 2 * kHA + kHB + kH1;     // words per row of the fused route's histograms
 enum { kResA = 0, kResD = 1, kResA2 = 2, kResB = 3, kResCompact = 4, kResCount = 5, kResSlots = 6 };
 constexpr int kSyncStride = 256;   // bytes of synchronisation memory per row: the counter in the first 128-byte line, the published words in the second
-constexpr uint32_t kSpinLimit = 1u << 22;
+constexpr uint32_t kSpinLimit = 1u << 22;     // polls per wait before a workgroup gives up (seconds)
 constexpr uint64_t kResValid = 1ull << 63;
 
 struct RowSync {
@@ -836,6 +837,7 @@ struct RowSync {
     uint32_t *sh;          // 3 LDS words
     uint32_t G;            // workgroups per row
     uint32_t rounds;       // arrival rounds so far (the same in every workgroup of the row)
+    uint32_t spin_limit;   // polls per wait
 };
 
 __device__ __forceinline__ void raise_abort(uint32_t *abort_flag)
@@ -875,7 +877,7 @@ __device__ __forceinline__ bool row_wait_result(RowSync &rs, int slot, uint32_t 
             v = __hip_atomic_load(rs.res + slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (v & kResValid) break;
             __builtin_amdgcn_s_sleep(1);
-            if (spins > kSpinLimit) { ok = 0u; raise_abort(rs.abort_flag); break; }
+            if (spins >= rs.spin_limit) { ok = 0u; raise_abort(rs.abort_flag); break; }
         }
         const uint32_t enc = static_cast<uint32_t>(v >> 32) & 0x7FFFFFFFu;
         rs.sh[0] = ok;
@@ -942,6 +944,7 @@ struct FinishArgs {
     uint32_t *fhist;       // [rows][kFRow], zero on entry
     char *sync;            // [rows][kSyncStride] arrival counter and published words, zero on entry
     uint32_t *abort_flag;
+    uint32_t spin_limit;
     uint32_t *grp_gt, *grp_eq;
     uint32_t *prev_T;
     float *buf;
@@ -958,7 +961,7 @@ __global__ __launch_bounds__(kBlock, 8) void k_topk_finish(FinishArgs a)
     const int row = blockIdx.y;
     const uint32_t G = gridDim.x;
     RowSync rs{reinterpret_cast<uint32_t *>(a.sync + row * kSyncStride), reinterpret_cast<uint64_t *>(a.sync + row * kSyncStride + 128),
-               a.abort_flag, sh, G, 0u};
+               a.abort_flag, sh, G, 0u, a.spin_limit};
     uint32_t *fh = a.fhist + static_cast<int64_t>(row) * kFRow;
     u32x2 *srow = a.slots + static_cast<int64_t>(row) * a.n_reg * kReg;
     uint32_t *cnt_row = a.reg_cnt + row * a.reg_pad;
@@ -1186,7 +1189,7 @@ ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t 
         FinishArgs a;
         a.slots = t->slots; a.reg_cnt = t->reg_cnt;
         a.n_reg = n_reg; a.reg_pad = reg_pad; a.n_groups = n_groups; a.n_sub = n_sub;
-        a.sel = t->sel; a.fhist = fh; a.sync = t->sync; a.abort_flag = t->abort_host;
+        a.sel = t->sel; a.fhist = fh; a.sync = t->sync; a.abort_flag = t->abort_host; a.spin_limit = t->spin_limit;
         a.grp_gt = t->grp_gt; a.grp_eq = t->grp_eq; a.prev_T = prev_T;
         a.buf = buf; a.stride = stride; a.d = d; a.k = k; a.pairs = pairs;
         a.zero_a = hist_next; a.zero_a_words = static_cast<int64_t>(t->rows) * kHistRow;
@@ -1256,6 +1259,13 @@ ds_status_t ds_topk_init(ds_ctx *c)
         t->capacity = static_cast<int64_t>(per_cu) * cus;
         // DS_TOPK_RESIDENT_LIMIT caps the workgroups the single launch uses, for devices that
         // are shared with other work
+        // DS_TOPK_SPIN_LIMIT: polls per wait (tests set 0 to see the give-up path: every wait
+        // that is not satisfied at once then fails, and every workgroup still exits)
+        t->spin_limit = kSpinLimit;
+        if (const char *sp = getenv("DS_TOPK_SPIN_LIMIT")) {
+            const long v = strtol(sp, nullptr, 10);
+            if (v >= 0 && v < static_cast<long>(kSpinLimit)) t->spin_limit = static_cast<uint32_t>(v);
+        }
         if (const char *lim = getenv("DS_TOPK_RESIDENT_LIMIT")) {
             const long v = strtol(lim, nullptr, 10);
             if (v >= 0 && v < t->capacity) t->capacity = v;

@@ -50,6 +50,28 @@ def test_topk_few_resident_workgroups(gpu_device, monkeypatch):
     _run(_wl(100 * 32768 + 999, n=3), gpu_device, steps=3)
 
 
+def test_topk_single_launch_gives_up_cleanly(gpu_device, monkeypatch, topk_route):
+    """Failure handling of the single-launch refinement, forced from the host: with a poll
+    budget of zero every wait that is not satisfied at once fails, so workgroups give up;
+    every kernel must still finish, and the context must report the failure from then on."""
+    if topk_route != "single_launch":
+        pytest.skip("the chain of launches has no waits")
+    monkeypatch.setenv("DS_TOPK_SPIN_LIMIT", "0")
+    wl = _wl(1 << 20, n=4)
+    pair = Pair(wl, gpu_device)
+    try:
+        g = wl.gradients(0, gpu_device)
+        with pytest.raises(P.DsError) as err:
+            for t in range(4):
+                pair.gpu_step(t, g)
+                torch.cuda.synchronize()          # must return: all workgroups exited
+        assert err.value.code == 6                # DS_ERR_DEVICE
+        with pytest.raises(P.DsError):
+            pair.ctx.worker_compress(9, g, pair.delta, pair.pw)
+    finally:
+        pair.close()
+
+
 def test_topk_all_zero_and_all_equal(gpu_device):
     d, n, k = 3 * 2048 + 5, 2, 77
     wl = _wl(d, n=n, k=k)
