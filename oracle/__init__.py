@@ -14,6 +14,9 @@ A message ("payload") is a dict of numpy arrays, one leading row axis:
   TOPK     : idx [rows, k] int32 (ascending), val [rows, k] float32
   QSGD     : levels [rows, ceil(d/2)] uint8, sign_words [rows, W] uint64, scales [rows, Bq]
   IDENTITY : dense [rows, d] float32
+  CLIP     : levels [rows, d*nb] uint8, the kept upper bits of every element (nb = 1, 2 or 4)
+  RSPARSE  : sign_words [rows, W] uint64 (bit = element kept), val [rows, d] float32 (the kept
+             values z/p packed in index order, zeros after them)
 """
 from __future__ import annotations
 
@@ -25,7 +28,7 @@ from typing import Optional
 
 import numpy as np
 
-IDENTITY, SIGN, TOPK, QSGD = 0, 1, 2, 3
+IDENTITY, SIGN, TOPK, QSGD, CLIP, RSPARSE = 0, 1, 2, 3, 4, 5
 SERVER_STREAM = 0xFFFFFFFF
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -50,7 +53,8 @@ class _Config(C.Structure):
     _fields_ = [("comp", C.c_int32), ("n", C.c_int32), ("d", C.c_int64),
                 ("grad_bf16", C.c_int32), ("n_groups", C.c_int32),
                 ("group_off", C.POINTER(C.c_int64)), ("k", C.c_int64),
-                ("bucket", C.c_int32), ("levels", C.c_int32), ("seed", C.c_uint64)]
+                ("bucket", C.c_int32), ("levels", C.c_int32), ("seed", C.c_uint64),
+                ("sign_rms", C.c_int32), ("clip_bits", C.c_int32), ("keep_prob", C.c_float)]
 
 
 class _Msg(C.Structure):
@@ -83,6 +87,18 @@ def lib():
         L.dso_qsgd_encode.restype = None
         L.dso_qsgd_decode.argtypes = [vp, vp, vp, i64, i32, i32, vp]
         L.dso_qsgd_decode.restype = None
+        L.dso_sign_encode_kind.argtypes = [vp, i64, vp, i32, i32, vp, vp]
+        L.dso_sign_encode_kind.restype = None
+        L.dso_clip_bytes.argtypes = [i32]
+        L.dso_clip_bytes.restype = C.c_int
+        L.dso_clip_encode.argtypes = [vp, i64, i32, vp]
+        L.dso_clip_encode.restype = None
+        L.dso_clip_decode.argtypes = [vp, i64, i32, vp]
+        L.dso_clip_decode.restype = None
+        L.dso_rsparse_encode.argtypes = [vp, i64, f32, u64, u64, u32, vp, vp]
+        L.dso_rsparse_encode.restype = None
+        L.dso_rsparse_decode.argtypes = [vp, vp, i64, vp]
+        L.dso_rsparse_decode.restype = None
         L.dso_worker_compress.argtypes = [vp, u64, vp, i64, vp, i64, vp]
         L.dso_worker_compress.restype = C.c_int
         L.dso_server_aggregate_compress.argtypes = [vp, u64, vp, vp, vp]
@@ -115,6 +131,9 @@ class Config:
     bucket: int = 512
     levels: int = 15
     seed: int = 0
+    sign_rms: bool = False                   # SIGN: root-mean-square scale instead of mean |v|
+    clip_bits: int = 16                      # CLIP: low bits set to zero
+    keep_prob: float = 1.0                   # RSPARSE: p
     _keep: list = field(default_factory=list, repr=False)
 
     def __post_init__(self):
@@ -142,7 +161,12 @@ class Config:
         if self.group_off is not None:
             go = self.group_off.ctypes.data_as(C.POINTER(C.c_int64))
         return _Config(self.comp, self.n, self.d, int(self.grad_bf16), self.n_groups, go,
-                       self.k, self.bucket, self.levels, self.seed)
+                       self.k, self.bucket, self.levels, self.seed, int(self.sign_rms),
+                       self.clip_bits, self.keep_prob)
+
+    @property
+    def clip_bytes(self) -> int:
+        return 1 if self.clip_bits >= 24 else 2 if self.clip_bits >= 16 else 4
 
 
 def chunk_offsets(d: int, chunk: int) -> np.ndarray:
@@ -164,6 +188,11 @@ def alloc_payload(cfg: Config, rows: int) -> dict:
         return {"levels": np.zeros((rows, (d + 1) // 2), np.uint8),
                 "sign_words": np.zeros((rows, cfg.n_words), np.uint64),
                 "scales": np.zeros((rows, cfg.n_buckets), np.float32)}
+    if cfg.comp == CLIP:
+        return {"levels": np.zeros((rows, d * cfg.clip_bytes), np.uint8)}
+    if cfg.comp == RSPARSE:
+        return {"sign_words": np.zeros((rows, cfg.n_words), np.uint64),
+                "val": np.zeros((rows, d), np.float32)}
     raise ValueError(cfg.comp)
 
 
@@ -243,6 +272,13 @@ def decode(cfg: Config, payload: dict, row: int = 0) -> np.ndarray:
         L.dso_qsgd_decode(payload["levels"][row].ctypes.data, payload["sign_words"][row].ctypes.data,
                           payload["scales"][row].ctypes.data, d, cfg.bucket, cfg.levels,
                           q.ctypes.data)
+    elif cfg.comp == CLIP:
+        L.dso_clip_decode(payload["levels"][row].ctypes.data, d, cfg.clip_bits, q.ctypes.data)
+    elif cfg.comp == RSPARSE:
+        L.dso_rsparse_decode(payload["sign_words"][row].ctypes.data, payload["val"][row].ctypes.data,
+                             d, q.ctypes.data)
+    else:
+        raise ValueError(cfg.comp)
     return q
 
 
@@ -255,8 +291,9 @@ def encode(cfg: Config, step: int, stream: int, v: np.ndarray) -> dict:
     if cfg.comp == IDENTITY:
         out["dense"][0] = v
     elif cfg.comp == SIGN:
-        L.dso_sign_encode(v.ctypes.data, cfg.d, cfg.group_off.ctypes.data, cfg.n_groups,
-                          out["sign_words"].ctypes.data, out["scales"].ctypes.data)
+        L.dso_sign_encode_kind(v.ctypes.data, cfg.d, cfg.group_off.ctypes.data, cfg.n_groups,
+                               int(cfg.sign_rms), out["sign_words"].ctypes.data,
+                               out["scales"].ctypes.data)
     elif cfg.comp == TOPK:
         _rc(L.dso_topk_encode(v.ctypes.data, cfg.d, cfg.k, out["idx"].ctypes.data,
                               out["val"].ctypes.data), "topk_encode")
@@ -264,6 +301,13 @@ def encode(cfg: Config, step: int, stream: int, v: np.ndarray) -> dict:
         L.dso_qsgd_encode(v.ctypes.data, cfg.d, cfg.bucket, cfg.levels, cfg.seed, step, stream,
                           out["levels"].ctypes.data, out["sign_words"].ctypes.data,
                           out["scales"].ctypes.data)
+    elif cfg.comp == CLIP:
+        L.dso_clip_encode(v.ctypes.data, cfg.d, cfg.clip_bits, out["levels"].ctypes.data)
+    elif cfg.comp == RSPARSE:
+        L.dso_rsparse_encode(v.ctypes.data, cfg.d, np.float32(cfg.keep_prob), cfg.seed, step, stream,
+                             out["sign_words"].ctypes.data, out["val"].ctypes.data)
+    else:
+        raise ValueError(cfg.comp)
     return out
 
 

@@ -12,7 +12,8 @@
  *     workers  : x  <- x - gamma * Q[v]
  *   Section 3.2 / Section 5.1 give the compressors Q: 1-bit (sign + scale so that the
  *   recovered vector has the magnitude of the compensated one), top-k by absolute
- *   value, and two-point unbiased randomised quantisation.
+ *   value, two-point unbiased randomised quantisation, clipping of low bits and
+ *   randomised sparsification.
  *
  * Every function follows the algorithm's steps in the paper's order: form v, encode,
  * decode, subtract.  The error buffers are always computed as "v minus the decoded
@@ -46,6 +47,8 @@
 #define DSO_SIGN 1
 #define DSO_TOPK 2
 #define DSO_QSGD 3
+#define DSO_CLIP 4
+#define DSO_RSPARSE 5
 
 #define DSO_SERVER_STREAM 0xFFFFFFFFu
 
@@ -59,16 +62,21 @@ typedef struct {
     int64_t k;              /* TOPK */
     int32_t bucket;         /* QSGD: elements per bucket */
     int32_t levels;         /* QSGD: s, 1..15 */
-    uint64_t seed;          /* QSGD */
+    uint64_t seed;          /* QSGD, RSPARSE */
+    int32_t sign_rms;       /* SIGN: 1 = scale is the root mean square of the group (l2 reading) */
+    int32_t clip_bits;      /* CLIP: b, the number of low bits set to zero, 1..31 */
+    float keep_prob;        /* RSPARSE: p in (0, 1] */
 } dso_config;
 
 /* One message (one row).  Unused members are NULL. */
 typedef struct {
-    uint64_t *sign_words;   /* [ceil(d/64)]  bit (j&63) of word j>>6 = (v_j < 0), pad bits 0 */
+    uint64_t *sign_words;   /* [ceil(d/64)]  bit (j&63) of word j>>6 = (v_j < 0), pad bits 0;
+                               RSPARSE: the same plane holds "element j is kept" */
     float *scales;          /* SIGN: [n_groups] ; QSGD: [ceil(d/bucket)] bucket norms */
-    uint8_t *levels;        /* QSGD: [ceil(d/2)], element j in byte j>>1, low nibble if j even */
+    uint8_t *levels;        /* QSGD: [ceil(d/2)], element j in byte j>>1, low nibble if j even;
+                               CLIP: [d * nb] the kept upper bits, nb = 1, 2 or 4 bytes per element */
     int32_t *idx;           /* TOPK: [k] ascending */
-    float *val;             /* TOPK: [k] */
+    float *val;             /* TOPK: [k] ; RSPARSE: [d] kept values z/p packed in index order, then zeros */
     float *dense;           /* IDENTITY: [d] */
 } dso_msg;
 
@@ -130,6 +138,24 @@ static uint32_t f32_bits(float f)
  * 1-bit compressor (Section 3.2 "1-Bit Quantization", Section 5.1 "1-bit compression").
  * One scale per group so that the decoded group has the same l1 magnitude as v.
  * ---------------------------------------------------------------------------------- */
+/* rms = 0: scale = mean |v| (the l1 reading of "same magnitude", used everywhere by default).
+ * rms = 1: scale = sqrt(mean v^2), the l2 reading: the decoded group then has the l2 norm of
+ * v, which is what Section 3.2's "||x|| sign(x)" gives once it is normalised by sqrt(|G|). */
+void dso_sign_encode_kind(const float *v, int64_t d, const int64_t *group_off, int32_t n_groups,
+                          int32_t rms, uint64_t *words, float *scales)
+{
+    int64_t n_words = (d + 63) / 64;
+    for (int64_t w = 0; w < n_words; ++w) words[w] = 0;
+    for (int64_t j = 0; j < d; ++j)
+        if (v[j] < 0.0f) words[j >> 6] |= (uint64_t)1 << (j & 63);
+    for (int32_t s = 0; s < n_groups; ++s) {
+        double sum = 0.0, len = (double)(group_off[s + 1] - group_off[s]);
+        for (int64_t j = group_off[s]; j < group_off[s + 1]; ++j)
+            sum += rms ? (double)v[j] * (double)v[j] : (double)fabsf(v[j]);
+        scales[s] = rms ? (float)sqrt(sum / len) : (float)(sum / len);
+    }
+}
+
 void dso_sign_encode(const float *v, int64_t d, const int64_t *group_off, int32_t n_groups,
                      uint64_t *words, float *scales)
 {
@@ -253,6 +279,66 @@ void dso_qsgd_decode(const uint8_t *levels, const uint64_t *words, const float *
 }
 
 /* ------------------------------------------------------------------------------------
+ * Clipping (Section 3.2 "Clipping"): the lower b bits of the number's binary
+ * representation are set to zero.  The message keeps the remaining upper 32-b bits of every
+ * element, in the smallest of 1, 2 or 4 bytes that holds them (b >= 24, b >= 16, otherwise),
+ * little endian.  b = 16 is the truncation of fp32 to the bf16 grid.
+ * ---------------------------------------------------------------------------------- */
+int dso_clip_bytes(int32_t b) { return b >= 24 ? 1 : b >= 16 ? 2 : 4; }
+
+void dso_clip_encode(const float *v, int64_t d, int32_t b, uint8_t *out)
+{
+    int nb = dso_clip_bytes(b);
+    uint32_t mask = ~(uint32_t)(((uint64_t)1 << b) - 1u);
+    for (int64_t j = 0; j < d; ++j) {
+        uint32_t top = (f32_bits(v[j]) & mask) >> (32 - 8 * nb);
+        for (int t = 0; t < nb; ++t) out[j * nb + t] = (uint8_t)(top >> (8 * t));
+    }
+}
+
+void dso_clip_decode(const uint8_t *in, int64_t d, int32_t b, float *q)
+{
+    int nb = dso_clip_bytes(b);
+    for (int64_t j = 0; j < d; ++j) {
+        uint32_t top = 0;
+        for (int t = 0; t < nb; ++t) top |= (uint32_t)in[j * nb + t] << (8 * t);
+        uint32_t u = top << (32 - 8 * nb);
+        float f;
+        memcpy(&f, &u, sizeof f);
+        q[j] = f;
+    }
+}
+
+/* ------------------------------------------------------------------------------------
+ * Randomised sparsification (Section 3.2 "Randomized Sparsification"): every element is
+ * kept with probability p and then scaled to z/p, and set to zero otherwise, which makes the
+ * operator unbiased.  (The section's sentence gives p for both outcomes; the zero outcome
+ * has probability 1 - p.)  Element j is kept iff its uniform (the same counter-based stream
+ * as the quantiser's) is below p.  The message is the plane of "kept" bits and the kept
+ * values z/p (one fp32 division) packed in index order.
+ * ---------------------------------------------------------------------------------- */
+void dso_rsparse_encode(const float *v, int64_t d, float p, uint64_t seed, uint64_t step, uint32_t stream,
+                        uint64_t *keep_words, float *vals)
+{
+    int64_t n_words = (d + 63) / 64, r = 0;
+    for (int64_t w = 0; w < n_words; ++w) keep_words[w] = 0;
+    for (int64_t j = 0; j < d; ++j) vals[j] = 0.0f;
+    for (int64_t j = 0; j < d; ++j) {
+        if (dso_uniform24(seed, step, stream, j) < p) {
+            keep_words[j >> 6] |= (uint64_t)1 << (j & 63);
+            vals[r++] = v[j] / p;
+        }
+    }
+}
+
+void dso_rsparse_decode(const uint64_t *keep_words, const float *vals, int64_t d, float *q)
+{
+    int64_t r = 0;
+    for (int64_t j = 0; j < d; ++j)
+        q[j] = ((keep_words[j >> 6] >> (j & 63)) & 1u) ? vals[r++] : 0.0f;
+}
+
+/* ------------------------------------------------------------------------------------
  * Q[.] and its decoder, selected by the configuration.
  * ---------------------------------------------------------------------------------- */
 int dso_encode(const dso_config *c, uint64_t step, uint32_t stream, const float *v, dso_msg *m)
@@ -262,13 +348,21 @@ int dso_encode(const dso_config *c, uint64_t step, uint32_t stream, const float 
         for (int64_t j = 0; j < c->d; ++j) m->dense[j] = v[j];
         return 0;
     case DSO_SIGN:
-        dso_sign_encode(v, c->d, c->group_off, c->n_groups, m->sign_words, m->scales);
+        dso_sign_encode_kind(v, c->d, c->group_off, c->n_groups, c->sign_rms, m->sign_words, m->scales);
         return 0;
     case DSO_TOPK:
         return dso_topk_encode(v, c->d, c->k, m->idx, m->val);
     case DSO_QSGD:
         dso_qsgd_encode(v, c->d, c->bucket, c->levels, c->seed, step, stream, m->levels,
                         m->sign_words, m->scales);
+        return 0;
+    case DSO_CLIP:
+        if (c->clip_bits < 1 || c->clip_bits > 31) return 3;
+        dso_clip_encode(v, c->d, c->clip_bits, m->levels);
+        return 0;
+    case DSO_RSPARSE:
+        if (!(c->keep_prob > 0.0f && c->keep_prob <= 1.0f)) return 3;
+        dso_rsparse_encode(v, c->d, c->keep_prob, c->seed, step, stream, m->sign_words, m->val);
         return 0;
     }
     return 3;
@@ -288,6 +382,12 @@ int dso_decode(const dso_config *c, const dso_msg *m, float *q)
         return 0;
     case DSO_QSGD:
         dso_qsgd_decode(m->levels, m->sign_words, m->scales, c->d, c->bucket, c->levels, q);
+        return 0;
+    case DSO_CLIP:
+        dso_clip_decode(m->levels, c->d, c->clip_bits, q);
+        return 0;
+    case DSO_RSPARSE:
+        dso_rsparse_decode(m->sign_words, m->val, c->d, q);
         return 0;
     }
     return 3;
