@@ -72,7 +72,7 @@ def _per_element(seg_off: np.ndarray, per_seg: np.ndarray, device) -> torch.Tens
 class Workload:
     """Shape and data recipe of one configuration."""
     name: str
-    comp: str                      # 'identity' | 'sign' | 'topk' | 'qsgd'
+    comp: str                      # 'identity' | 'sign' | 'topk' | 'qsgd' | 'clip' | 'rsparse'
     n: int
     d: int
     grad_dtype: str = "f32"        # 'f32' | 'bf16'
@@ -83,7 +83,10 @@ class Workload:
     k: int = 0
     bucket: int = 512
     levels: int = 15
-    seed: int = RNG_SEED           # Philox seed of the stochastic quantiser
+    seed: int = RNG_SEED           # Philox seed of the stochastic quantiser / sparsifier
+    sign_rms: bool = False         # sign: root-mean-square scale instead of mean |v|
+    clip_bits: int = 16            # clip: low bits set to zero
+    keep_prob: float = 1.0         # rsparse: probability of keeping an element
     gamma: float = 0.05
     beta: Optional[float] = None   # momentum coefficient, None = plain SGD
     dist: str = "normal"           # 'normal' | 'student_t3' | 'laplace_outliers' | 'segment_normal'

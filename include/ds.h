@@ -94,8 +94,12 @@ typedef enum {
  * the plain form).  The caller must pass the same logical buffers to consecutive calls and
  * call ds_materialize_error before it reads, copies, checkpoints or edits them.  Contexts for
  * which the flag has no effect (other compressors, chunk scales handled in one pass) ignore
- * it. */
-typedef enum { DS_FLAG_TOPK_MULTI_LAUNCH = 1, DS_FLAG_DEFERRED_ERROR = 2 } ds_flags_t;
+ * it.
+ *
+ * DS_FLAG_SIGN_RMS: the SIGN scale of a group is sqrt(mean v^2) instead of mean |v|: the l2
+ * reading of Section 3.2's "norm times sign vector" (the decoded group then has the l2 norm
+ * of v; with mean |v| it has its l1 norm). */
+typedef enum { DS_FLAG_TOPK_MULTI_LAUNCH = 1, DS_FLAG_DEFERRED_ERROR = 2, DS_FLAG_SIGN_RMS = 4 } ds_flags_t;
 
 typedef struct {
     int32_t comp;             /* ds_compressor_t */
@@ -125,7 +129,8 @@ typedef struct { int32_t idx; float val; } ds_pair_t;
  * W = ceil(d/64), Bq = ceil(d/bucket).  Sizes come from ds_payload_sizes.
  *   SIGN     sign_words [rows, W]: bit (j & 63) of word (j >> 6) is (v_j < 0), so zero and
  *            negative zero carry bit 0; bits past d are 0.   scales [rows, S]: mean |v|
- *            of each group.  Decoded element: bit ? -scale : +scale.
+ *            of each group (root mean square with DS_FLAG_SIGN_RMS).  Decoded element:
+ *            bit ? -scale : +scale.
  *   QSGD     levels [rows, ceil(d/2)]: 4-bit code of element j in byte j >> 1, low nibble
  *            for even j; sign_words as above; scales [rows, Bq]: L2 norm of each bucket.
  *            Decoded element: +-(code * (norm / s)).

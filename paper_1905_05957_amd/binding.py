@@ -18,6 +18,7 @@ SCALE_WHOLE, SCALE_SEGMENTS, SCALE_CHUNK = 0, 1, 2
 F32, BF16 = 0, 1
 FLAG_TOPK_MULTI_LAUNCH = 1
 FLAG_DEFERRED_ERROR = 2
+FLAG_SIGN_RMS = 4
 
 _COMP = {"identity": COMP_IDENTITY, "sign": COMP_SIGN, "topk": COMP_TOPK, "qsgd": COMP_QSGD}
 _MODE = {"whole": SCALE_WHOLE, "segments": SCALE_SEGMENTS, "chunk": SCALE_CHUNK}

@@ -17,6 +17,7 @@ struct ds_sign_tables {
     const int64_t *seg_off;           // [S + 1]
     int32_t n_pieces;
     int32_t n_seg;
+    bool rms;                         // group scale = root mean square instead of mean |v|
 };
 
 struct ds_topk_scratch;  // defined in topk.hip

@@ -65,10 +65,26 @@ __device__ __forceinline__ f32x4 chain4(f32x4 a, uint32_t nib, float s, float in
     return a;
 }
 
+// What a group sums to find its scale: |v| (scale = mean |v|, the l1 reading of "the same
+// magnitude", Section 5.1) or v^2 (scale = root mean square, the l2 reading of Section 3.2's
+// norm).  The product of two fp32 values is exact in fp64.
+// (A compile-time switch: as a run-time one it cost the 124 M-element step 4 %.)
+template <bool RMS>
+__device__ __forceinline__ double measure(float x)
+{
+    if constexpr (RMS) return static_cast<double>(x) * static_cast<double>(x);
+    else return static_cast<double>(fabsf(x));
+}
+
+template <bool RMS>
 __device__ __forceinline__ double abs_sum4(f32x4 v)
 {
-    return ((static_cast<double>(fabsf(v.x)) + static_cast<double>(fabsf(v.y))) +
-            static_cast<double>(fabsf(v.z))) + static_cast<double>(fabsf(v.w));
+    return ((measure<RMS>(v.x) + measure<RMS>(v.y)) + measure<RMS>(v.z)) + measure<RMS>(v.w);
+}
+
+__device__ __forceinline__ float group_scale(double total, double len, bool rms)
+{
+    return rms ? static_cast<float>(sqrt(total / len)) : static_cast<float>(total / len);
 }
 
 // delta' = v - Q[v] with Q[v]_j = (v_j < 0) ? -scale : +scale
@@ -86,6 +102,7 @@ __device__ __forceinline__ f32x4 sign_error4(f32x4 v, float s)
 // fused route: one workgroup per chunk
 // ---------------------------------------------------------------------------------------
 // Common tail: scale from the held values, sign plane, error, stores.
+template <bool RMS>
 __device__ __forceinline__ void fused_finish(f32x4 v, int64_t base, int64_t lim,
                                              float *__restrict__ err_row, bool err_vec,
                                              uint64_t *__restrict__ words_row, int64_t bit_lim,
@@ -93,15 +110,15 @@ __device__ __forceinline__ void fused_finish(f32x4 v, int64_t base, int64_t lim,
 {
     // sign words: gathered in LDS, one store per workgroup after the barrier of the reduction
     stash_sign_words(sw_lds, wave_sign_word(v.x < 0.f, v.y < 0.f, v.z < 0.f, v.w < 0.f));
-    const double total = block_sum(abs_sum4(v), lds, false);
-    const float scale = static_cast<float>(total / static_cast<double>(lim - base));
+    const double total = block_sum(abs_sum4<RMS>(v), lds, false);
+    const float scale = group_scale(total, static_cast<double>(lim - base), RMS);
     if (threadIdx.x == 0) *scale_out = scale;
     flush_sign_words(sw_lds, words_row, base, bit_lim);
     const int64_t e = base + threadIdx.x * 4;
     if (e < lim) st4(err_row, e, lim, err_vec, sign_error4(v, scale));
 }
 
-template <bool BF16>
+template <bool BF16, bool RMS>
 __global__ __launch_bounds__(kBlock) void k_sign_chunk_worker(WorkerSrc<BF16> src, float *delta,
                                                               int64_t d, int64_t chunk,
                                                               uint64_t *words, int64_t W,
@@ -119,11 +136,11 @@ __global__ __launch_bounds__(kBlock) void k_sign_chunk_worker(WorkerSrc<BF16> sr
     const bool dvec = aligned16(drow);
     const int64_t e = base + threadIdx.x * 4;
     const f32x4 v = ld4_grad<BF16>(grow, e, lim, gvec) + ld4(drow, e, lim, dvec);
-    fused_finish(v, base, lim, drow, dvec, words + row * W, (lim == d) ? W * 64 : lim,
-                 scales + row * S + ci, lds, sw_lds);
+    fused_finish<RMS>(v, base, lim, drow, dvec, words + row * W, (lim == d) ? W * 64 : lim,
+                      scales + row * S + ci, lds, sw_lds);
 }
 
-template <int CPW>   // chunks per workgroup: independent chunks, more bytes in flight per thread
+template <int CPW, bool RMS>   // CPW chunks per workgroup: independent chunks, more bytes in flight per thread
 __global__ __launch_bounds__(kBlock) void k_sign_chunk_server(ServerArgs a, float *delta_s, int64_t d,
                                                               int64_t chunk, uint64_t *words_out,
                                                               float *scales_out)
@@ -173,8 +190,8 @@ __global__ __launch_bounds__(kBlock) void k_sign_chunk_server(ServerArgs a, floa
         // components past lim must stay zero: they count in the sum of |v|
         v[c] = zero_past(v[c], base[c] + threadIdx.x * 4, lim[c]);
         if (base[c] < d)   // uniform over the workgroup
-            fused_finish(v[c], base[c], lim[c], delta_s, dvec, words_out, (lim[c] == d) ? a.W * 64 : lim[c],
-                         scales_out + ci, lds[c], sw_lds[c]);
+            fused_finish<RMS>(v[c], base[c], lim[c], delta_s, dvec, words_out, (lim[c] == d) ? a.W * 64 : lim[c],
+                              scales_out + ci, lds[c], sw_lds[c]);
     }
 }
 
@@ -206,9 +223,10 @@ __device__ __forceinline__ int32_t seg_of(const ds_sign_tables &tb, int32_t p0, 
     return tb.piece_seg[p];
 }
 
+template <bool RMS>
 __device__ __forceinline__ double masked_abs(float x, int64_t e, int64_t lo, int64_t hi)
 {
-    return (e >= lo && e < hi) ? static_cast<double>(fabsf(x)) : 0.0;
+    return (e >= lo && e < hi) ? measure<RMS>(x) : 0.0;
 }
 
 // v - Q[v] for the four elements of a thread, with the group scales of its tile's pieces.
@@ -226,7 +244,8 @@ __device__ __forceinline__ f32x4 sign_error_tile(f32x4 v, int64_t e, int64_t d, 
     return v;
 }
 
-// Pass-1 tail: store v, sign bits, per-piece partial sums of |v|.
+// Pass-1 tail: store v, sign bits, per-piece partial sums of |v| (or v^2).
+template <bool RMS>
 __device__ __forceinline__ void pass1_finish(f32x4 v, int64_t base, int64_t d,
                                              float *__restrict__ vrow, bool vvec,
                                              uint64_t *__restrict__ words_row, int64_t bit_lim,
@@ -237,7 +256,7 @@ __device__ __forceinline__ void pass1_finish(f32x4 v, int64_t base, int64_t d,
     if (e < d) st4(vrow, e, d, vvec, v);
     stash_sign_words(sw_lds, wave_sign_word(v.x < 0.f, v.y < 0.f, v.z < 0.f, v.w < 0.f));
     if (p1 - p0 == 1) {
-        const double total = block_sum(abs_sum4(v), lds, false);   // elements past d are zero
+        const double total = block_sum(abs_sum4<RMS>(v), lds, false);   // elements past d are zero
         if (threadIdx.x == 0) partial_row[p0] = total;
         flush_sign_words(sw_lds, words_row, base, bit_lim);
     } else {
@@ -245,8 +264,8 @@ __device__ __forceinline__ void pass1_finish(f32x4 v, int64_t base, int64_t d,
         flush_sign_words(sw_lds, words_row, base, bit_lim);
         for (int32_t p = p0; p < p1; ++p) {
             const int64_t lo = tb.piece_start[p], hi = tb.piece_start[p + 1];
-            const double part = ((masked_abs(v.x, e, lo, hi) + masked_abs(v.y, e + 1, lo, hi)) +
-                                 masked_abs(v.z, e + 2, lo, hi)) + masked_abs(v.w, e + 3, lo, hi);
+            const double part = ((masked_abs<RMS>(v.x, e, lo, hi) + masked_abs<RMS>(v.y, e + 1, lo, hi)) +
+                                 masked_abs<RMS>(v.z, e + 2, lo, hi)) + masked_abs<RMS>(v.w, e + 3, lo, hi);
             const double total = block_sum(part, lds, true);
             if (threadIdx.x == 0) partial_row[p] = total;
         }
@@ -256,7 +275,7 @@ __device__ __forceinline__ void pass1_finish(f32x4 v, int64_t base, int64_t d,
 // DEFERRED: the error buffer holds the previous call's v and `prev_scales` that call's group
 // scales; the error delta = v_prev - Q[v_prev] is formed on the fly (the same subtraction
 // pass 2 would have stored), so the buffer is looked at once per call.
-template <bool BF16, bool DEFERRED>
+template <bool BF16, bool DEFERRED, bool RMS>
 __global__ __launch_bounds__(kBlock) void k_sign_pass1_worker(WorkerSrc<BF16> src, float *delta,
                                                               int64_t d, uint64_t *words, int64_t W,
                                                               ds_sign_tables tb, double *partials,
@@ -276,11 +295,11 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass1_worker(WorkerSrc<BF16> sr
     f32x4 dl = ld4(drow, e, d, dvec);
     if (DEFERRED && e < d) dl = zero_past(sign_error_tile(dl, e, d, prev_scales + row * S, tb, p0, p1), e, d);
     const f32x4 v = ld4_grad<BF16>(grow, e, d, gvec) + dl;
-    pass1_finish(v, base, d, drow, dvec, words + row * W, W * 64, tb, p0, p1,
-                 partials + static_cast<int64_t>(row) * tb.n_pieces, lds, sw_lds);
+    pass1_finish<RMS>(v, base, d, drow, dvec, words + row * W, W * 64, tb, p0, p1,
+                      partials + static_cast<int64_t>(row) * tb.n_pieces, lds, sw_lds);
 }
 
-template <bool DEFERRED>
+template <bool DEFERRED, bool RMS>
 __global__ __launch_bounds__(kBlock) void k_sign_pass1_server(ServerArgs a, float *delta_s, int64_t d,
                                                               uint64_t *words_out, ds_sign_tables tb,
                                                               double *partials, const float *__restrict__ prev_scales)
@@ -327,7 +346,7 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass1_server(ServerArgs a, floa
         }
     }
     v = zero_past(v, e, d);
-    pass1_finish(v, base, d, delta_s, dvec, words_out, a.W * 64, tb, p0, p1, partials, lds, sw_lds);
+    pass1_finish<RMS>(v, base, d, delta_s, dvec, words_out, a.W * 64, tb, p0, p1, partials, lds, sw_lds);
 }
 
 // scale[row][s] = (float)( sum of the group's partials / |group| ), fixed order.
@@ -350,7 +369,7 @@ __global__ __launch_bounds__(kBlock) void k_sign_reduce(const double *__restrict
     }
     if (threadIdx.x == 0) {
         const double len = static_cast<double>(tb.seg_off[s + 1] - tb.seg_off[s]);
-        const float sc = static_cast<float>(lds[0] / len);
+        const float sc = group_scale(lds[0], len, tb.rms);
         scales[row * S + s] = sc;
         if (keep) keep[row * S + s] = sc;
     }
@@ -469,6 +488,7 @@ ds_status_t ds_sign_init(ds_ctx *c)
     c->sign_tb.seg_piece_first = static_cast<const int32_t *>(put(seg_piece_first.data(), b_spf));
     c->sign_tb.n_pieces = static_cast<int32_t>(n_pieces);
     c->sign_tb.n_seg = static_cast<int32_t>(S);
+    c->sign_tb.rms = (cfg.flags & DS_FLAG_SIGN_RMS) != 0;
     if (hipGetLastError() != hipSuccess) return DS_ERR_DEVICE;
     DS_HIP_TRY(hipMalloc(&c->sign_partials, sizeof(double) * n_pieces * static_cast<size_t>(cfg.n)));
     if (cfg.flags & DS_FLAG_DEFERRED_ERROR) {
@@ -490,34 +510,38 @@ void ds_sign_fini(ds_ctx *c)
     c->sign_partials = nullptr;
 }
 
+// Calls f with the run-time flags turned into compile-time constants (std::bool_constant).
+template <class F>
+static void with_flags(bool a, bool b, bool c, F f)
+{
+    auto l2 = [&](auto ta, auto tb) { if (c) f(ta, tb, std::true_type{}); else f(ta, tb, std::false_type{}); };
+    auto l1 = [&](auto ta) { if (b) l2(ta, std::true_type{}); else l2(ta, std::false_type{}); };
+    if (a) l1(std::true_type{}); else l1(std::false_type{});
+}
+
 ds_status_t ds_sign_worker(ds_ctx *c, const void *g, int64_t gs, float *delta, int64_t dstr,
                            const ds_payload_t *out, hipStream_t st)
 {
     const ds_config_t &cfg = c->cfg;
     const bool bf16 = cfg.grad_dtype == DS_BF16;
+    const bool rms = (cfg.flags & DS_FLAG_SIGN_RMS) != 0;
     if (c->sign_fused) {
         dim3 grid(static_cast<unsigned>(c->S), static_cast<unsigned>(cfg.n));
-        if (bf16) {
-            WorkerSrc<true> src{g, gs, delta, dstr};
-            k_sign_chunk_worker<true><<<grid, kBlock, 0, st>>>(src, delta, cfg.d, cfg.chunk, out->sign_words,
-                                                               c->W, out->scales, c->S);
-        } else {
-            WorkerSrc<false> src{g, gs, delta, dstr};
-            k_sign_chunk_worker<false><<<grid, kBlock, 0, st>>>(src, delta, cfg.d, cfg.chunk, out->sign_words,
-                                                                c->W, out->scales, c->S);
-        }
+        with_flags(bf16, rms, false, [&](auto bf, auto rm, auto) {
+            constexpr bool BF = decltype(bf)::value, RM = decltype(rm)::value;
+            WorkerSrc<BF> src{g, gs, delta, dstr};
+            k_sign_chunk_worker<BF, RM><<<grid, kBlock, 0, st>>>(src, delta, cfg.d, cfg.chunk, out->sign_words, c->W,
+                                                                 out->scales, c->S);
+        });
         return ds_launch_status();
     }
     dim3 grid(static_cast<unsigned>(c->n_tiles), static_cast<unsigned>(cfg.n));
-    const bool deferred = c->sign_defer && c->sign_w_deferred;
-    auto pass1 = [&](auto bf, auto df) {
-        constexpr bool BF = decltype(bf)::value, DF = decltype(df)::value;
+    with_flags(bf16, c->sign_defer && c->sign_w_deferred, rms, [&](auto bf, auto df, auto rm) {
+        constexpr bool BF = decltype(bf)::value, DF = decltype(df)::value, RM = decltype(rm)::value;
         WorkerSrc<BF> src{g, gs, delta, dstr};
-        k_sign_pass1_worker<BF, DF><<<grid, kBlock, 0, st>>>(src, delta, cfg.d, out->sign_words, c->W, c->sign_tb,
-                                                             c->sign_partials, c->sign_prev_w, c->S);
-    };
-    if (bf16) { if (deferred) pass1(std::true_type{}, std::true_type{}); else pass1(std::true_type{}, std::false_type{}); }
-    else { if (deferred) pass1(std::false_type{}, std::true_type{}); else pass1(std::false_type{}, std::false_type{}); }
+        k_sign_pass1_worker<BF, DF, RM><<<grid, kBlock, 0, st>>>(src, delta, cfg.d, out->sign_words, c->W, c->sign_tb,
+                                                                 c->sign_partials, c->sign_prev_w, c->S);
+    });
     k_sign_reduce<<<dim3(static_cast<unsigned>(c->S), static_cast<unsigned>(cfg.n)), kBlock, 0, st>>>(
         c->sign_partials, c->sign_tb, out->scales, c->S, c->sign_defer ? c->sign_prev_w : nullptr);
     if (c->sign_defer) {
@@ -533,20 +557,22 @@ ds_status_t ds_sign_server(ds_ctx *c, const ds_payload_t *in, float *delta_s, co
 {
     const ds_config_t &cfg = c->cfg;
     ServerArgs a{in->sign_words, in->scales, cfg.n, c->W, c->S, c->inv_n};
+    const bool rms = (cfg.flags & DS_FLAG_SIGN_RMS) != 0;
     if (c->sign_fused) {
         // two chunks per workgroup: more bytes in flight per thread (measured 271 us against
         // 292 us with one and 285 us with four on the 124 M-element workload)
-        k_sign_chunk_server<2><<<dim3(static_cast<unsigned>((c->S + 1) / 2)), kBlock, 0, st>>>(
-            a, delta_s, cfg.d, cfg.chunk, out->sign_words, out->scales);
+        const dim3 grid(static_cast<unsigned>((c->S + 1) / 2));
+        if (rms) k_sign_chunk_server<2, true><<<grid, kBlock, 0, st>>>(a, delta_s, cfg.d, cfg.chunk, out->sign_words, out->scales);
+        else k_sign_chunk_server<2, false><<<grid, kBlock, 0, st>>>(a, delta_s, cfg.d, cfg.chunk, out->sign_words, out->scales);
         return ds_launch_status();
     }
     dim3 grid(static_cast<unsigned>(c->n_tiles));
-    if (c->sign_defer && c->sign_s_deferred)
-        k_sign_pass1_server<true><<<grid, kBlock, 0, st>>>(a, delta_s, cfg.d, out->sign_words, c->sign_tb, c->sign_partials,
-                                                           c->sign_prev_s);
-    else
-        k_sign_pass1_server<false><<<grid, kBlock, 0, st>>>(a, delta_s, cfg.d, out->sign_words, c->sign_tb, c->sign_partials,
-                                                            nullptr);
+    const bool deferred = c->sign_defer && c->sign_s_deferred;
+    with_flags(deferred, rms, false, [&](auto df, auto rm, auto) {
+        constexpr bool DF = decltype(df)::value, RM = decltype(rm)::value;
+        k_sign_pass1_server<DF, RM><<<grid, kBlock, 0, st>>>(a, delta_s, cfg.d, out->sign_words, c->sign_tb, c->sign_partials,
+                                                             deferred ? c->sign_prev_s : nullptr);
+    });
     k_sign_reduce<<<dim3(static_cast<unsigned>(c->S), 1), kBlock, 0, st>>>(c->sign_partials, c->sign_tb, out->scales, c->S,
                                                                           c->sign_defer ? c->sign_prev_s : nullptr);
     if (c->sign_defer) {

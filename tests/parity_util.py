@@ -19,10 +19,12 @@ REL = 1e-6
 
 
 def oracle_config(wl) -> O.Config:
-    comp = {"identity": O.IDENTITY, "sign": O.SIGN, "topk": O.TOPK, "qsgd": O.QSGD}[wl.comp]
+    comp = {"identity": O.IDENTITY, "sign": O.SIGN, "topk": O.TOPK, "qsgd": O.QSGD, "clip": O.CLIP,
+            "rsparse": O.RSPARSE}[wl.comp]
     return O.Config(comp, n=wl.n, d=wl.d, grad_bf16=(wl.grad_dtype == "bf16"),
                     group_off=wl.group_offsets() if wl.comp == "sign" else None,
-                    k=wl.k, bucket=wl.bucket, levels=wl.levels, seed=wl.seed)
+                    k=wl.k, bucket=wl.bucket, levels=wl.levels, seed=wl.seed, sign_rms=wl.sign_rms,
+                    clip_bits=wl.clip_bits, keep_prob=wl.keep_prob)
 
 
 # ds_config_t::flags of the contexts that gpu_context builds; tests that cover both top-k
@@ -34,7 +36,8 @@ def gpu_context(wl) -> P.Context:
     return P.Context(wl.comp, wl.n, wl.d, grad_dtype=wl.grad_dtype, scale_mode=wl.scale_mode,
                      chunk=wl.chunk,
                      seg_offsets=wl.seg_offsets if wl.scale_mode == "segments" else None,
-                     k=wl.k, bucket=wl.bucket, levels=wl.levels, seed=wl.seed, flags=CONTEXT_FLAGS)
+                     k=wl.k, bucket=wl.bucket, levels=wl.levels, seed=wl.seed,
+                     flags=CONTEXT_FLAGS | (P.FLAG_SIGN_RMS if wl.sign_rms else 0))
 
 
 def host_grad(g: torch.Tensor) -> np.ndarray:

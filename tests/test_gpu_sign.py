@@ -39,6 +39,18 @@ def test_sign_chunks(gpu_device, d, chunk):
     _run(_sign_wl(d, scale_mode="chunk", chunk=chunk), gpu_device)
 
 
+@pytest.mark.parametrize("mode", ["whole", "chunk2048", "chunk320", "segments"])
+def test_sign_rms_scale(gpu_device, mode):
+    # scale = root mean square of the group (the l2 reading of the 1-bit compressor), every route
+    if mode == "whole":
+        wl = _sign_wl(3 * 2048 + 37, scale_mode="whole", sign_rms=True)
+    elif mode == "segments":
+        wl = dataclasses.replace(W.c2(d=300_001, n=3, n_seg=17, lo=64), sign_rms=True)
+    else:
+        wl = _sign_wl(5 * 2048 + 1280, scale_mode="chunk", chunk=int(mode[5:]), sign_rms=True)
+    _run(wl, gpu_device, steps=3)
+
+
 def test_sign_chunk_bf16_momentum_c5_slice(gpu_device):
     # 1/64-size slice of the large flat-gradient workload, 20 compared steps
     wl = W.c5(d=124_439_808 // 64, n=8)
