@@ -208,6 +208,11 @@ def c5(d: int = 124_439_808, n: int = 8, n_seg: int = 148, lo: int = 768,
                     dist="segment_normal", gamma=0.1, beta=0.9)
 
 
+def clip16(d: int = 25_557_032, n: int = 8) -> Workload:
+    """Not one of the five configurations: the clipping compressor at the shape of C3/C4."""
+    return Workload("X1_clip16_fp32", "clip", n=n, d=d, clip_bits=16, dist="normal", sigma=1e-3, gamma=0.05)
+
+
 # --------------------------------------------------------------------------------------
 # C1: the distributed least-squares toy (problem data and minibatch gradients only)
 # --------------------------------------------------------------------------------------

@@ -17,7 +17,8 @@
  * Q[.] is pluggable (Section 3.2, "Compression options"): 1-bit sign with a scale
  * (Section 5.1 "1-bit compression"), top-k by absolute value (Section 5.1 "Top-k
  * compression"), two-point unbiased randomised quantisation (Section 3.2 "Randomized
- * Quantization", bucketed with an L2 norm), and the identity (Section 5.1 "Vanilla SGD").
+ * Quantization", bucketed with an L2 norm), clipping of low bits (Section 3.2 "Clipping"), and
+ * the identity (Section 5.1 "Vanilla SGD").
  *
  * Conventions that hold for every call
  *   - Every data pointer is DEVICE memory owned by the caller (base address 16-byte
@@ -61,7 +62,8 @@ typedef enum {
     DS_COMP_IDENTITY = 0,
     DS_COMP_SIGN = 1,
     DS_COMP_TOPK = 2,
-    DS_COMP_QSGD = 3
+    DS_COMP_QSGD = 3,
+    DS_COMP_CLIP = 4
 } ds_compressor_t;
 
 typedef enum { DS_F32 = 0, DS_BF16 = 1 } ds_dtype_t;
@@ -111,7 +113,8 @@ typedef struct {
     const int64_t *seg_offsets; /* SIGN + SEGMENTS: HOST array of n_seg+1 offsets,
                                  [0] = 0, [n_seg] = d, strictly increasing; copied */
     int32_t n_seg;
-    int32_t levels;           /* QSGD: s, number of non-zero levels, 1 .. 15 */
+    int32_t levels;           /* QSGD: s, number of non-zero levels, 1 .. 15;
+                                 CLIP: b, number of low bits set to zero, 1 .. 31 */
     int64_t k;                /* TOPK: entries kept per vector, 1 .. d */
     int32_t bucket;           /* QSGD: elements per bucket, a multiple of 64 (built: the powers of
                                  two 64 .. 2048; other multiples give DS_ERR_UNSUPPORTED) */
@@ -137,6 +140,9 @@ typedef struct { int32_t idx; float val; } ds_pair_t;
  *   TOPK     pairs [rows, k]: exactly k entries, ascending idx; the k largest |v| (order
  *            of magnitudes = order of the bit patterns with the sign cleared), equal
  *            magnitudes resolved towards the lower index.  Decoded: val at idx, else 0.
+ *   CLIP     levels [rows, d * NB]: the upper 32 - b bits of element j in the NB bytes from
+ *            j * NB on, little endian, NB = 1 (b >= 24), 2 (b >= 16) or 4.  Decoded element:
+ *            those bits with the cleared low bits as zeros.
  *   IDENTITY dense [rows, d]. */
 typedef struct {
     uint64_t *sign_words;

@@ -13,14 +13,15 @@ from typing import Optional
 import numpy as np
 import torch
 
-COMP_IDENTITY, COMP_SIGN, COMP_TOPK, COMP_QSGD = 0, 1, 2, 3
+COMP_IDENTITY, COMP_SIGN, COMP_TOPK, COMP_QSGD, COMP_CLIP = 0, 1, 2, 3, 4
 SCALE_WHOLE, SCALE_SEGMENTS, SCALE_CHUNK = 0, 1, 2
 F32, BF16 = 0, 1
 FLAG_TOPK_MULTI_LAUNCH = 1
 FLAG_DEFERRED_ERROR = 2
 FLAG_SIGN_RMS = 4
 
-_COMP = {"identity": COMP_IDENTITY, "sign": COMP_SIGN, "topk": COMP_TOPK, "qsgd": COMP_QSGD}
+_COMP = {"identity": COMP_IDENTITY, "sign": COMP_SIGN, "topk": COMP_TOPK, "qsgd": COMP_QSGD,
+         "clip": COMP_CLIP}
 _MODE = {"whole": SCALE_WHOLE, "segments": SCALE_SEGMENTS, "chunk": SCALE_CHUNK}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -109,7 +110,7 @@ def _stream_ptr(stream) -> Optional[int]:
 class Payload:
     """Device buffers of a batch of compressed messages (torch tensors, caller-owned)."""
 
-    def __init__(self, comp: int, rows: int, d: int, W: int, S: int, k: int, device):
+    def __init__(self, comp: int, rows: int, d: int, W: int, S: int, k: int, device, sizes=None):
         self.comp, self.rows, self.d, self.k = comp, rows, d, k
         self.sign_words = self.scales = self.levels = self.pairs = self.dense = None
         if comp == COMP_IDENTITY:
@@ -123,6 +124,8 @@ class Payload:
             self.sign_words = torch.zeros((rows, W), dtype=torch.int64, device=device)
             self.scales = torch.zeros((rows, S), dtype=torch.float32, device=device)
             self.levels = torch.zeros((rows, (d + 1) // 2), dtype=torch.uint8, device=device)
+        elif comp == COMP_CLIP:
+            self.levels = torch.zeros((rows, sizes[2] // rows), dtype=torch.uint8, device=device)
 
     def c_struct(self) -> ds_payload_t:
         def p(t):
@@ -212,7 +215,7 @@ class Context:
         return list(out)
 
     def alloc_payload(self, rows: int, device="cuda") -> Payload:
-        return Payload(self.comp, rows, self.d, self.W, self.S, self.k, device)
+        return Payload(self.comp, rows, self.d, self.W, self.S, self.k, device, self.payload_sizes(rows))
 
     def worker_compress(self, step: int, g: torch.Tensor, delta: torch.Tensor, out: Payload,
                         stream=None):

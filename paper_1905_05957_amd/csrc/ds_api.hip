@@ -28,6 +28,10 @@ ds_status_t check_payload(const ds_ctx *c, const ds_payload_t *p)
         if (!p->sign_words || !p->scales || !p->levels) return DS_ERR_NULL;
         if (misaligned(p->sign_words) || misaligned(p->scales) || misaligned(p->levels)) return DS_ERR_ALIGN;
         break;
+    case DS_COMP_CLIP:
+        if (!p->levels) return DS_ERR_NULL;
+        if (misaligned(p->levels)) return DS_ERR_ALIGN;
+        break;
     }
     return DS_OK;
 }
@@ -100,6 +104,9 @@ ds_status_t ds_create(const ds_config_t *cfg, ds_ctx_t **out)
         if (cfg->levels < 1 || cfg->levels > 15) return DS_ERR_CONFIG;
         if (cfg->bucket > 2048 || (cfg->bucket & (cfg->bucket - 1)) != 0) return DS_ERR_UNSUPPORTED;
         break;
+    case DS_COMP_CLIP:
+        if (cfg->levels < 1 || cfg->levels > 31) return DS_ERR_CONFIG;
+        break;
     default:
         return DS_ERR_CONFIG;
     }
@@ -163,6 +170,9 @@ ds_status_t ds_payload_sizes(const ds_ctx_t *c, int32_t rows, size_t bytes_out[5
         bytes_out[1] = r * static_cast<size_t>(c->S) * sizeof(float);
         bytes_out[2] = r * ((d + 1) / 2);
         break;
+    case DS_COMP_CLIP:
+        bytes_out[2] = r * d * static_cast<size_t>(ds_clip_bytes(c->cfg.levels));
+        break;
     }
     return DS_OK;
 }
@@ -183,6 +193,7 @@ ds_status_t ds_worker_compress(ds_ctx_t *c, uint64_t step, const void *g, int64_
     case DS_COMP_SIGN: return ds_sign_worker(c, g, g_row_stride, delta, delta_row_stride, out, st);
     case DS_COMP_TOPK: return ds_topk_worker(c, g, g_row_stride, delta, delta_row_stride, out, st);
     case DS_COMP_QSGD: return ds_qsgd_worker(c, step, g, g_row_stride, delta, delta_row_stride, out, st);
+    case DS_COMP_CLIP: return ds_clip_worker(c, g, g_row_stride, delta, delta_row_stride, out, st);
     }
     return DS_ERR_CONFIG;
 }
@@ -204,6 +215,7 @@ ds_status_t ds_server_aggregate_compress(ds_ctx_t *c, uint64_t step, const ds_pa
     case DS_COMP_SIGN: return ds_sign_server(c, in, delta_s, out, st);
     case DS_COMP_TOPK: return ds_topk_server(c, in, delta_s, out, st);
     case DS_COMP_QSGD: return ds_qsgd_server(c, step, in, delta_s, out, st);
+    case DS_COMP_CLIP: return ds_clip_server(c, in, delta_s, out, st);
     }
     return DS_ERR_CONFIG;
 }
@@ -223,6 +235,7 @@ ds_status_t ds_apply_update(ds_ctx_t *c, const ds_payload_t *srv, float *x, floa
     case DS_COMP_SIGN: return ds_sign_update(c, srv, x, m, gamma, beta, st);
     case DS_COMP_TOPK: return ds_topk_update(c, srv, x, m, gamma, beta, st);
     case DS_COMP_QSGD: return ds_qsgd_update(c, srv, x, m, gamma, beta, st);
+    case DS_COMP_CLIP: return ds_clip_update(c, srv, x, m, gamma, beta, st);
     }
     return DS_ERR_CONFIG;
 }
@@ -243,6 +256,7 @@ ds_status_t ds_decompress(ds_ctx_t *c, const ds_payload_t *p, int32_t rows, int3
     case DS_COMP_SIGN: return ds_sign_decode(c, p, row, dense_out, st);
     case DS_COMP_TOPK: return ds_topk_decode(c, p, row, dense_out, st);
     case DS_COMP_QSGD: return ds_qsgd_decode(c, p, row, dense_out, st);
+    case DS_COMP_CLIP: return ds_clip_decode(c, p, row, dense_out, st);
     }
     return DS_ERR_CONFIG;
 }

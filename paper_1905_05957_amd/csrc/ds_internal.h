@@ -84,6 +84,16 @@ ds_status_t ds_qsgd_update(ds_ctx *c, const ds_payload_t *srv, float *x, float *
                            float beta, hipStream_t st);
 ds_status_t ds_qsgd_decode(ds_ctx *c, const ds_payload_t *p, int32_t row, float *out, hipStream_t st);
 
+// clip.hip
+int ds_clip_bytes(int bits);   // bytes per element of the message for `bits` cleared low bits
+ds_status_t ds_clip_worker(ds_ctx *c, const void *g, int64_t gs, float *delta, int64_t dstr,
+                           const ds_payload_t *out, hipStream_t st);
+ds_status_t ds_clip_server(ds_ctx *c, const ds_payload_t *in, float *delta_s,
+                           const ds_payload_t *out, hipStream_t st);
+ds_status_t ds_clip_update(ds_ctx *c, const ds_payload_t *srv, float *x, float *m, float gamma,
+                           float beta, hipStream_t st);
+ds_status_t ds_clip_decode(ds_ctx *c, const ds_payload_t *p, int32_t row, float *out, hipStream_t st);
+
 // topk.hip
 ds_status_t ds_topk_init(ds_ctx *c);
 void ds_topk_fini(ds_ctx *c);

@@ -36,8 +36,8 @@ def gpu_context(wl) -> P.Context:
     return P.Context(wl.comp, wl.n, wl.d, grad_dtype=wl.grad_dtype, scale_mode=wl.scale_mode,
                      chunk=wl.chunk,
                      seg_offsets=wl.seg_offsets if wl.scale_mode == "segments" else None,
-                     k=wl.k, bucket=wl.bucket, levels=wl.levels, seed=wl.seed,
-                     flags=CONTEXT_FLAGS | (P.FLAG_SIGN_RMS if wl.sign_rms else 0))
+                     k=wl.k, bucket=wl.bucket, levels=wl.clip_bits if wl.comp == "clip" else wl.levels,
+                     seed=wl.seed, flags=CONTEXT_FLAGS | (P.FLAG_SIGN_RMS if wl.sign_rms else 0))
 
 
 def host_grad(g: torch.Tensor) -> np.ndarray:
