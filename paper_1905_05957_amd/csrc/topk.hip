@@ -37,6 +37,7 @@
 
 #include <cstdlib>
 #include <new>
+#include <type_traits>
 
 using namespace ds;
 
@@ -499,6 +500,129 @@ __global__ __launch_bounds__(kBlock) void k_topk_pass1(Src src, float *buf, int6
     for (int64_t tile = blockIdx.x; tile < n_reg; tile += gridDim.x)
         pass1_tile<Src, FALLBACK>(src, buf, stride, d, n_sub, lo_key, slots, reg_cnt, n_reg, reg_pad, row, tile,
                                   strips[wave_id()], wtot);
+}
+
+// The server's dense pass (row 0 only): the same work as k_topk_pass1<ServerV, false> with
+// FOUR subtiles (1024 elements) per wavefront and four candidate regions per workgroup.  A
+// subtile holds only about 8 n k / d entries, so with one subtile per wavefront most lanes idle
+// through the entry handling; four subtiles fill the 64-entry batches, share one range
+// look-up and prefix, and keep four independent 128-bit loads in flight per lane.  The claim
+// tags are hashed (element & 255): two pending entries that share a tag but not an element
+// merely take turns.
+constexpr int kSpan = 4 * kSub;              // elements per wavefront
+constexpr int kSpanTile = kSpan * kWaves;    // elements per workgroup = 4 regions
+
+__global__ __launch_bounds__(kBlock) void k_topk_pass1_server(ServerV src, float *buf, int64_t d, const Sel *sel,
+                                                              u32x2 *slots, uint32_t *reg_cnt, int64_t n_reg)
+{
+    __shared__ float strips[kWaves][kSpan];
+    __shared__ uint32_t tags[kWaves][kSub];
+    __shared__ uint32_t wtot[kWaves];
+    const int lane = lane_id(), wv = wave_id();
+    float *strip = strips[wv];
+    uint32_t *tag = tags[wv];
+    for (int i = lane; i < kSub; i += 64) tag[i] = kNone;
+    const int64_t span_base = (static_cast<int64_t>(blockIdx.x) * kWaves + wv) * kSpan;
+    const uint32_t lo_key = sel[0].lo_key;
+    const bool vec = aligned16(buf);
+    f32x4 v[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        v[c] = ld4(src.delta_s, span_base + c * kSub + lane * 4, d, aligned16(src.delta_s));
+        float *p = strip + c * kSub + lane * 4;
+        p[0] = v[c].x; p[1] = v[c].y; p[2] = v[c].z; p[3] = v[c].w;
+    }
+    if (span_base < d) {                                   // uniform over the wavefront
+        const int64_t sub0 = span_base >> 8;
+        const int64_t sub1 = (sub0 + 4 < src.n_sub) ? sub0 + 4 : src.n_sub;
+        const uint32_t base = static_cast<uint32_t>(span_base);
+        const int n = src.n;
+        for (int w0 = 0; w0 < n; w0 += 64) {
+            const int nw = (n - w0 < 64) ? n - w0 : 64;
+            const int nsteps = (nw <= 1) ? 0 : 32 - __builtin_clz(static_cast<uint32_t>(nw - 1));
+            uint32_t s0 = 0u, c = 0u;
+            if (lane < nw) {
+                s0 = src.sub_start[sub0 * n + w0 + lane];
+                uint32_t s1 = src.sub_start[sub1 * n + w0 + lane];
+                if (s1 > static_cast<uint32_t>(src.k)) s1 = static_cast<uint32_t>(src.k);
+                c = (s1 > s0) ? s1 - s0 : 0u;
+            }
+            uint32_t P = c;
+            for (int o = 1; o < nw; o <<= 1) {
+                const uint32_t up = __shfl_up(P, o, 64);
+                if (lane >= o) P += up;
+            }
+            const uint32_t total = __shfl(P, nw - 1, 64);
+            for (uint32_t i0 = 0; i0 < total; i0 += 64) {
+                const uint32_t i = i0 + lane;
+                const bool valid = i < total;
+                int lo = 0, hi = nw - 1;
+                for (int step = 0; step < nsteps; ++step) {
+                    const int mid = (lo + hi) >> 1;
+                    if (__shfl(P, mid, 64) > (valid ? i : 0u)) hi = mid; else lo = mid + 1;
+                }
+                const uint32_t pw = __shfl(P, lo, 64), cw = __shfl(c, lo, 64), sw = __shfl(s0, lo, 64);
+                u32x2 pr = {0u, 0u};
+                if (valid) pr = src.pairs_in[static_cast<int64_t>(w0 + lo) * src.k + sw + (i - (pw - cw))];
+                const uint32_t rel = pr.x - base;
+                bool pending = valid && rel < static_cast<uint32_t>(kSpan);
+                while (__ballot(pending)) {
+                    if (pending) atomicMin(&tag[rel & (kSub - 1)], static_cast<uint32_t>(lane));
+                    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+                    const bool win = pending && tag[rel & (kSub - 1)] == static_cast<uint32_t>(lane);
+                    if (win) {
+                        strip[rel] = __fmaf_rn(__uint_as_float(pr.y), src.inv_n, strip[rel]);
+                        tag[rel & (kSub - 1)] = kNone;
+                    }
+                    pending = pending && !win;
+                    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+                }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const float *p = strip + c * kSub + lane * 4;
+            v[c] = f32x4{p[0], p[1], p[2], p[3]};
+        }
+    }
+    // classify, store v with 0 at the candidates, count
+    uint32_t bits[4][4];
+    bool f[4][4];
+    uint32_t before[4], cnt_c[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const int64_t e = span_base + c * kSub + lane * 4;
+        bits[c][0] = __float_as_uint(v[c].x); bits[c][1] = __float_as_uint(v[c].y);
+        bits[c][2] = __float_as_uint(v[c].z); bits[c][3] = __float_as_uint(v[c].w);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) f[c][j] = (e + j < d) && (bits[c][j] & 0x7FFFFFFFu) >= lo_key;
+        if (e < d)
+            st4(buf, e, d, vec, f32x4{f[c][0] ? 0.f : v[c].x, f[c][1] ? 0.f : v[c].y, f[c][2] ? 0.f : v[c].z,
+                                     f[c][3] ? 0.f : v[c].w});
+        const uint64_t m0 = __ballot(f[c][0]), m1 = __ballot(f[c][1]), m2 = __ballot(f[c][2]), m3 = __ballot(f[c][3]);
+        before[c] = lanes_below(m0) + lanes_below(m1) + lanes_below(m2) + lanes_below(m3);
+        cnt_c[c] = __popcll(m0) + __popcll(m1) + __popcll(m2) + __popcll(m3);
+    }
+    const uint32_t wave_total = cnt_c[0] + cnt_c[1] + cnt_c[2] + cnt_c[3];
+    if (lane == 0) wtot[wv] = wave_total;
+    __syncthreads();
+    // a region is the two wavefronts 2r, 2r+1: the odd one writes behind the even one
+    const int64_t region = static_cast<int64_t>(blockIdx.x) * 4 + (wv >> 1);
+    uint32_t off = (wv & 1) ? wtot[wv - 1] : 0u;
+    if (region < n_reg) {
+        u32x2 *out = slots + region * kReg;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int64_t e = span_base + c * kSub + lane * 4;
+            uint32_t r = off + before[c];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (f[c][j]) out[r++] = u32x2{static_cast<uint32_t>(e + j), bits[c][j]};
+            off += cnt_c[c];
+        }
+        if ((wv & 1) && lane == 0) reg_cnt[region] = wtot[wv - 1] + wtot[wv];
+    }
 }
 
 // Fallback rows: dense 12-bit histogram of the stored v.  Persistent workgroups.
@@ -1179,7 +1303,11 @@ ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t 
 
     k_topk_sample<Src><<<dim3(static_cast<unsigned>((ns + kWaves - 1) / kWaves), rows), kBlock, 0, st>>>(
         src, d, n_sub, ns, hist, t->sel, t->done, rank, prev_T);
-    k_topk_pass1<Src, false><<<dense, kBlock, 0, st>>>(src, buf, stride, d, n_sub, t->sel, t->slots, t->reg_cnt, n_reg, reg_pad);
+    if constexpr (std::is_same<Src, ServerV>::value)
+        k_topk_pass1_server<<<dim3(static_cast<unsigned>((n_reg + 3) / 4)), kBlock, 0, st>>>(src, buf, d, t->sel, t->slots,
+                                                                                         t->reg_cnt, n_reg);
+    else
+        k_topk_pass1<Src, false><<<dense, kBlock, 0, st>>>(src, buf, stride, d, n_sub, t->sel, t->slots, t->reg_cnt, n_reg, reg_pad);
     if (t->capacity >= rows) {
         // everything after the dense pass in one launch whose workgroups are all resident
         int64_t G = t->capacity / rows;
