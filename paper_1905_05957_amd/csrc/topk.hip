@@ -939,14 +939,15 @@ __global__ __launch_bounds__(kBlock) void k_topk_emit(const u32x2 *slots, const 
 // half the device each), the workgroup raises the context's abort word (host memory) and
 // the kernel drains; the context then reports DS_ERR_DEVICE on every later call.
 //
-// Radix levels here are relative to lo_key: level A = 256 bins of 4096 keys from lo_key
+// Radix levels here are relative to lo_key: level A = 1024 bins of 4096 keys from lo_key
 // upwards (the last bin also takes everything beyond), level B = the 12 low bits inside bin
 // A.  The sample's lower bound is known to 20 key bits and the k-th key lies a few per cent
-// above it, so two levels resolve all 31 bits.  A row whose k-th key is not below bin 255
-// (or that has fewer than k candidates) takes the exact two-look route inside the same
+// above it (100 to 400 bins on the 25.6 M-element top-1 % workload; with 256 bins one server
+// call in ten fell outside), so two levels resolve all 31 bits.  A row whose k-th key is not
+// below the last bin (or that has fewer than k candidates) takes the exact two-look route inside the same
 // launch: put v back, dense 12-bit histogram, pick b1, compact again with lo_key = b1 << 19
 // (the k-th key is then less than 2^19 above lo_key), level A again.
-constexpr int kHA = 256, kHB = 4096, kShiftA = 12;
+constexpr int kHA = 1024, kHB = 4096, kShiftA = 12;
 constexpr int kFOffA = 0, kFOffA2 = kHA, kFOffB = 2 * kHA, kFOffD = 2 * kHA + kHB;
 constexpr int kFRow = 2 * kHA + kHB + kH1;     // words per row of the fused route's histograms
 enum { kResA = 0, kResD = 1, kResA2 = 2, kResB = 3, kResCompact = 4, kResCount = 5, kResSlots = 6 };
