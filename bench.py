@@ -51,6 +51,8 @@ def algorithmic_bytes(wl, S: int) -> dict:
         msg = 8 * wl.k
     elif wl.comp == "clip":
         msg = d * (1 if wl.clip_bits >= 24 else 2 if wl.clip_bits >= 16 else 4)
+    elif wl.comp == "rsparse":
+        msg = W8 + int(4 * d * wl.keep_prob)        # kept-bit plane + the expected number of kept values
     else:
         msg = 4 * d
     worker = n * (d * (gb + 4 + 4) + msg)
@@ -65,7 +67,7 @@ def algorithmic_bytes(wl, S: int) -> dict:
 
 def make_workload(name: str):
     import ds_workloads as W
-    return {"c2": W.c2, "c3": W.c3, "c4": W.c4, "c5": W.c5, "clip16": W.clip16}[name]()
+    return {"c2": W.c2, "c3": W.c3, "c4": W.c4, "c5": W.c5, "clip16": W.clip16, "rsparse60": W.rsparse60}[name]()
 
 
 def run_gpu(wl, steps: int, warmup: int, sets: int = 2, calib_copy: bool = False, deferred_error: bool = True):
@@ -76,7 +78,8 @@ def run_gpu(wl, steps: int, warmup: int, sets: int = 2, calib_copy: bool = False
     ctx = P.Context(wl.comp, wl.n, wl.d, grad_dtype=wl.grad_dtype, scale_mode=wl.scale_mode,
                     chunk=wl.chunk, seg_offsets=wl.seg_offsets if wl.scale_mode == "segments" else None,
                     k=wl.k, bucket=wl.bucket, levels=wl.clip_bits if wl.comp == "clip" else wl.levels,
-                    seed=wl.seed, flags=P.FLAG_DEFERRED_ERROR if deferred_error else 0)
+                    seed=wl.seed, keep_prob=wl.keep_prob if wl.comp == "rsparse" else None,
+                    flags=P.FLAG_DEFERRED_ERROR if deferred_error else 0)
     grads = [wl.gradients(s, dev) for s in range(sets)]
     delta = wl.initial_delta(dev)
     delta_s = torch.zeros(wl.d, dtype=torch.float32, device=dev)
@@ -158,11 +161,13 @@ def run_oracle_sample(wl, target_elems: int):
         off = wl.seg_offsets[wl.seg_offsets < dq]
         sub.seg_offsets = np.concatenate([off, [dq]]).astype(np.int64)
         sub.seg_sigma = wl.seg_sigma[: len(off)]
-    comp = {"identity": O.IDENTITY, "sign": O.SIGN, "topk": O.TOPK, "qsgd": O.QSGD, "clip": O.CLIP}[sub.comp]
+    comp = {"identity": O.IDENTITY, "sign": O.SIGN, "topk": O.TOPK, "qsgd": O.QSGD, "clip": O.CLIP,
+            "rsparse": O.RSPARSE}[sub.comp]
     cfg = O.Config(comp, n=sub.n, d=dq, grad_bf16=(sub.grad_dtype == "bf16"),
                    group_off=sub.group_offsets() if sub.comp == "sign" else None, k=sub.k,
                    bucket=sub.bucket, levels=sub.levels, seed=sub.seed, sign_rms=sub.sign_rms,
-                   clip_bits=sub.clip_bits)
+                   clip_bits=sub.clip_bits,
+                   keep_prob=float(np.float32(round(sub.keep_prob * (1 << 24))) / np.float32(1 << 24)))
     g = sub.gradients(0, "cpu")
     hg = g.view(torch.int16).numpy().view(np.uint16) if g.dtype == torch.bfloat16 else g.numpy()
     delta = sub.initial_delta("cpu").numpy()
@@ -185,7 +190,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c5", choices=["c2", "c3", "c4", "c5", "clip16"])
+    ap.add_argument("--workload", default="c5", choices=["c2", "c3", "c4", "c5", "clip16", "rsparse60"])
     ap.add_argument("--others", default="c2,c3,c4", help="further workloads reported in the same line ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",

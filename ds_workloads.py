@@ -213,6 +213,13 @@ def clip16(d: int = 25_557_032, n: int = 8) -> Workload:
     return Workload("X1_clip16_fp32", "clip", n=n, d=d, clip_bits=16, dist="normal", sigma=1e-3, gamma=0.05)
 
 
+def rsparse60(d: int = 25_557_032, n: int = 8) -> Workload:
+    """Not one of the five configurations: randomised sparsification, p = 0.6 (with error
+    feedback the loop is stable only for p > 1/2), at the shape of C3/C4."""
+    return Workload("X2_rsparse_p60_fp32", "rsparse", n=n, d=d, keep_prob=0.6, dist="normal", sigma=1e-3,
+                    gamma=0.05)
+
+
 # --------------------------------------------------------------------------------------
 # C1: the distributed least-squares toy (problem data and minibatch gradients only)
 # --------------------------------------------------------------------------------------

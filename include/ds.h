@@ -17,8 +17,9 @@
  * Q[.] is pluggable (Section 3.2, "Compression options"): 1-bit sign with a scale
  * (Section 5.1 "1-bit compression"), top-k by absolute value (Section 5.1 "Top-k
  * compression"), two-point unbiased randomised quantisation (Section 3.2 "Randomized
- * Quantization", bucketed with an L2 norm), clipping of low bits (Section 3.2 "Clipping"), and
- * the identity (Section 5.1 "Vanilla SGD").
+ * Quantization", bucketed with an L2 norm), clipping of low bits (Section 3.2 "Clipping"),
+ * randomised sparsification (Section 3.2 "Randomized Sparsification") and the identity
+ * (Section 5.1 "Vanilla SGD").
  *
  * Conventions that hold for every call
  *   - Every data pointer is DEVICE memory owned by the caller (base address 16-byte
@@ -63,7 +64,8 @@ typedef enum {
     DS_COMP_SIGN = 1,
     DS_COMP_TOPK = 2,
     DS_COMP_QSGD = 3,
-    DS_COMP_CLIP = 4
+    DS_COMP_CLIP = 4,
+    DS_COMP_RSPARSE = 5
 } ds_compressor_t;
 
 typedef enum { DS_F32 = 0, DS_BF16 = 1 } ds_dtype_t;
@@ -115,11 +117,14 @@ typedef struct {
     int32_t n_seg;
     int32_t levels;           /* QSGD: s, number of non-zero levels, 1 .. 15;
                                  CLIP: b, number of low bits set to zero, 1 .. 31 */
-    int64_t k;                /* TOPK: entries kept per vector, 1 .. d */
+    int64_t k;                /* TOPK: entries kept per vector, 1 .. d;
+                                 RSPARSE: P24 = p * 2^24, 1 .. 2^24: an element is kept iff its
+                                 24-bit uniform is below P24, and kept values are divided by
+                                 p = P24 * 2^-24 */
     int32_t bucket;           /* QSGD: elements per bucket, a multiple of 64 (built: the powers of
                                  two 64 .. 2048; other multiples give DS_ERR_UNSUPPORTED) */
     int32_t flags;            /* ds_flags_t bits, 0 for the defaults */
-    uint64_t seed;            /* QSGD: Philox key */
+    uint64_t seed;            /* QSGD, RSPARSE: Philox key */
 } ds_config_t;
 
 typedef struct ds_ctx ds_ctx_t;
@@ -143,6 +148,10 @@ typedef struct { int32_t idx; float val; } ds_pair_t;
  *   CLIP     levels [rows, d * NB]: the upper 32 - b bits of element j in the NB bytes from
  *            j * NB on, little endian, NB = 1 (b >= 24), 2 (b >= 16) or 4.  Decoded element:
  *            those bits with the cleared low bits as zeros.
+ *   RSPARSE  sign_words [rows, W]: bit j = element j is kept (layout as above, bits past d
+ *            are written as 0 and ignored when read).  dense [rows, d]: the kept values z / p
+ *            of a row packed in index order at its start; what follows them is unspecified.
+ *            Decoded element: its packed value if kept, else 0.
  *   IDENTITY dense [rows, d]. */
 typedef struct {
     uint64_t *sign_words;
@@ -171,7 +180,8 @@ ds_status_t ds_payload_sizes(const ds_ctx_t *ctx, int32_t rows, size_t bytes_out
  *   out    n messages
  * Strides are in elements and >= d.  Rows that are 16-byte aligned take 128-bit loads;
  * other rows take an element-wise path with the same results.
- * QSGD draws its rounding from the stream (seed, step, worker i, element j). */
+ * QSGD draws its rounding, RSPARSE its keep decisions, from the stream (seed, step, worker i,
+ * element j). */
 ds_status_t ds_worker_compress(ds_ctx_t *ctx, uint64_t step, const void *g,
                                int64_t g_row_stride, float *delta, int64_t delta_row_stride,
                                const ds_payload_t *out, void *hip_stream);
@@ -182,7 +192,7 @@ ds_status_t ds_worker_compress(ds_ctx_t *ctx, uint64_t step, const void *g,
  *   delta_s  [d] server error, fp32, read and overwritten
  *   out      1 message
  * The average is the chain acc = delta_s; acc = fma(decode(in_i), 1/n, acc) for
- * i = 0 .. n-1.  QSGD uses the stream (seed, step, 0xFFFFFFFF, j). */
+ * i = 0 .. n-1.  QSGD and RSPARSE use the stream (seed, step, 0xFFFFFFFF, j). */
 ds_status_t ds_server_aggregate_compress(ds_ctx_t *ctx, uint64_t step, const ds_payload_t *in,
                                          float *delta_s, const ds_payload_t *out,
                                          void *hip_stream);

@@ -13,7 +13,7 @@ from typing import Optional
 import numpy as np
 import torch
 
-COMP_IDENTITY, COMP_SIGN, COMP_TOPK, COMP_QSGD, COMP_CLIP = 0, 1, 2, 3, 4
+COMP_IDENTITY, COMP_SIGN, COMP_TOPK, COMP_QSGD, COMP_CLIP, COMP_RSPARSE = 0, 1, 2, 3, 4, 5
 SCALE_WHOLE, SCALE_SEGMENTS, SCALE_CHUNK = 0, 1, 2
 F32, BF16 = 0, 1
 FLAG_TOPK_MULTI_LAUNCH = 1
@@ -21,7 +21,7 @@ FLAG_DEFERRED_ERROR = 2
 FLAG_SIGN_RMS = 4
 
 _COMP = {"identity": COMP_IDENTITY, "sign": COMP_SIGN, "topk": COMP_TOPK, "qsgd": COMP_QSGD,
-         "clip": COMP_CLIP}
+         "clip": COMP_CLIP, "rsparse": COMP_RSPARSE}
 _MODE = {"whole": SCALE_WHOLE, "segments": SCALE_SEGMENTS, "chunk": SCALE_CHUNK}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -126,6 +126,9 @@ class Payload:
             self.levels = torch.zeros((rows, (d + 1) // 2), dtype=torch.uint8, device=device)
         elif comp == COMP_CLIP:
             self.levels = torch.zeros((rows, sizes[2] // rows), dtype=torch.uint8, device=device)
+        elif comp == COMP_RSPARSE:
+            self.sign_words = torch.zeros((rows, W), dtype=torch.int64, device=device)
+            self.dense = torch.zeros((rows, d), dtype=torch.float32, device=device)
 
     def c_struct(self) -> ds_payload_t:
         def p(t):
@@ -152,7 +155,8 @@ class Payload:
             out["idx"] = np.ascontiguousarray(pr[:, :, 0])
             out["val"] = np.ascontiguousarray(pr[:, :, 1]).view(np.float32)
         if self.dense is not None:
-            out["dense"] = self.dense.cpu().numpy()
+            # randomised sparsification keeps its packed values in `dense`
+            out["val" if self.comp == COMP_RSPARSE else "dense"] = self.dense.cpu().numpy()
         return out
 
     def load_numpy(self, host: dict) -> None:
@@ -167,7 +171,7 @@ class Payload:
             pr = np.stack([host["idx"], host["val"].view(np.int32)], axis=-1)
             self.pairs.copy_(torch.from_numpy(np.ascontiguousarray(pr)))
         if self.dense is not None:
-            self.dense.copy_(torch.from_numpy(host["dense"]))
+            self.dense.copy_(torch.from_numpy(host["val" if self.comp == COMP_RSPARSE else "dense"]))
 
 
 class Context:
@@ -175,9 +179,11 @@ class Context:
 
     def __init__(self, comp, n: int, d: int, grad_dtype: str = "f32", scale_mode="whole",
                  chunk: int = 0, seg_offsets=None, k: int = 0, bucket: int = 512, levels: int = 15,
-                 seed: int = 0, flags: int = 0):
+                 seed: int = 0, flags: int = 0, keep_prob: Optional[float] = None):
         L = load_library()
         self.comp = _COMP[comp] if isinstance(comp, str) else int(comp)
+        if keep_prob is not None:       # RSPARSE: the probability as a 24-bit threshold
+            k = max(1, min(1 << 24, int(round(float(keep_prob) * (1 << 24)))))
         self.n, self.d, self.k = int(n), int(d), int(k)
         self.grad_dtype = BF16 if grad_dtype in ("bf16", BF16, torch.bfloat16) else F32
         mode = _MODE[scale_mode] if isinstance(scale_mode, str) else int(scale_mode)

@@ -32,6 +32,10 @@ ds_status_t check_payload(const ds_ctx *c, const ds_payload_t *p)
         if (!p->levels) return DS_ERR_NULL;
         if (misaligned(p->levels)) return DS_ERR_ALIGN;
         break;
+    case DS_COMP_RSPARSE:
+        if (!p->sign_words || !p->dense) return DS_ERR_NULL;
+        if (misaligned(p->sign_words) || misaligned(p->dense)) return DS_ERR_ALIGN;
+        break;
     }
     return DS_OK;
 }
@@ -107,6 +111,9 @@ ds_status_t ds_create(const ds_config_t *cfg, ds_ctx_t **out)
     case DS_COMP_CLIP:
         if (cfg->levels < 1 || cfg->levels > 31) return DS_ERR_CONFIG;
         break;
+    case DS_COMP_RSPARSE:
+        if (cfg->k < 1 || cfg->k > (1 << 24)) return DS_ERR_CONFIG;
+        break;
     default:
         return DS_ERR_CONFIG;
     }
@@ -119,6 +126,7 @@ ds_status_t ds_create(const ds_config_t *cfg, ds_ctx_t **out)
     c->S = 0;
     c->inv_n = 1.0f / static_cast<float>(cfg->n);
     c->topk = nullptr;
+    c->rs = nullptr;
     c->sign_tb_mem = nullptr;
     c->sign_partials = nullptr;
     ds_status_t rc = DS_OK;
@@ -128,6 +136,8 @@ ds_status_t ds_create(const ds_config_t *cfg, ds_ctx_t **out)
         c->S = (cfg->d + cfg->bucket - 1) / cfg->bucket;
     } else if (cfg->comp == DS_COMP_TOPK) {
         rc = ds_topk_init(c);
+    } else if (cfg->comp == DS_COMP_RSPARSE) {
+        rc = ds_rsparse_init(c);
     }
     c->cfg.seg_offsets = nullptr;
     if (rc != DS_OK) {
@@ -144,6 +154,7 @@ ds_status_t ds_destroy(ds_ctx_t *c)
     DeviceGuard guard(c->device);
     ds_sign_fini(c);
     ds_topk_fini(c);
+    ds_rsparse_fini(c);
     delete c;
     return DS_OK;
 }
@@ -173,6 +184,10 @@ ds_status_t ds_payload_sizes(const ds_ctx_t *c, int32_t rows, size_t bytes_out[5
     case DS_COMP_CLIP:
         bytes_out[2] = r * d * static_cast<size_t>(ds_clip_bytes(c->cfg.levels));
         break;
+    case DS_COMP_RSPARSE:
+        bytes_out[0] = r * static_cast<size_t>(c->W) * sizeof(uint64_t);
+        bytes_out[4] = r * d * sizeof(float);
+        break;
     }
     return DS_OK;
 }
@@ -194,6 +209,7 @@ ds_status_t ds_worker_compress(ds_ctx_t *c, uint64_t step, const void *g, int64_
     case DS_COMP_TOPK: return ds_topk_worker(c, g, g_row_stride, delta, delta_row_stride, out, st);
     case DS_COMP_QSGD: return ds_qsgd_worker(c, step, g, g_row_stride, delta, delta_row_stride, out, st);
     case DS_COMP_CLIP: return ds_clip_worker(c, g, g_row_stride, delta, delta_row_stride, out, st);
+    case DS_COMP_RSPARSE: return ds_rsparse_worker(c, step, g, g_row_stride, delta, delta_row_stride, out, st);
     }
     return DS_ERR_CONFIG;
 }
@@ -216,6 +232,7 @@ ds_status_t ds_server_aggregate_compress(ds_ctx_t *c, uint64_t step, const ds_pa
     case DS_COMP_TOPK: return ds_topk_server(c, in, delta_s, out, st);
     case DS_COMP_QSGD: return ds_qsgd_server(c, step, in, delta_s, out, st);
     case DS_COMP_CLIP: return ds_clip_server(c, in, delta_s, out, st);
+    case DS_COMP_RSPARSE: return ds_rsparse_server(c, step, in, delta_s, out, st);
     }
     return DS_ERR_CONFIG;
 }
@@ -236,6 +253,7 @@ ds_status_t ds_apply_update(ds_ctx_t *c, const ds_payload_t *srv, float *x, floa
     case DS_COMP_TOPK: return ds_topk_update(c, srv, x, m, gamma, beta, st);
     case DS_COMP_QSGD: return ds_qsgd_update(c, srv, x, m, gamma, beta, st);
     case DS_COMP_CLIP: return ds_clip_update(c, srv, x, m, gamma, beta, st);
+    case DS_COMP_RSPARSE: return ds_rsparse_update(c, srv, x, m, gamma, beta, st);
     }
     return DS_ERR_CONFIG;
 }
@@ -257,6 +275,7 @@ ds_status_t ds_decompress(ds_ctx_t *c, const ds_payload_t *p, int32_t rows, int3
     case DS_COMP_TOPK: return ds_topk_decode(c, p, row, dense_out, st);
     case DS_COMP_QSGD: return ds_qsgd_decode(c, p, row, dense_out, st);
     case DS_COMP_CLIP: return ds_clip_decode(c, p, row, dense_out, st);
+    case DS_COMP_RSPARSE: return ds_rsparse_decode(c, p, row, dense_out, st);
     }
     return DS_ERR_CONFIG;
 }

@@ -21,6 +21,7 @@ struct ds_sign_tables {
 };
 
 struct ds_topk_scratch;  // defined in topk.hip
+struct ds_rs_scratch;    // defined in rsparse.hip
 
 struct ds_ctx {
     ds_config_t cfg;
@@ -41,6 +42,8 @@ struct ds_ctx {
     float *sign_prev_s;    // [S]
     // TOPK
     ds_topk_scratch *topk;
+    // RSPARSE
+    ds_rs_scratch *rs;
 };
 
 #define DS_HIP_TRY(expr)                                 \
@@ -93,6 +96,17 @@ ds_status_t ds_clip_server(ds_ctx *c, const ds_payload_t *in, float *delta_s,
 ds_status_t ds_clip_update(ds_ctx *c, const ds_payload_t *srv, float *x, float *m, float gamma,
                            float beta, hipStream_t st);
 ds_status_t ds_clip_decode(ds_ctx *c, const ds_payload_t *p, int32_t row, float *out, hipStream_t st);
+
+// rsparse.hip
+ds_status_t ds_rsparse_init(ds_ctx *c);
+void ds_rsparse_fini(ds_ctx *c);
+ds_status_t ds_rsparse_worker(ds_ctx *c, uint64_t step, const void *g, int64_t gs, float *delta,
+                              int64_t dstr, const ds_payload_t *out, hipStream_t st);
+ds_status_t ds_rsparse_server(ds_ctx *c, uint64_t step, const ds_payload_t *in, float *delta_s,
+                              const ds_payload_t *out, hipStream_t st);
+ds_status_t ds_rsparse_update(ds_ctx *c, const ds_payload_t *srv, float *x, float *m, float gamma,
+                              float beta, hipStream_t st);
+ds_status_t ds_rsparse_decode(ds_ctx *c, const ds_payload_t *p, int32_t row, float *out, hipStream_t st);
 
 // topk.hip
 ds_status_t ds_topk_init(ds_ctx *c);

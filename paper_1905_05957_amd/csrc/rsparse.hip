@@ -1,0 +1,433 @@
+// Randomised sparsification (Section 3.2 "Randomized Sparsification" of the DoubleSqueeze
+// paper): every element is kept with probability p, and then scaled to z/p, or set to zero,
+// which makes the operator unbiased.  (The section prints p for both outcomes; the zero
+// outcome has probability 1 - p.)
+//
+// Element j of stream s (worker index, 0xFFFFFFFF for the server) at iteration t is kept iff
+// the upper 24 bits of word j & 3 of Philox4x32-10(counter (j >> 2, 0, s, lo32(t)), key
+// (lo32(seed), hi32(seed) ^ hi32(t))) are below P24 = p * 2^24: the same draws as the
+// quantiser's rounding.  The message is the plane of "kept" bits (layout of the sign plane)
+// and the kept values z/p, one IEEE fp32 division each, packed in index order.
+//
+// Packing in index order needs every element's rank among the kept ones.  The keep decisions
+// do not depend on the data, so the writer first runs the generator alone (k_rs_counts: it
+// writes the kept-bit plane, which is part of the message anyway, and the number of kept
+// elements per 256-element subtile), scans the counts, and the ONE dense pass then reads its
+// keep bits back from the plane (1/8 byte per element instead of a second evaluation of the
+// generator) and writes each kept value straight to its final slot: ballots give the rank
+// inside the wavefront's subtile.  A reader gets the same offsets from the population counts
+// of the plane (k_rs_popcounts), so the message carries no offsets.
+#include "ds_device.h"
+#include "ds_internal.h"
+
+#include <new>
+
+using namespace ds;
+
+namespace {
+
+constexpr int kSub = 256;   // elements per wavefront
+
+struct RsParams {
+    uint32_t key0, key1, step_lo;
+    uint32_t p24;    // keep iff 24-bit uniform < p24
+    float p;         // p24 * 2^-24, exact
+};
+
+// bits of a nibble whose elements e..e+3 lie below d
+__device__ __forceinline__ uint32_t valid_nibble(int64_t e, int64_t d)
+{
+    return (e + 4 <= d) ? 15u : (e >= d) ? 0u : ((1u << (d - e)) - 1u);
+}
+
+// keep flags of elements e..e+3 (e a multiple of 4) as a nibble
+__device__ __forceinline__ uint32_t keep_nibble(int64_t e, int64_t d, uint32_t stream, const RsParams &P)
+{
+    const u32x4 r = philox4x32_10(u32x4{static_cast<uint32_t>(e >> 2), 0u, stream, P.step_lo}, P.key0, P.key1);
+    uint32_t nib = 0u;
+    if (e + 0 < d && (r.x >> 8) < P.p24) nib |= 1u;
+    if (e + 1 < d && (r.y >> 8) < P.p24) nib |= 2u;
+    if (e + 2 < d && (r.z >> 8) < P.p24) nib |= 4u;
+    if (e + 3 < d && (r.w >> 8) < P.p24) nib |= 8u;
+    return nib;
+}
+
+__device__ __forceinline__ uint32_t lanes_below(uint64_t m)
+{
+    return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(m >> 32), __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(m), 0u));
+}
+
+// Rank of this lane's first flagged element among the flagged elements of the wavefront's
+// subtile (index order: lane-major, the four elements of a lane in order), and the 32-bit
+// words of the bit plane (lane q < 8 returns word q).
+struct Ranks {
+    uint32_t before;
+    uint32_t word;
+};
+
+__device__ __forceinline__ Ranks subtile_ranks(uint32_t nib)
+{
+    const uint64_t m0 = __ballot(nib & 1u), m1 = __ballot(nib & 2u), m2 = __ballot(nib & 4u), m3 = __ballot(nib & 8u);
+    Ranks r;
+    r.before = lanes_below(m0) + lanes_below(m1) + lanes_below(m2) + lanes_below(m3);
+    const int sh = (lane_id() & 7) * 8;
+    const uint32_t x0 = static_cast<uint32_t>(m0 >> sh) & 0xFFu, x1 = static_cast<uint32_t>(m1 >> sh) & 0xFFu;
+    const uint32_t x2 = static_cast<uint32_t>(m2 >> sh) & 0xFFu, x3 = static_cast<uint32_t>(m3 >> sh) & 0xFFu;
+    r.word = spread4(x0) | (spread4(x1) << 1) | (spread4(x2) << 2) | (spread4(x3) << 3);
+    return r;
+}
+
+// ---------------------------------------------------------------------------------------
+// offsets of the packed values per subtile
+// ---------------------------------------------------------------------------------------
+// Writer side: the kept-bit plane and the kept elements per subtile from the generator alone.
+// A wavefront takes kCountSubs consecutive subtiles (one subtile per workgroup-launch slot made
+// the launch overhead of 100 000 tiny workgroups the cost of this kernel).
+constexpr int kCountSubs = 8;
+
+__global__ __launch_bounds__(kBlock) void k_rs_counts(uint64_t *words, int64_t W, uint32_t *cnt, int64_t n_sub, int64_t d,
+                                                      bool server, RsParams P)
+{
+    const int row = blockIdx.y;
+    const int lane = lane_id();
+    const uint32_t stream = server ? 0xFFFFFFFFu : static_cast<uint32_t>(row);
+    const int64_t s0 = (static_cast<int64_t>(blockIdx.x) * kWaves + wave_id()) * kCountSubs;
+#pragma unroll 2
+    for (int j = 0; j < kCountSubs; ++j) {
+        const int64_t s = s0 + j;
+        if (s >= n_sub) return;                             // uniform over the wavefront
+        const uint32_t nib = keep_nibble(s * kSub + lane * 4, d, stream, P);
+        const Ranks rk = subtile_ranks(nib);
+        if (lane < 8 && s * 8 + lane < 2 * W) reinterpret_cast<uint32_t *>(words + row * W)[s * 8 + lane] = rk.word;
+        const uint32_t c = wave_sum_u32(__popc(nib));
+        if (lane == 0) cnt[row * (n_sub + 1) + s] = c;
+    }
+}
+
+// Reader side: the same counts from the kept-bit plane.  One thread per subtile.
+__global__ __launch_bounds__(kBlock) void k_rs_popcounts(const uint64_t *__restrict__ words, int64_t W, uint32_t *cnt,
+                                                         int64_t n_sub, int64_t d)
+{
+    const int row = blockIdx.y;
+    const int64_t s = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (s >= n_sub) return;
+    const uint64_t *w = words + row * W + s * 4;
+    uint32_t c = 0;
+    for (int q = 0; q < 4; ++q) {
+        const int64_t first = (s * 4 + q) * 64;             // bits at or past d do not count, whatever they hold
+        if (first >= d) break;
+        const uint64_t valid = (d - first >= 64) ? ~0ull : ((1ull << (d - first)) - 1ull);
+        c += __popcll(w[q] & valid);
+    }
+    cnt[row * (n_sub + 1) + s] = c;
+}
+
+// Counts [row][0 .. n_sub) -> exclusive offsets [row][0 .. n_sub], the last one the row's
+// total, in place, in two launches: every workgroup scans its block of 4096 entries and leaves
+// the block's total; then every workgroup adds the totals of the blocks before its own.
+constexpr int kScanPer = 8, kScanBlock = kBlock * kScanPer;
+
+__global__ __launch_bounds__(kBlock) void k_rs_scan_blocks(uint32_t *tab, uint32_t *blk, int64_t n_sub, int64_t n_blk)
+{
+    __shared__ uint32_t tmp[kWaves];
+    uint32_t *row = tab + static_cast<int64_t>(blockIdx.y) * (n_sub + 1);
+    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * kScanBlock + threadIdx.x * kScanPer;
+    uint32_t c[kScanPer], s = 0;
+#pragma unroll
+    for (int j = 0; j < kScanPer; ++j) {
+        c[j] = (t0 + j < n_sub) ? row[t0 + j] : 0u;
+        s += c[j];
+    }
+    const int lane = lane_id();
+    uint32_t p = s;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t up = __shfl_up(p, o, 64);
+        if (lane >= o) p += up;
+    }
+    if (lane == 63) tmp[wave_id()] = p;
+    __syncthreads();
+    uint32_t run = p - s, total = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        if (w < wave_id()) run += tmp[w];
+        total += tmp[w];
+    }
+#pragma unroll
+    for (int j = 0; j < kScanPer; ++j) {
+        if (t0 + j <= n_sub) row[t0 + j] = run;            // entry n_sub receives the running total
+        run += c[j];
+    }
+    if (threadIdx.x == 0) blk[blockIdx.y * n_blk + blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(kBlock) void k_rs_scan_add(uint32_t *tab, const uint32_t *__restrict__ blk, int64_t n_sub,
+                                                        int64_t n_blk)
+{
+    __shared__ uint32_t tmp[kWaves];
+    if (blockIdx.x == 0) return;                            // nothing before the first block
+    const uint32_t *b = blk + blockIdx.y * n_blk;
+    uint32_t s = 0;
+    for (int64_t t = threadIdx.x; t < blockIdx.x; t += kBlock) s += b[t];
+    s = wave_sum_u32(s);
+    if (lane_id() == 0) tmp[wave_id()] = s;
+    __syncthreads();
+    uint32_t before = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) before += tmp[w];
+    uint32_t *row = tab + static_cast<int64_t>(blockIdx.y) * (n_sub + 1);
+    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * kScanBlock + threadIdx.x * kScanPer;
+#pragma unroll
+    for (int j = 0; j < kScanPer; ++j)
+        if (t0 + j <= n_sub) row[t0 + j] += before;
+}
+
+// ---------------------------------------------------------------------------------------
+// the three calls
+// ---------------------------------------------------------------------------------------
+// Q[v] of the four elements of a thread, the message and the error.
+__device__ __forceinline__ void rs_store4(f32x4 v, uint32_t nib, const Ranks &rk, uint32_t base, int64_t e, int64_t d,
+                                          float *__restrict__ vals_row, float *__restrict__ err_row, bool err_vec, float p)
+{
+    const f32x4 q = {(nib & 1u) ? v.x / p : 0.f, (nib & 2u) ? v.y / p : 0.f, (nib & 4u) ? v.z / p : 0.f,
+                     (nib & 8u) ? v.w / p : 0.f};
+    float *out = vals_row + base + rk.before;
+    uint32_t r = 0;
+    if (nib & 1u) out[r++] = q.x;
+    if (nib & 2u) out[r++] = q.y;
+    if (nib & 4u) out[r++] = q.z;
+    if (nib & 8u) out[r++] = q.w;
+    if (e < d) st4(err_row, e, d, err_vec, v - q);
+}
+
+// Algorithm 1, worker block.
+template <bool BF16>
+__global__ __launch_bounds__(kBlock) void k_rs_worker(const void *g, int64_t gs, float *delta, int64_t dstr, int64_t d,
+                                                      const uint64_t *words, int64_t W, float *vals, const uint32_t *off,
+                                                      int64_t n_sub, float p)
+{
+    const int row = blockIdx.y;
+    const int64_t e = static_cast<int64_t>(blockIdx.x) * kTile + threadIdx.x * 4;
+    const int64_t sub = e >> 8;
+    if (sub >= n_sub) return;                               // whole wavefronts
+    const void *grow = BF16 ? static_cast<const void *>(static_cast<const uint16_t *>(g) + row * gs)
+                            : static_cast<const void *>(static_cast<const float *>(g) + row * gs);
+    float *drow = delta + row * dstr;
+    const bool gvec = BF16 ? aligned8(grow) : aligned16(grow);
+    const bool dvec = aligned16(drow);
+    const f32x4 v = ld4_grad<BF16>(grow, e, d, gvec) + ld4(drow, e, d, dvec);
+    const uint32_t nib = (e < d) ? load_sign_nibble(words + row * W, e) : 0u;   // written by k_rs_counts: no bits past d
+    const Ranks rk = subtile_ranks(nib);
+    rs_store4(v, nib, rk, off[row * (n_sub + 1) + sub], e, d, vals + static_cast<int64_t>(row) * d, drow, dvec, p);
+}
+
+// Parameter-server block: v = delta_s + (1/n) sum_i Q[v_i] as the chain acc = fma(q_i, 1/n, acc)
+// over workers in ascending order (elements a worker did not keep add nothing), then the same
+// compressor on the server's stream.
+__global__ __launch_bounds__(kBlock) void k_rs_server(const uint64_t *words_in, const float *vals_in, const uint32_t *off_in,
+                                                      int n, float inv_n, float *delta_s, int64_t d, int64_t W,
+                                                      const uint64_t *words_out, float *vals_out, const uint32_t *off_out,
+                                                      int64_t n_sub, float p)
+{
+    const int64_t base = static_cast<int64_t>(blockIdx.x) * kTile;
+    const int64_t e = base + threadIdx.x * 4;
+    const int lane = lane_id();
+    const int64_t wave_first = base + wave_id() * kSub;
+    const int64_t sub = wave_first >> 8;
+    if (sub >= n_sub) return;                               // whole wavefronts
+    const bool dvec = aligned16(delta_s);
+    f32x4 a = ld4(delta_s, e, d, dvec);
+    {
+        for (int i0 = 0; i0 < n; i0 += 8) {
+            const int nb = (n - i0 < 8) ? n - i0 : 8;
+            // lane L: 32-bit word L & 7 of the plane of worker i0 + (L >> 3); lane i: offset of worker i0 + i
+            uint32_t word = 0u;
+            if ((lane >> 3) < nb && wave_first + 32 * (lane & 7) < W * 64)
+                word = reinterpret_cast<const uint32_t *>(words_in + (i0 + (lane >> 3)) * W)[(wave_first >> 5) + (lane & 7)];
+            const uint32_t o = (lane < nb) ? off_in[(i0 + lane) * (n_sub + 1) + sub] : 0u;
+            // all loads of the batch first (independent), then the chain in worker order
+            f32x4 q[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                q[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (i < nb) {                               // uniform
+                    const uint32_t w = __shfl(word, i * 8 + (lane >> 3), 64);
+                    const uint32_t nib = (w >> (4 * (lane & 7))) & valid_nibble(e, d);
+                    const Ranks rk = subtile_ranks(nib);
+                    const float *src = vals_in + static_cast<int64_t>(i0 + i) * d +
+                                       static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(o), i)) + rk.before;
+                    uint32_t r = 0;
+                    if (nib & 1u) q[i].x = src[r++];
+                    if (nib & 2u) q[i].y = src[r++];
+                    if (nib & 4u) q[i].z = src[r++];
+                    if (nib & 8u) q[i].w = src[r++];
+                    // an element that was not kept adds nothing: fma(0, 1/n, a) = a
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (i < nb) a = fma4(inv_n, q[i], a);
+        }
+    }
+    const uint32_t nib = (e < d) ? load_sign_nibble(words_out, e) : 0u;         // written by k_rs_counts
+    const Ranks rk = subtile_ranks(nib);
+    rs_store4(a, nib, rk, off_out[sub], e, d, vals_out, delta_s, dvec, p);
+}
+
+// Model update / decoder from one message.  SPARSE (plain update, small p): only the kept
+// elements are touched, x - gamma * 0 is x exactly; otherwise 128-bit accesses to all of x.
+template <bool MOM, bool DECODE_ONLY, bool SPARSE>
+__global__ __launch_bounds__(kBlock) void k_rs_apply(const uint64_t *__restrict__ words, const float *__restrict__ vals,
+                                                     const uint32_t *__restrict__ off, float *x, float *m, int64_t d,
+                                                     int64_t W, int64_t n_sub, float gamma, float beta)
+{
+    const int64_t e = (static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x) * 4;
+    const int64_t sub = e >> 8;
+    if (sub >= n_sub) return;                               // whole wavefronts
+    const uint32_t nib = (e < d) ? (load_sign_nibble(words, e) & valid_nibble(e, d)) : 0u;
+    const Ranks rk = subtile_ranks(nib);
+    const float *src = vals + off[sub] + rk.before;
+    f32x4 q = {0.f, 0.f, 0.f, 0.f};
+    uint32_t r = 0;
+    if (nib & 1u) q.x = src[r++];
+    if (nib & 2u) q.y = src[r++];
+    if (nib & 4u) q.z = src[r++];
+    if (nib & 8u) q.w = src[r++];
+    if (e >= d) return;
+    if constexpr (SPARSE) {
+        if (nib & 1u) x[e] = __fmaf_rn(-gamma, q.x, x[e]);
+        if (nib & 2u) x[e + 1] = __fmaf_rn(-gamma, q.y, x[e + 1]);
+        if (nib & 4u) x[e + 2] = __fmaf_rn(-gamma, q.z, x[e + 2]);
+        if (nib & 8u) x[e + 3] = __fmaf_rn(-gamma, q.w, x[e + 3]);
+    } else {
+        apply_q4<MOM, DECODE_ONLY>(q, e, d, x, m, gamma, beta);
+    }
+}
+
+unsigned blocks4(int64_t d) { return static_cast<unsigned>((d + kBlock * 4 - 1) / (kBlock * 4)); }
+
+void scan_rows(uint32_t *tab, uint32_t *blk, int64_t n_sub, int64_t n_blk, unsigned rows, hipStream_t st)
+{
+    const dim3 grid(static_cast<unsigned>(n_blk), rows);
+    k_rs_scan_blocks<<<grid, kBlock, 0, st>>>(tab, blk, n_sub, n_blk);
+    if (n_blk > 1) k_rs_scan_add<<<grid, kBlock, 0, st>>>(tab, blk, n_sub, n_blk);
+}
+
+RsParams make_params(const ds_ctx *c, uint64_t step)
+{
+    RsParams P;
+    P.key0 = static_cast<uint32_t>(c->cfg.seed);
+    P.key1 = static_cast<uint32_t>(c->cfg.seed >> 32) ^ static_cast<uint32_t>(step >> 32);
+    P.step_lo = static_cast<uint32_t>(step);
+    P.p24 = static_cast<uint32_t>(c->cfg.k);
+    P.p = static_cast<float>(c->cfg.k) * (1.0f / 16777216.0f);
+    return P;
+}
+
+}  // namespace
+
+struct ds_rs_scratch {
+    int64_t n_sub;
+    uint32_t *off_w;    // [n][n_sub + 1]  worker messages, writer side
+    uint32_t *off_in;   // [n][n_sub + 1]  worker messages, as read by the server
+    uint32_t *off_s;    // [n_sub + 1]     server message, writer side
+    uint32_t *off_r;    // [n_sub + 1]     a message as read by the update / decoder
+    uint32_t *blk;      // [n][n_blk]      block totals of the scan
+    int64_t n_blk;
+};
+
+ds_status_t ds_rsparse_init(ds_ctx *c)
+{
+    ds_rs_scratch *t = new (std::nothrow) ds_rs_scratch();
+    if (!t) return DS_ERR_DEVICE;
+    *t = ds_rs_scratch{};
+    c->rs = t;
+    t->n_sub = (c->cfg.d + kSub - 1) / kSub;
+    const size_t row = static_cast<size_t>(t->n_sub + 1) * sizeof(uint32_t), n = static_cast<size_t>(c->cfg.n);
+    DS_HIP_TRY(hipMalloc(&t->off_w, n * row));
+    DS_HIP_TRY(hipMalloc(&t->off_in, n * row));
+    DS_HIP_TRY(hipMalloc(&t->off_s, row));
+    DS_HIP_TRY(hipMalloc(&t->off_r, row));
+    t->n_blk = (t->n_sub + 1 + kScanBlock - 1) / kScanBlock;
+    DS_HIP_TRY(hipMalloc(&t->blk, n * static_cast<size_t>(t->n_blk) * sizeof(uint32_t)));
+    return DS_OK;
+}
+
+void ds_rsparse_fini(ds_ctx *c)
+{
+    ds_rs_scratch *t = c->rs;
+    if (!t) return;
+    void *ptrs[5] = {t->off_w, t->off_in, t->off_s, t->off_r, t->blk};
+    for (void *p : ptrs)
+        if (p) (void)hipFree(p);
+    delete t;
+    c->rs = nullptr;
+}
+
+ds_status_t ds_rsparse_worker(ds_ctx *c, uint64_t step, const void *g, int64_t gs, float *delta, int64_t dstr,
+                              const ds_payload_t *out, hipStream_t st)
+{
+    ds_rs_scratch *t = c->rs;
+    const RsParams P = make_params(c, step);
+    const unsigned n = static_cast<unsigned>(c->cfg.n);
+    k_rs_counts<<<dim3(static_cast<unsigned>((t->n_sub + kWaves * kCountSubs - 1) / (kWaves * kCountSubs)), n), kBlock, 0, st>>>(
+        out->sign_words, c->W, t->off_w, t->n_sub, c->cfg.d, false, P);
+    scan_rows(t->off_w, t->blk, t->n_sub, t->n_blk, n, st);
+    const dim3 grid(static_cast<unsigned>(c->n_tiles), n);
+    if (c->cfg.grad_dtype == DS_BF16)
+        k_rs_worker<true><<<grid, kBlock, 0, st>>>(g, gs, delta, dstr, c->cfg.d, out->sign_words, c->W, out->dense, t->off_w,
+                                                   t->n_sub, P.p);
+    else
+        k_rs_worker<false><<<grid, kBlock, 0, st>>>(g, gs, delta, dstr, c->cfg.d, out->sign_words, c->W, out->dense, t->off_w,
+                                                    t->n_sub, P.p);
+    return ds_launch_status();
+}
+
+ds_status_t ds_rsparse_server(ds_ctx *c, uint64_t step, const ds_payload_t *in, float *delta_s, const ds_payload_t *out,
+                              hipStream_t st)
+{
+    ds_rs_scratch *t = c->rs;
+    const RsParams P = make_params(c, step);
+    const unsigned n = static_cast<unsigned>(c->cfg.n);
+    k_rs_popcounts<<<dim3(static_cast<unsigned>((t->n_sub + kBlock - 1) / kBlock), n), kBlock, 0, st>>>(in->sign_words, c->W,
+                                                                                                     t->off_in, t->n_sub, c->cfg.d);
+    scan_rows(t->off_in, t->blk, t->n_sub, t->n_blk, n, st);
+    k_rs_counts<<<dim3(static_cast<unsigned>((t->n_sub + kWaves * kCountSubs - 1) / (kWaves * kCountSubs)), 1), kBlock, 0, st>>>(
+        out->sign_words, c->W, t->off_s, t->n_sub, c->cfg.d, true, P);
+    scan_rows(t->off_s, t->blk, t->n_sub, t->n_blk, 1, st);
+    k_rs_server<<<static_cast<unsigned>(c->n_tiles), kBlock, 0, st>>>(in->sign_words, in->dense, t->off_in, c->cfg.n, c->inv_n,
+                                                                    delta_s, c->cfg.d, c->W, out->sign_words, out->dense,
+                                                                    t->off_s, t->n_sub, P.p);
+    return ds_launch_status();
+}
+
+template <bool DECODE_ONLY>
+static ds_status_t rs_apply(ds_ctx *c, const uint64_t *words, const float *vals, float *x, float *m, float gamma, float beta,
+                            hipStream_t st)
+{
+    ds_rs_scratch *t = c->rs;
+    k_rs_popcounts<<<dim3(static_cast<unsigned>((t->n_sub + kBlock - 1) / kBlock), 1), kBlock, 0, st>>>(words, c->W, t->off_r,
+                                                                                                     t->n_sub, c->cfg.d);
+    scan_rows(t->off_r, t->blk, t->n_sub, t->n_blk, 1, st);
+    const unsigned blocks = blocks4(t->n_sub * kSub);
+    if (DECODE_ONLY)
+        k_rs_apply<false, true, false><<<blocks, kBlock, 0, st>>>(words, vals, t->off_r, x, nullptr, c->cfg.d, c->W, t->n_sub, 0.f, 0.f);
+    else if (m)
+        k_rs_apply<true, false, false><<<blocks, kBlock, 0, st>>>(words, vals, t->off_r, x, m, c->cfg.d, c->W, t->n_sub, gamma, beta);
+    else if (c->cfg.k < (1 << 20))      // p < 1/16: most 64-byte lines of x hold no kept element
+        k_rs_apply<false, false, true><<<blocks, kBlock, 0, st>>>(words, vals, t->off_r, x, m, c->cfg.d, c->W, t->n_sub, gamma, beta);
+    else
+        k_rs_apply<false, false, false><<<blocks, kBlock, 0, st>>>(words, vals, t->off_r, x, m, c->cfg.d, c->W, t->n_sub, gamma, beta);
+    return ds_launch_status();
+}
+
+ds_status_t ds_rsparse_update(ds_ctx *c, const ds_payload_t *srv, float *x, float *m, float gamma, float beta, hipStream_t st)
+{
+    return rs_apply<false>(c, srv->sign_words, srv->dense, x, m, gamma, beta, st);
+}
+
+ds_status_t ds_rsparse_decode(ds_ctx *c, const ds_payload_t *p, int32_t row, float *out, hipStream_t st)
+{
+    return rs_apply<true>(c, p->sign_words + static_cast<int64_t>(row) * c->W, p->dense + static_cast<int64_t>(row) * c->cfg.d,
+                          out, nullptr, 0.f, 0.f, st);
+}
