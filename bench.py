@@ -33,6 +33,7 @@ MEASURED_WORKER_TRAFFIC = {
     "c4": 3.3100e9 + 1.9392e9,   # k_qsgd_worker
     "c3": 2.6375e9,              # all kernels of the worker call (dense pass 2.4962e9)
     "clip16": 1.6557e9 + 1.2374e9,   # k_clip_worker
+    "rsparse60": 1.7087e9 + 1.3114e9 + 0.0294e9 + 0.013e9,   # k_rs_worker + k_rs_counts + the two scan launches
     "c2": 1.1025e9,              # k_sign_pass1_worker, deferred error form (plain form: pass 1 + pass 2 = 1.8343e9)
 }
 
