@@ -68,6 +68,8 @@ def test_create_rejects_bad_arguments_before_any_device_work():
     assert _create(comp=B.COMP_TOPK, k=0) == 2 and _create(comp=B.COMP_TOPK, k=2000) == 2
     assert _create(comp=B.COMP_QSGD, bucket=100) == 3
     assert _create(comp=B.COMP_QSGD, levels=16) == 3
+    assert _create(comp=B.COMP_CLIP, levels=0) == 3 and _create(comp=B.COMP_CLIP, levels=32) == 3
+    assert _create(comp=B.COMP_RSPARSE, k=0) == 3 and _create(comp=B.COMP_RSPARSE, k=(1 << 24) + 1) == 3
 
 
 def test_destroy_accepts_null():
