@@ -71,7 +71,8 @@ def make_workload(name: str):
     return {"c2": W.c2, "c3": W.c3, "c4": W.c4, "c5": W.c5, "clip16": W.clip16, "rsparse60": W.rsparse60}[name]()
 
 
-def run_gpu(wl, steps: int, warmup: int, sets: int = 2, calib_copy: bool = False, deferred_error: bool = True):
+def run_gpu(wl, steps: int, warmup: int, sets: int = 2, calib_copy: bool = False, deferred_error: bool = True,
+            separate_update: bool = False):
     import torch
     import paper_1905_05957_amd as P
 
@@ -97,12 +98,15 @@ def run_gpu(wl, steps: int, warmup: int, sets: int = 2, calib_copy: bool = False
         ctx.worker_compress(t, g, delta, pw)
         if ev is not None:
             ev[1].record(stream)
-        ctx.server_aggregate_compress(t, pw, delta_s, ps)
-        if stages:
-            ev[2].record(stream)
-        ctx.apply_update(ps, x, m, wl.gamma, beta)
-        if stages:
-            ev[3].record(stream)
+        if stages or separate_update:
+            ctx.server_aggregate_compress(t, pw, delta_s, ps)
+            if stages:
+                ev[2].record(stream)
+            ctx.apply_update(ps, x, m, wl.gamma, beta)
+            if stages:
+                ev[3].record(stream)
+        else:       # the same two blocks of Algorithm 1 through the one-call entry point
+            ctx.server_aggregate_compress_update(t, pw, delta_s, ps, x, m, wl.gamma, beta)
 
     for t in range(warmup):
         step(t)
@@ -111,7 +115,7 @@ def run_gpu(wl, steps: int, warmup: int, sets: int = 2, calib_copy: bool = False
     # to back (seen in the kernel trace), so the timed region carries events only around the
     # worker call of every 3rd step: enough for the average launch duration of the dominant
     # kernel (roofline) at under 1 % of a step.  The per-stage split comes from a second,
-    # untimed pass over the same number of steps.
+    # untimed pass over the same number of steps (always the three separate calls).
     every = 3     # odd: the sampled steps alternate between the gradient sets
     evs = {t: [torch.cuda.Event(enable_timing=True) for _ in range(2)] for t in range(0, steps, every)}
     torch.cuda.synchronize()
@@ -197,6 +201,9 @@ def main():
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy (calibration dispatch for rocprofv3 --pmc byte counters)")
     ap.add_argument("--cpu-elems", type=int, default=400_000_000)
+    ap.add_argument("--separate-update", action="store_true",
+                    help="time ds_server_aggregate_compress and ds_apply_update as two calls (default: the "
+                         "one-call form ds_server_aggregate_compress_update, same results)")
     ap.add_argument("--plain-error", action="store_true",
                     help="keep the error buffers in plain form after every call (sign with scale groups that "
                          "span workgroups then takes two looks per call; default: DS_FLAG_DEFERRED_ERROR)")
@@ -213,12 +220,15 @@ def main():
 
     def measure(name, steps, warmup, calib_copy=False):
         wl = make_workload(name)
-        r = run_gpu(wl, steps, warmup, calib_copy=calib_copy, deferred_error=not a.plain_error)
+        r = run_gpu(wl, steps, warmup, calib_copy=calib_copy, deferred_error=not a.plain_error,
+                    separate_update=a.separate_update)
         ab = algorithmic_bytes(wl, r["S"])
         ms = r["ms_per_step"]
         wk_ms = r["worker_ms"]
         out = {
             "workload": wl.name, "n": wl.n, "d": wl.d, "ms_per_step": ms,
+            "calls": "ds_worker_compress + " + ("ds_server_aggregate_compress + ds_apply_update" if a.separate_update
+                                                else "ds_server_aggregate_compress_update"),
             "error_state": "plain" if a.plain_error or not (wl.comp == "sign" and wl.scale_mode != "chunk") else "deferred",
             "value": wl.n * wl.d / (ms * 1e-3),
             "stage_ms": {"worker": r["stage_ms"][0], "server": r["stage_ms"][1], "update": r["stage_ms"][2]},

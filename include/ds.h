@@ -205,6 +205,15 @@ ds_status_t ds_server_aggregate_compress(ds_ctx_t *ctx, uint64_t step, const ds_
 ds_status_t ds_apply_update(ds_ctx_t *ctx, const ds_payload_t *srv, float *x, float *m,
                             float gamma, float beta, void *hip_stream);
 
+/* The parameter-server block followed by the model update, as one call: the same results, bit
+ * for bit, as ds_server_aggregate_compress(ctx, step, in, delta_s, out, stream) followed by
+ * ds_apply_update(ctx, out, x, m, gamma, beta, stream), for the library to fold the update
+ * into the server's kernels where that saves a pass (TOPK without momentum: x is updated
+ * where the kept entries are emitted).  Arguments and errors as for those two calls. */
+ds_status_t ds_server_aggregate_compress_update(ds_ctx_t *ctx, uint64_t step, const ds_payload_t *in,
+                                                float *delta_s, const ds_payload_t *out, float *x,
+                                                float *m, float gamma, float beta, void *hip_stream);
+
 /* Decodes message `row` of a batch of `rows` messages into dense_out [d] (fp32): the
  * decoder of Q[.] that the server and the update use. */
 ds_status_t ds_decompress(ds_ctx_t *ctx, const ds_payload_t *p, int32_t rows, int32_t row,

@@ -49,7 +49,7 @@ class ds_payload_t(C.Structure):
 
 EXPORTS = ["ds_create", "ds_destroy", "ds_payload_sizes", "ds_worker_compress",
            "ds_server_aggregate_compress", "ds_apply_update", "ds_decompress", "ds_materialize_error",
-           "ds_status_string", "ds_version"]
+           "ds_server_aggregate_compress_update", "ds_status_string", "ds_version"]
 
 _lib = None
 
@@ -79,7 +79,9 @@ def load_library():
     L.ds_apply_update.argtypes = [vp, C.POINTER(ds_payload_t), vp, vp, f32, f32, vp]
     L.ds_decompress.argtypes = [vp, C.POINTER(ds_payload_t), i32, i32, vp, vp]
     L.ds_materialize_error.argtypes = [vp, vp, i64, vp, vp]
-    for name in EXPORTS[:8]:
+    L.ds_server_aggregate_compress_update.argtypes = [vp, u64, C.POINTER(ds_payload_t), vp, C.POINTER(ds_payload_t),
+                                                      vp, vp, f32, f32, vp]
+    for name in EXPORTS[:9]:
         getattr(L, name).restype = C.c_int
     L.ds_status_string.argtypes = [C.c_int]
     L.ds_status_string.restype = C.c_char_p
@@ -238,6 +240,15 @@ class Context:
                                                            _stream_ptr(stream)),
                "ds_server_aggregate_compress")
 
+    def server_aggregate_compress_update(self, step: int, inp: Payload, delta_s: torch.Tensor, out: Payload,
+                                         x: torch.Tensor, m: Optional[torch.Tensor], gamma: float,
+                                         beta: float = 0.0, stream=None):
+        a, b = inp.c_struct(), out.c_struct()
+        _check(load_library().ds_server_aggregate_compress_update(
+            self._h, step, C.byref(a), delta_s.data_ptr(), C.byref(b), x.data_ptr(),
+            None if m is None else m.data_ptr(), gamma, beta, _stream_ptr(stream)),
+            "ds_server_aggregate_compress_update")
+
     def apply_update(self, srv: Payload, x: torch.Tensor, m: Optional[torch.Tensor], gamma: float,
                      beta: float = 0.0, stream=None):
         s = srv.c_struct()
@@ -274,6 +285,10 @@ def ds_payload_sizes(ctx: Context, rows: int):
 
 def ds_worker_compress(ctx: Context, step, g, delta, out, stream=None):
     ctx.worker_compress(step, g, delta, out, stream)
+
+
+def ds_server_aggregate_compress_update(ctx: Context, step, inp, delta_s, out, x, m, gamma, beta=0.0, stream=None):
+    ctx.server_aggregate_compress_update(step, inp, delta_s, out, x, m, gamma, beta, stream)
 
 
 def ds_materialize_error(ctx: Context, delta, delta_s, stream=None):

@@ -280,6 +280,27 @@ ds_status_t ds_decompress(ds_ctx_t *c, const ds_payload_t *p, int32_t rows, int3
     return DS_ERR_CONFIG;
 }
 
+ds_status_t ds_server_aggregate_compress_update(ds_ctx_t *c, uint64_t step, const ds_payload_t *in, float *delta_s,
+                                                const ds_payload_t *out, float *x, float *m, float gamma, float beta,
+                                                void *hip_stream)
+{
+    if (!c || !delta_s || !x) return DS_ERR_NULL;
+    ds_status_t rc = check_payload(c, in);
+    if (rc != DS_OK) return rc;
+    rc = check_payload(c, out);
+    if (rc != DS_OK) return rc;
+    if (misaligned(delta_s) || misaligned(x) || (m && misaligned(m))) return DS_ERR_ALIGN;
+    if (c->cfg.comp == DS_COMP_TOPK && !m) {
+        // the kept entries of the server's message are the update: applied where they are emitted
+        DeviceGuard guard(c->device);
+        if (!guard.ok) return DS_ERR_DEVICE;
+        return ds_topk_server(c, in, delta_s, out, static_cast<hipStream_t>(hip_stream), x, gamma);
+    }
+    rc = ds_server_aggregate_compress(c, step, in, delta_s, out, hip_stream);
+    if (rc != DS_OK) return rc;
+    return ds_apply_update(c, out, x, m, gamma, beta, hip_stream);
+}
+
 ds_status_t ds_materialize_error(ds_ctx_t *c, float *delta, int64_t delta_row_stride, float *delta_s, void *hip_stream)
 {
     if (!c) return DS_ERR_NULL;

@@ -114,7 +114,7 @@ void ds_topk_fini(ds_ctx *c);
 ds_status_t ds_topk_worker(ds_ctx *c, const void *g, int64_t gs, float *delta, int64_t dstr,
                            const ds_payload_t *out, hipStream_t st);
 ds_status_t ds_topk_server(ds_ctx *c, const ds_payload_t *in, float *delta_s,
-                           const ds_payload_t *out, hipStream_t st);
+                           const ds_payload_t *out, hipStream_t st, float *x = nullptr, float gamma = 0.f);
 ds_status_t ds_topk_update(ds_ctx *c, const ds_payload_t *srv, float *x, float *m, float gamma,
                            float beta, hipStream_t st);
 ds_status_t ds_topk_decode(ds_ctx *c, const ds_payload_t *p, int32_t row, float *out, hipStream_t st);

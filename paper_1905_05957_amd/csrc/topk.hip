@@ -877,9 +877,12 @@ __global__ __launch_bounds__(kBlock) void k_topk_count(const u32x2 *slots, const
 // One group: write the kept entries in index order; the dense pass left 0 at every
 // candidate position of the error buffer, so the candidates that are not kept get v back
 // (delta = v - Q[v] is 0 at kept positions and v elsewhere).  eq_seen = ties at T in earlier
-// groups, out = first output slot of the group.  Called by whole wavefronts.
+// groups, out = first output slot of the group.  x != nullptr: the model update of Algorithm 1
+// for this message, x <- fma(-gamma, val, x) at the kept indices, in the same pass.
+// Called by whole wavefronts.
 __device__ __forceinline__ void emit_group(const GroupWalk &w, const u32x2 *__restrict__ srow, int64_t g, uint32_t T,
-                                           uint32_t k3, uint32_t eq_seen, uint32_t out, u32x2 *prow, float *brow, int64_t k)
+                                           uint32_t k3, uint32_t eq_seen, uint32_t out, u32x2 *prow, float *brow, int64_t k,
+                                           float *x = nullptr, float gamma = 0.f)
 {
     for (uint32_t i0 = 0; i0 < w.total; i0 += 64 * kPrefetch) {
         const Batch bt = group_fetch_batches(w, srow, g, i0);
@@ -896,6 +899,7 @@ __device__ __forceinline__ void emit_group(const GroupWalk &w, const u32x2 *__re
             if (keep) {
                 const uint32_t slot = out + lanes_below(keep_mask);
                 if (slot < k) prow[slot] = pr;
+                if (x) x[pr.x] = __fmaf_rn(-gamma, __uint_as_float(pr.y), x[pr.x]);
             } else if (valid) {
                 __builtin_nontemporal_store(__uint_as_float(pr.y), brow + pr.x);   // not kept: delta = v
             }
@@ -908,7 +912,7 @@ __device__ __forceinline__ void emit_group(const GroupWalk &w, const u32x2 *__re
 __global__ __launch_bounds__(kBlock) void k_topk_emit(const u32x2 *slots, const uint32_t *reg_cnt, int64_t n_reg,
                                                       int64_t reg_pad, int64_t n_groups, const Sel *sel,
                                                       const uint32_t *grp_eqb, const uint32_t *grp_out, int64_t k,
-                                                      u32x2 *pairs, float *buf, int64_t stride)
+                                                      u32x2 *pairs, float *buf, int64_t stride, float *x, float gamma)
 {
     const int row = blockIdx.y;
     const int64_t g = static_cast<int64_t>(blockIdx.x) * kWaves + wave_id();
@@ -916,7 +920,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_emit(const u32x2 *slots, const 
     const Sel s = sel[row];
     const GroupWalk w = group_begin(reg_cnt + row * reg_pad, g, n_reg);
     emit_group(w, slots + static_cast<int64_t>(row) * n_reg * kReg, g, s.T, s.k3, grp_eqb[row * n_groups + g],
-               grp_out[row * n_groups + g], pairs + static_cast<int64_t>(row) * k, buf + row * stride, k);
+               grp_out[row * n_groups + g], pairs + static_cast<int64_t>(row) * k, buf + row * stride, k, x, gamma);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1075,6 +1079,8 @@ struct FinishArgs {
     float *buf;
     int64_t stride, d, k;
     u32x2 *pairs;
+    float *x;              // not null: the model update is applied with the emission (one-row launches only)
+    float gamma;
     uint32_t *zero_a, *zero_b;   // histogram halves of the next call, cleared here
     int64_t zero_a_words, zero_b_words;
 };
@@ -1220,7 +1226,7 @@ __global__ __launch_bounds__(kBlock, 8) void k_topk_finish(FinishArgs a)
             if (lane_id() < wave_id()) { wg = dev_load(&gtr[gb + lane_id()]); we = dev_load(&eqr[gb + lane_id()]); }
             const uint32_t gtb = sum_gt + wave_sum_u32(wg), eqb = sum_eq + wave_sum_u32(we);
             const GroupWalk w = group_begin(cnt_row, g, a.n_reg);
-            emit_group(w, srow, g, T, k3, eqb, gtb + (eqb < k3 ? eqb : k3), prow, brow, a.k);
+            emit_group(w, srow, g, T, k3, eqb, gtb + (eqb < k3 ? eqb : k3), prow, brow, a.k, a.x, a.gamma);
         }
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) a.prev_T[row] = T;   // centre of the next call's fine sampling window
@@ -1280,7 +1286,7 @@ unsigned persistent_blocks(int64_t n_tiles, int rows)
 // sample -> dense pass -> refinement -> ordered emission, for `rows` vectors
 template <class Src>
 ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t stride, u32x2 *pairs, hipStream_t st,
-                       uint32_t *prev_T)
+                       uint32_t *prev_T, float *x = nullptr, float gamma = 0.f)
 {
     ds_topk_scratch *t = c->topk;
     if (__atomic_load_n(t->abort_host, __ATOMIC_RELAXED)) return DS_ERR_DEVICE;   // an earlier launch gave up waiting
@@ -1320,7 +1326,7 @@ ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t 
         a.n_reg = n_reg; a.reg_pad = reg_pad; a.n_groups = n_groups; a.n_sub = n_sub;
         a.sel = t->sel; a.fhist = fh; a.sync = t->sync; a.abort_flag = t->abort_host; a.spin_limit = t->spin_limit;
         a.grp_gt = t->grp_gt; a.grp_eq = t->grp_eq; a.prev_T = prev_T;
-        a.buf = buf; a.stride = stride; a.d = d; a.k = k; a.pairs = pairs;
+        a.buf = buf; a.stride = stride; a.d = d; a.k = k; a.pairs = pairs; a.x = x; a.gamma = gamma;
         a.zero_a = hist_next; a.zero_a_words = static_cast<int64_t>(t->rows) * kHistRow;
         a.zero_b = fh_next; a.zero_b_words = static_cast<int64_t>(t->rows) * kFRow;
         k_topk_finish<<<dim3(static_cast<unsigned>(G), rows), kBlock, 0, st>>>(a);
@@ -1339,7 +1345,7 @@ ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t 
                                           t->grp_eqb, t->grp_out, t->done, hist_next,
                                           static_cast<int64_t>(t->rows) * kHistRow);
     k_topk_emit<<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, t->grp_eqb, t->grp_out, k,
-                                         pairs, buf, stride);
+                                         pairs, buf, stride, x, gamma);
     return ds_launch_status();
 }
 
@@ -1425,7 +1431,9 @@ ds_status_t ds_topk_worker(ds_ctx *c, const void *g, int64_t gs, float *delta, i
     return run_select(c, rows, WorkerV<false>{g, gs, delta, dstr}, delta, dstr, pairs, st, c->topk->prev_T);
 }
 
-ds_status_t ds_topk_server(ds_ctx *c, const ds_payload_t *in, float *delta_s, const ds_payload_t *out, hipStream_t st)
+// x != nullptr: also x <- fma(-gamma, val, x) at the kept indices of the server's message.
+ds_status_t ds_topk_server(ds_ctx *c, const ds_payload_t *in, float *delta_s, const ds_payload_t *out, hipStream_t st,
+                           float *x, float gamma)
 {
     ds_topk_scratch *t = c->topk;
     const u32x2 *pairs_in = reinterpret_cast<const u32x2 *>(in->pairs);
@@ -1437,7 +1445,7 @@ ds_status_t ds_topk_server(ds_ctx *c, const ds_payload_t *in, float *delta_s, co
         k_topk_sub_starts<<<dim3(static_cast<unsigned>((t->n_sub + 1 + kBlock - 1) / kBlock), c->cfg.n), kBlock, 0, st>>>(
             pairs_in, k, t->n_sub, t->sub_start);
     const ServerV src{pairs_in, t->sub_start, delta_s, k, t->n_sub, c->cfg.n, c->inv_n};
-    return run_select(c, 1, src, delta_s, c->cfg.d, reinterpret_cast<u32x2 *>(out->pairs), st, t->prev_T + t->rows);
+    return run_select(c, 1, src, delta_s, c->cfg.d, reinterpret_cast<u32x2 *>(out->pairs), st, t->prev_T + t->rows, x, gamma);
 }
 
 ds_status_t ds_topk_update(ds_ctx *c, const ds_payload_t *srv, float *x, float *m, float gamma, float beta, hipStream_t st)
