@@ -200,7 +200,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy (calibration dispatch for rocprofv3 --pmc byte counters)")
-    ap.add_argument("--cpu-elems", type=int, default=400_000_000)
+    ap.add_argument("--cpu-elems", type=int, default=1_000_000_000)
     ap.add_argument("--separate-update", action="store_true",
                     help="time ds_server_aggregate_compress and ds_apply_update as two calls (default: the "
                          "one-call form ds_server_aggregate_compress_update, same results)")
