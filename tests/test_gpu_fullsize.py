@@ -5,7 +5,8 @@ so each test compares what it can compute exactly in seconds:
       scale), gathered into a smaller problem with the same structure;
   C4  two whole worker rows (first and last stream), the whole server pass and update;
   C3  one whole worker row, the whole server pass and update, plus properties of every row;
-  C2  the whole step.
+  C2  the whole step;
+  X1, X2 (clipping, randomised sparsification at 8 x 25.6 M)  as C4.
 """
 import numpy as np
 import pytest
@@ -142,5 +143,40 @@ def test_c3_row_server_and_properties(gpu_device):
         assert_close_rows(pair.delta_s.cpu().numpy(), h_ds, "C3 delta_s")
         O.apply_update(cfg, gpu_ps, h_x, None, wl.gamma)
         assert_close_rows(pair.x.cpu().numpy(), h_x, "C3 x")
+    finally:
+        pair.close()
+
+
+@pytest.mark.parametrize("which", ["clip16", "rsparse60"])
+def test_x_rows_and_server(gpu_device, which):
+    """The two further compressors at 8 x 25.6 M: two whole worker rows (first and last stream),
+    the whole server pass and the update."""
+    from parity_util import keep_prob_24
+    wl = W.clip16() if which == "clip16" else W.rsparse60()
+    n, d = wl.n, wl.d
+    cfg = oracle_config(wl)
+    comp = O.CLIP if which == "clip16" else O.RSPARSE
+    pair = Pair(wl, gpu_device)
+    try:
+        pair.gpu_step(0, wl.gradients(0, gpu_device))
+        g = wl.gradients(1, gpu_device)
+        t = 1
+        rows = [0, n - 1]
+        v = {r: (g[r] + pair.delta[r]).cpu().numpy() for r in rows}      # one fp32 add per element
+        h_ds = pair.delta_s.cpu().numpy().copy()
+        h_x = pair.x.cpu().numpy().copy()
+        pair.gpu_step(t, g)
+        gpu_pw, gpu_ps = pair.pw.to_numpy(), pair.ps.to_numpy()
+        one = O.Config(comp, n=1, d=d, seed=wl.seed, clip_bits=wl.clip_bits, keep_prob=keep_prob_24(wl.keep_prob))
+        for r in rows:
+            ref = O.encode(one, t, r, v[r])                              # stream = worker index
+            got = {k: a[r:r + 1] for k, a in gpu_pw.items()}
+            assert_payload_equal(got, ref, f"{which} worker row {r}")
+            assert_close_rows(pair.delta[r].cpu().numpy(), v[r] - O.decode(one, ref), f"{which} delta row {r}")
+        ref_ps = O.server_aggregate_compress(cfg, t, gpu_pw, h_ds)
+        assert_payload_equal(gpu_ps, ref_ps, f"{which} server payload")
+        assert_close_rows(pair.delta_s.cpu().numpy(), h_ds, f"{which} delta_s")
+        O.apply_update(cfg, gpu_ps, h_x, None, wl.gamma)
+        assert_close_rows(pair.x.cpu().numpy(), h_x, f"{which} x")
     finally:
         pair.close()
