@@ -28,6 +28,10 @@
  *   - State (delta, delta_s, x, m) is updated in place.
  *   - Calls are asynchronous: they enqueue kernels on the given HIP stream
  *     (hipStream_t passed as void*, NULL = the default stream) and return.
+ *   - The step calls allocate nothing, never synchronise with the host and change no
+ *     host-side state from one call to the next (exception: the first call of a context in
+ *     deferred error form, see DS_FLAG_DEFERRED_ERROR), so they can be captured into a HIP
+ *     graph and replayed; a replay draws its random numbers for the `step` it was captured with.
  *   - Errors are return codes only.  Argument errors are detected before anything is
  *     launched and leave every buffer untouched.
  *   - `step` is the caller's iteration counter t; together with the seed it is the only

@@ -81,7 +81,7 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t m)
 }  // namespace
 
 struct ds_topk_scratch {
-    uint32_t *hist;       // [2][rows][kHistRow]: the call in flight uses one half and zeroes the other
+    uint32_t *hist;       // [rows][kHistRow], zero between calls: every call clears what it used
     uint32_t *prev_T;     // [rows + 1] threshold key of the previous call per worker row, and of the server
     uint32_t *done;       // [rows][kStages] arrival counters of the "last workgroup finishes the row" steps
     Sel *sel;             // [rows]
@@ -95,9 +95,8 @@ struct ds_topk_scratch {
     int64_t n_sub;        // 256-element subtiles per row (sampling, server ranges)
     int64_t n_reg, reg_pad, n_groups;
     int rows;
-    int parity;           // which half of hist / fhist the next call uses
     // fused refinement route (k_topk_finish)
-    uint32_t *fhist;      // [2][rows][kFRow]
+    uint32_t *fhist;      // [rows][kFRow], zero between calls
     char *sync;           // [rows][kSyncStride] arrival counters and published picks
     uint32_t *abort_host; // pinned host word, raised by a kernel that gave up waiting
     int64_t capacity;     // workgroups of k_topk_finish the device holds at once; 0: route off
@@ -834,8 +833,9 @@ __device__ __forceinline__ void scan_row(int row, const Sel *sel, int64_t n_grou
 }
 
 // Per group: candidates above T, candidates tying with T; the last workgroup of the row
-// then scans the groups.  The kernel also zeroes the histogram half that the NEXT call will
-// use (`zero`, `zero_words`), which replaces a separate clearing launch.
+// then scans the groups.  Every pick of this call is done by now, so the kernel also clears
+// the call's histograms (`zero`, `zero_words`) for the next call, which replaces a separate
+// clearing launch and leaves no host-side state behind (calls can be captured and replayed).
 __global__ __launch_bounds__(kBlock) void k_topk_count(const u32x2 *slots, const uint32_t *reg_cnt, int64_t n_reg,
                                                        int64_t reg_pad, int64_t n_groups, const Sel *sel,
                                                        uint32_t *grp_gt, uint32_t *grp_eq, uint32_t *grp_eqb,
@@ -1081,8 +1081,8 @@ struct FinishArgs {
     u32x2 *pairs;
     float *x;              // not null: the model update is applied with the emission (one-row launches only)
     float gamma;
-    uint32_t *zero_a, *zero_b;   // histogram halves of the next call, cleared here
-    int64_t zero_a_words, zero_b_words;
+    uint32_t *zero_a;            // the sample's histograms of this call (dead by now), cleared here
+    int64_t zero_a_words;
 };
 
 __global__ __launch_bounds__(kBlock, 8) void k_topk_finish(FinishArgs a)
@@ -1102,7 +1102,6 @@ __global__ __launch_bounds__(kBlock, 8) void k_topk_finish(FinishArgs a)
         const int64_t first = (static_cast<int64_t>(blockIdx.y) * G + blockIdx.x) * kBlock + threadIdx.x;
         const int64_t step = static_cast<int64_t>(gridDim.y) * G * kBlock;
         for (int64_t i = first; i < a.zero_a_words; i += step) a.zero_a[i] = 0u;
-        for (int64_t i = first; i < a.zero_b_words; i += step) a.zero_b[i] = 0u;
     }
     uint32_t lo_key = a.sel[row].lo_key;
     uint32_t bA = kNone, kA = 0u;
@@ -1230,6 +1229,9 @@ __global__ __launch_bounds__(kBlock, 8) void k_topk_finish(FinishArgs a)
         }
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) a.prev_T[row] = T;   // centre of the next call's fine sampling window
+    // every pick of the row is done (the emission needed the last one): clear the row's
+    // histograms for the next call
+    for (int i = blockIdx.x * kBlock + threadIdx.x; i < kFRow; i += G * kBlock) fh[i] = 0u;
     if (row_arrive(rs) && threadIdx.x == 0) {                      // everyone is past every poll: reset for the next launch
         for (int sl = 0; sl < kResSlots; ++sl) __hip_atomic_store(rs.res + sl, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         dev_store(rs.bar, 0u);
@@ -1303,9 +1305,7 @@ ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t 
     const dim3 dense(static_cast<unsigned>(c->n_tiles), rows), cand(grp_blocks, rows);
     const BufferV bsrc{buf, stride};
 
-    uint32_t *hist = t->hist + static_cast<int64_t>(t->parity) * t->rows * kHistRow;
-    uint32_t *hist_next = t->hist + static_cast<int64_t>(t->parity ^ 1) * t->rows * kHistRow;
-    t->parity ^= 1;
+    uint32_t *hist = t->hist;
     const uint32_t k32 = static_cast<uint32_t>(k);
 
     k_topk_sample<Src><<<dim3(static_cast<unsigned>((ns + kWaves - 1) / kWaves), rows), kBlock, 0, st>>>(
@@ -1319,16 +1319,13 @@ ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t 
         // everything after the dense pass in one launch whose workgroups are all resident
         int64_t G = t->capacity / rows;
         if (G > grp_blocks) G = grp_blocks;
-        uint32_t *fh = t->fhist + static_cast<int64_t>(t->parity ^ 1) * t->rows * kFRow;        // parity was flipped above
-        uint32_t *fh_next = t->fhist + static_cast<int64_t>(t->parity) * t->rows * kFRow;
         FinishArgs a;
         a.slots = t->slots; a.reg_cnt = t->reg_cnt;
         a.n_reg = n_reg; a.reg_pad = reg_pad; a.n_groups = n_groups; a.n_sub = n_sub;
-        a.sel = t->sel; a.fhist = fh; a.sync = t->sync; a.abort_flag = t->abort_host; a.spin_limit = t->spin_limit;
+        a.sel = t->sel; a.fhist = t->fhist; a.sync = t->sync; a.abort_flag = t->abort_host; a.spin_limit = t->spin_limit;
         a.grp_gt = t->grp_gt; a.grp_eq = t->grp_eq; a.prev_T = prev_T;
         a.buf = buf; a.stride = stride; a.d = d; a.k = k; a.pairs = pairs; a.x = x; a.gamma = gamma;
-        a.zero_a = hist_next; a.zero_a_words = static_cast<int64_t>(t->rows) * kHistRow;
-        a.zero_b = fh_next; a.zero_b_words = static_cast<int64_t>(t->rows) * kFRow;
+        a.zero_a = hist; a.zero_a_words = static_cast<int64_t>(rows) * kHistRow;
         k_topk_finish<<<dim3(static_cast<unsigned>(G), rows), kBlock, 0, st>>>(a);
         return ds_launch_status();
     }
@@ -1342,8 +1339,8 @@ ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t 
     k_topk_cand_hist<2><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32, prev_T, buf, stride);
     k_topk_cand_hist<3><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32, prev_T, buf, stride);
     k_topk_count<<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, t->grp_gt, t->grp_eq,
-                                          t->grp_eqb, t->grp_out, t->done, hist_next,
-                                          static_cast<int64_t>(t->rows) * kHistRow);
+                                          t->grp_eqb, t->grp_out, t->done, hist,
+                                          static_cast<int64_t>(rows) * kHistRow);
     k_topk_emit<<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, t->grp_eqb, t->grp_out, k,
                                          pairs, buf, stride, x, gamma);
     return ds_launch_status();
@@ -1363,13 +1360,12 @@ ds_status_t ds_topk_init(ds_ctx *c)
     t->n_reg = c->n_tiles;
     t->n_groups = (t->n_reg + kGroupRegs - 1) / kGroupRegs;
     t->reg_pad = t->n_groups * kGroupRegs;
-    DS_HIP_TRY(hipMalloc(&t->hist, 2 * rows * kHistRow * sizeof(uint32_t)));
-    DS_HIP_TRY(hipMemset(t->hist, 0, 2 * rows * kHistRow * sizeof(uint32_t)));
+    DS_HIP_TRY(hipMalloc(&t->hist, rows * kHistRow * sizeof(uint32_t)));
+    DS_HIP_TRY(hipMemset(t->hist, 0, rows * kHistRow * sizeof(uint32_t)));
     DS_HIP_TRY(hipMalloc(&t->prev_T, (rows + 1) * sizeof(uint32_t)));
     DS_HIP_TRY(hipMemset(t->prev_T, 0, (rows + 1) * sizeof(uint32_t)));
     DS_HIP_TRY(hipMalloc(&t->done, rows * kStages * sizeof(uint32_t)));
     DS_HIP_TRY(hipMemset(t->done, 0, rows * kStages * sizeof(uint32_t)));
-    t->parity = 0;
     DS_HIP_TRY(hipMalloc(&t->sel, rows * sizeof(Sel)));
     DS_HIP_TRY(hipMalloc(&t->slots, rows * static_cast<size_t>(t->n_reg) * kReg * sizeof(u32x2)));
     DS_HIP_TRY(hipMalloc(&t->reg_cnt, rows * static_cast<size_t>(t->reg_pad) * sizeof(uint32_t)));
@@ -1378,8 +1374,8 @@ ds_status_t ds_topk_init(ds_ctx *c)
     DS_HIP_TRY(hipMalloc(&t->sub_start, rows * static_cast<size_t>(t->n_sub + 1) * sizeof(uint32_t)));
     DS_HIP_TRY(hipMemset(t->sub_start, 0, rows * static_cast<size_t>(t->n_sub + 1) * sizeof(uint32_t)));
     DS_HIP_TRY(hipMemset(t->reg_cnt, 0, rows * static_cast<size_t>(t->reg_pad) * sizeof(uint32_t)));
-    DS_HIP_TRY(hipMalloc(&t->fhist, 2 * rows * kFRow * sizeof(uint32_t)));
-    DS_HIP_TRY(hipMemset(t->fhist, 0, 2 * rows * kFRow * sizeof(uint32_t)));
+    DS_HIP_TRY(hipMalloc(&t->fhist, rows * kFRow * sizeof(uint32_t)));
+    DS_HIP_TRY(hipMemset(t->fhist, 0, rows * kFRow * sizeof(uint32_t)));
     DS_HIP_TRY(hipMalloc(&t->sync, rows * kSyncStride));
     DS_HIP_TRY(hipMemset(t->sync, 0, rows * kSyncStride));
     DS_HIP_TRY(hipHostMalloc(reinterpret_cast<void **>(&t->abort_host), sizeof(uint32_t), hipHostMallocDefault));
