@@ -190,6 +190,44 @@ def run_oracle_sample(wl, target_elems: int):
                       f"({dt:.1f} s, single thread)"}
 
 
+def run_ceiling():
+    """Reference points for the roofline fractions, with torch's own kernels (nothing of this
+    library): a device-to-device copy, and out = a + b in place at the shape of C3's dense
+    worker pass (read 8 B, write 4 B per element: the traffic no top-k worker pass can avoid)."""
+    import torch
+    dev = torch.device("cuda:0")
+    out = {}
+
+    def timed(f, reps=20):
+        for _ in range(3):
+            f()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            f()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+    dst = torch.empty_like(src)
+    ms = timed(lambda: dst.copy_(src))
+    out["copy_1GiB"] = {"ms": ms, "GBs": 2 * src.numel() * 4 / ms / 1e6}
+    del src, dst
+    n, d = 8, 25_557_032
+    g = [torch.empty((n, d), dtype=torch.float32, device=dev).normal_() for _ in range(2)]
+    delta = torch.zeros((n, d), dtype=torch.float32, device=dev)
+    it = [0]
+
+    def axpy():
+        it[0] += 1
+        torch.add(g[it[0] % 2], delta, out=delta)
+    ms = timed(axpy)
+    out["add_in_place_8x25557032"] = {"ms": ms, "GBs": 12 * n * d / ms / 1e6}
+    print(json.dumps({"hbm_peak_GBs": HBM_PEAK_GBS, "reference": out}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -201,6 +239,8 @@ def main():
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy (calibration dispatch for rocprofv3 --pmc byte counters)")
     ap.add_argument("--cpu-elems", type=int, default=1_000_000_000)
+    ap.add_argument("--ceiling", action="store_true",
+                    help="instead of the benchmark: time torch's copy and in-place add kernels as reference points")
     ap.add_argument("--separate-update", action="store_true",
                     help="time ds_server_aggregate_compress and ds_apply_update as two calls (default: the "
                          "one-call form ds_server_aggregate_compress_update, same results)")
@@ -217,6 +257,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if a.ceiling:
+        run_ceiling()
+        return
 
     def measure(name, steps, warmup, calib_copy=False):
         wl = make_workload(name)

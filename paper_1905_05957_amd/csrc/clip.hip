@@ -91,7 +91,7 @@ __device__ __forceinline__ void clip_store4(f32x4 v, uint32_t mask, int64_t e, i
     const uint32_t top[4] = {u[0] >> sh, u[1] >> sh, u[2] >> sh, u[3] >> sh};
     store_msg4<NB>(msg_row, e, d, top);
     const f32x4 q = {__uint_as_float(u[0]), __uint_as_float(u[1]), __uint_as_float(u[2]), __uint_as_float(u[3])};
-    st4(err_row, e, d, err_vec, v - q);
+    st4_stream(err_row, e, d, err_vec, v - q);
 }
 
 // Algorithm 1, worker block: v = g + delta ; message = Q[v] ; delta <- v - Q[v].
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(kBlock) void k_clip_worker(const void *g, int64_t g
     float *drow = delta + row * dstr;
     const bool gvec = BF16 ? aligned8(grow) : aligned16(grow);
     const bool dvec = aligned16(drow);
-    const f32x4 v = ld4_grad<BF16>(grow, e, d, gvec) + ld4(drow, e, d, dvec);
+    const f32x4 v = ld4_grad<BF16>(grow, e, d, gvec) + ld4_stream(drow, e, d, dvec);
     clip_store4<NB>(v, mask, e, d, msg + static_cast<int64_t>(row) * d * NB, drow, dvec);
 }
 
@@ -120,7 +120,7 @@ __global__ __launch_bounds__(kBlock) void k_clip_server(const uint8_t *msg_in, i
     const int64_t e = (static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x) * 4;
     if (e >= d) return;
     const bool dvec = aligned16(delta_s);
-    f32x4 a = ld4(delta_s, e, d, dvec);
+    f32x4 a = ld4_stream(delta_s, e, d, dvec);
     for (int i = 0; i < n; ++i) a = fma4(inv_n, load_msg4<NB>(msg_in + static_cast<int64_t>(i) * d * NB, e, d), a);
     clip_store4<NB>(a, mask, e, d, msg_out, delta_s, dvec);
 }

@@ -100,6 +100,17 @@ __device__ __forceinline__ void st4(float *__restrict__ row, int64_t e, int64_t 
     if (e + 3 < lim) row[e + 3] = v.w;
 }
 
+// Store of state that is rewritten in place and not read again before the next call.  A
+// buffer that is read and written in the same pass is fastest with BOTH sides non-temporal:
+// in-place g + delta -> delta over 8 x 25.6 M elements took 441 us with plain accesses to
+// delta, 480 us with only the load non-temporal, 438 us with only the store, 399 us with both
+// (424 us out of place).
+__device__ __forceinline__ void st4_stream(float *__restrict__ row, int64_t e, int64_t lim, bool vec, f32x4 v)
+{
+    if (vec && e + 4 <= lim) { __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(row + e)); return; }
+    st4(row, e, lim, vec, v);
+}
+
 // Gradient row of either dtype.
 template <bool BF16>
 __device__ __forceinline__ f32x4 ld4_grad(const void *__restrict__ row, int64_t e, int64_t lim, bool vec)
@@ -241,15 +252,15 @@ __device__ __forceinline__ void apply_q4(f32x4 q, int64_t e, int64_t d, float *x
 {
     const bool xvec = aligned16(x);
     if constexpr (DECODE_ONLY) {
-        st4(x, e, d, xvec, q);
+        st4_stream(x, e, d, xvec, q);
     } else {
-        const f32x4 xv = ld4(x, e, d, xvec);
+        const f32x4 xv = ld4_stream(x, e, d, xvec);
         if constexpr (MOM) {
             const bool mvec = aligned16(m);
-            q = fma4(beta, ld4(m, e, d, mvec), q);
-            st4(m, e, d, mvec, q);
+            q = fma4(beta, ld4_stream(m, e, d, mvec), q);
+            st4_stream(m, e, d, mvec, q);
         }
-        st4(x, e, d, xvec, fma4(-gamma, q, xv));
+        st4_stream(x, e, d, xvec, fma4(-gamma, q, xv));
     }
 }
 

@@ -143,10 +143,10 @@ __global__ __launch_bounds__(kBlock) void k_qsgd_worker(const void *g, int64_t g
     float *drow = delta + row * dstr;
     const bool gvec = BF16 ? aligned8(grow) : aligned16(grow);
     const bool dvec = aligned16(drow);
-    const f32x4 v = ld4_grad<BF16>(grow, e, P.d, gvec) + ld4(drow, e, P.d, dvec);
+    const f32x4 v = ld4_grad<BF16>(grow, e, P.d, gvec) + ld4_stream(drow, e, P.d, dvec);
     const f32x4 q = quantise4(v, e, static_cast<uint32_t>(row), P, levels + row * ((P.d + 1) / 2),
                               words + row * P.W, norms + row * P.Bq, lds, sw_lds);
-    if (e < P.d) st4(drow, e, P.d, dvec, v - q);
+    if (e < P.d) st4_stream(drow, e, P.d, dvec, v - q);
 }
 
 // Parameter-server block: v = delta_s + (1/n) sum_i decode(msg_i) as the fma chain over
@@ -166,7 +166,7 @@ __global__ __launch_bounds__(kBlock) void k_qsgd_server(const uint8_t *levels_in
     const int64_t b0 = tile_base >> P.bshift;
     const int my_b = (threadIdx.x * 4) >> P.bshift;
     const int64_t lev_stride = (P.d + 1) / 2;
-    f32x4 a = ld4(delta_s, e, P.d, dvec);
+    f32x4 a = ld4_stream(delta_s, e, P.d, dvec);
     for (int i0 = 0; i0 < n; i0 += kUnitGroup) {
         const int cnt = (n - i0 < kUnitGroup) ? n - i0 : kUnitGroup;
         __syncthreads();
@@ -221,7 +221,7 @@ __global__ __launch_bounds__(kBlock) void k_qsgd_server(const uint8_t *levels_in
     }
     a = zero_past(a, e, P.d);
     const f32x4 q = quantise4(a, e, kServerStream, P, levels_out, words_out, norms_out, lds, sw_lds);
-    if (e < P.d) st4(delta_s, e, P.d, dvec, a - q);
+    if (e < P.d) st4_stream(delta_s, e, P.d, dvec, a - q);
 }
 
 template <bool MOM, bool DECODE_ONLY>

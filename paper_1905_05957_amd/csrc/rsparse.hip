@@ -203,7 +203,7 @@ __device__ __forceinline__ void rs_store4(f32x4 v, uint32_t nib, const Ranks &rk
     if (nib & 2u) out[r++] = q.y;
     if (nib & 4u) out[r++] = q.z;
     if (nib & 8u) out[r++] = q.w;
-    if (e < d) st4(err_row, e, d, err_vec, v - q);
+    if (e < d) st4_stream(err_row, e, d, err_vec, v - q);
 }
 
 // Algorithm 1, worker block.
@@ -221,7 +221,7 @@ __global__ __launch_bounds__(kBlock) void k_rs_worker(const void *g, int64_t gs,
     float *drow = delta + row * dstr;
     const bool gvec = BF16 ? aligned8(grow) : aligned16(grow);
     const bool dvec = aligned16(drow);
-    const f32x4 v = ld4_grad<BF16>(grow, e, d, gvec) + ld4(drow, e, d, dvec);
+    const f32x4 v = ld4_grad<BF16>(grow, e, d, gvec) + ld4_stream(drow, e, d, dvec);
     const uint32_t nib = (e < d) ? load_sign_nibble(words + row * W, e) : 0u;   // written by k_rs_counts: no bits past d
     const Ranks rk = subtile_ranks(nib);
     rs_store4(v, nib, rk, off[row * (n_sub + 1) + sub], e, d, vals + static_cast<int64_t>(row) * d, drow, dvec, p);
@@ -242,7 +242,7 @@ __global__ __launch_bounds__(kBlock) void k_rs_server(const uint64_t *words_in, 
     const int64_t sub = wave_first >> 8;
     if (sub >= n_sub) return;                               // whole wavefronts
     const bool dvec = aligned16(delta_s);
-    f32x4 a = ld4(delta_s, e, d, dvec);
+    f32x4 a = ld4_stream(delta_s, e, d, dvec);
     {
         for (int i0 = 0; i0 < n; i0 += 8) {
             const int nb = (n - i0 < 8) ? n - i0 : 8;

@@ -115,7 +115,7 @@ __device__ __forceinline__ void fused_finish(f32x4 v, int64_t base, int64_t lim,
     if (threadIdx.x == 0) *scale_out = scale;
     flush_sign_words(sw_lds, words_row, base, bit_lim);
     const int64_t e = base + threadIdx.x * 4;
-    if (e < lim) st4(err_row, e, lim, err_vec, sign_error4(v, scale));
+    if (e < lim) st4_stream(err_row, e, lim, err_vec, sign_error4(v, scale));
 }
 
 template <bool BF16, bool RMS>
@@ -135,7 +135,7 @@ __global__ __launch_bounds__(kBlock) void k_sign_chunk_worker(WorkerSrc<BF16> sr
     const bool gvec = BF16 ? aligned8(grow) : aligned16(grow);
     const bool dvec = aligned16(drow);
     const int64_t e = base + threadIdx.x * 4;
-    const f32x4 v = ld4_grad<BF16>(grow, e, lim, gvec) + ld4(drow, e, lim, dvec);
+    const f32x4 v = ld4_grad<BF16>(grow, e, lim, gvec) + ld4_stream(drow, e, lim, dvec);
     fused_finish<RMS>(v, base, lim, drow, dvec, words + row * W, (lim == d) ? W * 64 : lim,
                       scales + row * S + ci, lds, sw_lds);
 }
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(kBlock) void k_sign_chunk_server(ServerArgs a, floa
         const int64_t ci = static_cast<int64_t>(blockIdx.x) * CPW + c;
         base[c] = ci * chunk;
         lim[c] = (base[c] + chunk < d) ? base[c] + chunk : d;     // base >= d: empty chunk, lim < base
-        v[c] = ld4(delta_s, base[c] + threadIdx.x * 4, lim[c], dvec);
+        v[c] = ld4_stream(delta_s, base[c] + threadIdx.x * 4, lim[c], dvec);
     }
     // The wavefront's 256 elements are 32 bytes of each worker's sign plane.  Eight workers at
     // a time: lane L loads 32-bit word (L & 7) of worker (L >> 3), one load instruction for

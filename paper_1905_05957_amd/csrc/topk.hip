@@ -121,7 +121,7 @@ struct WorkerV {   // v = g + delta
         const void *grow = BF16 ? static_cast<const void *>(static_cast<const uint16_t *>(g) + row * gs)
                                 : static_cast<const void *>(static_cast<const float *>(g) + row * gs);
         const float *drow = delta + row * dstr;
-        return ld4_grad<BF16>(grow, e, d, BF16 ? aligned8(grow) : aligned16(grow)) + ld4(drow, e, d, aligned16(drow));
+        return ld4_grad<BF16>(grow, e, d, BF16 ? aligned8(grow) : aligned16(grow)) + ld4_stream(drow, e, d, aligned16(drow));
     }
 };
 
@@ -460,7 +460,7 @@ __device__ __forceinline__ void pass1_tile(const Src &src, float *buf, int64_t s
     // the few candidates that are not kept instead of zeroing every kept position.
     if (e < d) {
         float *brow = buf + row * stride;
-        st4(brow, e, d, aligned16(brow), f32x4{f[0] ? 0.f : v.x, f[1] ? 0.f : v.y, f[2] ? 0.f : v.z, f[3] ? 0.f : v.w});
+        st4_stream(brow, e, d, aligned16(brow), f32x4{f[0] ? 0.f : v.x, f[1] ? 0.f : v.y, f[2] ? 0.f : v.z, f[3] ? 0.f : v.w});
     }
     // index-ordered compaction over the workgroup: ballots inside a wavefront, wavefront
     // totals through LDS
@@ -527,7 +527,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_pass1_server(ServerV src, float
     f32x4 v[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-        v[c] = ld4(src.delta_s, span_base + c * kSub + lane * 4, d, aligned16(src.delta_s));
+        v[c] = ld4_stream(src.delta_s, span_base + c * kSub + lane * 4, d, aligned16(src.delta_s));
         float *p = strip + c * kSub + lane * 4;
         p[0] = v[c].x; p[1] = v[c].y; p[2] = v[c].z; p[3] = v[c].w;
     }
@@ -597,7 +597,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_pass1_server(ServerV src, float
 #pragma unroll
         for (int j = 0; j < 4; ++j) f[c][j] = (e + j < d) && (bits[c][j] & 0x7FFFFFFFu) >= lo_key;
         if (e < d)
-            st4(buf, e, d, vec, f32x4{f[c][0] ? 0.f : v[c].x, f[c][1] ? 0.f : v[c].y, f[c][2] ? 0.f : v[c].z,
+            st4_stream(buf, e, d, vec, f32x4{f[c][0] ? 0.f : v[c].x, f[c][1] ? 0.f : v[c].y, f[c][2] ? 0.f : v[c].z,
                                      f[c][3] ? 0.f : v[c].w});
         const uint64_t m0 = __ballot(f[c][0]), m1 = __ballot(f[c][1]), m2 = __ballot(f[c][2]), m3 = __ballot(f[c][3]);
         before[c] = lanes_below(m0) + lanes_below(m1) + lanes_below(m2) + lanes_below(m3);
