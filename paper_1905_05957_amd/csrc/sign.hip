@@ -244,8 +244,9 @@ __device__ __forceinline__ f32x4 sign_error_tile(f32x4 v, int64_t e, int64_t d, 
     return v;
 }
 
-// Pass-1 tail: store v, sign bits, per-piece partial sums of |v| (or v^2).
-template <bool RMS>
+// Pass-1 tail: store v, sign bits, per-piece partial sums of |v| (or v^2).  STREAM: v is not
+// read again in this call (deferred error form), so it leaves non-temporally.
+template <bool RMS, bool STREAM>
 __device__ __forceinline__ void pass1_finish(f32x4 v, int64_t base, int64_t d,
                                              float *__restrict__ vrow, bool vvec,
                                              uint64_t *__restrict__ words_row, int64_t bit_lim,
@@ -253,7 +254,10 @@ __device__ __forceinline__ void pass1_finish(f32x4 v, int64_t base, int64_t d,
                                              double *__restrict__ partial_row, double *lds, uint32_t *sw_lds)
 {
     const int64_t e = base + threadIdx.x * 4;
-    if (e < d) st4(vrow, e, d, vvec, v);
+    if (e < d) {
+        if constexpr (STREAM) st4_stream(vrow, e, d, vvec, v);
+        else st4(vrow, e, d, vvec, v);
+    }
     stash_sign_words(sw_lds, wave_sign_word(v.x < 0.f, v.y < 0.f, v.z < 0.f, v.w < 0.f));
     if (p1 - p0 == 1) {
         const double total = block_sum(abs_sum4<RMS>(v), lds, false);   // elements past d are zero
@@ -292,10 +296,10 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass1_worker(WorkerSrc<BF16> sr
     const bool dvec = aligned16(drow);
     const int64_t e = base + threadIdx.x * 4;
     const int32_t p0 = tb.tile_piece_first[tile], p1 = tb.tile_piece_first[tile + 1];
-    f32x4 dl = ld4(drow, e, d, dvec);
+    f32x4 dl = DEFERRED ? ld4_stream(drow, e, d, dvec) : ld4(drow, e, d, dvec);
     if (DEFERRED && e < d) dl = zero_past(sign_error_tile(dl, e, d, prev_scales + row * S, tb, p0, p1), e, d);
     const f32x4 v = ld4_grad<BF16>(grow, e, d, gvec) + dl;
-    pass1_finish<RMS>(v, base, d, drow, dvec, words + row * W, W * 64, tb, p0, p1,
+    pass1_finish<RMS, DEFERRED>(v, base, d, drow, dvec, words + row * W, W * 64, tb, p0, p1,
                       partials + static_cast<int64_t>(row) * tb.n_pieces, lds, sw_lds);
 }
 
@@ -311,7 +315,7 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass1_server(ServerArgs a, floa
     const bool dvec = aligned16(delta_s);
     const int32_t p0 = tb.tile_piece_first[tile], p1 = tb.tile_piece_first[tile + 1];
     const int64_t e = base + threadIdx.x * 4;
-    f32x4 v = ld4(delta_s, e, d, dvec);
+    f32x4 v = DEFERRED ? ld4_stream(delta_s, e, d, dvec) : ld4(delta_s, e, d, dvec);
     if (DEFERRED && e < d) v = sign_error_tile(v, e, d, prev_scales, tb, p0, p1);   // past d: cleared below
     const int lane = lane_id();
     const int64_t wave_first = base + wave_id() * 256;
@@ -346,7 +350,7 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass1_server(ServerArgs a, floa
         }
     }
     v = zero_past(v, e, d);
-    pass1_finish<RMS>(v, base, d, delta_s, dvec, words_out, a.W * 64, tb, p0, p1, partials, lds, sw_lds);
+    pass1_finish<RMS, DEFERRED>(v, base, d, delta_s, dvec, words_out, a.W * 64, tb, p0, p1, partials, lds, sw_lds);
 }
 
 // scale[row][s] = (float)( sum of the group's partials / |group| ), fixed order.
@@ -391,8 +395,8 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass2(float *buf, int64_t strid
     const int32_t p0 = tb.tile_piece_first[tile], p1 = tb.tile_piece_first[tile + 1];
     const int64_t e = tile * kTile + threadIdx.x * 4;
     if (e >= d) return;
-    const f32x4 v = ld4(brow, e, d, vec);
-    st4(brow, e, d, vec, sign_error_tile(v, e, d, srow, tb, p0, p1));
+    const f32x4 v = ld4_stream(brow, e, d, vec);
+    st4_stream(brow, e, d, vec, sign_error_tile(v, e, d, srow, tb, p0, p1));
 }
 
 template <bool MOM, bool DECODE_ONLY>
