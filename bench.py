@@ -29,12 +29,12 @@ HBM_PEAK_GBS = 8000.0
 # WRITE_SIZE runs, each scaled by the same counter's reading for a 1 GiB copy); the runs and
 # the scale factors are recorded under profiles/.  None = not profiled yet.
 MEASURED_WORKER_TRAFFIC = {
-    "c5": 5.9729e9 + 4.1613e9,   # k_sign_chunk_worker
-    "c4": 3.3100e9 + 1.9392e9,   # k_qsgd_worker
-    "c3": 2.6375e9,              # all kernels of the worker call (dense pass 2.4962e9)
-    "clip16": 1.6557e9 + 1.2374e9,   # k_clip_worker
-    "rsparse60": 1.7087e9 + 1.3114e9 + 0.0294e9 + 0.013e9,   # k_rs_worker + k_rs_counts + the two scan launches
-    "c2": 1.1025e9,              # k_sign_pass1_worker, deferred error form (plain form: pass 1 + pass 2 = 1.8343e9)
+    "c5": 5.9728e9 + 4.1221e9,   # k_sign_chunk_worker
+    "c4": 3.3108e9 + 1.9352e9,   # k_qsgd_worker
+    "c3": 2.6524e9,              # all kernels of the worker call (dense pass 1.6550e9 + 0.8488e9)
+    "clip16": 1.6562e9 + 1.2442e9,   # k_clip_worker
+    "rsparse60": 1.7117e9 + 1.3277e9 + 0.0295e9 + 0.013e9,   # k_rs_worker + k_rs_counts + the two scan launches
+    "c2": 1.1024e9,              # k_sign_pass1_worker + k_sign_reduce, deferred error form (plain form: + pass 2)
 }
 
 
