@@ -72,7 +72,7 @@ def make_workload(name: str):
 
 
 def run_gpu(wl, steps: int, warmup: int, sets: int = 2, calib_copy: bool = False, deferred_error: bool = True,
-            separate_update: bool = False):
+            separate_update: bool = False, settle_ms: float = 150.0):
     import torch
     import paper_1905_05957_amd as P
 
@@ -108,9 +108,22 @@ def run_gpu(wl, steps: int, warmup: int, sets: int = 2, calib_copy: bool = False
         else:       # the same two blocks of Algorithm 1 through the one-call entry point
             ctx.server_aggregate_compress_update(t, pw, delta_s, ps, x, m, wl.gamma, beta)
 
-    for t in range(warmup):
-        step(t)
+    # The first tens of milliseconds of a memory-bound phase run slower on this machine (seen in
+    # kernel traces: the 124 M-element worker pass takes 1.9 ms in steps 1-3 and settles at
+    # 1.68 ms after about 30 ms, whatever came before), so the clocks get `settle_ms` of the same
+    # steps before the W warm-up steps and the K timed steps.
+    t_settle = 0
+    t_end = time.perf_counter() + settle_ms * 1e-3
+    while time.perf_counter() < t_end:
+        step(t_settle)
+        t_settle += 1
+        if t_settle % 8 == 0:
+            torch.cuda.synchronize()
     torch.cuda.synchronize()
+    for t in range(warmup):
+        step(t_settle + t)
+    torch.cuda.synchronize()
+    warmup += t_settle      # step numbers below continue after the settle steps
     # An event record costs a bubble of about 6 us between two kernels that otherwise run back
     # to back (seen in the kernel trace), so the timed region carries events only around the
     # worker call of every 3rd step: enough for the average launch duration of the dominant
@@ -239,6 +252,8 @@ def main():
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy (calibration dispatch for rocprofv3 --pmc byte counters)")
     ap.add_argument("--cpu-elems", type=int, default=1_000_000_000)
+    ap.add_argument("--settle-ms", type=float, default=150.0,
+                    help="untimed steps run for this long before the warm-up steps, for the clocks to settle")
     ap.add_argument("--ceiling", action="store_true",
                     help="instead of the benchmark: time torch's copy and in-place add kernels as reference points")
     ap.add_argument("--separate-update", action="store_true",
@@ -264,7 +279,7 @@ def main():
     def measure(name, steps, warmup, calib_copy=False):
         wl = make_workload(name)
         r = run_gpu(wl, steps, warmup, calib_copy=calib_copy, deferred_error=not a.plain_error,
-                    separate_update=a.separate_update)
+                    separate_update=a.separate_update, settle_ms=a.settle_ms)
         ab = algorithmic_bytes(wl, r["S"])
         ms = r["ms_per_step"]
         wk_ms = r["worker_ms"]
@@ -303,7 +318,7 @@ def main():
         "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": head["workload"], "n_workers": wl.n, "d": wl.d,
-                   "grad_dtype": wl.grad_dtype, "compressor": wl.comp},
+                   "grad_dtype": wl.grad_dtype, "compressor": wl.comp, "settle_ms": a.settle_ms},
         "stage_ms": head["stage_ms"],
         "algorithmic_bytes_per_step": head["algorithmic_bytes_per_step"],
         "step_hbm_GBs": head["step_hbm_GBs"], "step_frac_of_peak": head["step_frac_of_peak"],
