@@ -26,13 +26,11 @@ __device__ __forceinline__ void store_msg4(uint8_t *__restrict__ row, int64_t e,
     uint8_t *p = row + e * NB;
     if (e + 4 <= d && (reinterpret_cast<uintptr_t>(p) & (4 * NB - 1)) == 0) {
         if constexpr (NB == 1) {
-            __builtin_nontemporal_store(top[0] | (top[1] << 8) | (top[2] << 16) | (top[3] << 24),
-                                        reinterpret_cast<uint32_t *>(p));
+            *reinterpret_cast<uint32_t *>(p) = top[0] | (top[1] << 8) | (top[2] << 16) | (top[3] << 24);
         } else if constexpr (NB == 2) {
-            __builtin_nontemporal_store(u32x2{top[0] | (top[1] << 16), top[2] | (top[3] << 16)},
-                                        reinterpret_cast<u32x2 *>(p));
+            *reinterpret_cast<u32x2 *>(p) = u32x2{top[0] | (top[1] << 16), top[2] | (top[3] << 16)};
         } else {
-            __builtin_nontemporal_store(u32x4{top[0], top[1], top[2], top[3]}, reinterpret_cast<u32x4 *>(p));
+            *reinterpret_cast<u32x4 *>(p) = u32x4{top[0], top[1], top[2], top[3]};
         }
         return;
     }

@@ -178,9 +178,12 @@ __device__ __forceinline__ uint32_t wave_sign_word(bool n0, bool n1, bool n2, bo
 // non-temporal store of 16 x 16 bytes.  Only 128-bit groups whose first element is below
 // `bit_lim` are written; bit_lim is a multiple of 64: the end of the caller's chunk, or
 // 64*ceil(d/64) at the end of the row so that the pad bits of the last word are written as zero.
-// Measured on the fused sign worker pass: the 1.2 % side stream of sign words costs 9 % with
-// ordinary stores (1.77 ms against 1.61 ms without them), 1.69 ms with one non-temporal
-// 32-byte store per wavefront and 1.66 ms with this single store per workgroup.
+// Measured on the fused sign worker pass while the error buffer was still accessed with
+// plain loads and stores: the 1.2 % side stream of sign words cost 9 % with ordinary stores
+// per wavefront (1.77 ms against 1.61 ms without them), 1.69 ms with one non-temporal 32-byte
+// store per wavefront and 1.66 ms with a single non-temporal store per workgroup.  With the
+// error buffer streamed non-temporally the words are best left in the cache for the server
+// that reads them next: 1.668 ms with a plain store here against 1.682 ms non-temporal.
 __device__ __forceinline__ void stash_sign_words(uint32_t *sw_lds, uint32_t word)
 {
     if (lane_id() < 8) sw_lds[wave_id() * 8 + lane_id()] = word;
@@ -194,7 +197,7 @@ __device__ __forceinline__ void flush_sign_words(const uint32_t *sw_lds, uint64_
         uint32_t *dst = reinterpret_cast<uint32_t *>(words_row) + (tile_first >> 5) + 4 * t;
         const u32x4 w4 = reinterpret_cast<const u32x4 *>(sw_lds)[t];
         if (tile_first + 128 * (t + 1) <= bit_lim) {
-            __builtin_nontemporal_store(w4, reinterpret_cast<u32x4 *>(dst));
+            *reinterpret_cast<u32x4 *>(dst) = w4;
         } else {                                  // bit_lim is a multiple of 64: two of the four words
             dst[0] = w4.x;
             dst[1] = w4.y;

@@ -90,7 +90,7 @@ __device__ __forceinline__ f32x4 quantise4(f32x4 v, int64_t e, uint32_t stream, 
         const uint32_t packed = code[0] | (code[1] << 4) | (code[2] << 8) | (code[3] << 12);
         uint8_t *dst = levels_row + (e >> 1);
         if (e + 4 <= P.d && (reinterpret_cast<uintptr_t>(dst) & 1u) == 0) {
-            __builtin_nontemporal_store(static_cast<uint16_t>(packed), reinterpret_cast<uint16_t *>(dst));
+            *reinterpret_cast<uint16_t *>(dst) = static_cast<uint16_t>(packed);
         } else {
             dst[0] = static_cast<uint8_t>(packed);
             if (e + 2 < P.d) dst[1] = static_cast<uint8_t>(packed >> 8);
