@@ -119,13 +119,15 @@ __device__ __forceinline__ uint32_t load_codes4(const uint8_t *__restrict__ leve
     return r;
 }
 
+// +-(code * unit): the sign bit of the magnitude is flipped where the element's bit of `nib`
+// is set (what "bit ? -mag : mag" does, without compare and select).
 __device__ __forceinline__ f32x4 decode4(uint32_t codes, uint32_t nib, float unit)
 {
     f32x4 q;
-    q.x = static_cast<float>(codes & 15u) * unit;          q.x = (nib & 1u) ? -q.x : q.x;
-    q.y = static_cast<float>((codes >> 4) & 15u) * unit;   q.y = (nib & 2u) ? -q.y : q.y;
-    q.z = static_cast<float>((codes >> 8) & 15u) * unit;   q.z = (nib & 4u) ? -q.z : q.z;
-    q.w = static_cast<float>((codes >> 12) & 15u) * unit;  q.w = (nib & 8u) ? -q.w : q.w;
+    q.x = __uint_as_float(__float_as_uint(static_cast<float>(codes & 15u) * unit) ^ ((nib << 31) & 0x80000000u));
+    q.y = __uint_as_float(__float_as_uint(static_cast<float>((codes >> 4) & 15u) * unit) ^ ((nib << 30) & 0x80000000u));
+    q.z = __uint_as_float(__float_as_uint(static_cast<float>((codes >> 8) & 15u) * unit) ^ ((nib << 29) & 0x80000000u));
+    q.w = __uint_as_float(__float_as_uint(static_cast<float>((codes >> 12) & 15u) * unit) ^ ((nib << 28) & 0x80000000u));
     return q;
 }
 

@@ -56,15 +56,6 @@ struct ServerArgs {
     float inv_n;
 };
 
-__device__ __forceinline__ f32x4 chain4(f32x4 a, uint32_t nib, float s, float inv_n)
-{
-    a.x = __fmaf_rn((nib & 1u) ? -s : s, inv_n, a.x);
-    a.y = __fmaf_rn((nib & 2u) ? -s : s, inv_n, a.y);
-    a.z = __fmaf_rn((nib & 4u) ? -s : s, inv_n, a.z);
-    a.w = __fmaf_rn((nib & 8u) ? -s : s, inv_n, a.w);
-    return a;
-}
-
 // What a group sums to find its scale: |v| (scale = mean |v|, the l1 reading of "the same
 // magnitude", Section 5.1) or v^2 (scale = root mean square, the l2 reading of Section 3.2's
 // norm).  The product of two fp32 values is exact in fp64.
@@ -74,6 +65,29 @@ __device__ __forceinline__ double measure(float x)
 {
     if constexpr (RMS) return static_cast<double>(x) * static_cast<double>(x);
     else return static_cast<double>(fabsf(x));
+}
+
+// (s0, s1, s2, s3) with the sign flipped where the element's bit of `nib` is set.
+__device__ __forceinline__ f32x4 signed4(float s0, float s1, float s2, float s3, uint32_t nib)
+{
+    return f32x4{__uint_as_float(__float_as_uint(s0) ^ ((nib << 31) & 0x80000000u)),
+                 __uint_as_float(__float_as_uint(s1) ^ ((nib << 30) & 0x80000000u)),
+                 __uint_as_float(__float_as_uint(s2) ^ ((nib << 29) & 0x80000000u)),
+                 __uint_as_float(__float_as_uint(s3) ^ ((nib << 28) & 0x80000000u))};
+}
+
+// The same chain step with the lane's four sign bits in bits 28..31 of `top` (element 0 in bit
+// 28): the sign bit of the scale is flipped where the element's bit is set, which is what
+// "bit ? -scale : scale" does for every float.  Shift, mask, exclusive-or instead of test,
+// compare and select: no condition-code hazards in a loop that runs n times per element.
+__device__ __forceinline__ f32x4 chain4_top(f32x4 a, uint32_t top, float s, float inv_n)
+{
+    const uint32_t sb = __float_as_uint(s);
+    a.x = __fmaf_rn(__uint_as_float(sb ^ ((top << 3) & 0x80000000u)), inv_n, a.x);
+    a.y = __fmaf_rn(__uint_as_float(sb ^ ((top << 2) & 0x80000000u)), inv_n, a.y);
+    a.z = __fmaf_rn(__uint_as_float(sb ^ ((top << 1) & 0x80000000u)), inv_n, a.z);
+    a.w = __fmaf_rn(__uint_as_float(sb ^ (top & 0x80000000u)), inv_n, a.w);
+    return a;
 }
 
 template <bool RMS>
@@ -175,12 +189,28 @@ __global__ __launch_bounds__(kBlock) void k_sign_chunk_server(ServerArgs a, floa
                 word[c] = reinterpret_cast<const uint32_t *>(a.words_in + (i0 + wi) * a.W)[(wave_first >> 5) + (lane & 7)];
             sc[c] = (lane < nb && base[c] < d) ? a.scales_in[(i0 + lane) * a.S + ci] : 0.f;
         }
-        for (int i = 0; i < nb; ++i) {
+        // Lanes past the end of their chunk run the chain too (their values are cleared below):
+        // no branch inside the loop.  A full batch of eight workers is unrolled, so that the
+        // eight cross-lane fetches are in flight together instead of one wait per worker.
+        const int top_shift = 28 - 4 * (lane & 7);
+        if (nb == 8) {
 #pragma unroll
-            for (int c = 0; c < CPW; ++c) {
-                const uint32_t w = __shfl(word[c], i * 8 + (lane >> 3), 64);
-                const float s = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sc[c]), i));
-                if (base[c] + threadIdx.x * 4 < lim[c]) v[c] = chain4(v[c], (w >> (4 * (lane & 7))) & 15u, s, a.inv_n);
+            for (int i = 0; i < 8; ++i) {
+#pragma unroll
+                for (int c = 0; c < CPW; ++c) {
+                    const uint32_t w = __shfl(word[c], i * 8 + (lane >> 3), 64);
+                    const float s = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sc[c]), i));
+                    v[c] = chain4_top(v[c], w << top_shift, s, a.inv_n);
+                }
+            }
+        } else {
+            for (int i = 0; i < nb; ++i) {
+#pragma unroll
+                for (int c = 0; c < CPW; ++c) {
+                    const uint32_t w = __shfl(word[c], i * 8 + (lane >> 3), 64);
+                    const float s = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sc[c]), i));
+                    v[c] = chain4_top(v[c], w << top_shift, s, a.inv_n);
+                }
             }
         }
     }
@@ -208,8 +238,7 @@ __global__ __launch_bounds__(kBlock) void k_sign_chunk_update(const uint64_t *__
     // e < 2^31, so the chunk index is a 32-bit division
     const float s = scales[static_cast<uint32_t>(e) / static_cast<uint32_t>(chunk)];
     const uint32_t nib = load_sign_nibble(words, e);
-    const f32x4 q = {(nib & 1u) ? -s : s, (nib & 2u) ? -s : s, (nib & 4u) ? -s : s, (nib & 8u) ? -s : s};
-    apply_q4<MOM, DECODE_ONLY>(q, e, d, x, m, gamma, beta);
+    apply_q4<MOM, DECODE_ONLY>(signed4(s, s, s, s, nib), e, d, x, m, gamma, beta);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -329,10 +358,22 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass1_server(ServerArgs a, floa
             if ((lane >> 3) < nb && wave_first + 32 * (lane & 7) < a.W * 64)
                 word = reinterpret_cast<const uint32_t *>(a.words_in + (i0 + (lane >> 3)) * a.W)[(wave_first >> 5) + (lane & 7)];
             const float sc = (lane < nb) ? a.scales_in[(i0 + lane) * a.S + sg] : 0.f;
-            for (int i = 0; i < nb; ++i) {
-                const uint32_t w = __shfl(word, i * 8 + (lane >> 3), 64);
-                const float sv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sc), i));
-                if (e < d) v = chain4(v, (w >> (4 * (lane & 7))) & 15u, sv, a.inv_n);
+            // lanes past d run the chain too (cleared below); a full batch is unrolled so that
+            // its eight cross-lane fetches are in flight together
+            const int top_shift = 28 - 4 * (lane & 7);
+            if (nb == 8) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const uint32_t w = __shfl(word, i * 8 + (lane >> 3), 64);
+                    const float sv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sc), i));
+                    v = chain4_top(v, w << top_shift, sv, a.inv_n);
+                }
+            } else {
+                for (int i = 0; i < nb; ++i) {
+                    const uint32_t w = __shfl(word, i * 8 + (lane >> 3), 64);
+                    const float sv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sc), i));
+                    v = chain4_top(v, w << top_shift, sv, a.inv_n);
+                }
             }
         }
     } else if (e < d) {
@@ -343,10 +384,7 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass1_server(ServerArgs a, floa
             const float *srow = a.scales_in + i * a.S;
             const uint32_t nib = load_sign_nibble(a.words_in + i * a.W, e);
             const float s0 = srow[seg[0]], s1 = srow[seg[1]], s2 = srow[seg[2]], s3 = srow[seg[3]];
-            v.x = __fmaf_rn((nib & 1u) ? -s0 : s0, a.inv_n, v.x);
-            v.y = __fmaf_rn((nib & 2u) ? -s1 : s1, a.inv_n, v.y);
-            v.z = __fmaf_rn((nib & 4u) ? -s2 : s2, a.inv_n, v.z);
-            v.w = __fmaf_rn((nib & 8u) ? -s3 : s3, a.inv_n, v.w);
+            v = fma4(a.inv_n, signed4(s0, s1, s2, s3, nib), v);
         }
     }
     v = zero_past(v, e, d);
@@ -412,11 +450,8 @@ __global__ __launch_bounds__(kBlock) void k_sign_update(const uint64_t *__restri
     const uint32_t nib = load_sign_nibble(words, e);
     float q[4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        const float s = (e + c < d) ? scales[seg_of(tb, p0, p1, e + c)] : 0.f;
-        q[c] = ((nib >> c) & 1u) ? -s : s;
-    }
-    apply_q4<MOM, DECODE_ONLY>(f32x4{q[0], q[1], q[2], q[3]}, e, d, x, m, gamma, beta);
+    for (int c = 0; c < 4; ++c) q[c] = (e + c < d) ? scales[seg_of(tb, p0, p1, e + c)] : 0.f;
+    apply_q4<MOM, DECODE_ONLY>(signed4(q[0], q[1], q[2], q[3], nib), e, d, x, m, gamma, beta);
 }
 
 }  // namespace
