@@ -7,6 +7,9 @@ so each test compares what it can compute exactly in seconds:
   C3  one whole worker row, the whole server pass and update, plus properties of every row;
   C2  the whole step;
   X1, X2 (clipping, randomised sparsification at 8 x 25.6 M)  as C4.
+Those comparisons go through the three calls of Algorithm 1; the last test runs the call
+sequence that bench.py times (worker call + the one-call server-and-update, sign per segment in
+the deferred error form) beside them at full size and requires identical bits.
 """
 import numpy as np
 import pytest
@@ -14,6 +17,8 @@ import torch
 
 import ds_workloads as W
 import oracle as O
+import paper_1905_05957_amd as P
+import parity_util
 from parity_util import Pair, assert_close_rows, assert_payload_equal, host_grad, oracle_config
 
 pytestmark = pytest.mark.gpu
@@ -180,3 +185,46 @@ def test_x_rows_and_server(gpu_device, which):
         assert_close_rows(pair.x.cpu().numpy(), h_x, f"{which} x")
     finally:
         pair.close()
+
+
+@pytest.mark.parametrize("which", ["c2", "c3", "c4", "c5", "clip16", "rsparse60"])
+def test_timed_call_sequence_equals_three_calls(gpu_device, which):
+    """Three steps at full size through the calls bench.py times against the three separate
+    calls in the plain error form: messages, errors, x and m bit for bit."""
+    wl = getattr(W, which)()
+    three = Pair(wl, gpu_device)
+    parity_util.CONTEXT_FLAGS = P.FLAG_DEFERRED_ERROR if wl.comp == "sign" else 0
+    try:
+        timed = Pair(wl, gpu_device)
+    finally:
+        parity_util.CONTEXT_FLAGS = 0
+    try:
+        beta = 0.0 if wl.beta is None else wl.beta
+        for t in range(3):
+            g = wl.gradients(t % 2, gpu_device)
+            three.gpu_step(t, g)
+            timed.ctx.worker_compress(t, g, timed.delta, timed.pw)
+            timed.ctx.server_aggregate_compress_update(t, timed.pw, timed.delta_s, timed.ps, timed.x, timed.m,
+                                                       wl.gamma, beta)
+            del g
+            for side, a_p, b_p in (("worker", three.pw, timed.pw), ("server", three.ps, timed.ps)):
+                for key, a in a_p.tensors().items():
+                    b = b_p.tensors()[key]
+                    if wl.comp == "rsparse" and key == "dense":     # packed values count as far as the kept bits say:
+                        da = torch.empty(wl.d, dtype=torch.float32, device=gpu_device)      # compare what they decode to
+                        db = torch.empty_like(da)
+                        for r in range(a.shape[0]):
+                            three.ctx.decompress(a_p, r, da)
+                            timed.ctx.decompress(b_p, r, db)
+                            assert torch.equal(da, db), f"{which} t={t} {side} decoded row {r}"
+                        continue
+                    assert torch.equal(a, b), f"{which} t={t} {side} {key}"
+            assert torch.equal(three.x, timed.x), f"{which} t={t} x"
+            if three.m is not None:
+                assert torch.equal(three.m, timed.m), f"{which} t={t} m"
+        timed.ctx.materialize_error(timed.delta, timed.delta_s)
+        assert torch.equal(three.delta, timed.delta), f"{which} delta"
+        assert torch.equal(three.delta_s, timed.delta_s), f"{which} delta_s"
+    finally:
+        three.close()
+        timed.close()
