@@ -296,6 +296,11 @@ ds_status_t ds_server_aggregate_compress_update(ds_ctx_t *c, uint64_t step, cons
         if (!guard.ok) return DS_ERR_DEVICE;
         return ds_topk_server(c, in, delta_s, out, static_cast<hipStream_t>(hip_stream), x, gamma);
     }
+    if (c->cfg.comp == DS_COMP_RSPARSE) {
+        DeviceGuard guard(c->device);
+        if (!guard.ok) return DS_ERR_DEVICE;
+        return ds_rsparse_server_update(c, step, in, delta_s, out, x, m, gamma, beta, static_cast<hipStream_t>(hip_stream));
+    }
     rc = ds_server_aggregate_compress(c, step, in, delta_s, out, hip_stream);
     if (rc != DS_OK) return rc;
     return ds_apply_update(c, out, x, m, gamma, beta, hip_stream);

@@ -104,6 +104,9 @@ ds_status_t ds_rsparse_worker(ds_ctx *c, uint64_t step, const void *g, int64_t g
                               int64_t dstr, const ds_payload_t *out, hipStream_t st);
 ds_status_t ds_rsparse_server(ds_ctx *c, uint64_t step, const ds_payload_t *in, float *delta_s,
                               const ds_payload_t *out, hipStream_t st);
+ds_status_t ds_rsparse_server_update(ds_ctx *c, uint64_t step, const ds_payload_t *in, float *delta_s,
+                                     const ds_payload_t *out, float *x, float *m, float gamma, float beta,
+                                     hipStream_t st);
 ds_status_t ds_rsparse_update(ds_ctx *c, const ds_payload_t *srv, float *x, float *m, float gamma,
                               float beta, hipStream_t st);
 ds_status_t ds_rsparse_decode(ds_ctx *c, const ds_payload_t *p, int32_t row, float *out, hipStream_t st);

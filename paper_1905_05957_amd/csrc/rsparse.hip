@@ -46,18 +46,6 @@ __device__ __forceinline__ uint32_t valid_nibble(int64_t e, int64_t d)
     return (e + 4 <= d) ? 15u : (e >= d) ? 0u : ((1u << (d - e)) - 1u);
 }
 
-// keep flags of elements e..e+3 (e a multiple of 4) as a nibble
-__device__ __forceinline__ uint32_t keep_nibble(int64_t e, int64_t d, uint32_t stream, const RsParams &P)
-{
-    const u32x4 r = philox4x32_10(u32x4{static_cast<uint32_t>(e >> 2), 0u, stream, P.step_lo}, P.key0, P.key1);
-    uint32_t nib = 0u;
-    if (e + 0 < d && (r.x >> 8) < P.p24) nib |= 1u;
-    if (e + 1 < d && (r.y >> 8) < P.p24) nib |= 2u;
-    if (e + 2 < d && (r.z >> 8) < P.p24) nib |= 4u;
-    if (e + 3 < d && (r.w >> 8) < P.p24) nib |= 8u;
-    return nib;
-}
-
 __device__ __forceinline__ uint32_t lanes_below(uint64_t m)
 {
     return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(m >> 32), __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(m), 0u));
@@ -88,8 +76,41 @@ __device__ __forceinline__ Ranks subtile_ranks(uint32_t nib)
 // ---------------------------------------------------------------------------------------
 // Writer side: the kept-bit plane and the kept elements per subtile from the generator alone.
 // A wavefront takes kCountSubs consecutive subtiles (one subtile per workgroup-launch slot made
-// the launch overhead of 100 000 tiny workgroups the cost of this kernel).
+// the launch overhead of 100 000 tiny workgroups the cost of this kernel).  The kernel is bound
+// by integer ALU work, so everything around the ten Philox rounds is kept short: one compare
+// per element ((r >> 8) < P24 as r <= 256 P24 - 1), the count from the compare masks with
+// scalar instructions, and the plane's 32-bit words by three shift-and-merge steps between
+// neighbouring lanes (lane 8q ends up with word q).
 constexpr int kCountSubs = 8;
+
+// x of the lane N places above this one, inside a row of 16 lanes
+template <int N>
+__device__ __forceinline__ uint32_t from_lane_above(uint32_t x)
+{
+    return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), 0x100 | N, 0xF, 0xF, true));   // row_shl:N
+}
+
+// One subtile: PARTIAL for the row's last one when d cuts it (nothing at or past d is kept).
+template <bool PARTIAL>
+__device__ __forceinline__ void count_subtile(int64_t s, int lane, int64_t d, uint32_t stream, uint32_t thr, const RsParams &P,
+                                              uint32_t *wrow, int64_t words32, uint32_t *cnt_row)
+{
+    const uint32_t blk = static_cast<uint32_t>(s) * (kSub / 4) + lane;        // (s * 256 + 4 * lane) >> 2
+    const u32x4 r = philox4x32_10(u32x4{blk, 0u, stream, P.step_lo}, P.key0, P.key1);
+    bool k0 = r.x <= thr, k1 = r.y <= thr, k2 = r.z <= thr, k3 = r.w <= thr;
+    if (PARTIAL) {
+        const int left = static_cast<int>(d - s * kSub) - lane * 4;            // elements of the row from this lane's first on
+        k0 = k0 && left > 0; k1 = k1 && left > 1; k2 = k2 && left > 2; k3 = k3 && left > 3;
+    }
+    const uint32_t c = __popcll(__ballot(k0)) + __popcll(__ballot(k1)) + __popcll(__ballot(k2)) + __popcll(__ballot(k3));
+    uint32_t t = (k0 ? 1u : 0u) | (k1 ? 2u : 0u) | (k2 ? 4u : 0u) | (k3 ? 8u : 0u);
+    t |= from_lane_above<1>(t) << 4;
+    t |= from_lane_above<2>(t) << 8;
+    t |= from_lane_above<4>(t) << 16;
+    const int64_t w = s * 8 + (lane >> 3);
+    if ((lane & 7) == 0 && (!PARTIAL || w < words32)) wrow[w] = t;
+    if (lane == 0) cnt_row[s] = c;
+}
 
 __global__ __launch_bounds__(kBlock) void k_rs_counts(uint64_t *words, int64_t W, uint32_t *cnt, int64_t n_sub, int64_t d,
                                                       bool server, RsParams P)
@@ -97,17 +118,22 @@ __global__ __launch_bounds__(kBlock) void k_rs_counts(uint64_t *words, int64_t W
     const int row = blockIdx.y;
     const int lane = lane_id();
     const uint32_t stream = server ? 0xFFFFFFFFu : static_cast<uint32_t>(row);
-    const int64_t s0 = (static_cast<int64_t>(blockIdx.x) * kWaves + wave_id()) * kCountSubs;
+    const uint32_t thr = static_cast<uint32_t>((static_cast<uint64_t>(P.p24) << 8) - 1u);
+    uint32_t *wrow = reinterpret_cast<uint32_t *>(words + row * W);
+    uint32_t *cnt_row = cnt + row * (n_sub + 1);
+    const int wave = __builtin_amdgcn_readfirstlane(wave_id());               // the loop bounds are scalars
+    const int64_t s0 = (static_cast<int64_t>(blockIdx.x) * kWaves + wave) * kCountSubs;
+    const int64_t s1 = (s0 + kCountSubs < n_sub) ? s0 + kCountSubs : n_sub;
+    const int64_t full = d / kSub;                                            // subtiles before this one are whole
+    if (s0 + kCountSubs <= full) {
 #pragma unroll 2
-    for (int j = 0; j < kCountSubs; ++j) {
-        const int64_t s = s0 + j;
-        if (s >= n_sub) return;                             // uniform over the wavefront
-        const uint32_t nib = keep_nibble(s * kSub + lane * 4, d, stream, P);
-        const Ranks rk = subtile_ranks(nib);
-        if (lane < 8 && s * 8 + lane < 2 * W) reinterpret_cast<uint32_t *>(words + row * W)[s * 8 + lane] = rk.word;
-        const uint32_t c = wave_sum_u32(__popc(nib));
-        if (lane == 0) cnt[row * (n_sub + 1) + s] = c;
+        for (int j = 0; j < kCountSubs; ++j) count_subtile<false>(s0 + j, lane, d, stream, thr, P, wrow, 2 * W, cnt_row);
+        return;
     }
+    // the end of the row
+    const int64_t s_whole = (s1 < full) ? s1 : full;
+    for (int64_t s = s0; s < s_whole; ++s) count_subtile<false>(s, lane, d, stream, thr, P, wrow, 2 * W, cnt_row);
+    if (s0 <= full && full < s1) count_subtile<true>(full, lane, d, stream, thr, P, wrow, 2 * W, cnt_row);   // d % 256 != 0
 }
 
 // Reader side: the same counts from the kept-bit plane.  One thread per subtile.
@@ -407,24 +433,38 @@ ds_status_t ds_rsparse_server(ds_ctx *c, uint64_t step, const ds_payload_t *in, 
     return ds_launch_status();
 }
 
+// off == nullptr: the offsets of the packed values are derived from the message's own plane.
 template <bool DECODE_ONLY>
 static ds_status_t rs_apply(ds_ctx *c, const uint64_t *words, const float *vals, float *x, float *m, float gamma, float beta,
-                            hipStream_t st)
+                            hipStream_t st, const uint32_t *off = nullptr)
 {
     ds_rs_scratch *t = c->rs;
-    k_rs_popcounts<<<dim3(static_cast<unsigned>((t->n_sub + kBlock - 1) / kBlock), 1), kBlock, 0, st>>>(words, c->W, t->off_r,
-                                                                                                     t->n_sub, c->cfg.d);
-    scan_rows(t->off_r, t->blk, t->n_sub, t->n_blk, 1, st);
+    if (!off) {
+        k_rs_popcounts<<<dim3(static_cast<unsigned>((t->n_sub + kBlock - 1) / kBlock), 1), kBlock, 0, st>>>(words, c->W, t->off_r,
+                                                                                                         t->n_sub, c->cfg.d);
+        scan_rows(t->off_r, t->blk, t->n_sub, t->n_blk, 1, st);
+        off = t->off_r;
+    }
     const unsigned blocks = blocks4(t->n_sub * kSub);
     if (DECODE_ONLY)
-        k_rs_apply<false, true, false><<<blocks, kBlock, 0, st>>>(words, vals, t->off_r, x, nullptr, c->cfg.d, c->W, t->n_sub, 0.f, 0.f);
+        k_rs_apply<false, true, false><<<blocks, kBlock, 0, st>>>(words, vals, off, x, nullptr, c->cfg.d, c->W, t->n_sub, 0.f, 0.f);
     else if (m)
-        k_rs_apply<true, false, false><<<blocks, kBlock, 0, st>>>(words, vals, t->off_r, x, m, c->cfg.d, c->W, t->n_sub, gamma, beta);
+        k_rs_apply<true, false, false><<<blocks, kBlock, 0, st>>>(words, vals, off, x, m, c->cfg.d, c->W, t->n_sub, gamma, beta);
     else if (c->cfg.k < (1 << 20))      // p < 1/16: most 64-byte lines of x hold no kept element
-        k_rs_apply<false, false, true><<<blocks, kBlock, 0, st>>>(words, vals, t->off_r, x, m, c->cfg.d, c->W, t->n_sub, gamma, beta);
+        k_rs_apply<false, false, true><<<blocks, kBlock, 0, st>>>(words, vals, off, x, m, c->cfg.d, c->W, t->n_sub, gamma, beta);
     else
-        k_rs_apply<false, false, false><<<blocks, kBlock, 0, st>>>(words, vals, t->off_r, x, m, c->cfg.d, c->W, t->n_sub, gamma, beta);
+        k_rs_apply<false, false, false><<<blocks, kBlock, 0, st>>>(words, vals, off, x, m, c->cfg.d, c->W, t->n_sub, gamma, beta);
     return ds_launch_status();
+}
+
+// The server block followed by the model update: the update reads the server's message with
+// the offsets the server has just written it with, instead of deriving them from the plane again.
+ds_status_t ds_rsparse_server_update(ds_ctx *c, uint64_t step, const ds_payload_t *in, float *delta_s, const ds_payload_t *out,
+                                     float *x, float *m, float gamma, float beta, hipStream_t st)
+{
+    const ds_status_t rc = ds_rsparse_server(c, step, in, delta_s, out, st);
+    if (rc != DS_OK) return rc;
+    return rs_apply<false>(c, out->sign_words, out->dense, x, m, gamma, beta, st, c->rs->off_s);
 }
 
 ds_status_t ds_rsparse_update(ds_ctx *c, const ds_payload_t *srv, float *x, float *m, float gamma, float beta, hipStream_t st)
