@@ -92,7 +92,7 @@ __device__ __forceinline__ uint32_t from_lane_above(uint32_t x)
 
 // One subtile: PARTIAL for the row's last one when d cuts it (nothing at or past d is kept).
 template <bool PARTIAL>
-__device__ __forceinline__ void count_subtile(int64_t s, int lane, int64_t d, uint32_t stream, uint32_t thr, const RsParams &P,
+__device__ __forceinline__ uint32_t count_subtile(int64_t s, int lane, int64_t d, uint32_t stream, uint32_t thr, const RsParams &P,
                                               uint32_t *wrow, int64_t words32, uint32_t *cnt_row)
 {
     const uint32_t blk = static_cast<uint32_t>(s) * (kSub / 4) + lane;        // (s * 256 + 4 * lane) >> 2
@@ -110,11 +110,16 @@ __device__ __forceinline__ void count_subtile(int64_t s, int lane, int64_t d, ui
     const int64_t w = s * 8 + (lane >> 3);
     if ((lane & 7) == 0 && (!PARTIAL || w < words32)) wrow[w] = t;
     if (lane == 0) cnt_row[s] = c;
+    return c;
 }
 
-__global__ __launch_bounds__(kBlock) void k_rs_counts(uint64_t *words, int64_t W, uint32_t *cnt, int64_t n_sub, int64_t d,
-                                                      bool server, RsParams P)
+// tot64 [row][ceil(n_sub / 64)]: kept elements per 64 consecutive subtiles (= per workgroup
+// here), which spares the scan a launch.
+__global__ __launch_bounds__(kBlock) void k_rs_counts(uint64_t *words, int64_t W, uint32_t *cnt, uint32_t *tot64, int64_t n_sub,
+                                                      int64_t n_t64, int64_t d, bool server, RsParams P)
 {
+    static_assert(kWaves * kCountSubs == 64, "one workgroup = one entry of tot64");
+    __shared__ uint32_t wsum[kWaves];
     const int row = blockIdx.y;
     const int lane = lane_id();
     const uint32_t stream = server ? 0xFFFFFFFFu : static_cast<uint32_t>(row);
@@ -125,44 +130,58 @@ __global__ __launch_bounds__(kBlock) void k_rs_counts(uint64_t *words, int64_t W
     const int64_t s0 = (static_cast<int64_t>(blockIdx.x) * kWaves + wave) * kCountSubs;
     const int64_t s1 = (s0 + kCountSubs < n_sub) ? s0 + kCountSubs : n_sub;
     const int64_t full = d / kSub;                                            // subtiles before this one are whole
+    uint32_t total = 0;
     if (s0 + kCountSubs <= full) {
 #pragma unroll 2
-        for (int j = 0; j < kCountSubs; ++j) count_subtile<false>(s0 + j, lane, d, stream, thr, P, wrow, 2 * W, cnt_row);
-        return;
+        for (int j = 0; j < kCountSubs; ++j) total += count_subtile<false>(s0 + j, lane, d, stream, thr, P, wrow, 2 * W, cnt_row);
+    } else {
+        // the end of the row
+        const int64_t s_whole = (s1 < full) ? s1 : full;
+        for (int64_t s = s0; s < s_whole; ++s) total += count_subtile<false>(s, lane, d, stream, thr, P, wrow, 2 * W, cnt_row);
+        if (s0 <= full && full < s1) total += count_subtile<true>(full, lane, d, stream, thr, P, wrow, 2 * W, cnt_row);   // d % 256 != 0
     }
-    // the end of the row
-    const int64_t s_whole = (s1 < full) ? s1 : full;
-    for (int64_t s = s0; s < s_whole; ++s) count_subtile<false>(s, lane, d, stream, thr, P, wrow, 2 * W, cnt_row);
-    if (s0 <= full && full < s1) count_subtile<true>(full, lane, d, stream, thr, P, wrow, 2 * W, cnt_row);   // d % 256 != 0
+    if (lane == 0) wsum[wave] = total;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t t = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) t += wsum[w];
+        tot64[row * n_t64 + blockIdx.x] = t;
+    }
 }
 
-// Reader side: the same counts from the kept-bit plane.  One thread per subtile.
+// Reader side: the same counts from the kept-bit plane.  One thread per subtile, so one
+// wavefront per entry of tot64.
 __global__ __launch_bounds__(kBlock) void k_rs_popcounts(const uint64_t *__restrict__ words, int64_t W, uint32_t *cnt,
-                                                         int64_t n_sub, int64_t d)
+                                                         uint32_t *tot64, int64_t n_sub, int64_t n_t64, int64_t d)
 {
     const int row = blockIdx.y;
     const int64_t s = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
-    if (s >= n_sub) return;
-    const uint64_t *w = words + row * W + s * 4;
     uint32_t c = 0;
-    for (int q = 0; q < 4; ++q) {
-        const int64_t first = (s * 4 + q) * 64;             // bits at or past d do not count, whatever they hold
-        if (first >= d) break;
-        const uint64_t valid = (d - first >= 64) ? ~0ull : ((1ull << (d - first)) - 1ull);
-        c += __popcll(w[q] & valid);
+    if (s < n_sub) {
+        const uint64_t *w = words + row * W + s * 4;
+        for (int q = 0; q < 4; ++q) {
+            const int64_t first = (s * 4 + q) * 64;         // bits at or past d do not count, whatever they hold
+            if (first >= d) break;
+            const uint64_t valid = (d - first >= 64) ? ~0ull : ((1ull << (d - first)) - 1ull);
+            c += __popcll(w[q] & valid);
+        }
+        cnt[row * (n_sub + 1) + s] = c;
     }
-    cnt[row * (n_sub + 1) + s] = c;
+    const uint32_t t = wave_sum_u32(c);
+    if (lane_id() == 0 && (s >> 6) < n_t64) tot64[row * n_t64 + (s >> 6)] = t;
 }
 
 // Counts [row][0 .. n_sub) -> exclusive offsets [row][0 .. n_sub], the last one the row's
-// total, in place, in two launches: every workgroup scans its block of 4096 entries and leaves
-// the block's total; then every workgroup adds the totals of the blocks before its own.
+// total, in place and in one launch: a workgroup scans its block of 4096 entries and gets what
+// lies before the block from tot64 (64 entries per block).
 constexpr int kScanPer = 8, kScanBlock = kBlock * kScanPer;
 
-__global__ __launch_bounds__(kBlock) void k_rs_scan_blocks(uint32_t *tab, uint32_t *blk, int64_t n_sub, int64_t n_blk)
+__global__ __launch_bounds__(kBlock) void k_rs_scan(uint32_t *tab, const uint32_t *__restrict__ tot64, int64_t n_sub, int64_t n_t64)
 {
-    __shared__ uint32_t tmp[kWaves];
+    __shared__ uint32_t tmp[kWaves], pre[kWaves];
     uint32_t *row = tab + static_cast<int64_t>(blockIdx.y) * (n_sub + 1);
+    const uint32_t *trow = tot64 + static_cast<int64_t>(blockIdx.y) * n_t64;
     const int64_t t0 = static_cast<int64_t>(blockIdx.x) * kScanBlock + threadIdx.x * kScanPer;
     uint32_t c[kScanPer], s = 0;
 #pragma unroll
@@ -170,6 +189,10 @@ __global__ __launch_bounds__(kBlock) void k_rs_scan_blocks(uint32_t *tab, uint32
         c[j] = (t0 + j < n_sub) ? row[t0 + j] : 0u;
         s += c[j];
     }
+    uint32_t b = 0;
+    const int64_t n_before = static_cast<int64_t>(blockIdx.x) * (kScanBlock / 64);
+    for (int64_t t = threadIdx.x; t < n_before; t += kBlock) b += trow[t];
+    b = wave_sum_u32(b);
     const int lane = lane_id();
     uint32_t p = s;
 #pragma unroll
@@ -178,40 +201,19 @@ __global__ __launch_bounds__(kBlock) void k_rs_scan_blocks(uint32_t *tab, uint32
         if (lane >= o) p += up;
     }
     if (lane == 63) tmp[wave_id()] = p;
+    if (lane == 0) pre[wave_id()] = b;
     __syncthreads();
-    uint32_t run = p - s, total = 0;
+    uint32_t run = p - s;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
         if (w < wave_id()) run += tmp[w];
-        total += tmp[w];
+        run += pre[w];
     }
 #pragma unroll
     for (int j = 0; j < kScanPer; ++j) {
         if (t0 + j <= n_sub) row[t0 + j] = run;            // entry n_sub receives the running total
         run += c[j];
     }
-    if (threadIdx.x == 0) blk[blockIdx.y * n_blk + blockIdx.x] = total;
-}
-
-__global__ __launch_bounds__(kBlock) void k_rs_scan_add(uint32_t *tab, const uint32_t *__restrict__ blk, int64_t n_sub,
-                                                        int64_t n_blk)
-{
-    __shared__ uint32_t tmp[kWaves];
-    if (blockIdx.x == 0) return;                            // nothing before the first block
-    const uint32_t *b = blk + blockIdx.y * n_blk;
-    uint32_t s = 0;
-    for (int64_t t = threadIdx.x; t < blockIdx.x; t += kBlock) s += b[t];
-    s = wave_sum_u32(s);
-    if (lane_id() == 0) tmp[wave_id()] = s;
-    __syncthreads();
-    uint32_t before = 0;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) before += tmp[w];
-    uint32_t *row = tab + static_cast<int64_t>(blockIdx.y) * (n_sub + 1);
-    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * kScanBlock + threadIdx.x * kScanPer;
-#pragma unroll
-    for (int j = 0; j < kScanPer; ++j)
-        if (t0 + j <= n_sub) row[t0 + j] += before;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -338,12 +340,6 @@ __global__ __launch_bounds__(kBlock) void k_rs_apply(const uint64_t *__restrict_
 
 unsigned blocks4(int64_t d) { return static_cast<unsigned>((d + kBlock * 4 - 1) / (kBlock * 4)); }
 
-void scan_rows(uint32_t *tab, uint32_t *blk, int64_t n_sub, int64_t n_blk, unsigned rows, hipStream_t st)
-{
-    const dim3 grid(static_cast<unsigned>(n_blk), rows);
-    k_rs_scan_blocks<<<grid, kBlock, 0, st>>>(tab, blk, n_sub, n_blk);
-    if (n_blk > 1) k_rs_scan_add<<<grid, kBlock, 0, st>>>(tab, blk, n_sub, n_blk);
-}
 
 RsParams make_params(const ds_ctx *c, uint64_t step)
 {
@@ -364,9 +360,15 @@ struct ds_rs_scratch {
     uint32_t *off_in;   // [n][n_sub + 1]  worker messages, as read by the server
     uint32_t *off_s;    // [n_sub + 1]     server message, writer side
     uint32_t *off_r;    // [n_sub + 1]     a message as read by the update / decoder
-    uint32_t *blk;      // [n][n_blk]      block totals of the scan
-    int64_t n_blk;
+    uint32_t *tot64;    // [n][n_t64]      kept elements per 64 subtiles, from the count kernels for the scan
+    int64_t n_t64;
 };
+
+static void scan_rows(const ds_rs_scratch *t, uint32_t *tab, unsigned rows, hipStream_t st)
+{
+    const unsigned n_blk = static_cast<unsigned>((t->n_sub + 1 + kScanBlock - 1) / kScanBlock);
+    k_rs_scan<<<dim3(n_blk, rows), kBlock, 0, st>>>(tab, t->tot64, t->n_sub, t->n_t64);
+}
 
 ds_status_t ds_rsparse_init(ds_ctx *c)
 {
@@ -380,8 +382,8 @@ ds_status_t ds_rsparse_init(ds_ctx *c)
     DS_HIP_TRY(hipMalloc(&t->off_in, n * row));
     DS_HIP_TRY(hipMalloc(&t->off_s, row));
     DS_HIP_TRY(hipMalloc(&t->off_r, row));
-    t->n_blk = (t->n_sub + 1 + kScanBlock - 1) / kScanBlock;
-    DS_HIP_TRY(hipMalloc(&t->blk, n * static_cast<size_t>(t->n_blk) * sizeof(uint32_t)));
+    t->n_t64 = (t->n_sub + 63) / 64;
+    DS_HIP_TRY(hipMalloc(&t->tot64, n * static_cast<size_t>(t->n_t64) * sizeof(uint32_t)));
     return DS_OK;
 }
 
@@ -389,7 +391,7 @@ void ds_rsparse_fini(ds_ctx *c)
 {
     ds_rs_scratch *t = c->rs;
     if (!t) return;
-    void *ptrs[5] = {t->off_w, t->off_in, t->off_s, t->off_r, t->blk};
+    void *ptrs[5] = {t->off_w, t->off_in, t->off_s, t->off_r, t->tot64};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     delete t;
@@ -403,8 +405,8 @@ ds_status_t ds_rsparse_worker(ds_ctx *c, uint64_t step, const void *g, int64_t g
     const RsParams P = make_params(c, step);
     const unsigned n = static_cast<unsigned>(c->cfg.n);
     k_rs_counts<<<dim3(static_cast<unsigned>((t->n_sub + kWaves * kCountSubs - 1) / (kWaves * kCountSubs)), n), kBlock, 0, st>>>(
-        out->sign_words, c->W, t->off_w, t->n_sub, c->cfg.d, false, P);
-    scan_rows(t->off_w, t->blk, t->n_sub, t->n_blk, n, st);
+        out->sign_words, c->W, t->off_w, t->tot64, t->n_sub, t->n_t64, c->cfg.d, false, P);
+    scan_rows(t, t->off_w, n, st);
     const dim3 grid(static_cast<unsigned>(c->n_tiles), n);
     if (c->cfg.grad_dtype == DS_BF16)
         k_rs_worker<true><<<grid, kBlock, 0, st>>>(g, gs, delta, dstr, c->cfg.d, out->sign_words, c->W, out->dense, t->off_w,
@@ -421,12 +423,12 @@ ds_status_t ds_rsparse_server(ds_ctx *c, uint64_t step, const ds_payload_t *in, 
     ds_rs_scratch *t = c->rs;
     const RsParams P = make_params(c, step);
     const unsigned n = static_cast<unsigned>(c->cfg.n);
-    k_rs_popcounts<<<dim3(static_cast<unsigned>((t->n_sub + kBlock - 1) / kBlock), n), kBlock, 0, st>>>(in->sign_words, c->W,
-                                                                                                     t->off_in, t->n_sub, c->cfg.d);
-    scan_rows(t->off_in, t->blk, t->n_sub, t->n_blk, n, st);
+    k_rs_popcounts<<<dim3(static_cast<unsigned>((t->n_sub + kBlock - 1) / kBlock), n), kBlock, 0, st>>>(
+        in->sign_words, c->W, t->off_in, t->tot64, t->n_sub, t->n_t64, c->cfg.d);
+    scan_rows(t, t->off_in, n, st);
     k_rs_counts<<<dim3(static_cast<unsigned>((t->n_sub + kWaves * kCountSubs - 1) / (kWaves * kCountSubs)), 1), kBlock, 0, st>>>(
-        out->sign_words, c->W, t->off_s, t->n_sub, c->cfg.d, true, P);
-    scan_rows(t->off_s, t->blk, t->n_sub, t->n_blk, 1, st);
+        out->sign_words, c->W, t->off_s, t->tot64, t->n_sub, t->n_t64, c->cfg.d, true, P);
+    scan_rows(t, t->off_s, 1, st);
     k_rs_server<<<static_cast<unsigned>(c->n_tiles), kBlock, 0, st>>>(in->sign_words, in->dense, t->off_in, c->cfg.n, c->inv_n,
                                                                     delta_s, c->cfg.d, c->W, out->sign_words, out->dense,
                                                                     t->off_s, t->n_sub, P.p);
@@ -440,9 +442,9 @@ static ds_status_t rs_apply(ds_ctx *c, const uint64_t *words, const float *vals,
 {
     ds_rs_scratch *t = c->rs;
     if (!off) {
-        k_rs_popcounts<<<dim3(static_cast<unsigned>((t->n_sub + kBlock - 1) / kBlock), 1), kBlock, 0, st>>>(words, c->W, t->off_r,
-                                                                                                         t->n_sub, c->cfg.d);
-        scan_rows(t->off_r, t->blk, t->n_sub, t->n_blk, 1, st);
+        k_rs_popcounts<<<dim3(static_cast<unsigned>((t->n_sub + kBlock - 1) / kBlock), 1), kBlock, 0, st>>>(
+            words, c->W, t->off_r, t->tot64, t->n_sub, t->n_t64, c->cfg.d);
+        scan_rows(t, t->off_r, 1, st);
         off = t->off_r;
     }
     const unsigned blocks = blocks4(t->n_sub * kSub);
