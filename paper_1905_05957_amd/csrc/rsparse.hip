@@ -219,6 +219,17 @@ __global__ __launch_bounds__(kBlock) void k_rs_scan(uint32_t *tab, const uint32_
 // ---------------------------------------------------------------------------------------
 // the three calls
 // ---------------------------------------------------------------------------------------
+// p0..p3: the four floats that follow a lane's position in the packed values; the kept ones
+// among its four elements (flags in nib) are the first of them, in element order.  Returns
+// them at their elements and 0 for the others (selects instead of a load per kept element).
+__device__ __forceinline__ f32x4 place_kept4(float p0, float p1, float p2, float p3, uint32_t nib)
+{
+    const bool k0 = nib & 1u, k1 = nib & 2u, k2 = nib & 4u, k3 = nib & 8u;
+    const float a1 = k0 ? p1 : p0, a2 = k0 ? p2 : p1, a3 = k0 ? p3 : p2;     // ranks k0, k0 + 1, k0 + 2
+    const float b1 = k1 ? a2 : a1, b2 = k1 ? a3 : a2;                        // ranks k0 + k1, k0 + k1 + 1
+    return f32x4{k0 ? p0 : 0.f, k1 ? a1 : 0.f, k2 ? b1 : 0.f, k3 ? (k2 ? b2 : b1) : 0.f};
+}
+
 // Q[v] of the four elements of a thread, the message and the error.
 __device__ __forceinline__ void rs_store4(f32x4 v, uint32_t nib, const Ranks &rk, uint32_t base, int64_t e, int64_t d,
                                           float *__restrict__ vals_row, float *__restrict__ err_row, bool err_vec, float p)
@@ -279,28 +290,41 @@ __global__ __launch_bounds__(kBlock) void k_rs_server(const uint64_t *words_in, 
             if ((lane >> 3) < nb && wave_first + 32 * (lane & 7) < W * 64)
                 word = reinterpret_cast<const uint32_t *>(words_in + (i0 + (lane >> 3)) * W)[(wave_first >> 5) + (lane & 7)];
             const uint32_t o = (lane < nb) ? off_in[(i0 + lane) * (n_sub + 1) + sub] : 0u;
-            // all loads of the batch first (independent), then the chain in worker order
-            f32x4 q[8];
+            const uint32_t vn = valid_nibble(e, d);
+            if (nb == 8 && (sub + 1) * kSub + 4 <= d) {
+                // A full batch away from the end of the rows: a lane's kept values start at most
+                // at float (sub + 1) * 256 of a row, so four floats from there stay inside it.
+                // All eight fetches are issued before the first is used.
+                typedef float f32x4_unaligned __attribute__((ext_vector_type(4), aligned(4)));
+                f32x4_unaligned pk[8];
+                uint32_t nibs[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                q[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-                if (i < nb) {                               // uniform
+                for (int i = 0; i < 8; ++i) {
                     const uint32_t w = __shfl(word, i * 8 + (lane >> 3), 64);
-                    const uint32_t nib = (w >> (4 * (lane & 7))) & valid_nibble(e, d);
+                    nibs[i] = (w >> (4 * (lane & 7))) & vn;
+                    const Ranks rk = subtile_ranks(nibs[i]);
+                    const int64_t at = static_cast<int64_t>(i0 + i) * d +
+                                       static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(o), i)) + rk.before;
+                    pk[i] = *reinterpret_cast<const f32x4_unaligned *>(vals_in + at);
+                }
+#pragma unroll
+                for (int i = 0; i < 8; ++i) a = fma4(inv_n, place_kept4(pk[i].x, pk[i].y, pk[i].z, pk[i].w, nibs[i]), a);
+            } else {
+                for (int i = 0; i < nb; ++i) {
+                    const uint32_t w = __shfl(word, i * 8 + (lane >> 3), 64);
+                    const uint32_t nib = (w >> (4 * (lane & 7))) & vn;
                     const Ranks rk = subtile_ranks(nib);
                     const float *src = vals_in + static_cast<int64_t>(i0 + i) * d +
                                        static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(o), i)) + rk.before;
+                    f32x4 q = {0.f, 0.f, 0.f, 0.f};
                     uint32_t r = 0;
-                    if (nib & 1u) q[i].x = src[r++];
-                    if (nib & 2u) q[i].y = src[r++];
-                    if (nib & 4u) q[i].z = src[r++];
-                    if (nib & 8u) q[i].w = src[r++];
-                    // an element that was not kept adds nothing: fma(0, 1/n, a) = a
+                    if (nib & 1u) q.x = src[r++];
+                    if (nib & 2u) q.y = src[r++];
+                    if (nib & 4u) q.z = src[r++];
+                    if (nib & 8u) q.w = src[r++];
+                    a = fma4(inv_n, q, a);                  // an element that was not kept adds nothing: fma(0, 1/n, a) = a
                 }
             }
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                if (i < nb) a = fma4(inv_n, q[i], a);
         }
     }
     const uint32_t nib = (e < d) ? load_sign_nibble(words_out, e) : 0u;         // written by k_rs_counts
