@@ -212,8 +212,10 @@ ds_status_t ds_apply_update(ds_ctx_t *ctx, const ds_payload_t *srv, float *x, fl
 /* The parameter-server block followed by the model update, as one call: the same results, bit
  * for bit, as ds_server_aggregate_compress(ctx, step, in, delta_s, out, stream) followed by
  * ds_apply_update(ctx, out, x, m, gamma, beta, stream), for the library to fold the update
- * into the server's kernels where that saves a pass (TOPK without momentum: x is updated
- * where the kept entries are emitted).  Arguments and errors as for those two calls. */
+ * into the server's kernels where that saves work (TOPK without momentum: x is updated
+ * where the kept entries are emitted; RSPARSE: the update takes the offsets of the packed
+ * values from the server pass instead of deriving them from the message again).  Arguments
+ * and errors as for those two calls. */
 ds_status_t ds_server_aggregate_compress_update(ds_ctx_t *ctx, uint64_t step, const ds_payload_t *in,
                                                 float *delta_s, const ds_payload_t *out, float *x,
                                                 float *m, float gamma, float beta, void *hip_stream);
