@@ -14,12 +14,6 @@ using namespace ds;
 
 namespace {
 
-// the kept upper bits of four elements, NB bytes each, packed little endian
-template <int NB> struct Packed;
-template <> struct Packed<1> { typedef uint32_t type; };
-template <> struct Packed<2> { typedef u32x2 type; };
-template <> struct Packed<4> { typedef u32x4 type; };
-
 template <int NB>
 __device__ __forceinline__ void store_msg4(uint8_t *__restrict__ row, int64_t e, int64_t d, const uint32_t top[4])
 {

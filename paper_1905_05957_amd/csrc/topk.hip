@@ -45,8 +45,7 @@ namespace {
 
 constexpr int kSub = 256;                  // elements per subtile = one wavefront of the dense pass
 constexpr int kReg = kTile;                // elements per candidate region = one workgroup of the dense pass
-constexpr int kGroupRegs = 16;             // regions per group = one wavefront of the candidate passes
-constexpr int kGroup = kReg * kGroupRegs;  // 32768 elements
+constexpr int kGroupRegs = 16;             // regions per group (32768 elements) = one wavefront of the candidate passes
 constexpr int kH1 = 4096, kH2 = 2048, kH3 = 256;
 // The candidates' level-1 histogram covers only the 256 top-12-bit bins from lo_bin upwards
 // (16 octaves of magnitude); anything above is clamped into its last bin.  If the k-th key
@@ -509,7 +508,6 @@ __global__ __launch_bounds__(kBlock) void k_topk_pass1(Src src, float *buf, int6
 // tags are hashed (element & 255): two pending entries that share a tag but not an element
 // merely take turns.
 constexpr int kSpan = 4 * kSub;              // elements per wavefront
-constexpr int kSpanTile = kSpan * kWaves;    // elements per workgroup = 4 regions
 
 __global__ __launch_bounds__(kBlock) void k_topk_pass1_server(ServerV src, float *buf, int64_t d, const Sel *sel,
                                                               u32x2 *slots, uint32_t *reg_cnt, int64_t n_reg)
