@@ -459,3 +459,150 @@ def test_server_average_uses_every_worker_once():
     want = 0.5 + msgs["dense"].astype(np.float64).mean(0)
     assert np.array_equal(ps["dense"][0], want.astype(np.float32))
     assert not delta_s.any()
+
+
+# ----------------------------------------------------------------------------------------
+# Section 3.1: the compression randomness omega_t^(i) is drawn independently on every worker
+# and on the server
+# ----------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name", ["qsgd", "rsparse"])
+def test_every_worker_and_the_server_draw_from_their_own_stream(name):
+    n, d, seed, t = 3, 4096, 11, 5
+    if name == "qsgd":
+        cfg = O.Config(O.QSGD, n=n, d=d, bucket=512, levels=15, seed=seed)
+        plane = "levels"
+    else:
+        cfg = O.Config(O.RSPARSE, n=n, d=d, seed=seed, keep_prob=0.5)
+        plane = "sign_words"
+    one = O.Config(cfg.comp, n=1, d=d, bucket=512, levels=15, seed=seed, keep_prob=0.5)
+    r = _rng(3)
+    row = (r.standard_normal(d) * 1e-2).astype(np.float32)
+    g = np.tile(row, (n, 1))                         # the same vector on every worker
+    delta = np.zeros((n, d), np.float32)
+    pw = O.worker_compress(cfg, t, g, delta)
+    # identical inputs, different draws: the messages of two workers differ ...
+    for i in range(n):
+        for k in range(i + 1, n):
+            assert not np.array_equal(pw[plane][i], pw[plane][k]), (i, k)
+    # ... and worker i's message is what the compressor gives on stream i (counter word 2)
+    for i in range(n):
+        ref = O.encode(one, t, i, row)
+        assert np.array_equal(pw[plane][i], ref[plane][0])
+    # the server compresses its own vector on the stream 0xFFFFFFFF, not on a worker's
+    v_s = np.zeros(d, np.float64)
+    for i in range(n):
+        v_s += O.decode(cfg, pw, i).astype(np.float64) / n
+    delta_s = np.zeros(d, np.float32)
+    ps = O.server_aggregate_compress(cfg, t, pw, delta_s)
+    v32 = v_s.astype(np.float32)
+    if name == "rsparse":                            # the keep decisions do not depend on the data
+        assert np.array_equal(ps[plane][0], O.encode(one, t, 0xFFFFFFFF, v32)[plane][0])
+        for i in range(n):
+            assert not np.array_equal(ps[plane][0], O.encode(one, t, i, v32)[plane][0])
+    else:
+        # codes depend on v as well: redo the two-point rule on the first bucket with the
+        # uniforms of a stream and count how many codes it explains (v_s here is the fp64
+        # average, the oracle's is the fp32 chain, so a few codes may differ either way)
+        lev = ps["levels"][0]
+        codes = np.where(np.arange(512) % 2 == 0, lev[np.arange(512) // 2] & 15, lev[np.arange(512) // 2] >> 4)
+        norm = float(ps["scales"][0, 0])
+        rr = np.abs(v_s[:512]) * 15 / norm
+
+        def explained(stream):
+            u = np.array([O.uniform24(seed, t, stream, j) for j in range(512)])
+            return np.mean(np.minimum(np.floor(rr) + (u < rr - np.floor(rr)), 15) == codes)
+
+        assert explained(0xFFFFFFFF) > 0.98
+        for i in range(n):
+            assert explained(i) < 0.9
+
+
+# ----------------------------------------------------------------------------------------
+# Algorithm 1, "Average": v = delta + (1/n) sum_i Q[v_i], evaluated as one correctly rounded
+# multiply-add per worker in ascending order (1/n rounded once) -- checked against exact
+# rational arithmetic
+# ----------------------------------------------------------------------------------------
+def test_server_chain_is_one_rounding_per_worker():
+    from fractions import Fraction
+    n, d = 3, 400
+    cfg = O.Config(O.IDENTITY, n=n, d=d)
+    r = _rng(17)
+    msgs = {"dense": (r.standard_normal((n, d)) * np.exp(r.uniform(-3, 3, (n, d)))).astype(np.float32)}
+    delta_s = (r.standard_normal(d) * 0.3).astype(np.float32)
+    start = delta_s.copy()
+    ps = O.server_aggregate_compress(cfg, 0, msgs, delta_s)
+    inv_n = Fraction(float(np.float32(1.0) / np.float32(n)))
+
+    def round32(x: Fraction) -> float:
+        # nearest fp32, ties to even, from the exact value: bracket it between neighbouring floats
+        f = np.float32(float(x))                      # close; then fix up by comparing exactly
+        lo, hi = np.nextafter(f, np.float32(-np.inf)), np.nextafter(f, np.float32(np.inf))
+        best = min((lo, f, hi), key=lambda c: (abs(Fraction(float(c)) - x), int(np.float32(c).view(np.uint32)) & 1))
+        return float(best)
+
+    differs_from_two_roundings = 0
+    for j in range(d):
+        acc = Fraction(float(start[j]))
+        acc2 = np.float32(start[j])
+        for i in range(n):
+            q = Fraction(float(msgs["dense"][i, j]))
+            acc = Fraction(round32(q * inv_n + acc))
+            acc2 = np.float32(acc2 + np.float32(msgs["dense"][i, j] * (np.float32(1.0) / np.float32(n))))
+        assert float(ps["dense"][0, j]) == float(acc), j
+        differs_from_two_roundings += float(acc2) != float(acc)
+    assert differs_from_two_roundings > 0                # the inputs do tell the two evaluations apart
+
+
+# ----------------------------------------------------------------------------------------
+# Section 3.2: "b with probability (z - a)/(b - a)", "z/p with probability p".  A 24-bit
+# uniform u = U 2^-24 realises a probability P 2^-24 exactly iff the event is u < P 2^-24
+# (U in {0, .., P-1}); with <= it would be (P + 1) 2^-24.  The two draws below sit on that
+# edge: seed 7, stream 0, U = 0 at (step 5837, element 66) and U = 1 at (step 4875, element 140).
+# ----------------------------------------------------------------------------------------
+def test_the_random_decisions_are_strict_comparisons():
+    seed, d = 7, 1024
+    (t0, j0), (t1, j1) = (5837, 66), (4875, 140)
+    assert O.uniform24(seed, t0, 0, j0) == 0.0 and O.uniform24(seed, t1, 0, j1) == 2.0 ** -24
+    ones = np.ones(d, np.float32)
+
+    def kept(p, t, j):
+        cfg = O.Config(O.RSPARSE, n=1, d=d, seed=seed, keep_prob=float(np.float32(p)))
+        return bool(unpack_bits(O.encode(cfg, t, 0, ones)["sign_words"][0], d)[j])
+
+    assert kept(2.0 ** -24, t0, j0)                  # U = 0 < 1
+    assert not kept(2.0 ** -24, t1, j1)              # U = 1 is not below 1
+    assert kept(2.0 ** -23, t1, j1)                  # but below 2
+
+    # the quantiser on the same edge: one element of size 1 makes the bucket norm 1, the element
+    # under test sits at 2^-24 of a level (s = 1), so it goes up iff u < 2^-24
+    def code(t, j):
+        v = np.zeros(d, np.float32)
+        v[(j + 1) % d] = 1.0
+        v[j] = np.float32(2.0 ** -24)
+        cfg = O.Config(O.QSGD, n=1, d=d, bucket=d, levels=1, seed=seed)
+        m = O.encode(cfg, t, 0, v)
+        assert m["scales"][0, 0] == 1.0
+        return int(m["levels"][0, j >> 1] >> ((j & 1) * 4)) & 15
+
+    assert code(t0, j0) == 1
+    assert code(t1, j1) == 0
+
+
+def test_qsgd_position_a_hair_above_the_top_level_stays_at_the_top_level():
+    """A lone element x in its bucket sits at r = |x| fl(s/|x|), which fp32 can round to just
+    above s; the two representable neighbours of |x| = norm are s-1 and s (Section 3.2), so
+    the code is s whatever the draw.  Here the draw is the U = 0 one (it would go "up")."""
+    seed, d, s = 7, 1024, 15
+    t0, j0 = 5837, 66
+    x = np.float32(float.fromhex("0x1.4ea5a4p+0"))
+    assert np.float32(x * np.float32(np.float32(s) / x)) > s       # the premise, in fp32
+    assert O.uniform24(seed, t0, 0, j0) == 0.0
+    v = np.zeros(d, np.float32)
+    v[j0] = -x
+    cfg = O.Config(O.QSGD, n=1, d=d, bucket=d, levels=s, seed=seed)
+    m = O.encode(cfg, t0, 0, v)
+    lev = m["levels"][0]
+    codes = np.where(np.arange(d) % 2 == 0, lev[np.arange(d) // 2] & 15, lev[np.arange(d) // 2] >> 4)
+    assert codes[j0] == s and codes.sum() == s
+    q = O.decode(cfg, m, 0)
+    assert q[j0] == -x and np.count_nonzero(q) == 1
