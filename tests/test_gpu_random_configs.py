@@ -1,0 +1,73 @@
+"""GPU parity on seeded random configurations: compressor, worker count, vector length (every
+residue mod 4 and mod 64, below and above one tile), groups, k, buckets, clip width, keep
+probability, gradient type, momentum, step counter and the top-k route are drawn together, so
+that combinations no hand-written case lists get run.  Every case is two compared steps from
+identical state, to the same bar as the other parity tests."""
+import os
+
+import numpy as np
+import pytest
+
+import ds_workloads as W
+import paper_1905_05957_amd as P
+import parity_util
+from parity_util import Pair
+
+pytestmark = pytest.mark.gpu
+
+CASES = int(os.environ.get("DS_RANDOM_CASES", "72"))      # a wider hunt: DS_RANDOM_CASES=2000
+
+
+def _draw(case: int):
+    r = np.random.default_rng(20_000 + case)
+    comp = ["sign", "topk", "qsgd", "clip", "rsparse", "identity"][case % 6]
+    n = int(r.choice([1, 2, 3, 4, 7, 8, 9, 16, 17]))
+    d = int(np.exp(r.uniform(np.log(1), np.log(60_000)))) + int(r.integers(0, 4))
+    kw = dict(n=n, d=d, gamma=float(r.choice([0.05, 0.1, 1.0])), dist="normal", sigma=float(10.0 ** r.uniform(-4, 0)))
+    if r.random() < 0.4:
+        kw["grad_dtype"] = "bf16"
+    if r.random() < 0.4:
+        kw["beta"] = float(r.choice([0.5, 0.9]))
+    flags = 0
+    if comp == "sign":
+        mode = ["whole", "chunk", "segments"][(case // 6) % 3]
+        kw["scale_mode"] = mode
+        if mode == "chunk":
+            kw["chunk"] = int(r.choice([7, 64, 100, 128, 320, 512, 640, 1024, 1920, 2048, 4096, 5000]))
+        elif mode == "segments":
+            n_seg = int(r.integers(1, min(d, 40) + 1))
+            cuts = np.sort(r.choice(np.arange(1, d), size=n_seg - 1, replace=False)) if n_seg > 1 else np.array([], np.int64)
+            kw["seg_offsets"] = np.concatenate([[0], cuts, [d]]).astype(np.int64)
+            kw["seg_sigma"] = 10.0 ** r.uniform(-4, -1, n_seg)
+            kw["dist"] = "segment_normal"
+        if r.random() < 0.3:
+            kw["sign_rms"] = True
+    elif comp == "topk":
+        kw["k"] = int(r.choice([1, max(1, d // 100), max(1, d // 7), d]))
+        kw["dist"] = str(r.choice(["laplace_outliers", "levels8", "normal"]))
+        if r.random() < 0.3:
+            flags |= P.FLAG_TOPK_MULTI_LAUNCH
+    elif comp == "qsgd":
+        kw["bucket"] = int(r.choice([64, 128, 256, 512, 1024, 2048]))
+        kw["levels"] = int(r.choice([1, 2, 7, 15]))
+    elif comp == "clip":
+        kw["clip_bits"] = int(r.choice([1, 8, 15, 16, 17, 23, 24, 31]))
+    elif comp == "rsparse":
+        kw["keep_prob"] = float(r.choice([0.6, 0.75, 0.99, 1.0, 0.05]))
+    first_step = int(r.choice([0, 1, 12345, (1 << 32) - 1, (1 << 40) + 3]))
+    return W.Workload(f"random_{case}_{comp}", comp, **kw), flags, first_step
+
+
+@pytest.mark.parametrize("case", range(CASES))
+def test_random_configuration(gpu_device, case):
+    wl, flags, t0 = _draw(case)
+    parity_util.CONTEXT_FLAGS = flags
+    try:
+        pair = Pair(wl, gpu_device)
+    finally:
+        parity_util.CONTEXT_FLAGS = 0
+    try:
+        for t in range(2):
+            pair.compared_step(t0 + t, wl.gradients(t, gpu_device), tag=f" flags={flags}")
+    finally:
+        pair.close()
