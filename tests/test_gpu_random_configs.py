@@ -16,13 +16,14 @@ from parity_util import Pair
 pytestmark = pytest.mark.gpu
 
 CASES = int(os.environ.get("DS_RANDOM_CASES", "72"))      # a wider hunt: DS_RANDOM_CASES=2000
+MAX_D = int(os.environ.get("DS_RANDOM_MAX_D", "60000"))   # and longer vectors: DS_RANDOM_MAX_D=3000000
 
 
 def _draw(case: int):
     r = np.random.default_rng(20_000 + case)
     comp = ["sign", "topk", "qsgd", "clip", "rsparse", "identity"][case % 6]
     n = int(r.choice([1, 2, 3, 4, 7, 8, 9, 16, 17]))
-    d = int(np.exp(r.uniform(np.log(1), np.log(60_000)))) + int(r.integers(0, 4))
+    d = int(np.exp(r.uniform(np.log(1), np.log(MAX_D)))) + int(r.integers(0, 4))
     kw = dict(n=n, d=d, gamma=float(r.choice([0.05, 0.1, 1.0])), dist="normal", sigma=float(10.0 ** r.uniform(-4, 0)))
     if r.random() < 0.4:
         kw["grad_dtype"] = "bf16"
