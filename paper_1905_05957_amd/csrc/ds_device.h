@@ -212,6 +212,13 @@ __device__ __forceinline__ uint32_t load_sign_nibble(const uint64_t *__restrict_
     return (byte >> (e & 4)) & 15u;
 }
 
+// a ^ b ^ c as one three-input bit operation (truth table 0x96) of gfx950; the compiler emits
+// two exclusive-ors for the plain expression.
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c)
+{
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+
 // Philox4x32-10 (Salmon et al., SC'11): ten rounds of two 32x32->64 multiplies.
 __device__ __forceinline__ u32x4 philox4x32_10(u32x4 c, uint32_t k0, uint32_t k1)
 {
@@ -220,9 +227,9 @@ __device__ __forceinline__ u32x4 philox4x32_10(u32x4 c, uint32_t k0, uint32_t k1
         const uint64_t p0 = static_cast<uint64_t>(0xD2511F53u) * c.x;
         const uint64_t p1 = static_cast<uint64_t>(0xCD9E8D57u) * c.z;
         u32x4 nx;
-        nx.x = static_cast<uint32_t>(p1 >> 32) ^ c.y ^ k0;
+        nx.x = xor3(static_cast<uint32_t>(p1 >> 32), c.y, k0);
         nx.y = static_cast<uint32_t>(p1);
-        nx.z = static_cast<uint32_t>(p0 >> 32) ^ c.w ^ k1;
+        nx.z = xor3(static_cast<uint32_t>(p0 >> 32), c.w, k1);
         nx.w = static_cast<uint32_t>(p0);
         c = nx;
         k0 += 0x9E3779B9u;
