@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0
 # the scale factors are recorded under profiles/.  None = not profiled yet.
 MEASURED_WORKER_TRAFFIC = {
     "c5": 5.9728e9 + 4.1221e9,   # k_sign_chunk_worker
-    "c4": 3.3117e9 + 1.9175e9,   # k_qsgd_worker
+    "c4": 3.3116e9 + 1.9177e9,   # k_qsgd_worker
     "c3": 2.6548e9,              # all kernels of the worker call (dense pass 1.6551e9 + 0.8493e9)
     "clip16": 1.6568e9 + 1.2368e9,   # k_clip_worker
     "rsparse60": 1.7116e9 + 1.3278e9 + 0.0299e9 + 0.0068e9,   # k_rs_worker + k_rs_counts + k_rs_scan

@@ -19,7 +19,7 @@
 // of the plane (k_rs_popcounts), so the message carries no offsets.
 //
 // The generator is pure integer ALU, and as a launch of its own it overlaps with nothing
-// (about 100 us for 8 x 25.6 M elements against 490 us for the dense pass).  Folding it into
+// (about 80 us for 8 x 25.6 M elements against 490 us for the dense pass).  Folding it into
 // the dense pass needs the offsets inside that pass; a chained scan with decoupled look-back
 // over the 2048-element tiles was tried and took 1250 us: a tile is too little work, the
 // look-back of a workgroup runs over most of the thousand workgroups that are resident with it.
