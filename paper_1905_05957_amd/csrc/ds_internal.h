@@ -10,6 +10,10 @@
 // odd chunk sizes).  A "piece" is a maximal run of elements inside one tile and one group;
 // pieces are numbered in element order, so piece p spans [piece_start[p], piece_start[p+1]).
 struct ds_sign_tables {
+    // [n_tiles] {first piece, group}: group >= 0 for a tile that lies inside one group (one piece),
+    // else minus the number of its pieces.  One 8-byte load tells a workgroup its pieces and, in
+    // the common case, the group whose scale it needs.
+    const int2 *tile_info;
     const int32_t *tile_piece_first;  // [n_tiles + 1]
     const int64_t *piece_start;       // [n_pieces + 1]
     const int32_t *piece_seg;         // [n_pieces]

@@ -244,6 +244,17 @@ __global__ __launch_bounds__(kBlock) void k_sign_chunk_update(const uint64_t *__
 // ---------------------------------------------------------------------------------------
 // general route: tiles x pieces
 // ---------------------------------------------------------------------------------------
+// Pieces [p0, p1) of a tile; seg0 = its group when it has one piece, else -1.
+struct TilePieces {
+    int32_t p0, p1, seg0;
+};
+
+__device__ __forceinline__ TilePieces tile_pieces(const ds_sign_tables &tb, int64_t tile)
+{
+    const int2 ti = tb.tile_info[tile];
+    return (ti.y >= 0) ? TilePieces{ti.x, ti.x + 1, ti.y} : TilePieces{ti.x, ti.x - ti.y, -1};
+}
+
 // Group of element e, given the pieces [p0, p1) of its tile.
 __device__ __forceinline__ int32_t seg_of(const ds_sign_tables &tb, int32_t p0, int32_t p1, int64_t e)
 {
@@ -260,9 +271,9 @@ __device__ __forceinline__ double masked_abs(float x, int64_t e, int64_t lo, int
 
 // v - Q[v] for the four elements of a thread, with the group scales of its tile's pieces.
 __device__ __forceinline__ f32x4 sign_error_tile(f32x4 v, int64_t e, int64_t d, const float *__restrict__ srow,
-                                                 const ds_sign_tables &tb, int32_t p0, int32_t p1)
+                                                 const ds_sign_tables &tb, int32_t p0, int32_t p1, int32_t seg0)
 {
-    if (p1 - p0 == 1) return sign_error4(v, srow[tb.piece_seg[p0]]);
+    if (seg0 >= 0) return sign_error4(v, srow[seg0]);
     float s[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) s[c] = (e + c < d) ? srow[seg_of(tb, p0, p1, e + c)] : 0.f;
@@ -324,9 +335,10 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass1_worker(WorkerSrc<BF16> sr
     const bool gvec = BF16 ? aligned8(grow) : aligned16(grow);
     const bool dvec = aligned16(drow);
     const int64_t e = base + threadIdx.x * 4;
-    const int32_t p0 = tb.tile_piece_first[tile], p1 = tb.tile_piece_first[tile + 1];
+    const TilePieces tp = tile_pieces(tb, tile);
+    const int32_t p0 = tp.p0, p1 = tp.p1;
     f32x4 dl = DEFERRED ? ld4_stream(drow, e, d, dvec) : ld4(drow, e, d, dvec);
-    if (DEFERRED && e < d) dl = zero_past(sign_error_tile(dl, e, d, prev_scales + row * S, tb, p0, p1), e, d);
+    if (DEFERRED && e < d) dl = zero_past(sign_error_tile(dl, e, d, prev_scales + row * S, tb, p0, p1, tp.seg0), e, d);
     const f32x4 v = ld4_grad<BF16>(grow, e, d, gvec) + dl;
     pass1_finish<RMS, DEFERRED>(v, base, d, drow, dvec, words + row * W, W * 64, tb, p0, p1,
                       partials + static_cast<int64_t>(row) * tb.n_pieces, lds, sw_lds);
@@ -342,16 +354,17 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass1_server(ServerArgs a, floa
     const int64_t tile = blockIdx.x;
     const int64_t base = tile * kTile;
     const bool dvec = aligned16(delta_s);
-    const int32_t p0 = tb.tile_piece_first[tile], p1 = tb.tile_piece_first[tile + 1];
+    const TilePieces tp = tile_pieces(tb, tile);
+    const int32_t p0 = tp.p0, p1 = tp.p1;
     const int64_t e = base + threadIdx.x * 4;
     f32x4 v = DEFERRED ? ld4_stream(delta_s, e, d, dvec) : ld4(delta_s, e, d, dvec);
-    if (DEFERRED && e < d) v = sign_error_tile(v, e, d, prev_scales, tb, p0, p1);   // past d: cleared below
+    if (DEFERRED && e < d) v = sign_error_tile(v, e, d, prev_scales, tb, p0, p1, tp.seg0);   // past d: cleared below
     const int lane = lane_id();
     const int64_t wave_first = base + wave_id() * 256;
     if (p1 - p0 == 1) {
         // the whole tile lies in one scale group: same batched loads as the chunk route
         // (lane L: sign word L & 7 of worker L >> 3; lane i: scale of worker i)
-        const int32_t sg = tb.piece_seg[p0];
+        const int32_t sg = tp.seg0;
         for (int i0 = 0; i0 < a.n; i0 += 8) {
             const int nb = (a.n - i0 < 8) ? a.n - i0 : 8;
             uint32_t word = 0u;
@@ -430,11 +443,11 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass2(float *buf, int64_t strid
     float *brow = buf + row * stride;
     const float *srow = scales + row * S;
     const bool vec = aligned16(brow);
-    const int32_t p0 = tb.tile_piece_first[tile], p1 = tb.tile_piece_first[tile + 1];
+    const TilePieces tp = tile_pieces(tb, tile);
     const int64_t e = tile * kTile + threadIdx.x * 4;
     if (e >= d) return;
     const f32x4 v = ld4_stream(brow, e, d, vec);
-    st4_stream(brow, e, d, vec, sign_error_tile(v, e, d, srow, tb, p0, p1));
+    st4_stream(brow, e, d, vec, sign_error_tile(v, e, d, srow, tb, tp.p0, tp.p1, tp.seg0));
 }
 
 template <bool MOM, bool DECODE_ONLY>
@@ -444,13 +457,19 @@ __global__ __launch_bounds__(kBlock) void k_sign_update(const uint64_t *__restri
                                                         int64_t d, float gamma, float beta)
 {
     const int64_t tile = blockIdx.x;
-    const int32_t p0 = tb.tile_piece_first[tile], p1 = tb.tile_piece_first[tile + 1];
+    const TilePieces tp = tile_pieces(tb, tile);
     const int64_t e = tile * kTile + threadIdx.x * 4;
     if (e >= d) return;
     const uint32_t nib = load_sign_nibble(words, e);
     float q[4];
+    if (tp.seg0 >= 0) {
+        const float s = scales[tp.seg0];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) q[c] = (e + c < d) ? scales[seg_of(tb, p0, p1, e + c)] : 0.f;
+        for (int c = 0; c < 4; ++c) q[c] = (e + c < d) ? s : 0.f;
+    } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) q[c] = (e + c < d) ? scales[seg_of(tb, tp.p0, tp.p1, e + c)] : 0.f;
+    }
     apply_q4<MOM, DECODE_ONLY>(signed4(q[0], q[1], q[2], q[3], nib), e, d, x, m, gamma, beta);
 }
 
@@ -486,6 +505,7 @@ ds_status_t ds_sign_init(ds_ctx *c)
     c->S = S;
     const int64_t n_tiles = c->n_tiles;
     std::vector<int32_t> tile_piece_first(n_tiles + 1), piece_seg, seg_piece_first(S + 1);
+    std::vector<int2> tile_info(n_tiles);
     std::vector<int64_t> piece_start;
     int64_t s = 0;
     for (int64_t t = 0; t < n_tiles; ++t) {
@@ -505,13 +525,17 @@ ds_status_t ds_sign_init(ds_ctx *c)
     tile_piece_first[n_tiles] = static_cast<int32_t>(n_pieces);
     seg_piece_first[S] = static_cast<int32_t>(n_pieces);
     piece_start.push_back(d);
+    for (int64_t t = 0; t < n_tiles; ++t) {
+        const int32_t p0 = tile_piece_first[t], cnt = tile_piece_first[t + 1] - p0;
+        tile_info[t] = int2{p0, cnt == 1 ? piece_seg[p0] : -cnt};
+    }
 
     // one allocation: int64 arrays first (8-byte aligned), then the int32 arrays
     const size_t b_ps = sizeof(int64_t) * (n_pieces + 1), b_so = sizeof(int64_t) * (S + 1);
     const size_t b_tpf = sizeof(int32_t) * (n_tiles + 1), b_pseg = sizeof(int32_t) * n_pieces;
-    const size_t b_spf = sizeof(int32_t) * (S + 1);
+    const size_t b_spf = sizeof(int32_t) * (S + 1), b_ti = sizeof(int2) * n_tiles;
     char *mem = nullptr;
-    DS_HIP_TRY(hipMalloc(&mem, b_ps + b_so + b_tpf + b_pseg + b_spf));
+    DS_HIP_TRY(hipMalloc(&mem, b_ps + b_so + b_ti + b_tpf + b_pseg + b_spf));
     c->sign_tb_mem = mem;
     char *p = mem;
     auto put = [&](const void *src, size_t bytes) -> const void * {
@@ -522,6 +546,7 @@ ds_status_t ds_sign_init(ds_ctx *c)
     };
     c->sign_tb.piece_start = static_cast<const int64_t *>(put(piece_start.data(), b_ps));
     c->sign_tb.seg_off = static_cast<const int64_t *>(put(seg_off.data(), b_so));
+    c->sign_tb.tile_info = static_cast<const int2 *>(put(tile_info.data(), b_ti));
     c->sign_tb.tile_piece_first = static_cast<const int32_t *>(put(tile_piece_first.data(), b_tpf));
     c->sign_tb.piece_seg = static_cast<const int32_t *>(put(piece_seg.data(), b_pseg));
     c->sign_tb.seg_piece_first = static_cast<const int32_t *>(put(seg_piece_first.data(), b_spf));
