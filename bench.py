@@ -34,7 +34,7 @@ MEASURED_WORKER_TRAFFIC = {
     "c3": 2.6548e9,              # all kernels of the worker call (dense pass 1.6551e9 + 0.8493e9)
     "clip16": 1.6568e9 + 1.2368e9,   # k_clip_worker
     "rsparse60": 1.7116e9 + 1.3278e9 + 0.0299e9 + 0.0068e9,   # k_rs_worker + k_rs_counts + k_rs_scan
-    "c2": 1.1030e9,              # k_sign_pass1_worker + k_sign_reduce, deferred error form (plain form: + pass 2)
+    "c2": 1.1027e9,              # k_sign_pass1_worker + k_sign_reduce, deferred error form (plain form: + pass 2)
 }
 
 
