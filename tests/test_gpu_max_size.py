@@ -1,0 +1,186 @@
+"""GPU: the largest vector the boundary accepts, d = 2^31 - 1 (one worker row, 8.6 GB per fp32
+buffer).  The oracle cannot run whole steps at this size, so each compressor is checked the way
+the full-size tests do it: compressors whose groups are local (sign per chunk, clipping) on
+gathered groups against the oracle -- the first, the last (ragged) ones, those around the
+2^30 and 2^31 - 2^20 element marks and random ones --; the others (top-k, the two randomised
+ones, whose draws depend on the absolute element index) through properties that hold at any
+size, evaluated on the device over the whole vector, plus draws recomputed for sampled elements."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_1905_05957_amd as P
+from parity_util import assert_close_rows, assert_payload_equal
+
+pytestmark = pytest.mark.gpu
+
+D = (1 << 31) - 1
+
+
+def _vectors(dev, seed):
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    g = torch.randn(D, generator=gen, device=dev, dtype=torch.float32).mul_(1e-2).unsqueeze(0)
+    delta = torch.randn(D, generator=gen, device=dev, dtype=torch.float32).mul_(1e-3).unsqueeze(0)
+    return g, delta
+
+
+def _group_sample(group: int, count: int, seed: int) -> np.ndarray:
+    """Indices of sampled groups of `group` elements: ends, the middle marks, random ones."""
+    n_groups = (D + group - 1) // group
+    marks = [0, 1, n_groups - 2, n_groups - 1, (1 << 30) // group - 1, (1 << 30) // group,
+             ((1 << 31) - (1 << 20)) // group]
+    r = np.random.default_rng(seed)
+    return np.unique(np.concatenate([marks, r.integers(0, n_groups, count)])).astype(np.int64)
+
+
+def _elements_of(groups: np.ndarray, group: int) -> np.ndarray:
+    return np.concatenate([np.arange(c * group, min((c + 1) * group, D)) for c in groups])
+
+
+def _plane_bits(words: torch.Tensor, lo: int, hi: int) -> torch.Tensor:
+    """bits lo .. hi (multiples of 64) of a sign-word row as a bool tensor"""
+    w = words[lo // 64:hi // 64]
+    return ((w.unsqueeze(1) >> torch.arange(64, device=w.device)) & 1).bool().reshape(-1)
+
+
+def test_sign_per_chunk_and_clipping_at_2_31(gpu_device):
+    dev = gpu_device
+    for comp in ("sign", "clip"):
+        g, delta = _vectors(dev, 5)
+        x = torch.zeros(D, dtype=torch.float32, device=dev)
+        delta_s = torch.zeros(D, dtype=torch.float32, device=dev)
+        chunk = 2048
+        if comp == "sign":
+            ctx = P.Context("sign", 1, D, scale_mode="chunk", chunk=chunk)
+        else:
+            ctx = P.Context("clip", 1, D, levels=16)
+        try:
+            groups = _group_sample(chunk, 40, 1)
+            e_t = torch.from_numpy(_elements_of(groups, chunk)).to(dev)
+            d_sub = e_t.numel()
+            take = lambda a: a[..., e_t].contiguous()
+            h_g, h_delta = take(g).cpu().numpy(), take(delta).cpu().numpy()
+            if comp == "sign":
+                cfg = O.Config(O.SIGN, n=1, d=d_sub, group_off=O.chunk_offsets(d_sub, chunk))
+                w_t = torch.from_numpy(np.concatenate(
+                    [np.arange(c * chunk // 64, (min((c + 1) * chunk, D) + 63) // 64) for c in groups])).to(dev)
+                c_t = torch.from_numpy(groups).to(dev)
+                sub = lambda p: {"sign_words": p.sign_words[:, w_t].cpu().numpy().view(np.uint64),
+                                 "scales": p.scales[:, c_t].cpu().numpy()}
+            else:
+                cfg = O.Config(O.CLIP, n=1, d=d_sub, clip_bits=16)
+                b_t = (e_t[:, None] * 2 + torch.arange(2, device=dev)[None, :]).reshape(-1)
+                sub = lambda p: {"levels": p.levels[:, b_t].cpu().numpy()}
+            pw, ps = ctx.alloc_payload(1, dev), ctx.alloc_payload(1, dev)
+            ctx.worker_compress(3, g, delta, pw)
+            ref_pw = O.worker_compress(cfg, 3, h_g, h_delta)
+            gpu_pw = sub(pw)
+            assert_payload_equal(gpu_pw, ref_pw, f"{comp} worker payload (sampled groups)")
+            assert_close_rows(take(delta).cpu().numpy(), h_delta, f"{comp} delta")
+            ctx.server_aggregate_compress_update(3, pw, delta_s, ps, x, None, 0.5, 0.0)
+            h_ds = np.zeros(d_sub, np.float32)
+            ref_ps = O.server_aggregate_compress(cfg, 3, gpu_pw, h_ds)
+            gpu_ps = sub(ps)
+            assert_payload_equal(gpu_ps, ref_ps, f"{comp} server payload (sampled groups)")
+            assert_close_rows(take(delta_s).cpu().numpy(), h_ds, f"{comp} delta_s")
+            h_x = np.zeros(d_sub, np.float32)
+            O.apply_update(cfg, gpu_ps, h_x, None, 0.5, 0.0)
+            assert_close_rows(take(x).cpu().numpy(), h_x, f"{comp} x")
+            # the whole vector, on the device: the server's message decodes to what moved x
+            dec = torch.empty(D, dtype=torch.float32, device=dev)
+            ctx.decompress(ps, 0, dec)
+            assert torch.equal(x, dec.mul_(-0.5))
+        finally:
+            ctx.close()
+        del g, delta, x, delta_s, dec, pw, ps
+        torch.cuda.empty_cache()
+
+
+def test_topk_at_2_31(gpu_device):
+    dev = gpu_device
+    k = 1_000_003
+    g, delta = _vectors(dev, 6)
+    v = g + delta
+    ctx = P.Context("topk", 1, D, k=k)
+    try:
+        pw = ctx.alloc_payload(1, dev)
+        ctx.worker_compress(0, g, delta, pw)
+        idx = pw.pairs[0, :, 0].long()
+        val = pw.pairs[0, :, 1].contiguous().view(torch.float32)
+        assert bool((idx[1:] > idx[:-1]).all()) and int(idx[0]) >= 0 and int(idx[-1]) < D
+        assert int(idx[-1]) > (1 << 30)                       # the far half is reached
+        assert torch.equal(val, v[0, idx])
+        kept = torch.zeros(D, dtype=torch.bool, device=dev)
+        kept[idx] = True
+        mag = v[0].abs()
+        floor_kept = float(mag[idx].min())
+        mag.masked_fill_(kept, 0.0)
+        assert floor_kept >= float(mag.max())
+        del mag
+        assert torch.equal(delta[0], torch.where(kept, torch.zeros((), device=dev), v[0]))
+    finally:
+        ctx.close()
+
+
+def test_randomised_compressors_at_2_31(gpu_device):
+    dev = gpu_device
+    seed, t = 99, 7
+    g, delta = _vectors(dev, 7)
+    v = (g + delta)[0]
+    sampled = np.unique(np.concatenate([[0, 1, 2, 3, D - 1, D - 2, D - 3, D - 4, (1 << 30) - 1, 1 << 30],
+                                        np.random.default_rng(2).integers(0, D, 300)])).astype(np.int64)
+    s_t = torch.from_numpy(sampled).to(dev)
+    # ---- sparsification ----
+    p = 0.5                      # dividing by p is exact, whatever way the reference below computes it
+    ctx = P.Context("rsparse", 1, D, seed=seed, keep_prob=p)
+    try:
+        pw = ctx.alloc_payload(1, dev)
+        d0 = delta.clone()
+        ctx.worker_compress(t, g, d0, pw)
+        dec = torch.empty(D, dtype=torch.float32, device=dev)
+        ctx.decompress(pw, 0, dec)
+        kept = dec != 0
+        share = float(kept.float().mean())
+        assert abs(share - p) < 1e-3
+        assert torch.equal(dec, torch.where(kept, v / p, torch.zeros((), device=dev)))
+        assert torch.equal(d0[0], v - dec)
+        u = np.array([O.uniform24(seed, t, 0, int(j)) for j in sampled])
+        nz = (v[s_t] != 0).cpu().numpy()
+        assert np.array_equal(kept[s_t].cpu().numpy()[nz], (u < p)[nz])
+        words = pw.sign_words[0]
+        for lo in (0, (1 << 30) - 64, D // 64 * 64 - 64):
+            assert torch.equal(_plane_bits(words, lo, lo + 64) & (v[lo:lo + 64] != 0), kept[lo:lo + 64])
+        del dec, kept, d0, pw
+    finally:
+        ctx.close()
+    torch.cuda.empty_cache()
+    # ---- quantisation ----
+    bucket, s = 512, 15
+    ctx = P.Context("qsgd", 1, D, bucket=bucket, levels=s, seed=seed)
+    try:
+        pw = ctx.alloc_payload(1, dev)
+        d0 = delta.clone()
+        ctx.worker_compress(t, g, d0, pw)
+        dec = torch.empty(D, dtype=torch.float32, device=dev)
+        ctx.decompress(pw, 0, dec)
+        assert torch.equal(d0[0], v - dec)
+        n_b = (D + bucket - 1) // bucket
+        full = v[:(n_b - 1) * bucket].reshape(n_b - 1, bucket).double()
+        norms = torch.cat([full.pow(2).sum(1), v[(n_b - 1) * bucket:].double().pow(2).sum().reshape(1)]).sqrt()
+        del full
+        got = pw.scales[0].double()
+        assert bool(((got - norms).abs() <= 1e-6 * norms).all())
+        unit = torch.repeat_interleave(pw.scales[0] / s, bucket)[:D]
+        # two neighbouring levels, the sign of v, never further than one level away
+        assert bool(((dec - v).abs() <= unit * (1 + 1e-6)).all())
+        assert bool(((dec == 0) | (torch.sign(dec) == torch.sign(v))).all())
+        # the draws of sampled elements: up iff u < frac
+        r = (v[s_t].abs() * (torch.tensor(float(s), device=dev) / pw.scales[0][s_t // bucket])).cpu().numpy()
+        code = (dec[s_t].abs() / unit[s_t]).round().cpu().numpy()
+        u = np.array([O.uniform24(seed, t, 0, int(j)) for j in sampled], dtype=np.float32)
+        want = np.minimum(np.floor(r) + (u < (r - np.floor(r))), s)
+        assert np.array_equal(code, want)
+    finally:
+        ctx.close()
