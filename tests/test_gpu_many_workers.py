@@ -1,6 +1,7 @@
 """GPU parity at worker counts that are not the configurations' 4, 8, 16: a single worker
 (the average is the message itself), counts that are no multiple of the kernels' worker
-batches (8 per load for sign planes, 64 per wavefront for sparse messages), and more than 64."""
+batches (8 per load for sign planes, 64 per wavefront for sparse messages), more than 64, and a
+thousand."""
 import dataclasses
 
 import pytest
@@ -25,7 +26,7 @@ def _workloads(n):
     ]
 
 
-@pytest.mark.parametrize("n", [1, 5, 13, 70])
+@pytest.mark.parametrize("n", [1, 5, 13, 70, 1000])
 @pytest.mark.parametrize("which", range(7), ids=["sign_whole", "sign_chunk", "topk", "qsgd", "clip", "rsparse", "identity"])
 def test_worker_counts(gpu_device, n, which):
     wl = _workloads(n)[which]
