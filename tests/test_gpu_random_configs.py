@@ -1,12 +1,13 @@
 """GPU parity on seeded random configurations: compressor, worker count, vector length (every
 residue mod 4 and mod 64, below and above one tile), groups, k, buckets, clip width, keep
-probability, gradient type, momentum, step counter and the top-k route are drawn together, so
+probability, gradient type, momentum, step counter, row strides and the top-k route are drawn together, so
 that combinations no hand-written case lists get run.  Every case is two compared steps from
 identical state, to the same bar as the other parity tests."""
 import os
 
 import numpy as np
 import pytest
+import torch
 
 import ds_workloads as W
 import paper_1905_05957_amd as P
@@ -56,19 +57,32 @@ def _draw(case: int):
     elif comp == "rsparse":
         kw["keep_prob"] = float(r.choice([0.6, 0.75, 0.99, 1.0, 0.05]))
     first_step = int(r.choice([0, 1, 12345, (1 << 32) - 1, (1 << 40) + 3]))
-    return W.Workload(f"random_{case}_{comp}", comp, **kw), flags, first_step
+    # row strides of g and of the worker errors: d (contiguous) or d plus a few elements, so
+    # that rows start on 16-, 8-, 4- and (bf16) 2-byte boundaries
+    pads = (int(r.choice([0, 0, 1, 2, 3, 4, 6, 9])), int(r.choice([0, 0, 1, 2, 3, 4, 6, 9])))
+    return W.Workload(f"random_{case}_{comp}", comp, **kw), flags, first_step, pads
+
+
+def _with_row_stride(t: torch.Tensor, pad: int) -> torch.Tensor:
+    if pad == 0:
+        return t
+    buf = torch.zeros((t.shape[0], t.shape[1] + pad), dtype=t.dtype, device=t.device)
+    buf[:, :t.shape[1]] = t
+    return buf[:, :t.shape[1]]
 
 
 @pytest.mark.parametrize("case", range(CASES))
 def test_random_configuration(gpu_device, case):
-    wl, flags, t0 = _draw(case)
+    wl, flags, t0, (pad_g, pad_delta) = _draw(case)
     parity_util.CONTEXT_FLAGS = flags
     try:
         pair = Pair(wl, gpu_device)
     finally:
         parity_util.CONTEXT_FLAGS = 0
     try:
+        pair.delta = _with_row_stride(pair.delta, pad_delta)
         for t in range(2):
-            pair.compared_step(t0 + t, wl.gradients(t, gpu_device), tag=f" flags={flags}")
+            pair.compared_step(t0 + t, _with_row_stride(wl.gradients(t, gpu_device), pad_g),
+                               tag=f" flags={flags} pads={pad_g},{pad_delta}")
     finally:
         pair.close()
