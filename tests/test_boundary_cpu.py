@@ -80,3 +80,17 @@ def test_bench_refuses_more_than_one_gpu():
     import subprocess, sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "ONE GPU" in r.stderr
+
+
+def test_header_is_plain_c99_and_cxx():
+    """include/ds.h is the boundary: it must compile on its own as C99 and as C++ (no torch or
+    HIP types in the signatures)."""
+    import shutil
+    import subprocess
+    header = os.path.join(ROOT, "include", "ds.h")
+    if shutil.which("gcc") is None:
+        pytest.skip("no host compiler")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", header], check=True)
+    subprocess.run(["g++", "-std=c++17", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", header], check=True)
+    text = open(header).read()
+    assert "torch" not in text and "hipStream_t hip" not in text and "#include <hip" not in text
