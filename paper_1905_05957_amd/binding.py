@@ -103,6 +103,21 @@ def _check(code: int, what: str):
         raise DsError(code, what)
 
 
+def _need(t: torch.Tensor, what: str, dtype, shape) -> torch.Tensor:
+    """A tensor is handed over as a bare pointer, so what the library assumes about it is checked
+    here: device memory of the right element type, rows of the right length laid out densely
+    (any row stride).  A wrong buffer would otherwise be a memory fault on the device."""
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise ValueError(f"{what}: a CUDA/HIP device tensor is required")
+    if t.dtype != dtype:
+        raise ValueError(f"{what}: dtype {t.dtype}, expected {dtype}")
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{what}: shape {tuple(t.shape)}, expected {tuple(shape)}")
+    if t.stride(-1) != 1 or (t.dim() == 2 and t.shape[0] > 1 and t.stride(0) < t.shape[1]):
+        raise ValueError(f"{what}: rows must be dense (element stride 1, row stride >= row length)")
+    return t
+
+
 def _stream_ptr(stream) -> Optional[int]:
     if stream is None:
         stream = torch.cuda.current_stream()
@@ -131,6 +146,14 @@ class Payload:
         elif comp == COMP_RSPARSE:
             self.sign_words = torch.zeros((rows, W), dtype=torch.int64, device=device)
             self.dense = torch.zeros((rows, d), dtype=torch.float32, device=device)
+
+    def check(self, ctx: "Context", rows: int, what: str) -> "Payload":
+        if self.comp != ctx.comp or self.d != ctx.d or self.k != ctx.k or self.rows != rows:
+            raise ValueError(f"{what}: a payload of {rows} message(s) allocated by this context is required")
+        for t in self.tensors().values():
+            if not t.is_cuda or not t.is_contiguous():
+                raise ValueError(f"{what}: payload buffers must be contiguous device tensors")
+        return self
 
     def c_struct(self) -> ds_payload_t:
         def p(t):
@@ -227,14 +250,20 @@ class Context:
 
     def worker_compress(self, step: int, g: torch.Tensor, delta: torch.Tensor, out: Payload,
                         stream=None):
-        s = out.c_struct()
-        _check(load_library().ds_worker_compress(self._h, step, g.data_ptr(), g.stride(0),
-                                                 delta.data_ptr(), delta.stride(0), C.byref(s),
+        _need(g, "g", torch.bfloat16 if self.grad_dtype == BF16 else torch.float32, (self.n, self.d))
+        _need(delta, "delta", torch.float32, (self.n, self.d))
+        s = out.check(self, self.n, "out").c_struct()
+        # a single row has no meaningful row stride (torch may report anything for it)
+        gs = g.stride(0) if self.n > 1 else max(g.stride(0), self.d)
+        ds_ = delta.stride(0) if self.n > 1 else max(delta.stride(0), self.d)
+        _check(load_library().ds_worker_compress(self._h, step, g.data_ptr(), gs,
+                                                 delta.data_ptr(), ds_, C.byref(s),
                                                  _stream_ptr(stream)), "ds_worker_compress")
 
     def server_aggregate_compress(self, step: int, inp: Payload, delta_s: torch.Tensor,
                                   out: Payload, stream=None):
-        a, b = inp.c_struct(), out.c_struct()
+        _need(delta_s, "delta_s", torch.float32, (self.d,))
+        a, b = inp.check(self, self.n, "in").c_struct(), out.check(self, 1, "out").c_struct()
         _check(load_library().ds_server_aggregate_compress(self._h, step, C.byref(a),
                                                            delta_s.data_ptr(), C.byref(b),
                                                            _stream_ptr(stream)),
@@ -243,7 +272,11 @@ class Context:
     def server_aggregate_compress_update(self, step: int, inp: Payload, delta_s: torch.Tensor, out: Payload,
                                          x: torch.Tensor, m: Optional[torch.Tensor], gamma: float,
                                          beta: float = 0.0, stream=None):
-        a, b = inp.c_struct(), out.c_struct()
+        _need(delta_s, "delta_s", torch.float32, (self.d,))
+        _need(x, "x", torch.float32, (self.d,))
+        if m is not None:
+            _need(m, "m", torch.float32, (self.d,))
+        a, b = inp.check(self, self.n, "in").c_struct(), out.check(self, 1, "out").c_struct()
         _check(load_library().ds_server_aggregate_compress_update(
             self._h, step, C.byref(a), delta_s.data_ptr(), C.byref(b), x.data_ptr(),
             None if m is None else m.data_ptr(), gamma, beta, _stream_ptr(stream)),
@@ -251,21 +284,29 @@ class Context:
 
     def apply_update(self, srv: Payload, x: torch.Tensor, m: Optional[torch.Tensor], gamma: float,
                      beta: float = 0.0, stream=None):
-        s = srv.c_struct()
+        _need(x, "x", torch.float32, (self.d,))
+        if m is not None:
+            _need(m, "m", torch.float32, (self.d,))
+        s = srv.check(self, 1, "srv").c_struct()
         _check(load_library().ds_apply_update(self._h, C.byref(s), x.data_ptr(),
                                               None if m is None else m.data_ptr(), gamma, beta,
                                               _stream_ptr(stream)), "ds_apply_update")
 
     def materialize_error(self, delta: Optional[torch.Tensor], delta_s: Optional[torch.Tensor],
                           stream=None):
+        if delta is not None:
+            _need(delta, "delta", torch.float32, (self.n, self.d))
+        if delta_s is not None:
+            _need(delta_s, "delta_s", torch.float32, (self.d,))
         _check(load_library().ds_materialize_error(
             self._h, None if delta is None else delta.data_ptr(),
-            0 if delta is None else delta.stride(0),
+            0 if delta is None else (delta.stride(0) if self.n > 1 else max(delta.stride(0), self.d)),
             None if delta_s is None else delta_s.data_ptr(), _stream_ptr(stream)),
             "ds_materialize_error")
 
     def decompress(self, p: Payload, row: int, out: torch.Tensor, stream=None):
-        s = p.c_struct()
+        _need(out, "dense_out", torch.float32, (self.d,))
+        s = p.check(self, p.rows, "p").c_struct()
         _check(load_library().ds_decompress(self._h, C.byref(s), p.rows, row, out.data_ptr(),
                                             _stream_ptr(stream)), "ds_decompress")
 
