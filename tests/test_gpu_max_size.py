@@ -184,3 +184,32 @@ def test_randomised_compressors_at_2_31(gpu_device):
         assert np.array_equal(code, want)
     finally:
         ctx.close()
+
+
+def test_sign_whole_vector_scale_at_2_31(gpu_device):
+    """One scale for all 2^31 - 1 elements: the route whose groups span workgroups (a million
+    per-tile partial sums reduced in a fixed order)."""
+    dev = gpu_device
+    g, delta = _vectors(dev, 8)
+    v = (g + delta)[0]
+    ctx = P.Context("sign", 1, D, scale_mode="whole")
+    try:
+        pw = ctx.alloc_payload(1, dev)
+        ctx.worker_compress(0, g, delta, pw)
+        want = float(v.abs().double().sum() / D)
+        got = float(pw.scales[0, 0])
+        assert abs(got - want) <= 1e-6 * want
+        q = torch.where(v < 0, -pw.scales[0, 0], pw.scales[0, 0])
+        assert torch.equal(delta[0], v - q)
+        words = pw.sign_words[0]
+        for lo in (0, (1 << 30) - 64, (1 << 30), D // 64 * 64 - 64):
+            assert torch.equal(_plane_bits(words, lo, lo + 64), v[lo:lo + 64] < 0)
+        tail = D // 64 * 64
+        last = int(words[-1].item()) & 0xFFFFFFFFFFFFFFFF
+        assert [(last >> b) & 1 for b in range(D - tail)] == [int(x) for x in (v[tail:] < 0).tolist()]
+        assert last >> (D - tail) == 0                          # pad bits are zero
+        dec = torch.empty(D, dtype=torch.float32, device=dev)
+        ctx.decompress(pw, 0, dec)
+        assert torch.equal(dec, q)
+    finally:
+        ctx.close()
