@@ -47,3 +47,48 @@ def test_wrong_buffers_are_refused_before_any_launch(gpu_device):
     finally:
         ctx.close()
         other.close()
+
+
+def test_library_error_codes_on_a_live_context(gpu_device):
+    """The C-ABI's own argument checks (include/ds.h: errors are return codes, detected before
+    anything is launched, every buffer untouched), called through ctypes without the binding's."""
+    import ctypes as C
+    from paper_1905_05957_amd import binding as B
+    dev, n, d = gpu_device, 2, 4100
+    L = P.load_library()
+    ctx = P.Context("sign", n, d, scale_mode="chunk", chunk=1024)
+    try:
+        g = torch.randn(n, d + 4, device=dev)
+        delta = torch.zeros(n, d + 4, device=dev)
+        delta_s = torch.zeros(d + 4, device=dev)
+        x = torch.zeros(d + 4, device=dev)
+        pw, ps = ctx.alloc_payload(n, dev), ctx.alloc_payload(1, dev)
+        sw, ss = pw.c_struct(), ps.c_struct()
+        null_words = B.ds_payload_t(None, pw.scales.data_ptr(), None, None, None)
+        st = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+        h = ctx._h
+        NULL, SHAPE, ALIGN = 1, 2, 4
+        assert L.ds_worker_compress(h, 0, None, d + 4, delta.data_ptr(), d + 4, C.byref(sw), st) == NULL
+        assert L.ds_worker_compress(h, 0, g.data_ptr(), d + 4, None, d + 4, C.byref(sw), st) == NULL
+        assert L.ds_worker_compress(h, 0, g.data_ptr(), d + 4, delta.data_ptr(), d + 4, None, st) == NULL
+        assert L.ds_worker_compress(h, 0, g.data_ptr(), d + 4, delta.data_ptr(), d + 4, C.byref(null_words), st) == NULL
+        assert L.ds_worker_compress(h, 0, g.data_ptr(), d - 1, delta.data_ptr(), d + 4, C.byref(sw), st) == SHAPE
+        assert L.ds_worker_compress(h, 0, g.data_ptr(), d + 4, delta.data_ptr(), d - 1, C.byref(sw), st) == SHAPE
+        assert L.ds_worker_compress(h, 0, g.data_ptr() + 4, d + 4, delta.data_ptr(), d + 4, C.byref(sw), st) == ALIGN
+        assert L.ds_worker_compress(h, 0, g.data_ptr(), d + 4, delta.data_ptr() + 8, d + 4, C.byref(sw), st) == ALIGN
+        assert L.ds_server_aggregate_compress(h, 0, C.byref(sw), None, C.byref(ss), st) == NULL
+        assert L.ds_server_aggregate_compress(h, 0, C.byref(sw), delta_s.data_ptr() + 4, C.byref(ss), st) == ALIGN
+        assert L.ds_apply_update(h, C.byref(ss), None, None, 0.1, 0.0, st) == NULL
+        assert L.ds_apply_update(h, C.byref(ss), x.data_ptr() + 4, None, 0.1, 0.0, st) == ALIGN
+        assert L.ds_decompress(h, C.byref(sw), n, n, x.data_ptr(), st) == SHAPE
+        assert L.ds_decompress(h, C.byref(sw), n, -1, x.data_ptr(), st) == SHAPE
+        assert L.ds_materialize_error(h, delta.data_ptr(), d - 1, None, st) == SHAPE
+        torch.cuda.synchronize()
+        assert not delta.any() and not delta_s.any() and not x.any()
+        assert not pw.sign_words.any() and not pw.scales.any()
+        # rows that start 4 elements into a padded buffer row are fine (stride d + 4)
+        assert L.ds_worker_compress(h, 0, g.data_ptr(), d + 4, delta.data_ptr(), d + 4, C.byref(sw), st) == 0
+        torch.cuda.synchronize()
+        assert delta[:, :d].any() and not delta[:, d:].any()
+    finally:
+        ctx.close()
