@@ -233,6 +233,25 @@ ds_status_t ds_decompress(ds_ctx_t *ctx, const ds_payload_t *p, int32_t rows, in
 ds_status_t ds_materialize_error(ds_ctx_t *ctx, float *delta, int64_t delta_row_stride,
                                  float *delta_s, void *hip_stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): ds_worker_compress for DS_COMP_SIGN with
+ * DS_SCALE_WHOLE (one scale per row), without a context.  It calls no allocating routine.  The
+ * per-tile fp64 partial sums that a context would hold live in a fixed array inside the
+ * library, 512 KiB on every device the library runs on, held until the process ends; its
+ * device address is looked up on the first call on a device (make that call outside a
+ * capture).  Limit: n * ceil(d / 2048) <= 65536, beyond it DS_ERR_SHAPE.
+ *   flags       0 or DS_FLAG_SIGN_RMS (anything else: DS_ERR_CONFIG)
+ *   g, delta    as for ds_worker_compress
+ *   sign_words  [n, ceil(d/64)]   scales [n]     (the SIGN message, layout above)
+ * Results equal those of ds_worker_compress on a context with the same configuration.  Every
+ * call on one device uses the same array (nothing in it needs clearing: each call writes
+ * what it reads), so calls that overlap on one device, on any streams, race; calls on one
+ * stream are ordered. */
+ds_status_t ds_worker_compress_sign_noalloc(int32_t n, int64_t d, int32_t grad_dtype, int32_t flags,
+                                            const void *g, int64_t g_row_stride, float *delta,
+                                            int64_t delta_row_stride, uint64_t *sign_words,
+                                            float *scales, void *hip_stream);
+
 /* Static string for a status code. */
 const char *ds_status_string(ds_status_t s);
 

@@ -49,7 +49,8 @@ class ds_payload_t(C.Structure):
 
 EXPORTS = ["ds_create", "ds_destroy", "ds_payload_sizes", "ds_worker_compress",
            "ds_server_aggregate_compress", "ds_apply_update", "ds_decompress", "ds_materialize_error",
-           "ds_server_aggregate_compress_update", "ds_status_string", "ds_version"]
+           "ds_server_aggregate_compress_update", "ds_worker_compress_sign_noalloc",
+           "ds_status_string", "ds_version"]
 
 _lib = None
 
@@ -81,8 +82,10 @@ def load_library():
     L.ds_materialize_error.argtypes = [vp, vp, i64, vp, vp]
     L.ds_server_aggregate_compress_update.argtypes = [vp, u64, C.POINTER(ds_payload_t), vp, C.POINTER(ds_payload_t),
                                                       vp, vp, f32, f32, vp]
-    for name in EXPORTS[:9]:
-        getattr(L, name).restype = C.c_int
+    L.ds_worker_compress_sign_noalloc.argtypes = [i32, i64, i32, i32, vp, i64, vp, i64, vp, vp, vp]
+    for name in EXPORTS:
+        if name not in ("ds_status_string", "ds_version"):
+            getattr(L, name).restype = C.c_int
     L.ds_status_string.argtypes = [C.c_int]
     L.ds_status_string.restype = C.c_char_p
     L.ds_version.argtypes = []
@@ -346,3 +349,24 @@ def ds_apply_update(ctx: Context, srv, x, m, gamma, beta=0.0, stream=None):
 
 def ds_decompress(ctx: Context, p, row, out, stream=None):
     ctx.decompress(p, row, out, stream)
+
+
+def ds_worker_compress_sign_noalloc(g: torch.Tensor, delta: torch.Tensor, sign_words: torch.Tensor,
+                                    scales: torch.Tensor, flags: int = 0, stream=None) -> None:
+    """The context-free, allocation-free worker block (1-bit, one scale per row)."""
+    if g.dim() != 2:
+        raise ValueError("g: [n, d] required")
+    n, d = g.shape
+    if g.dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError(f"g: dtype {g.dtype}")
+    _need(g, "g", g.dtype, (n, d))
+    _need(delta, "delta", torch.float32, (n, d))
+    _need(sign_words, "sign_words", torch.int64, (n, (d + 63) // 64))
+    _need(scales, "scales", torch.float32, (n, 1))
+    if not (sign_words.is_contiguous() and scales.is_contiguous()):
+        raise ValueError("message buffers must be contiguous")
+    gs = g.stride(0) if n > 1 else max(g.stride(0), d)
+    ds_ = delta.stride(0) if n > 1 else max(delta.stride(0), d)
+    _check(load_library().ds_worker_compress_sign_noalloc(
+        n, d, BF16 if g.dtype == torch.bfloat16 else F32, int(flags), g.data_ptr(), gs, delta.data_ptr(), ds_,
+        sign_words.data_ptr(), scales.data_ptr(), _stream_ptr(stream)), "ds_worker_compress_sign_noalloc")

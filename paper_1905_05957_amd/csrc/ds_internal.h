@@ -22,6 +22,9 @@ struct ds_sign_tables {
     int32_t n_pieces;
     int32_t n_seg;
     bool rms;                         // group scale = root mean square instead of mean |v|
+    // whole_d > 0: one group = the whole vector of whole_d elements, piece p = tile p; none of
+    // the tables above is read (they may be null)
+    int64_t whole_d;
 };
 
 struct ds_topk_scratch;  // defined in topk.hip

@@ -18,8 +18,8 @@
 #include "ds_device.h"
 #include "ds_internal.h"
 
+#include <mutex>
 #include <type_traits>
-
 #include <vector>
 
 using namespace ds;
@@ -251,6 +251,7 @@ struct TilePieces {
 
 __device__ __forceinline__ TilePieces tile_pieces(const ds_sign_tables &tb, int64_t tile)
 {
+    if (tb.whole_d > 0) return TilePieces{static_cast<int32_t>(tile), static_cast<int32_t>(tile) + 1, 0};
     const int2 ti = tb.tile_info[tile];
     return (ti.y >= 0) ? TilePieces{ti.x, ti.x + 1, ti.y} : TilePieces{ti.x, ti.x - ti.y, -1};
 }
@@ -413,7 +414,8 @@ __global__ __launch_bounds__(kBlock) void k_sign_reduce(const double *__restrict
     const int32_t s = blockIdx.x;
     const int row = blockIdx.y;
     const double *prow = partials + static_cast<int64_t>(row) * tb.n_pieces;
-    const int32_t p0 = tb.seg_piece_first[s], p1 = tb.seg_piece_first[s + 1];
+    const bool whole = tb.whole_d > 0;
+    const int32_t p0 = whole ? 0 : tb.seg_piece_first[s], p1 = whole ? tb.n_pieces : tb.seg_piece_first[s + 1];
     double acc = 0.0;
     for (int32_t p = p0 + threadIdx.x; p < p1; p += kBlock) acc += prow[p];
     lds[threadIdx.x] = acc;
@@ -423,7 +425,7 @@ __global__ __launch_bounds__(kBlock) void k_sign_reduce(const double *__restrict
         __syncthreads();
     }
     if (threadIdx.x == 0) {
-        const double len = static_cast<double>(tb.seg_off[s + 1] - tb.seg_off[s]);
+        const double len = static_cast<double>(whole ? tb.whole_d : tb.seg_off[s + 1] - tb.seg_off[s]);
         const float sc = group_scale(lds[0], len, tb.rms);
         scales[row * S + s] = sc;
         if (keep) keep[row * S + s] = sc;
@@ -553,6 +555,7 @@ ds_status_t ds_sign_init(ds_ctx *c)
     c->sign_tb.n_pieces = static_cast<int32_t>(n_pieces);
     c->sign_tb.n_seg = static_cast<int32_t>(S);
     c->sign_tb.rms = (cfg.flags & DS_FLAG_SIGN_RMS) != 0;
+    c->sign_tb.whole_d = 0;
     if (hipGetLastError() != hipSuccess) return DS_ERR_DEVICE;
     DS_HIP_TRY(hipMalloc(&c->sign_partials, sizeof(double) * n_pieces * static_cast<size_t>(cfg.n)));
     if (cfg.flags & DS_FLAG_DEFERRED_ERROR) {
@@ -695,4 +698,65 @@ ds_status_t ds_sign_update(ds_ctx *c, const ds_payload_t *srv, float *x, float *
 ds_status_t ds_sign_decode(ds_ctx *c, const ds_payload_t *p, int32_t row, float *out, hipStream_t st)
 {
     return sign_update_impl<true>(c, p->sign_words + row * c->W, p->scales + row * c->S, out, nullptr, 0.f, 0.f, st);
+}
+
+// ---------------------------------------------------------------------------------------
+// the worker block without a context and without any allocation
+// ---------------------------------------------------------------------------------------
+// The general route needs the fp64 partial sums of every tile between its first pass and the
+// reduce.  ds_create allocates them; callers that cannot allocate get them from this fixed
+// array instead (one copy per device, held until the process ends).
+#define DS_NOALLOC_MAX_PARTIALS 65536
+static __device__ __align__(256) double scratch[DS_NOALLOC_MAX_PARTIALS];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+double *g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each device, looked up once
+}  // namespace
+
+extern "C" ds_status_t ds_worker_compress_sign_noalloc(int32_t n, int64_t d, int32_t grad_dtype, int32_t flags,
+                                                       const void *g, int64_t g_row_stride, float *delta,
+                                                       int64_t delta_row_stride, uint64_t *sign_words, float *scales,
+                                                       void *hip_stream)
+{
+    if (!g || !delta || !sign_words || !scales) return DS_ERR_NULL;
+    if (n < 1 || n > 65535 || d < 1 || d > 0x7FFFFFFFLL) return DS_ERR_SHAPE;
+    if (g_row_stride < d || delta_row_stride < d) return DS_ERR_SHAPE;
+    if (grad_dtype != DS_F32 && grad_dtype != DS_BF16) return DS_ERR_CONFIG;
+    if (flags & ~static_cast<int32_t>(DS_FLAG_SIGN_RMS)) return DS_ERR_CONFIG;
+    const int64_t n_tiles = (d + kTile - 1) / kTile;
+    if (n_tiles * n > DS_NOALLOC_MAX_PARTIALS) return DS_ERR_SHAPE;
+    auto misaligned = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; };
+    if (misaligned(g) || misaligned(delta) || misaligned(sign_words) || misaligned(scales)) return DS_ERR_ALIGN;
+    int dev = -1;
+    DS_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return DS_ERR_DEVICE;
+    double *partials = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            // every device holds its own copy of the array at its own address
+            void *p = nullptr;
+            DS_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+            g_scratch_ptr[dev] = static_cast<double *>(p);
+        }
+        partials = g_scratch_ptr[dev];
+    }
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    ds_sign_tables tb{};
+    tb.n_pieces = static_cast<int32_t>(n_tiles);
+    tb.n_seg = 1;
+    tb.rms = (flags & DS_FLAG_SIGN_RMS) != 0;
+    tb.whole_d = d;
+    const int64_t W = (d + 63) / 64;
+    const dim3 grid(static_cast<unsigned>(n_tiles), static_cast<unsigned>(n));
+    with_flags(grad_dtype == DS_BF16, tb.rms, false, [&](auto bf, auto rm, auto) {
+        constexpr bool BF = decltype(bf)::value, RM = decltype(rm)::value;
+        WorkerSrc<BF> src{g, g_row_stride, delta, delta_row_stride};
+        k_sign_pass1_worker<BF, false, RM><<<grid, kBlock, 0, st>>>(src, delta, d, sign_words, W, tb, partials, nullptr, 1);
+    });
+    k_sign_reduce<<<dim3(1, static_cast<unsigned>(n)), kBlock, 0, st>>>(partials, tb, scales, 1, nullptr);
+    k_sign_pass2<<<grid, kBlock, 0, st>>>(delta, delta_row_stride, d, scales, 1, tb);
+    return ds_launch_status();
 }
