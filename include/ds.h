@@ -83,14 +83,14 @@ typedef enum {
 } ds_scale_mode_t;
 
 /* ds_config_t::flags.
- * DS_FLAG_TOPK_MULTI_LAUNCH: TOPK refines its threshold in a chain of small launches instead
- * of one launch whose workgroups wait for each other.  The results are the same.  The
- * single launch needs its whole grid resident on the device at once: contexts that may run
- * TOPK calls concurrently on different streams of one device should set this flag (a single
- * launch that finds the device shared gives up after a bounded wait, and its context then
- * returns DS_ERR_DEVICE from every later call).  The environment variable
- * DS_TOPK_RESIDENT_LIMIT=<workgroups>, read by ds_create, caps the size of the single launch
- * (default: what the device holds at once; fewer workgroups than rows selects the chain).
+ * DS_FLAG_TOPK_MULTI_LAUNCH: TOPK refines its threshold in a chain of small launches, none of
+ * which waits for anything, instead of one launch whose workgroups wait for each other row by
+ * row.  The results are the same.  In the single launch (the default, about 45 us faster per
+ * worker call at 8 x 25.6 M elements) a workgroup waits only for workgroups of its own row,
+ * which precede or surround it in dispatch order, and every wait is bounded
+ * (ds_config_t::topk_spin_limit polls).  A launch that gives up a wait raises a flag in
+ * host-visible memory; see ds_status for what follows.  ds_config_t::topk_max_workgroups caps
+ * the size of the single launch (fewer workgroups than rows selects the chain).
  *
  * DS_FLAG_DEFERRED_ERROR: SIGN with scale groups that span workgroups (whole vector,
  * arbitrary segments, chunks that are no multiple of 128 or exceed 2048) needs the group
@@ -129,6 +129,12 @@ typedef struct {
                                  two 64 .. 2048; other multiples give DS_ERR_UNSUPPORTED) */
     int32_t flags;            /* ds_flags_t bits, 0 for the defaults */
     uint64_t seed;            /* QSGD, RSPARSE: Philox key */
+    int32_t topk_max_workgroups; /* TOPK single launch: most workgroups it may use; 0 = what the
+                                 device holds at once */
+    int32_t topk_spin_limit;  /* TOPK single launch: polls a workgroup spends on one wait before it
+                                 gives up; 0 = the default (about 4 million, seconds); -1 = none
+                                 (every wait that is not satisfied at once fails: a host-forced
+                                 failure for tests of the error path, every kernel still exits) */
 } ds_config_t;
 
 typedef struct ds_ctx ds_ctx_t;
@@ -251,6 +257,20 @@ ds_status_t ds_worker_compress_sign_noalloc(int32_t n, int64_t d, int32_t grad_d
                                             const void *g, int64_t g_row_stride, float *delta,
                                             int64_t delta_row_stride, uint64_t *sign_words,
                                             float *scales, void *hip_stream);
+
+/* Asynchronous failures.  The step calls only enqueue work; the one failure a kernel of this
+ * library can meet after its call has returned DS_OK is a TOPK single launch that gives up a
+ * bounded wait (see DS_FLAG_TOPK_MULTI_LAUNCH).  ds_status returns DS_ERR_DEVICE from then on
+ * (it reads a word in host memory and neither launches nor synchronises: synchronise the
+ * stream first to learn about the calls enqueued so far), DS_OK otherwise and for every other
+ * compressor.  The first ds_worker_compress / ds_server_aggregate_compress(_update) call after
+ * the failure does none of its own work: it enqueues the reset of the context's scratch state on
+ * its stream, switches the context to the chain of launches for good, lowers the flag and
+ * returns DS_ERR_DEVICE.  Every later call works.  What the failed call left in its error
+ * buffer and message is undefined (rows that finished are complete): restore them from the
+ * caller's last good copy.  A captured graph that contains a failed single launch must be
+ * captured again after that call. */
+ds_status_t ds_status(const ds_ctx_t *ctx);
 
 /* Static string for a status code. */
 const char *ds_status_string(ds_status_t s);

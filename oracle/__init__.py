@@ -75,8 +75,6 @@ def lib():
         L.dso_philox4x32_10.restype = None
         L.dso_uniform24.argtypes = [u64, u64, u32, i64]
         L.dso_uniform24.restype = f32
-        L.dso_sign_encode.argtypes = [vp, i64, vp, i32, vp, vp]
-        L.dso_sign_encode.restype = None
         L.dso_sign_decode.argtypes = [vp, vp, i64, vp, i32, vp]
         L.dso_sign_decode.restype = None
         L.dso_topk_encode.argtypes = [vp, i64, i64, vp, vp]

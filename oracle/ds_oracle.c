@@ -156,20 +156,6 @@ void dso_sign_encode_kind(const float *v, int64_t d, const int64_t *group_off, i
     }
 }
 
-void dso_sign_encode(const float *v, int64_t d, const int64_t *group_off, int32_t n_groups,
-                     uint64_t *words, float *scales)
-{
-    int64_t n_words = (d + 63) / 64;
-    for (int64_t w = 0; w < n_words; ++w) words[w] = 0;
-    for (int64_t j = 0; j < d; ++j)
-        if (v[j] < 0.0f) words[j >> 6] |= (uint64_t)1 << (j & 63);
-    for (int32_t s = 0; s < n_groups; ++s) {
-        double sum = 0.0;
-        for (int64_t j = group_off[s]; j < group_off[s + 1]; ++j) sum += (double)fabsf(v[j]);
-        scales[s] = (float)(sum / (double)(group_off[s + 1] - group_off[s]));
-    }
-}
-
 void dso_sign_decode(const uint64_t *words, const float *scales, int64_t d,
                      const int64_t *group_off, int32_t n_groups, float *q)
 {

@@ -39,7 +39,7 @@ class ds_config_t(C.Structure):
                 ("scale_mode", C.c_int32), ("chunk", C.c_int64),
                 ("seg_offsets", C.POINTER(C.c_int64)), ("n_seg", C.c_int32), ("levels", C.c_int32),
                 ("k", C.c_int64), ("bucket", C.c_int32), ("flags", C.c_int32),
-                ("seed", C.c_uint64)]
+                ("seed", C.c_uint64), ("topk_max_workgroups", C.c_int32), ("topk_spin_limit", C.c_int32)]
 
 
 class ds_payload_t(C.Structure):
@@ -49,7 +49,7 @@ class ds_payload_t(C.Structure):
 
 EXPORTS = ["ds_create", "ds_destroy", "ds_payload_sizes", "ds_worker_compress",
            "ds_server_aggregate_compress", "ds_apply_update", "ds_decompress", "ds_materialize_error",
-           "ds_server_aggregate_compress_update", "ds_worker_compress_sign_noalloc",
+           "ds_server_aggregate_compress_update", "ds_worker_compress_sign_noalloc", "ds_status",
            "ds_status_string", "ds_version"]
 
 _lib = None
@@ -82,6 +82,7 @@ def load_library():
     L.ds_materialize_error.argtypes = [vp, vp, i64, vp, vp]
     L.ds_server_aggregate_compress_update.argtypes = [vp, u64, C.POINTER(ds_payload_t), vp, C.POINTER(ds_payload_t),
                                                       vp, vp, f32, f32, vp]
+    L.ds_status.argtypes = [vp]
     L.ds_worker_compress_sign_noalloc.argtypes = [i32, i64, i32, i32, vp, i64, vp, i64, vp, vp, vp]
     for name in EXPORTS:
         if name not in ("ds_status_string", "ds_version"):
@@ -207,7 +208,8 @@ class Context:
 
     def __init__(self, comp, n: int, d: int, grad_dtype: str = "f32", scale_mode="whole",
                  chunk: int = 0, seg_offsets=None, k: int = 0, bucket: int = 512, levels: int = 15,
-                 seed: int = 0, flags: int = 0, keep_prob: Optional[float] = None):
+                 seed: int = 0, flags: int = 0, keep_prob: Optional[float] = None,
+                 topk_max_workgroups: int = 0, topk_spin_limit: int = 0):
         L = load_library()
         self.comp = _COMP[comp] if isinstance(comp, str) else int(comp)
         if keep_prob is not None:       # RSPARSE: the probability as a 24-bit threshold
@@ -225,6 +227,7 @@ class Context:
             cfg.n_seg = len(self._seg) - 1
         cfg.k, cfg.bucket, cfg.levels, cfg.seed = self.k, int(bucket), int(levels), int(seed)
         cfg.flags = int(flags)
+        cfg.topk_max_workgroups, cfg.topk_spin_limit = int(topk_max_workgroups), int(topk_spin_limit)
         self._h = C.c_void_p()
         _check(L.ds_create(C.byref(cfg), C.byref(self._h)), "ds_create")
         sizes = self.payload_sizes(1)
@@ -242,6 +245,10 @@ class Context:
             self.close()
         except Exception:
             pass
+
+    def status(self) -> int:
+        """ds_status: 0, or the code of an asynchronous failure that no call has reported yet."""
+        return int(load_library().ds_status(self._h))
 
     def payload_sizes(self, rows: int):
         out = (C.c_size_t * 5)()

@@ -102,6 +102,7 @@ ds_status_t ds_create(const ds_config_t *cfg, ds_ctx_t **out)
         break;
     case DS_COMP_TOPK:
         if (cfg->k < 1 || cfg->k > cfg->d) return DS_ERR_SHAPE;
+        if (cfg->topk_max_workgroups < 0 || cfg->topk_spin_limit < -1) return DS_ERR_CONFIG;
         break;
     case DS_COMP_QSGD:
         if (cfg->bucket < 64 || cfg->bucket % 64 != 0) return DS_ERR_CONFIG;
@@ -157,6 +158,12 @@ ds_status_t ds_destroy(ds_ctx_t *c)
     ds_rsparse_fini(c);
     delete c;
     return DS_OK;
+}
+
+ds_status_t ds_status(const ds_ctx_t *c)
+{
+    if (!c) return DS_ERR_NULL;
+    return (c->cfg.comp == DS_COMP_TOPK) ? ds_topk_status(c) : DS_OK;
 }
 
 ds_status_t ds_payload_sizes(const ds_ctx_t *c, int32_t rows, size_t bytes_out[5])

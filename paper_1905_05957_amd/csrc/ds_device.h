@@ -253,7 +253,7 @@ __device__ __forceinline__ f32x4 fma4(float a, f32x4 b, f32x4 c)
     return f32x4{__fmaf_rn(a, b.x, c.x), __fmaf_rn(a, b.y, c.y), __fmaf_rn(a, b.z, c.z), __fmaf_rn(a, b.w, c.w)};
 }
 
-// Tail shared by every update kernel (Algorithm 1, "Update the local model"), q = decoded
+// Tail shared by every update kernel (Algorithm 1, last worker block), q = decoded
 // server message for elements e..e+3:
 //   DECODE_ONLY: x <- q ;  plain: x <- fma(-gamma, q, x) ;
 //   MOM: m <- fma(beta, m, q), x <- fma(-gamma, m, x).

@@ -121,6 +121,7 @@ ds_status_t ds_rsparse_decode(ds_ctx *c, const ds_payload_t *p, int32_t row, flo
 // topk.hip
 ds_status_t ds_topk_init(ds_ctx *c);
 void ds_topk_fini(ds_ctx *c);
+ds_status_t ds_topk_status(const ds_ctx *c);
 ds_status_t ds_topk_worker(ds_ctx *c, const void *g, int64_t gs, float *delta, int64_t dstr,
                            const ds_payload_t *out, hipStream_t st);
 ds_status_t ds_topk_server(ds_ctx *c, const ds_payload_t *in, float *delta_s,

@@ -30,7 +30,7 @@ namespace {
 // sources of the vector v that is being compressed
 // ---------------------------------------------------------------------------------------
 
-// Worker: v = g + delta  (Algorithm 1, "Compute the error-compensated stochastic gradient").
+// Worker: v = g + delta  (Algorithm 1, worker block, first step; Section 3.1).
 template <bool BF16>
 struct WorkerSrc {
     const void *g;
@@ -46,8 +46,8 @@ struct WorkerSrc {
 };
 
 // Server with one scale per chunk: v = delta_s + (1/n) sum_i Q[v_i], taken as the chain
-// acc = fma(q_i, 1/n, acc) over workers in ascending order (Algorithm 1, "Average all
-// gradients received from workers").
+// acc = fma(q_i, 1/n, acc) over workers in ascending order (Algorithm 1, parameter-server
+// block, first step).
 struct ServerArgs {
     const uint64_t *words_in;  // [n, W]
     const float *scales_in;    // [n, S]

@@ -35,7 +35,6 @@
 #include "ds_device.h"
 #include "ds_internal.h"
 
-#include <cstdlib>
 #include <new>
 #include <type_traits>
 
@@ -936,10 +935,14 @@ __global__ __launch_bounds__(kBlock) void k_topk_emit(const u32x2 *slots, const 
 //                 that word, which lies in another cache line than the counter so that the
 //                 polls do not queue up in front of the remaining arrivals.  Rows are 256
 //                 bytes apart for the same reason.
-// Every poll loop is bounded: if a round does not complete within kSpinLimit polls (the grid
-// was not resident as a whole after all, e.g. two such launches from different streams took
-// half the device each), the workgroup raises the context's abort word (host memory) and
-// the kernel drains; the context then reports DS_ERR_DEVICE on every later call.
+// A workgroup waits only for workgroups of its own row.  Workgroups are handed to the compute
+// units in the order of their linear index (row-major here), so when other kernels share the
+// device the rows become resident one after the other: at most the one row at the front of the
+// dispatch is incomplete and waiting, the others run, finish and make room.  That order is
+// what the hardware does, not a documented guarantee, so every poll loop is bounded as well:
+// if a round does not complete within the spin limit, the workgroup raises the context's abort
+// word (host memory) and the kernel drains.  ds_status reports it; the next step call resets
+// the context's scratch state, switches it to the chain of launches and reports it once.
 //
 // Radix levels here are relative to lo_key: level A = 1024 bins of 4096 keys from lo_key
 // upwards (the last bin also takes everything beyond), level B = the 12 low bits inside bin
@@ -1275,6 +1278,18 @@ __global__ __launch_bounds__(kBlock) void k_topk_dense_apply(const u32x2 *pairs,
     apply_q4<MOM, DECODE_ONLY>(q, e, d, x, m, gamma, beta);
 }
 
+// Zeroes up to five arrays of 32-bit words (the context's scratch state after a failed launch).
+__global__ __launch_bounds__(kBlock) void k_topk_clear(uint32_t *a, int64_t na, uint32_t *b, int64_t nb, uint32_t *c,
+                                                       int64_t nc, uint32_t *d, int64_t nd, uint32_t *e, int64_t ne)
+{
+    const int64_t first = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x, step = static_cast<int64_t>(gridDim.x) * kBlock;
+    for (int64_t i = first; i < na; i += step) a[i] = 0u;
+    for (int64_t i = first; i < nb; i += step) b[i] = 0u;
+    for (int64_t i = first; i < nc; i += step) c[i] = 0u;
+    for (int64_t i = first; i < nd; i += step) d[i] = 0u;
+    for (int64_t i = first; i < ne; i += step) e[i] = 0u;
+}
+
 unsigned persistent_blocks(int64_t n_tiles, int rows)
 {
     int64_t per_row = (1024 + rows - 1) / rows;   // about 4 workgroups per compute unit in total
@@ -1289,7 +1304,20 @@ ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t 
                        uint32_t *prev_T, float *x = nullptr, float gamma = 0.f)
 {
     ds_topk_scratch *t = c->topk;
-    if (__atomic_load_n(t->abort_host, __ATOMIC_RELAXED)) return DS_ERR_DEVICE;   // an earlier launch gave up waiting
+    if (__atomic_load_n(t->abort_host, __ATOMIC_RELAXED)) {
+        // An earlier single launch gave up a wait and left its synchronisation words and
+        // histograms dirty.  This call clears them on its stream (kernels: the call may be
+        // under capture), moves the context to the chain of launches, which waits for nothing,
+        // and reports the failure once.
+        const int64_t n_rows = t->rows;
+        k_topk_clear<<<64, kBlock, 0, st>>>(t->hist, n_rows * kHistRow, t->fhist, n_rows * kFRow,
+                                            reinterpret_cast<uint32_t *>(t->sync), n_rows * (kSyncStride / 4), t->done,
+                                            n_rows * kStages, t->prev_T, n_rows + 1);
+        t->capacity = 0;
+        __atomic_store_n(t->abort_host, 0u, __ATOMIC_RELAXED);
+        (void)ds_launch_status();
+        return DS_ERR_DEVICE;
+    }
     const int64_t d = c->cfg.d, k = c->cfg.k, n_sub = t->n_sub, n_reg = t->n_reg, reg_pad = t->reg_pad, n_groups = t->n_groups;
     const int64_t ns = (n_sub < kSampleSubs) ? n_sub : kSampleSubs;
     // sample rank: 1.15 x the expected number of top-k members in the sample, plus slack
@@ -1386,21 +1414,22 @@ ds_status_t ds_topk_init(ds_ctx *c)
         DS_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_topk_finish, kBlock, 0));
         DS_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device));
         t->capacity = static_cast<int64_t>(per_cu) * cus;
-        // DS_TOPK_RESIDENT_LIMIT caps the workgroups the single launch uses, for devices that
-        // are shared with other work
-        // DS_TOPK_SPIN_LIMIT: polls per wait (tests set 0 to see the give-up path: every wait
-        // that is not satisfied at once then fails, and every workgroup still exits)
+        // ds_config_t::topk_max_workgroups caps the workgroups the single launch uses;
+        // ds_config_t::topk_spin_limit sets the polls per wait (-1: none, the host-forced
+        // failure for tests of the error path: every wait that is not satisfied at once fails
+        // and every workgroup still exits)
         t->spin_limit = kSpinLimit;
-        if (const char *sp = getenv("DS_TOPK_SPIN_LIMIT")) {
-            const long v = strtol(sp, nullptr, 10);
-            if (v >= 0 && v < static_cast<long>(kSpinLimit)) t->spin_limit = static_cast<uint32_t>(v);
-        }
-        if (const char *lim = getenv("DS_TOPK_RESIDENT_LIMIT")) {
-            const long v = strtol(lim, nullptr, 10);
-            if (v >= 0 && v < t->capacity) t->capacity = v;
-        }
+        if (c->cfg.topk_spin_limit > 0) t->spin_limit = static_cast<uint32_t>(c->cfg.topk_spin_limit);
+        if (c->cfg.topk_spin_limit < 0) t->spin_limit = 0u;
+        if (c->cfg.topk_max_workgroups > 0 && c->cfg.topk_max_workgroups < t->capacity) t->capacity = c->cfg.topk_max_workgroups;
     }
     return DS_OK;
+}
+
+ds_status_t ds_topk_status(const ds_ctx *c)
+{
+    const ds_topk_scratch *t = c->topk;
+    return (t && __atomic_load_n(t->abort_host, __ATOMIC_RELAXED)) ? DS_ERR_DEVICE : DS_OK;
 }
 
 void ds_topk_fini(ds_ctx *c)

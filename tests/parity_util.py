@@ -36,6 +36,8 @@ def oracle_config(wl) -> O.Config:
 # ds_config_t::flags of the contexts that gpu_context builds; tests that cover both top-k
 # refinement routes set it through the `topk_route` fixture of their module.
 CONTEXT_FLAGS = 0
+# further keyword arguments of P.Context for those contexts (top-k launch limits)
+CONTEXT_KW: dict = {}
 
 
 def gpu_context(wl) -> P.Context:
@@ -43,7 +45,7 @@ def gpu_context(wl) -> P.Context:
                      chunk=wl.chunk,
                      seg_offsets=wl.seg_offsets if wl.scale_mode == "segments" else None,
                      k=wl.k, bucket=wl.bucket, levels=wl.clip_bits if wl.comp == "clip" else wl.levels,
-                     seed=wl.seed, keep_prob=wl.keep_prob if wl.comp == "rsparse" else None, flags=CONTEXT_FLAGS | (P.FLAG_SIGN_RMS if wl.sign_rms else 0))
+                     seed=wl.seed, keep_prob=wl.keep_prob if wl.comp == "rsparse" else None, flags=CONTEXT_FLAGS | (P.FLAG_SIGN_RMS if wl.sign_rms else 0), **CONTEXT_KW)
 
 
 def host_grad(g: torch.Tensor) -> np.ndarray:

@@ -1,6 +1,9 @@
 """GPU: contexts keep no state outside themselves, so two of them can run their steps on two
-streams at the same time; each must produce what it produces alone.  (Top-k contexts that
-overlap on one device are created with the chain of launches, as include/ds.h says.)"""
+streams at the same time; each must produce what it produces alone.  Top-k runs on both of its
+refinement routes: in the single launch a workgroup waits only for workgroups of its own row,
+which the dispatch order makes resident together, so two such launches that share the device
+take turns row by row (and every wait is bounded, so a violated assumption would show as an
+error, never as a hang)."""
 import pytest
 import torch
 
@@ -18,6 +21,8 @@ def _cases():
         ("sign_segments_deferred", W.c2(d=600_002, n=3, n_seg=12, lo=64), P.FLAG_DEFERRED_ERROR),
         ("qsgd", W.c4(d=2048 * 200 + 40, n=5), 0),
         ("topk_chain", W.c3(d=700_007, n=4), P.FLAG_TOPK_MULTI_LAUNCH),
+        ("topk_single_launch", W.c3(d=700_007, n=4), 0),
+        ("topk_single_launch_64_rows", W.c3(d=2_000_003, n=64), 0),    # 512 waiting workgroups per launch
         ("rsparse", W.rsparse60(d=500_001, n=3), 0),
     ]
 
@@ -45,6 +50,8 @@ def test_two_contexts_on_two_streams(gpu_device, name, wl, flags):
         for pair in (alone, a, b):
             pair.ctx.materialize_error(pair.delta, pair.delta_s)
         torch.cuda.synchronize()
+        for pair in (alone, a, b):
+            assert pair.ctx.status() == 0
         for pair in (a, b):
             assert torch.equal(pair.x, alone.x) and torch.equal(pair.delta, alone.delta)
             assert torch.equal(pair.delta_s, alone.delta_s)

@@ -43,31 +43,53 @@ def test_topk_shapes(gpu_device, d, k):
     _run(_wl(d, k=k), gpu_device)
 
 
-def test_topk_few_resident_workgroups(gpu_device, monkeypatch):
+def test_topk_few_resident_workgroups(gpu_device):
     # 2 workgroups per row for 100 groups of 32768 elements: every wavefront of the single
     # launch walks several groups and the offsets run over several rounds
-    monkeypatch.setenv("DS_TOPK_RESIDENT_LIMIT", "6")
-    _run(_wl(100 * 32768 + 999, n=3), gpu_device, steps=3)
+    parity_util.CONTEXT_KW = {"topk_max_workgroups": 6}
+    try:
+        _run(_wl(100 * 32768 + 999, n=3), gpu_device, steps=3)
+    finally:
+        parity_util.CONTEXT_KW = {}
 
 
-def test_topk_single_launch_gives_up_cleanly(gpu_device, monkeypatch, topk_route):
-    """Failure handling of the single-launch refinement, forced from the host: with a poll
-    budget of zero every wait that is not satisfied at once fails, so workgroups give up;
-    every kernel must still finish, and the context must report the failure from then on."""
+def test_topk_single_launch_gives_up_cleanly_and_the_context_recovers(gpu_device, topk_route):
+    """Failure handling of the single-launch refinement, forced from the host: without any
+    polls every wait that is not satisfied at once fails, so workgroups give up; every kernel
+    must still finish.  ds_status shows the failure without another call, the next step call
+    reports it once and resets the context, and from then on the context works again (on the
+    chain of launches) and matches the oracle."""
     if topk_route != "single_launch":
         pytest.skip("the chain of launches has no waits")
-    monkeypatch.setenv("DS_TOPK_SPIN_LIMIT", "0")
+    parity_util.CONTEXT_KW = {"topk_spin_limit": -1}
     wl = _wl(1 << 20, n=4)
-    pair = Pair(wl, gpu_device)
+    try:
+        pair = Pair(wl, gpu_device)
+    finally:
+        parity_util.CONTEXT_KW = {}
     try:
         g = wl.gradients(0, gpu_device)
+        assert pair.ctx.status() == 0
+        failed_after = None
+        for t in range(4):                            # a launch may get through: all arrivals can be in before the first poll
+            pair.ctx.worker_compress(t, g, pair.delta, pair.pw)
+            torch.cuda.synchronize()                  # must return: all workgroups exited
+            if pair.ctx.status() != 0:
+                failed_after = t
+                break
+        assert failed_after is not None, "no wait failed although no polls are allowed"
+        assert pair.ctx.status() == 6                 # DS_ERR_DEVICE, and it stays until a call reports it
         with pytest.raises(P.DsError) as err:
-            for t in range(4):
-                pair.gpu_step(t, g)
-                torch.cuda.synchronize()          # must return: all workgroups exited
-        assert err.value.code == 6                # DS_ERR_DEVICE
-        with pytest.raises(P.DsError):
             pair.ctx.worker_compress(9, g, pair.delta, pair.pw)
+        assert err.value.code == 6
+        torch.cuda.synchronize()
+        assert pair.ctx.status() == 0
+        # the failed call's outputs are undefined: start again from defined state
+        pair.delta.copy_(wl.initial_delta(gpu_device))
+        pair.delta_s.zero_()
+        for t in range(10, 13):
+            pair.compared_step(t, wl.gradients(t % 2, gpu_device))
+        assert pair.ctx.status() == 0
     finally:
         pair.close()
 
