@@ -56,6 +56,7 @@ constexpr int kFineBins = 16;                   // 12-bit bins covered by the fi
 constexpr int kHistRow = 4 * kH1 + kH2 + kH3;
 constexpr int kSampleSubs = 512;           // subtiles sampled per row
 constexpr uint32_t kNone = 0xFFFFFFFFu;
+constexpr int kSyncStride = 256;           // bytes of synchronisation memory per row of k_topk_finish: the counter in the first 128-byte line, the published words in the second
 constexpr int kStages = 4;                 // arrival counters per row: sample, candidate histogram, fallback histogram, count
 enum { kStageSample = 0, kStageHist = 1, kStageFallback = 2, kStageCount = 3 };
 
@@ -387,8 +388,13 @@ __device__ __forceinline__ int64_t sample_subtile(int64_t j, int64_t ns, int64_t
 // 12-bit histogram of v over the sampled subtiles.
 template <class Src>
 __global__ __launch_bounds__(kBlock) void k_topk_sample(Src src, int64_t d, int64_t n_sub, int64_t ns, uint32_t *hist,
-                                                        Sel *sel, uint32_t *done, uint32_t rank, const uint32_t *prev_T)
+                                                        Sel *sel, uint32_t *done, uint32_t rank, const uint32_t *prev_T,
+                                                        uint32_t *sync_words)
 {
+    // the single-launch refinement of this call finds its row's synchronisation words at zero
+    // (its own previous launch is complete by stream order and did not clear them itself)
+    if (blockIdx.x == 0 && threadIdx.x < kSyncStride / 4)
+        __hip_atomic_store(&sync_words[blockIdx.y * (kSyncStride / 4) + threadIdx.x], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __shared__ uint32_t h[kH1];        // 12-bit bins
     __shared__ uint32_t hf[kH1];       // fine window: kFineBins 12-bit bins x 256 sub-bins (key bits 18..11)
     __shared__ uint32_t part[kBlock], out[2], flag;
@@ -507,17 +513,18 @@ __global__ __launch_bounds__(kBlock) void k_topk_pass1(Src src, float *buf, int6
 // tags are hashed (element & 255): two pending entries that share a tag but not an element
 // merely take turns.
 constexpr int kSpan = 4 * kSub;              // elements per wavefront
+constexpr int kTags = kSub;                  // claim tags per wavefront (128 would let a fourth workgroup share a compute unit; measured: no gain, the pass is bound by instruction issue)
 
 __global__ __launch_bounds__(kBlock) void k_topk_pass1_server(ServerV src, float *buf, int64_t d, const Sel *sel,
                                                               u32x2 *slots, uint32_t *reg_cnt, int64_t n_reg)
 {
     __shared__ float strips[kWaves][kSpan];
-    __shared__ uint32_t tags[kWaves][kSub];
+    __shared__ uint32_t tags[kWaves][kTags];
     __shared__ uint32_t wtot[kWaves];
     const int lane = lane_id(), wv = wave_id();
     float *strip = strips[wv];
     uint32_t *tag = tags[wv];
-    for (int i = lane; i < kSub; i += 64) tag[i] = kNone;
+    for (int i = lane; i < kTags; i += 64) tag[i] = kNone;
     const int64_t span_base = (static_cast<int64_t>(blockIdx.x) * kWaves + wv) * kSpan;
     const uint32_t lo_key = sel[0].lo_key;
     const bool vec = aligned16(buf);
@@ -563,12 +570,12 @@ __global__ __launch_bounds__(kBlock) void k_topk_pass1_server(ServerV src, float
                 const uint32_t rel = pr.x - base;
                 bool pending = valid && rel < static_cast<uint32_t>(kSpan);
                 while (__ballot(pending)) {
-                    if (pending) atomicMin(&tag[rel & (kSub - 1)], static_cast<uint32_t>(lane));
+                    if (pending) atomicMin(&tag[rel & (kTags - 1)], static_cast<uint32_t>(lane));
                     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-                    const bool win = pending && tag[rel & (kSub - 1)] == static_cast<uint32_t>(lane);
+                    const bool win = pending && tag[rel & (kTags - 1)] == static_cast<uint32_t>(lane);
                     if (win) {
                         strip[rel] = __fmaf_rn(__uint_as_float(pr.y), src.inv_n, strip[rel]);
-                        tag[rel & (kSub - 1)] = kNone;
+                        tag[rel & (kTags - 1)] = kNone;
                     }
                     pending = pending && !win;
                     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
@@ -877,31 +884,48 @@ __global__ __launch_bounds__(kBlock) void k_topk_count(const u32x2 *slots, const
 // groups, out = first output slot of the group.  x != nullptr: the model update of Algorithm 1
 // for this message, x <- fma(-gamma, val, x) at the kept indices, in the same pass.
 // Called by whole wavefronts.
+// One batch of up to 64 candidates in index order (lane = position), see emit_group: the kept
+// ones go to their output slots, the others get v back in the error buffer.  Returns whether
+// this lane's candidate is kept.
+__device__ __forceinline__ bool emit_batch(u32x2 pr, bool valid, uint32_t T, uint32_t k3, uint32_t &eq_seen, uint32_t &out,
+                                           u32x2 *prow, float *brow, int64_t k)
+{
+    const uint32_t key = pr.y & 0x7FFFFFFFu;
+    const bool is_eq = valid && key == T;
+    const uint64_t eq_mask = __ballot(is_eq);
+    const bool keep = valid && (key > T || (is_eq && eq_seen + lanes_below(eq_mask) < k3));
+    const uint64_t keep_mask = __ballot(keep);
+    if (keep) {
+        const uint32_t slot = out + lanes_below(keep_mask);
+        if (slot < k) prow[slot] = pr;
+    } else if (valid) {
+        __builtin_nontemporal_store(__uint_as_float(pr.y), brow + pr.x);   // not kept: delta = v
+    }
+    out += __popcll(keep_mask);
+    eq_seen += __popcll(eq_mask);
+    return keep;
+}
+
 __device__ __forceinline__ void emit_group(const GroupWalk &w, const u32x2 *__restrict__ srow, int64_t g, uint32_t T,
                                            uint32_t k3, uint32_t eq_seen, uint32_t out, u32x2 *prow, float *brow, int64_t k,
                                            float *x = nullptr, float gamma = 0.f)
 {
     for (uint32_t i0 = 0; i0 < w.total; i0 += 64 * kPrefetch) {
         const Batch bt = group_fetch_batches(w, srow, g, i0);
+        bool kept[kPrefetch];
 #pragma unroll
         for (int j = 0; j < kPrefetch; ++j) {
-            if (i0 + j * 64 >= w.total) break;                 // uniform over the wavefront
-            const bool valid = i0 + j * 64 + lane_id() < w.total;
-            const u32x2 pr = bt.pr[j];
-            const uint32_t key = pr.y & 0x7FFFFFFFu;
-            const bool is_eq = valid && key == T;
-            const uint64_t eq_mask = __ballot(is_eq);
-            const bool keep = valid && (key > T || (is_eq && eq_seen + lanes_below(eq_mask) < k3));
-            const uint64_t keep_mask = __ballot(keep);
-            if (keep) {
-                const uint32_t slot = out + lanes_below(keep_mask);
-                if (slot < k) prow[slot] = pr;
-                if (x) x[pr.x] = __fmaf_rn(-gamma, __uint_as_float(pr.y), x[pr.x]);
-            } else if (valid) {
-                __builtin_nontemporal_store(__uint_as_float(pr.y), brow + pr.x);   // not kept: delta = v
-            }
-            out += __popcll(keep_mask);
-            eq_seen += __popcll(eq_mask);
+            kept[j] = false;
+            if (i0 + j * 64 >= w.total) continue;              // uniform over the wavefront
+            kept[j] = emit_batch(bt.pr[j], i0 + j * 64 + lane_id() < w.total, T, k3, eq_seen, out, prow, brow, k);
+        }
+        if (x) {
+            float xv[kPrefetch];
+#pragma unroll
+            for (int j = 0; j < kPrefetch; ++j) xv[j] = kept[j] ? x[bt.pr[j].x] : 0.f;
+#pragma unroll
+            for (int j = 0; j < kPrefetch; ++j)
+                if (kept[j]) x[bt.pr[j].x] = __fmaf_rn(-gamma, __uint_as_float(bt.pr[j].y), xv[j]);
         }
     }
 }
@@ -944,19 +968,20 @@ __global__ __launch_bounds__(kBlock) void k_topk_emit(const u32x2 *slots, const 
 // word (host memory) and the kernel drains.  ds_status reports it; the next step call resets
 // the context's scratch state, switches it to the chain of launches and reports it once.
 //
-// Radix levels here are relative to lo_key: level A = 1024 bins of 4096 keys from lo_key
-// upwards (the last bin also takes everything beyond), level B = the 12 low bits inside bin
+// Radix levels here are relative to lo_key: level A = 2048 bins of 2048 keys from lo_key
+// upwards (the last bin also takes everything beyond), level B = the 11 low bits inside bin
 // A.  The sample's lower bound is known to 20 key bits and the k-th key lies a few per cent
-// above it (100 to 400 bins on the 25.6 M-element top-1 % workload; with 256 bins one server
-// call in ten fell outside), so two levels resolve all 31 bits.  A row whose k-th key is not
-// below the last bin (or that has fewer than k candidates) takes the exact two-look route inside the same
-// launch: put v back, dense 12-bit histogram, pick b1, compact again with lo_key = b1 << 19
-// (the k-th key is then less than 2^19 above lo_key), level A again.
-constexpr int kHA = 1024, kHB = 4096, kShiftA = 12;
+// above it (200 to 800 such bins on the 25.6 M-element top-1 % workload; a window of a quarter
+// of this width missed one server call in ten), so two levels resolve all 31 bits.  A row whose
+// k-th key is not below the last bin (or that has fewer than k candidates) takes the exact
+// two-look route inside the same launch: put v back, dense 12-bit histogram, pick b1, compact
+// again with lo_key = b1 << 19 (the k-th key is then less than 2^19 above lo_key), level A
+// again.  Both histograms take 8 KiB of LDS, which leaves room for the wavefronts' candidate
+// caches at four workgroups per compute unit.
+constexpr int kHA = 2048, kHB = 2048, kShiftA = 11;
 constexpr int kFOffA = 0, kFOffA2 = kHA, kFOffB = 2 * kHA, kFOffD = 2 * kHA + kHB;
 constexpr int kFRow = 2 * kHA + kHB + kH1;     // words per row of the fused route's histograms
 enum { kResA = 0, kResD = 1, kResA2 = 2, kResB = 3, kResCompact = 4, kResCount = 5, kResSlots = 6 };
-constexpr int kSyncStride = 256;   // bytes of synchronisation memory per row: the counter in the first 128-byte line, the published words in the second
 constexpr uint32_t kSpinLimit = 1u << 22;     // polls per wait before a workgroup gives up (seconds)
 constexpr uint64_t kResValid = 1ull << 63;
 
@@ -1042,21 +1067,54 @@ __device__ __forceinline__ void row_pick_publish(RowSync &rs, int slot, const ui
     if (threadIdx.x == 0) row_publish(rs, slot, out[0], out[1]);
 }
 
+// The candidates of the first group a wavefront owns, kept in LDS across the phases of
+// k_topk_finish: the wavefront walks the same groups in every phase, and with one group per
+// wavefront (the usual case: the grid is sized for it) only the first phase then reads the
+// candidate lists from memory.  A group spans 32768 elements, so an index is kept as 16 bits
+// relative to the group's first element.  Holds up to 64 * kPrefetch candidates; a larger group
+// is simply not cached.
+constexpr uint32_t kCacheCap = 64 * kPrefetch;
+struct WaveCache {
+    uint32_t *bits;      // LDS, kCacheCap words: value bits (key = bits & 0x7FFFFFFF)
+    uint16_t *rel;       // LDS, kCacheCap halfwords: index - 32768 * group
+    uint32_t total;      // candidates of the cached group
+    bool valid;
+};
+
 // f(key) for every candidate of the groups this wavefront owns (the same groups in every
 // phase: group = workgroup * 8 + wavefront, then strided by the row's wavefront count).
-template <class F>
+// FILL: the walk fills the cache from its first group; otherwise a valid cache replaces the
+// fetch of that group.
+template <bool FILL, class F>
 __device__ __forceinline__ void for_each_candidate(const u32x2 *__restrict__ srow, const uint32_t *__restrict__ cnt_row,
-                                                   int64_t n_reg, int64_t n_groups, uint32_t G, F f)
+                                                   int64_t n_reg, int64_t n_groups, uint32_t G, WaveCache &wc, F f)
 {
-    for (int64_t g = static_cast<int64_t>(blockIdx.x) * kWaves + wave_id(); g < n_groups;
-         g += static_cast<int64_t>(G) * kWaves) {
+    const int64_t g0 = static_cast<int64_t>(blockIdx.x) * kWaves + wave_id();
+    if (FILL) wc.valid = false;
+    for (int64_t g = g0; g < n_groups; g += static_cast<int64_t>(G) * kWaves) {
+        if (!FILL && g == g0 && wc.valid) {
+#pragma unroll
+            for (int j = 0; j < kPrefetch; ++j) {
+                const uint32_t i = j * 64 + lane_id();
+                if (i < wc.total) f(wc.bits[i] & 0x7FFFFFFFu);
+            }
+            continue;
+        }
         const GroupWalk w = group_begin(cnt_row, g, n_reg);
+        const bool fill = FILL && g == g0 && w.total <= kCacheCap;
         for (uint32_t i0 = 0; i0 < w.total; i0 += 64 * kPrefetch) {
             const Batch bt = group_fetch_batches(w, srow, g, i0);
 #pragma unroll
             for (int j = 0; j < kPrefetch; ++j)
-                if (i0 + j * 64 + lane_id() < w.total) f(bt.pr[j].y & 0x7FFFFFFFu);
+                if (i0 + j * 64 + lane_id() < w.total) {
+                    if (fill) {
+                        wc.bits[j * 64 + lane_id()] = bt.pr[j].y;
+                        wc.rel[j * 64 + lane_id()] = static_cast<uint16_t>(bt.pr[j].x & (kGroupRegs * kReg - 1));
+                    }
+                    f(bt.pr[j].y & 0x7FFFFFFFu);
+                }
         }
+        if (fill) { wc.total = w.total; wc.valid = true; }
     }
 }
 
@@ -1089,9 +1147,12 @@ struct FinishArgs {
 __global__ __launch_bounds__(kBlock, 8) void k_topk_finish(FinishArgs a)
 {
     __shared__ uint32_t h[kHB];
+    __shared__ uint32_t cache_bits[kWaves][kCacheCap];
+    __shared__ uint16_t cache_rel[kWaves][kCacheCap];
     __shared__ uint32_t part[kWaves], out[2], sh[3], wtot[kWaves], red[2 * kWaves];
     const int row = blockIdx.y;
     const uint32_t G = gridDim.x;
+    WaveCache wc{cache_bits[wave_id()], cache_rel[wave_id()], 0u, false};
     RowSync rs{reinterpret_cast<uint32_t *>(a.sync + row * kSyncStride), reinterpret_cast<uint64_t *>(a.sync + row * kSyncStride + 128),
                a.abort_flag, sh, G, 0u, a.spin_limit};
     uint32_t *fh = a.fhist + static_cast<int64_t>(row) * kFRow;
@@ -1110,7 +1171,7 @@ __global__ __launch_bounds__(kBlock, 8) void k_topk_finish(FinishArgs a)
     auto level_a = [&](uint32_t *gh, int slot) -> bool {
         for (int i = threadIdx.x; i < kHA; i += kBlock) h[i] = 0u;
         __syncthreads();
-        for_each_candidate(srow, cnt_row, a.n_reg, a.n_groups, G, [&](uint32_t key) {
+        for_each_candidate<true>(srow, cnt_row, a.n_reg, a.n_groups, G, wc, [&](uint32_t key) {
             const uint32_t rel = (key - lo_key) >> kShiftA;
             atomicAdd(&h[rel < kHA ? rel : kHA - 1], 1u);
         });
@@ -1124,6 +1185,12 @@ __global__ __launch_bounds__(kBlock, 8) void k_topk_finish(FinishArgs a)
     if (bA == kNone || bA == kHA - 1) {
         // exact two-look route.  A workgroup owns the same tiles in all of its steps, so what
         // it reads back is what it wrote itself.
+        // (the dense histogram has 4096 bins: it takes the memory of the wavefronts' caches, whose
+        // candidates are about to be replaced)
+        wc.valid = false;
+        uint32_t *h = &cache_bits[0][0];
+        static_assert(kWaves * kCacheCap >= kH1, "the caches must hold the dense histogram");
+        __syncthreads();
         for (int i = threadIdx.x; i < kH1; i += kBlock) h[i] = 0u;
         __syncthreads();
         const bool vec = aligned16(brow);
@@ -1161,10 +1228,10 @@ __global__ __launch_bounds__(kBlock, 8) void k_topk_finish(FinishArgs a)
         if (bA == kNone || bA == kHA - 1) { raise_abort(a.abort_flag); return; }   // cannot happen
     }
 
-    // level B: the 12 low bits inside bin A
+    // level B: the low bits inside bin A
     for (int i = threadIdx.x; i < kHB; i += kBlock) h[i] = 0u;
     __syncthreads();
-    for_each_candidate(srow, cnt_row, a.n_reg, a.n_groups, G, [&](uint32_t key) {
+    for_each_candidate<false>(srow, cnt_row, a.n_reg, a.n_groups, G, wc, [&](uint32_t key) {
         const uint32_t rel = key - lo_key;
         if ((rel >> kShiftA) == bA) atomicAdd(&h[rel & (kHB - 1)], 1u);
     });
@@ -1178,35 +1245,52 @@ __global__ __launch_bounds__(kBlock, 8) void k_topk_finish(FinishArgs a)
 
     // per group: candidates above T, candidates tying with T
     uint32_t *gtr = a.grp_gt + row * a.n_groups, *eqr = a.grp_eq + row * a.n_groups;
-    for (int64_t g = static_cast<int64_t>(blockIdx.x) * kWaves + wave_id(); g < a.n_groups;
-         g += static_cast<int64_t>(G) * kWaves) {
-        const GroupWalk w = group_begin(cnt_row, g, a.n_reg);
-        uint32_t gt = 0, eq = 0;
-        for (uint32_t i0 = 0; i0 < w.total; i0 += 64 * kPrefetch) {
-            const Batch bt = group_fetch_batches(w, srow, g, i0);
+    {
+        const int64_t g0 = static_cast<int64_t>(blockIdx.x) * kWaves + wave_id();
+        for (int64_t g = g0; g < a.n_groups; g += static_cast<int64_t>(G) * kWaves) {
+            uint32_t gt = 0, eq = 0;
+            if (g == g0 && wc.valid) {
 #pragma unroll
-            for (int j = 0; j < kPrefetch; ++j) {
-                const bool valid = i0 + j * 64 + lane_id() < w.total;
-                const uint32_t key = bt.pr[j].y & 0x7FFFFFFFu;
-                gt += valid && key > T;
-                eq += valid && key == T;
+                for (int j = 0; j < kPrefetch; ++j) {
+                    const uint32_t i = j * 64 + lane_id();
+                    const uint32_t key = (i < wc.total) ? (wc.bits[i] & 0x7FFFFFFFu) : 0u;
+                    gt += i < wc.total && key > T;
+                    eq += i < wc.total && key == T;
+                }
+            } else {
+                const GroupWalk w = group_begin(cnt_row, g, a.n_reg);
+                for (uint32_t i0 = 0; i0 < w.total; i0 += 64 * kPrefetch) {
+                    const Batch bt = group_fetch_batches(w, srow, g, i0);
+#pragma unroll
+                    for (int j = 0; j < kPrefetch; ++j) {
+                        const bool valid = i0 + j * 64 + lane_id() < w.total;
+                        const uint32_t key = bt.pr[j].y & 0x7FFFFFFFu;
+                        gt += valid && key > T;
+                        eq += valid && key == T;
+                    }
+                }
             }
-        }
-        gt = wave_sum_u32(gt);
-        eq = wave_sum_u32(eq);
-        if (lane_id() == 0) {
-            dev_store(&gtr[g], gt);
-            dev_store(&eqr[g], eq);
+            gt = wave_sum_u32(gt);
+            eq = wave_sum_u32(eq);
+            if (lane_id() == 0) {
+                dev_store(&gtr[g], gt);
+                dev_store(&eqr[g], eq);
+            }
         }
     }
     if (!row_barrier(rs, kResCount)) return;
 
     // emit.  Ties are taken in index order, so the ties kept before a group number
-    // min(k3, ties before it): two running sums over the groups give every offset.
+    // min(k3, ties before it): two running sums over the groups give every offset.  All the
+    // loads of a round are issued before the first is used.
     uint32_t sum_gt = 0, sum_eq = 0;
     int64_t upto = 0;
     u32x2 *prow = a.pairs + static_cast<int64_t>(row) * a.k;
+    const int64_t g0 = static_cast<int64_t>(blockIdx.x) * kWaves + wave_id();
     for (int64_t gb = static_cast<int64_t>(blockIdx.x) * kWaves; gb < a.n_groups; gb += static_cast<int64_t>(G) * kWaves) {
+        const int64_t g = gb + wave_id();
+        uint32_t wg = 0, we = 0;                               // groups gb .. g-1 of this workgroup's round
+        if (g < a.n_groups && lane_id() < wave_id()) { wg = dev_load(&gtr[gb + lane_id()]); we = dev_load(&eqr[gb + lane_id()]); }
         uint32_t pg = 0, pe = 0;
         for (int64_t t = upto + threadIdx.x; t < gb; t += kBlock) {
             pg += dev_load(&gtr[t]);
@@ -1220,23 +1304,44 @@ __global__ __launch_bounds__(kBlock, 8) void k_topk_finish(FinishArgs a)
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) { sum_gt += red[w]; sum_eq += red[kWaves + w]; }
         upto = gb;
-        const int64_t g = gb + wave_id();
         if (g < a.n_groups) {
-            uint32_t wg = 0, we = 0;
-            if (lane_id() < wave_id()) { wg = dev_load(&gtr[gb + lane_id()]); we = dev_load(&eqr[gb + lane_id()]); }
             const uint32_t gtb = sum_gt + wave_sum_u32(wg), eqb = sum_eq + wave_sum_u32(we);
-            const GroupWalk w = group_begin(cnt_row, g, a.n_reg);
-            emit_group(w, srow, g, T, k3, eqb, gtb + (eqb < k3 ? eqb : k3), prow, brow, a.k, a.x, a.gamma);
+            uint32_t out_slot = gtb + (eqb < k3 ? eqb : k3), eq_seen = eqb;
+            if (g == g0 && wc.valid) {
+                const uint32_t base = static_cast<uint32_t>(g) * (kGroupRegs * kReg);
+                uint32_t kept = 0u;                            // bit j: this lane's candidate of batch j is kept
+#pragma unroll
+                for (int j = 0; j < kPrefetch; ++j) {
+                    if (j * 64u >= wc.total) continue;         // uniform over the wavefront
+                    const uint32_t i = j * 64 + lane_id();
+                    const bool valid = i < wc.total;
+                    const u32x2 pr = valid ? u32x2{base + wc.rel[i], wc.bits[i]} : u32x2{0u, 0u};
+                    if (emit_batch(pr, valid, T, k3, eq_seen, out_slot, prow, brow, a.k)) kept |= 1u << j;
+                }
+                if (a.x) {
+                    // the model update at the kept entries: all loads first (the entries of a
+                    // group are distinct elements), so that they are in flight together
+                    float xv[kPrefetch];
+#pragma unroll
+                    for (int j = 0; j < kPrefetch; ++j) xv[j] = ((kept >> j) & 1u) ? a.x[base + wc.rel[j * 64 + lane_id()]] : 0.f;
+#pragma unroll
+                    for (int j = 0; j < kPrefetch; ++j)
+                        if ((kept >> j) & 1u)
+                            a.x[base + wc.rel[j * 64 + lane_id()]] =
+                                __fmaf_rn(-a.gamma, __uint_as_float(wc.bits[j * 64 + lane_id()]), xv[j]);
+                }
+            } else {
+                const GroupWalk w = group_begin(cnt_row, g, a.n_reg);
+                emit_group(w, srow, g, T, k3, eqb, out_slot, prow, brow, a.k, a.x, a.gamma);
+            }
         }
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) a.prev_T[row] = T;   // centre of the next call's fine sampling window
-    // every pick of the row is done (the emission needed the last one): clear the row's
-    // histograms for the next call
+    // every pick of the row is done (the emission needed the last one) and every workgroup
+    // flushed before the pick it waited for: clear the row's histograms for the next call.  The
+    // row's synchronisation words are cleared by the next call's sample kernel, which no
+    // workgroup of this launch can overlap with.
     for (int i = blockIdx.x * kBlock + threadIdx.x; i < kFRow; i += G * kBlock) fh[i] = 0u;
-    if (row_arrive(rs) && threadIdx.x == 0) {                      // everyone is past every poll: reset for the next launch
-        for (int sl = 0; sl < kResSlots; ++sl) __hip_atomic_store(rs.res + sl, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        dev_store(rs.bar, 0u);
-    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1335,7 +1440,7 @@ ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t 
     const uint32_t k32 = static_cast<uint32_t>(k);
 
     k_topk_sample<Src><<<dim3(static_cast<unsigned>((ns + kWaves - 1) / kWaves), rows), kBlock, 0, st>>>(
-        src, d, n_sub, ns, hist, t->sel, t->done, rank, prev_T);
+        src, d, n_sub, ns, hist, t->sel, t->done, rank, prev_T, reinterpret_cast<uint32_t *>(t->sync));
     if constexpr (std::is_same<Src, ServerV>::value)
         k_topk_pass1_server<<<dim3(static_cast<unsigned>((n_reg + 3) / 4)), kBlock, 0, st>>>(src, buf, d, t->sel, t->slots,
                                                                                          t->reg_cnt, n_reg);
