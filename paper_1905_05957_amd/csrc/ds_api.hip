@@ -308,6 +308,14 @@ ds_status_t ds_server_aggregate_compress_update(ds_ctx_t *c, uint64_t step, cons
         if (!guard.ok) return DS_ERR_DEVICE;
         return ds_rsparse_server_update(c, step, in, delta_s, out, x, m, gamma, beta, static_cast<hipStream_t>(hip_stream));
     }
+    if ((c->cfg.comp == DS_COMP_SIGN && c->sign_fused) || c->cfg.comp == DS_COMP_QSGD) {
+        // one pass: x (and m) are updated from the registers that hold the server's message
+        DeviceGuard guard(c->device);
+        if (!guard.ok) return DS_ERR_DEVICE;
+        hipStream_t st = static_cast<hipStream_t>(hip_stream);
+        return (c->cfg.comp == DS_COMP_SIGN) ? ds_sign_server(c, in, delta_s, out, st, x, m, gamma, beta)
+                                             : ds_qsgd_server(c, step, in, delta_s, out, st, x, m, gamma, beta);
+    }
     rc = ds_server_aggregate_compress(c, step, in, delta_s, out, hip_stream);
     if (rc != DS_OK) return rc;
     return ds_apply_update(c, out, x, m, gamma, beta, hip_stream);

@@ -79,7 +79,8 @@ void ds_sign_fini(ds_ctx *c);
 ds_status_t ds_sign_worker(ds_ctx *c, const void *g, int64_t gs, float *delta, int64_t dstr,
                            const ds_payload_t *out, hipStream_t st);
 ds_status_t ds_sign_server(ds_ctx *c, const ds_payload_t *in, float *delta_s,
-                           const ds_payload_t *out, hipStream_t st);
+                           const ds_payload_t *out, hipStream_t st, float *x = nullptr, float *m = nullptr,
+                           float gamma = 0.f, float beta = 0.f);
 ds_status_t ds_sign_update(ds_ctx *c, const ds_payload_t *srv, float *x, float *m, float gamma,
                            float beta, hipStream_t st);
 ds_status_t ds_sign_decode(ds_ctx *c, const ds_payload_t *p, int32_t row, float *out, hipStream_t st);
@@ -89,7 +90,8 @@ ds_status_t ds_sign_materialize(ds_ctx *c, float *delta, int64_t dstr, float *de
 ds_status_t ds_qsgd_worker(ds_ctx *c, uint64_t step, const void *g, int64_t gs, float *delta,
                            int64_t dstr, const ds_payload_t *out, hipStream_t st);
 ds_status_t ds_qsgd_server(ds_ctx *c, uint64_t step, const ds_payload_t *in, float *delta_s,
-                           const ds_payload_t *out, hipStream_t st);
+                           const ds_payload_t *out, hipStream_t st, float *x = nullptr, float *m = nullptr,
+                           float gamma = 0.f, float beta = 0.f);
 ds_status_t ds_qsgd_update(ds_ctx *c, const ds_payload_t *srv, float *x, float *m, float gamma,
                            float beta, hipStream_t st);
 ds_status_t ds_qsgd_decode(ds_ctx *c, const ds_payload_t *p, int32_t row, float *out, hipStream_t st);

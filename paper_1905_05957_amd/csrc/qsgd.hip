@@ -153,10 +153,13 @@ __global__ __launch_bounds__(kBlock) void k_qsgd_worker(const void *g, int64_t g
 
 // Parameter-server block: v = delta_s + (1/n) sum_i decode(msg_i) as the fma chain over
 // workers in ascending order, then the same quantiser on the server's stream.
+// UPD: 0 = that block alone; 1, 2 = followed by the model update of Algorithm 1 for the same
+// elements (2: through the momentum buffer) from the decoded values the thread already holds.
+template <int UPD>
 __global__ __launch_bounds__(kBlock) void k_qsgd_server(const uint8_t *levels_in, const uint64_t *words_in,
                                                         const float *norms_in, int n, float inv_n, float *delta_s,
                                                         QParams P, uint8_t *levels_out, uint64_t *words_out,
-                                                        float *norms_out)
+                                                        float *norms_out, float *x, float *m, float gamma, float beta)
 {
     __shared__ double lds[kWaves];
     __shared__ __attribute__((aligned(16))) uint32_t sw_lds[kWaves * 8];
@@ -169,6 +172,9 @@ __global__ __launch_bounds__(kBlock) void k_qsgd_server(const uint8_t *levels_in
     const int my_b = (threadIdx.x * 4) >> P.bshift;
     const int64_t lev_stride = (P.d + 1) / 2;
     f32x4 a = ld4_stream(delta_s, e, P.d, dvec);
+    f32x4 xv = {0.f, 0.f, 0.f, 0.f}, mv = {0.f, 0.f, 0.f, 0.f};      // fetched up front, beside the error
+    if constexpr (UPD != 0) xv = ld4_stream(x, e, P.d, aligned16(x));
+    if constexpr (UPD == 2) mv = ld4_stream(m, e, P.d, aligned16(m));
     for (int i0 = 0; i0 < n; i0 += kUnitGroup) {
         const int cnt = (n - i0 < kUnitGroup) ? n - i0 : kUnitGroup;
         __syncthreads();
@@ -222,8 +228,18 @@ __global__ __launch_bounds__(kBlock) void k_qsgd_server(const uint8_t *levels_in
         }
     }
     a = zero_past(a, e, P.d);
-    const f32x4 q = quantise4(a, e, kServerStream, P, levels_out, words_out, norms_out, lds, sw_lds);
+    f32x4 q = quantise4(a, e, kServerStream, P, levels_out, words_out, norms_out, lds, sw_lds);
     if (e < P.d) st4_stream(delta_s, e, P.d, dvec, a - q);
+    if constexpr (UPD != 0) {
+        if (e < P.d) {
+            q = zero_past(q, e, P.d);
+            if constexpr (UPD == 2) {
+                q = fma4(beta, mv, q);
+                st4_stream(m, e, P.d, aligned16(m), q);
+            }
+            st4_stream(x, e, P.d, aligned16(x), fma4(-gamma, q, xv));
+        }
+    }
 }
 
 template <bool MOM, bool DECODE_ONLY>
@@ -271,14 +287,22 @@ ds_status_t ds_qsgd_worker(ds_ctx *c, uint64_t step, const void *g, int64_t gs, 
     return ds_launch_status();
 }
 
+// x != nullptr: the model update for the same elements in the same kernel.
 ds_status_t ds_qsgd_server(ds_ctx *c, uint64_t step, const ds_payload_t *in, float *delta_s,
-                           const ds_payload_t *out, hipStream_t st)
+                           const ds_payload_t *out, hipStream_t st, float *x, float *m, float gamma, float beta)
 {
     if (!bucket_ok(c->cfg.bucket)) return DS_ERR_UNSUPPORTED;
     const QParams P = make_params(c, step);
-    k_qsgd_server<<<static_cast<unsigned>(c->n_tiles), kBlock, 0, st>>>(in->levels, in->sign_words, in->scales,
-                                                                       c->cfg.n, c->inv_n, delta_s, P, out->levels,
-                                                                       out->sign_words, out->scales);
+    const unsigned blocks = static_cast<unsigned>(c->n_tiles);
+    if (!x)
+        k_qsgd_server<0><<<blocks, kBlock, 0, st>>>(in->levels, in->sign_words, in->scales, c->cfg.n, c->inv_n, delta_s, P,
+                                                    out->levels, out->sign_words, out->scales, x, m, gamma, beta);
+    else if (!m)
+        k_qsgd_server<1><<<blocks, kBlock, 0, st>>>(in->levels, in->sign_words, in->scales, c->cfg.n, c->inv_n, delta_s, P,
+                                                    out->levels, out->sign_words, out->scales, x, m, gamma, beta);
+    else
+        k_qsgd_server<2><<<blocks, kBlock, 0, st>>>(in->levels, in->sign_words, in->scales, c->cfg.n, c->inv_n, delta_s, P,
+                                                    out->levels, out->sign_words, out->scales, x, m, gamma, beta);
     return ds_launch_status();
 }
 

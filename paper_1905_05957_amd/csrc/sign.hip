@@ -117,7 +117,7 @@ __device__ __forceinline__ f32x4 sign_error4(f32x4 v, float s)
 // ---------------------------------------------------------------------------------------
 // Common tail: scale from the held values, sign plane, error, stores.
 template <bool RMS>
-__device__ __forceinline__ void fused_finish(f32x4 v, int64_t base, int64_t lim,
+__device__ __forceinline__ float fused_finish(f32x4 v, int64_t base, int64_t lim,
                                              float *__restrict__ err_row, bool err_vec,
                                              uint64_t *__restrict__ words_row, int64_t bit_lim,
                                              float *__restrict__ scale_out, double *lds, uint32_t *sw_lds)
@@ -130,6 +130,7 @@ __device__ __forceinline__ void fused_finish(f32x4 v, int64_t base, int64_t lim,
     flush_sign_words(sw_lds, words_row, base, bit_lim);
     const int64_t e = base + threadIdx.x * 4;
     if (e < lim) st4_stream(err_row, e, lim, err_vec, sign_error4(v, scale));
+    return scale;
 }
 
 template <bool BF16, bool RMS>
@@ -154,10 +155,15 @@ __global__ __launch_bounds__(kBlock) void k_sign_chunk_worker(WorkerSrc<BF16> sr
                       scales + row * S + ci, lds, sw_lds);
 }
 
-template <int CPW, bool RMS>   // CPW chunks per workgroup: independent chunks, more bytes in flight per thread
+// UPD: 0 = the parameter-server block alone; 1, 2 = followed by the model update of Algorithm 1
+// for the same elements (2: through the momentum buffer), from the registers that hold the
+// server's sign bits and scale: x and m stream through once and the server's message is not
+// read back.
+template <int CPW, bool RMS, int UPD>   // CPW chunks per workgroup: independent chunks, more bytes in flight per thread
 __global__ __launch_bounds__(kBlock) void k_sign_chunk_server(ServerArgs a, float *delta_s, int64_t d,
                                                               int64_t chunk, uint64_t *words_out,
-                                                              float *scales_out)
+                                                              float *scales_out, float *x, float *m, float gamma,
+                                                              float beta)
 {
     __shared__ double lds[CPW][kWaves];
     __shared__ __attribute__((aligned(16))) uint32_t sw_lds[CPW][kWaves * 8];
@@ -171,6 +177,15 @@ __global__ __launch_bounds__(kBlock) void k_sign_chunk_server(ServerArgs a, floa
         base[c] = ci * chunk;
         lim[c] = (base[c] + chunk < d) ? base[c] + chunk : d;     // base >= d: empty chunk, lim < base
         v[c] = ld4_stream(delta_s, base[c] + threadIdx.x * 4, lim[c], dvec);
+    }
+    // the update's operands are fetched up front, beside the error: more bytes in flight
+    f32x4 xv[CPW], mv[CPW];
+    if constexpr (UPD != 0) {
+#pragma unroll
+        for (int c = 0; c < CPW; ++c) {
+            xv[c] = ld4_stream(x, base[c] + threadIdx.x * 4, lim[c], aligned16(x));
+            if constexpr (UPD == 2) mv[c] = ld4_stream(m, base[c] + threadIdx.x * 4, lim[c], aligned16(m));
+        }
     }
     // The wavefront's 256 elements are 32 bytes of each worker's sign plane.  Eight workers at
     // a time: lane L loads 32-bit word (L & 7) of worker (L >> 3), one load instruction for
@@ -219,9 +234,22 @@ __global__ __launch_bounds__(kBlock) void k_sign_chunk_server(ServerArgs a, floa
         const int64_t ci = static_cast<int64_t>(blockIdx.x) * CPW + c;
         // components past lim must stay zero: they count in the sum of |v|
         v[c] = zero_past(v[c], base[c] + threadIdx.x * 4, lim[c]);
-        if (base[c] < d)   // uniform over the workgroup
-            fused_finish<RMS>(v[c], base[c], lim[c], delta_s, dvec, words_out, (lim[c] == d) ? a.W * 64 : lim[c],
-                              scales_out + ci, lds[c], sw_lds[c]);
+        if (base[c] < d) {   // uniform over the workgroup
+            const float s = fused_finish<RMS>(v[c], base[c], lim[c], delta_s, dvec, words_out,
+                                              (lim[c] == d) ? a.W * 64 : lim[c], scales_out + ci, lds[c], sw_lds[c]);
+            if constexpr (UPD != 0) {
+                // q = decode of the message just written: bit ? -scale : +scale, bit = (v < 0)
+                const int64_t e = base[c] + threadIdx.x * 4;
+                if (e < lim[c]) {
+                    f32x4 q = {(v[c].x < 0.f) ? -s : s, (v[c].y < 0.f) ? -s : s, (v[c].z < 0.f) ? -s : s, (v[c].w < 0.f) ? -s : s};
+                    if constexpr (UPD == 2) {
+                        q = fma4(beta, mv[c], q);
+                        st4_stream(m, e, lim[c], aligned16(m), q);
+                    }
+                    st4_stream(x, e, lim[c], aligned16(x), fma4(-gamma, q, xv[c]));
+                }
+            }
+        }
     }
 }
 
@@ -619,8 +647,9 @@ ds_status_t ds_sign_worker(ds_ctx *c, const void *g, int64_t gs, float *delta, i
     return ds_launch_status();
 }
 
+// x != nullptr (chunk route only): the model update for the same elements in the same kernel.
 ds_status_t ds_sign_server(ds_ctx *c, const ds_payload_t *in, float *delta_s, const ds_payload_t *out,
-                           hipStream_t st)
+                           hipStream_t st, float *x, float *m, float gamma, float beta)
 {
     const ds_config_t &cfg = c->cfg;
     ServerArgs a{in->sign_words, in->scales, cfg.n, c->W, c->S, c->inv_n};
@@ -629,10 +658,21 @@ ds_status_t ds_sign_server(ds_ctx *c, const ds_payload_t *in, float *delta_s, co
         // two chunks per workgroup: more bytes in flight per thread (measured 271 us against
         // 292 us with one and 285 us with four on the 124 M-element workload)
         const dim3 grid(static_cast<unsigned>((c->S + 1) / 2));
-        if (rms) k_sign_chunk_server<2, true><<<grid, kBlock, 0, st>>>(a, delta_s, cfg.d, cfg.chunk, out->sign_words, out->scales);
-        else k_sign_chunk_server<2, false><<<grid, kBlock, 0, st>>>(a, delta_s, cfg.d, cfg.chunk, out->sign_words, out->scales);
+        auto launch = [&](auto rm, auto upd) {
+            constexpr bool RM = decltype(rm)::value;
+            constexpr int UPD = decltype(upd)::value;
+            k_sign_chunk_server<2, RM, UPD><<<grid, kBlock, 0, st>>>(a, delta_s, cfg.d, cfg.chunk, out->sign_words, out->scales,
+                                                                      x, m, gamma, beta);
+        };
+        auto with_upd = [&](auto rm) {
+            if (!x) launch(rm, std::integral_constant<int, 0>{});
+            else if (!m) launch(rm, std::integral_constant<int, 1>{});
+            else launch(rm, std::integral_constant<int, 2>{});
+        };
+        if (rms) with_upd(std::true_type{}); else with_upd(std::false_type{});
         return ds_launch_status();
     }
+    if (x) return DS_ERR_UNSUPPORTED;   // the caller asks for the fused form on the chunk route only
     dim3 grid(static_cast<unsigned>(c->n_tiles));
     const bool deferred = c->sign_defer && c->sign_s_deferred;
     with_flags(deferred, rms, false, [&](auto df, auto rm, auto) {

@@ -19,6 +19,9 @@ def _cases():
         ("topk_multi_launch", W.c3(d=300_007, n=4), P.FLAG_TOPK_MULTI_LAUNCH),
         ("topk_momentum", dataclasses.replace(W.c3(d=100_003, n=3), beta=0.9), 0),
         ("sign_chunk_momentum", W.c5(d=2048 * 30 + 1280, n=4, n_seg=8), 0),
+        ("sign_chunk_plain_sgd_odd_length", dataclasses.replace(W.c5(d=2048 * 31 + 1283, n=3, n_seg=8), beta=None), 0),
+        ("sign_chunk_rms_9_workers", dataclasses.replace(W.c5(d=2048 * 9 + 130, n=9, n_seg=4), sign_rms=True), 0),
+        ("qsgd_momentum_odd_length", dataclasses.replace(W.c4(d=2048 * 11 + 37, n=3), beta=0.8), 0),
         ("sign_segments_deferred", W.c2(d=200_002, n=3, n_seg=12, lo=64), P.FLAG_DEFERRED_ERROR),
         ("qsgd", W.c4(d=2048 * 20 + 40, n=5), 0),
         ("clip", W.clip16(d=50_001, n=3), 0),
