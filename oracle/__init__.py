@@ -17,6 +17,8 @@ A message ("payload") is a dict of numpy arrays, one leading row axis:
   CLIP     : levels [rows, d*nb] uint8, the kept upper bits of every element (nb = 1, 2 or 4)
   RSPARSE  : sign_words [rows, W] uint64 (bit = element kept), val [rows, d] float32 (the kept
              values z/p packed in index order, zeros after them)
+  TERNARY  : sign_words [rows, W] uint64 (bit = code is -1), levels [rows, 8 W] uint8 (the bytes of
+             a second plane of W little-endian words: bit = code is not 0), scales [rows, 1]
 """
 from __future__ import annotations
 
@@ -28,7 +30,7 @@ from typing import Optional
 
 import numpy as np
 
-IDENTITY, SIGN, TOPK, QSGD, CLIP, RSPARSE = 0, 1, 2, 3, 4, 5
+IDENTITY, SIGN, TOPK, QSGD, CLIP, RSPARSE, TERNARY = 0, 1, 2, 3, 4, 5, 6
 SERVER_STREAM = 0xFFFFFFFF
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -97,6 +99,10 @@ def lib():
         L.dso_rsparse_encode.restype = None
         L.dso_rsparse_decode.argtypes = [vp, vp, i64, vp]
         L.dso_rsparse_decode.restype = None
+        L.dso_ternary_encode.argtypes = [vp, i64, u64, u64, u32, vp, vp, vp]
+        L.dso_ternary_encode.restype = None
+        L.dso_ternary_decode.argtypes = [vp, vp, f32, i64, vp]
+        L.dso_ternary_decode.restype = None
         L.dso_worker_compress.argtypes = [vp, u64, vp, i64, vp, i64, vp]
         L.dso_worker_compress.restype = C.c_int
         L.dso_server_aggregate_compress.argtypes = [vp, u64, vp, vp, vp]
@@ -191,6 +197,10 @@ def alloc_payload(cfg: Config, rows: int) -> dict:
     if cfg.comp == RSPARSE:
         return {"sign_words": np.zeros((rows, cfg.n_words), np.uint64),
                 "val": np.zeros((rows, d), np.float32)}
+    if cfg.comp == TERNARY:
+        return {"sign_words": np.zeros((rows, cfg.n_words), np.uint64),
+                "levels": np.zeros((rows, 8 * cfg.n_words), np.uint8),
+                "scales": np.zeros((rows, 1), np.float32)}
     raise ValueError(cfg.comp)
 
 
@@ -275,6 +285,9 @@ def decode(cfg: Config, payload: dict, row: int = 0) -> np.ndarray:
     elif cfg.comp == RSPARSE:
         L.dso_rsparse_decode(payload["sign_words"][row].ctypes.data, payload["val"][row].ctypes.data,
                              d, q.ctypes.data)
+    elif cfg.comp == TERNARY:
+        L.dso_ternary_decode(payload["sign_words"][row].ctypes.data, payload["levels"][row].ctypes.data,
+                             np.float32(payload["scales"][row, 0]), d, q.ctypes.data)
     else:
         raise ValueError(cfg.comp)
     return q
@@ -304,6 +317,9 @@ def encode(cfg: Config, step: int, stream: int, v: np.ndarray) -> dict:
     elif cfg.comp == RSPARSE:
         L.dso_rsparse_encode(v.ctypes.data, cfg.d, np.float32(cfg.keep_prob), cfg.seed, step, stream,
                              out["sign_words"].ctypes.data, out["val"].ctypes.data)
+    elif cfg.comp == TERNARY:
+        L.dso_ternary_encode(v.ctypes.data, cfg.d, cfg.seed, step, stream, out["sign_words"].ctypes.data,
+                             out["levels"].ctypes.data, out["scales"].ctypes.data)
     else:
         raise ValueError(cfg.comp)
     return out

@@ -13,7 +13,8 @@
  *   Section 3.2 / Section 5.1 give the compressors Q: 1-bit (sign + scale so that the
  *   recovered vector has the magnitude of the compensated one), top-k by absolute
  *   value, two-point unbiased randomised quantisation, clipping of low bits and
- *   randomised sparsification.
+ *   randomised sparsification; Section 5.1 adds the ternary quantiser of its QSGD comparison
+ *   system.
  *
  * Every function follows the algorithm's steps in the paper's order: form v, encode,
  * decode, subtract.  The error buffers are always computed as "v minus the decoded
@@ -34,6 +35,8 @@
  *     numbers from Philox4x32-10 (Salmon et al., SC'11) keyed on
  *     (seed, step, stream, index).
  *   - momentum (not in the paper, which uses none): m <- beta m + q ; x <- x - gamma m.
+ *   - ternary quantiser: "magnitude" in its scale factor read as the l1 norm, as for the 1-bit
+ *     compressor; probability |e|/m as one fp32 division.
  *
  * Parity pins live in tests/test_oracle_*.py; no function here is unpinned except the
  * conventions listed above (sum order, counter layout), which no text fixes.
@@ -49,6 +52,7 @@
 #define DSO_QSGD 3
 #define DSO_CLIP 4
 #define DSO_RSPARSE 5
+#define DSO_TERNARY 6
 
 #define DSO_SERVER_STREAM 0xFFFFFFFFu
 
@@ -74,7 +78,9 @@ typedef struct {
                                RSPARSE: the same plane holds "element j is kept" */
     float *scales;          /* SIGN: [n_groups] ; QSGD: [ceil(d/bucket)] bucket norms */
     uint8_t *levels;        /* QSGD: [ceil(d/2)], element j in byte j>>1, low nibble if j even;
-                               CLIP: [d * nb] the kept upper bits, nb = 1, 2 or 4 bytes per element */
+                               CLIP: [d * nb] the kept upper bits, nb = 1, 2 or 4 bytes per element;
+                               TERNARY: [8 * ceil(d/64)] a second bit plane (bytes of little-endian
+                               64-bit words), bit j = (code_j != 0) */
     int32_t *idx;           /* TOPK: [k] ascending */
     float *val;             /* TOPK: [k] ; RSPARSE: [d] kept values z/p packed in index order, then zeros */
     float *dense;           /* IDENTITY: [d] */
@@ -325,6 +331,54 @@ void dso_rsparse_decode(const uint64_t *keep_words, const float *vals, int64_t d
 }
 
 /* ------------------------------------------------------------------------------------
+ * Ternary quantiser (Section 5.1, the compressor of the paper's QSGD comparison system):
+ * every element becomes a code in {-1, 0, +1}.  With m the largest absolute value of the
+ * vector, element e becomes sign(e) with probability |e| / m and 0 otherwise (so the largest
+ * element is always kept, and m * code is an unbiased estimate of e).  One scale factor per
+ * vector, "magnitude of original gradient over magnitude of compressed gradient", in the same
+ * l1 reading as the 1-bit compressor: scale = sum |v_j| / #(non-zero codes), so that the
+ * decoded vector code * scale has the l1 magnitude of v.  The draw for element j is the
+ * counter-based uniform of the quantiser above; an all-zero vector gives all-zero codes and
+ * scale 0.
+ * Message: plane `neg` (bit j = code_j is -1), plane `nz` (bit j = code_j is not 0), scale.
+ * ---------------------------------------------------------------------------------- */
+void dso_ternary_encode(const float *v, int64_t d, uint64_t seed, uint64_t step, uint32_t stream,
+                        uint64_t *neg, uint64_t *nz, float *scale)
+{
+    int64_t n_words = (d + 63) / 64;
+    for (int64_t w = 0; w < n_words; ++w) { neg[w] = 0; nz[w] = 0; }
+    float m = 0.0f;
+    double sum_abs = 0.0;
+    for (int64_t j = 0; j < d; ++j) {
+        float a = fabsf(v[j]);
+        if (a > m) m = a;
+        sum_abs += (double)a;
+    }
+    int64_t kept = 0;
+    if (m > 0.0f) {
+        for (int64_t j = 0; j < d; ++j) {
+            float p = fabsf(v[j]) / m;               /* one fp32 divide; 1 for the largest element */
+            float u = dso_uniform24(seed, step, stream, j);
+            if (u < p) {
+                nz[j >> 6] |= (uint64_t)1 << (j & 63);
+                if (v[j] < 0.0f) neg[j >> 6] |= (uint64_t)1 << (j & 63);
+                ++kept;
+            }
+        }
+    }
+    *scale = kept > 0 ? (float)(sum_abs / (double)kept) : 0.0f;
+}
+
+void dso_ternary_decode(const uint64_t *neg, const uint64_t *nz, float scale, int64_t d, float *q)
+{
+    for (int64_t j = 0; j < d; ++j) {
+        int kept = (int)((nz[j >> 6] >> (j & 63)) & 1u);
+        int minus = (int)((neg[j >> 6] >> (j & 63)) & 1u);
+        q[j] = kept ? (minus ? -scale : scale) : 0.0f;
+    }
+}
+
+/* ------------------------------------------------------------------------------------
  * Q[.] and its decoder, selected by the configuration.
  * ---------------------------------------------------------------------------------- */
 int dso_encode(const dso_config *c, uint64_t step, uint32_t stream, const float *v, dso_msg *m)
@@ -350,6 +404,9 @@ int dso_encode(const dso_config *c, uint64_t step, uint32_t stream, const float 
         if (!(c->keep_prob > 0.0f && c->keep_prob <= 1.0f)) return 3;
         dso_rsparse_encode(v, c->d, c->keep_prob, c->seed, step, stream, m->sign_words, m->val);
         return 0;
+    case DSO_TERNARY:
+        dso_ternary_encode(v, c->d, c->seed, step, stream, m->sign_words, (uint64_t *)m->levels, m->scales);
+        return 0;
     }
     return 3;
 }
@@ -374,6 +431,9 @@ int dso_decode(const dso_config *c, const dso_msg *m, float *q)
         return 0;
     case DSO_RSPARSE:
         dso_rsparse_decode(m->sign_words, m->val, c->d, q);
+        return 0;
+    case DSO_TERNARY:
+        dso_ternary_decode(m->sign_words, (const uint64_t *)m->levels, m->scales[0], c->d, q);
         return 0;
     }
     return 3;

@@ -237,3 +237,120 @@ def test_conservation_no_information_is_dropped(name):
     assert np.abs(sum_q + omega - sum_gbar).max() <= 1e-5 * scale
     assert np.abs(x - (x0 - gamma * (sum_gbar - omega))).max() <= 1e-5 * np.abs(x0).max()
     assert np.abs(omega).max() > 1e-4 * scale
+
+
+# ----------------------------------------------------------------------------------------
+# Ternary quantiser (Section 5.1, compressor of the paper's QSGD comparison system)
+# ----------------------------------------------------------------------------------------
+def _ternary_planes(p, d, row=0):
+    nz = unpack_bits(np.ascontiguousarray(p["levels"][row]).view(np.uint64), d)
+    neg = unpack_bits(p["sign_words"][row], d)
+    return nz, neg
+
+
+def test_ternary_hand_example():
+    rows = _read_rows(os.path.join(GOLD, "ternary_hand_example.txt"))
+    v = np.array([float(t) for t in rows["v"]], np.float32)
+    cfg = O.Config(O.TERNARY, n=1, d=len(v), seed=77)
+    for step in (0, 1, 12345):                                   # no draw matters here
+        p = O.encode(cfg, step, 0, v)
+        assert int(np.ascontiguousarray(p["levels"][0]).view(np.uint64)[0]) == int(rows["nz"][0])
+        assert int(p["sign_words"][0, 0]) == int(rows["neg"][0])
+        assert p["scales"][0, 0] == np.float32(float(rows["scale"][0]))
+        assert O.decode(cfg, p, 0).tolist() == [float(t) for t in rows["q"]]
+
+
+def test_ternary_codes_draws_and_scale():
+    """Codes are -1, 0 or +1 with the sign of the element; element j is kept exactly when its
+    draw (the counter-based uniform, pinned by its own known answers) is below |v_j| / m in
+    fp32; the largest element is always kept, zeros never; count * scale = sum |v| (the decoded
+    vector has the l1 magnitude of v)."""
+    d = 3000
+    r = _rng(5)
+    v = (r.standard_normal(d) * 1e-2).astype(np.float32)
+    v[17] = 0.0
+    v[1234] = -0.2                                               # the largest magnitude, negative
+    m = np.float32(0.2)
+    cfg = O.Config(O.TERNARY, n=1, d=d, seed=0xABCDEF)
+    for step, stream in ((0, 0), (3, 5), (2 ** 32 + 1, O.SERVER_STREAM)):
+        p = O.encode(cfg, step, stream, v)
+        nz, neg = _ternary_planes(p, d)
+        assert not np.any(neg & ~nz)                             # a code of -1 is a non-zero code
+        assert np.array_equal(neg, nz & (v < 0))                 # the code carries the element's sign
+        u = np.array([O.uniform24(cfg.seed, step, stream, j) for j in range(d)], np.float32)
+        prob = np.abs(v) / m                                     # fp32 division
+        assert prob.dtype == np.float32
+        assert np.array_equal(nz, u < prob)
+        assert nz[1234] and not nz[17]
+        scale = float(p["scales"][0, 0])
+        total = np.abs(v.astype(np.float64)).sum()
+        assert abs(nz.sum() * scale - total) <= 1e-6 * total
+        q = O.decode(cfg, p, 0)
+        assert np.array_equal(q, np.where(nz, np.where(neg, -np.float32(scale), np.float32(scale)), np.float32(0)))
+
+
+def test_ternary_is_unbiased_before_the_rescale():
+    """E[m * code_j] = v_j (probability |v_j|/m of sign(v_j)); the variance of m * code_j is
+    m |v_j| - v_j^2 <= m^2 / 4, so the mean over S steps lies within 5 m / (2 sqrt S)."""
+    d, S = 400, 3000
+    r = _rng(9)
+    v = (r.standard_normal(d) * 0.3).astype(np.float32)
+    m = np.abs(v).max()
+    cfg = O.Config(O.TERNARY, n=1, d=d, seed=2024)
+    acc = np.zeros(d)
+    kept_max = 0
+    for step in range(S):
+        p = O.encode(cfg, step, 1, v)
+        nz, neg = _ternary_planes(p, d)
+        acc += np.where(nz, np.where(neg, -1.0, 1.0), 0.0) * float(m)
+        kept_max += int(nz[np.abs(v).argmax()])
+    assert kept_max == S
+    assert np.abs(acc / S - v).max() <= 5 * float(m) / (2 * np.sqrt(S))
+    # a small element is mostly dropped: the quantiser is not the sign compressor
+    small = np.abs(v).argmin()
+    assert abs(acc[small] / S) < 0.2 * float(m)
+
+
+def test_ternary_zero_vector_and_step_identity():
+    d, n = 130, 3
+    cfg = O.Config(O.TERNARY, n=n, d=d, seed=1)
+    p = O.encode(O.Config(O.TERNARY, n=1, d=d, seed=1), 4, 0, np.zeros(d, np.float32))
+    assert not p["levels"].any() and not p["sign_words"].any() and p["scales"][0, 0] == 0.0
+    assert not O.decode(cfg, p, 0).any()
+    # in the step: worker i draws from stream i, and delta = v - decode(message) bit for bit
+    r = _rng(2)
+    g = (r.standard_normal((n, d)) * 1e-2).astype(np.float32)
+    g[1] = g[0]
+    delta = (r.standard_normal((n, d)) * 1e-3).astype(np.float32)
+    delta[1] = delta[0]
+    v = g + delta
+    pw = O.worker_compress(cfg, 7, g, delta)
+    one = O.Config(O.TERNARY, n=1, d=d, seed=1)
+    for i in range(n):
+        ref = O.encode(one, 7, i, v[i])
+        for key in ref:
+            assert np.array_equal(pw[key][i], ref[key][0]), (key, i)
+        assert np.array_equal(delta[i], v[i] - O.decode(one, ref, 0))
+    assert not np.array_equal(pw["levels"][0], pw["levels"][1])   # same input, different streams
+
+
+def test_ternary_decision_is_a_strict_comparison():
+    """Probability |e|/m realised by a 24-bit uniform means u < |e|/m: an element of size zero
+    is never kept, not even by the draw U = 0; an element at 2^-24 of the maximum is kept by
+    U = 0 and dropped by U = 1.  (seed 7, stream 0: U = 0 at step 5837, element 66; U = 1 at
+    step 4875, element 140.)"""
+    seed, d = 7, 1024
+    (t0, j0), (t1, j1) = (5837, 66), (4875, 140)
+    assert O.uniform24(seed, t0, 0, j0) == 0.0 and O.uniform24(seed, t1, 0, j1) == 2.0 ** -24
+    cfg = O.Config(O.TERNARY, n=1, d=d, seed=seed)
+
+    def kept(t, j, size):
+        v = np.zeros(d, np.float32)
+        v[(j + 1) % d] = 1.0                         # the maximum
+        v[j] = np.float32(size)
+        return bool(_ternary_planes(O.encode(cfg, t, 0, v), d)[0][j])
+
+    assert not kept(t0, j0, 0.0)                     # U = 0 is not below 0
+    assert kept(t0, j0, 2.0 ** -24)                  # U = 0 < 1
+    assert not kept(t1, j1, 2.0 ** -24)              # U = 1 is not below 1
+    assert kept(t1, j1, 2.0 ** -23)

@@ -82,6 +82,16 @@ MISTAKES = [
  ("sign rms uses l1 flag ignored", "dso_sign_encode_kind(v, c->d, c->group_off, c->n_groups, c->sign_rms,", "dso_sign_encode_kind(v, c->d, c->group_off, c->n_groups, 0,"),
  ("update applies server error not message", "int rc = dso_decode(c, srv, q);", "int rc = dso_decode(c, srv, q); for (int64_t j = 0; j < d; ++j) q[j] = 0.5f * q[j];"),
  ("server error uses undecoded v", "delta_s[j] = v[j] - q[j];", "delta_s[j] = v[j] - 0.0f * q[j];"),
+ ("ternary u<=p", "if (u < p) {\n                nz[", "if (u <= p) {\n                nz["),
+ ("ternary keeps w.p. 1-p", "float p = fabsf(v[j]) / m; ", "float p = 1.0f - fabsf(v[j]) / m; "),
+ ("ternary norm is the sum not the max", "if (a > m) m = a;", "m += a;"),
+ ("ternary negative plane of all negatives", "                if (v[j] < 0.0f) neg[j >> 6] |= (uint64_t)1 << (j & 63);\n                ++kept;", "                ++kept;\n            }\n            if (v[j] < 0.0f) { neg[j >> 6] |= (uint64_t)1 << (j & 63);"),
+ ("ternary sign dropped", "if (v[j] < 0.0f) neg[j >> 6] |= (uint64_t)1 << (j & 63);\n                ++kept;", "++kept;"),
+ ("ternary scale is the max", "*scale = kept > 0 ? (float)(sum_abs / (double)kept) : 0.0f;", "*scale = kept > 0 ? m : 0.0f;"),
+ ("ternary scale over d", "*scale = kept > 0 ? (float)(sum_abs / (double)kept) : 0.0f;", "*scale = kept > 0 ? (float)(sum_abs / (double)d) : 0.0f;"),
+ ("ternary decode sign swapped", "q[j] = kept ? (minus ? -scale : scale) : 0.0f;", "q[j] = kept ? (minus ? scale : -scale) : 0.0f;"),
+ ("ternary decode ignores the non-zero plane", "q[j] = kept ? (minus ? -scale : scale) : 0.0f;", "q[j] = minus ? -scale : scale;"),
+ ("ternary draws from the server stream", "float u = dso_uniform24(seed, step, stream, j);\n            if (u < p) {\n                nz[", "float u = dso_uniform24(seed, step, DSO_SERVER_STREAM, j);\n            if (u < p) {\n                nz["),
 ]
 
 
