@@ -72,7 +72,7 @@ def _per_element(seg_off: np.ndarray, per_seg: np.ndarray, device) -> torch.Tens
 class Workload:
     """Shape and data recipe of one configuration."""
     name: str
-    comp: str                      # 'identity' | 'sign' | 'topk' | 'qsgd' | 'clip' | 'rsparse'
+    comp: str                      # 'identity' | 'sign' | 'topk' | 'qsgd' | 'clip' | 'rsparse' | 'ternary'
     n: int
     d: int
     grad_dtype: str = "f32"        # 'f32' | 'bf16'

@@ -18,8 +18,11 @@
  * (Section 5.1 "1-bit compression"), top-k by absolute value (Section 5.1 "Top-k
  * compression"), two-point unbiased randomised quantisation (Section 3.2 "Randomized
  * Quantization", bucketed with an L2 norm), clipping of low bits (Section 3.2 "Clipping"),
- * randomised sparsification (Section 3.2 "Randomized Sparsification") and the identity
- * (Section 5.1 "Vanilla SGD").
+ * randomised sparsification (Section 3.2 "Randomized Sparsification"), the identity
+ * (Section 5.1 "Vanilla SGD") and the ternary quantiser of Section 5.1's "QSGD" comparison
+ * system.  Two flags turn Algorithm 1 into the other comparison algorithms of Section 5.1:
+ * DS_FLAG_SERVER_IDENTITY (no second compression: "MEM-SGD") and DS_FLAG_NO_ERROR_FEEDBACK
+ * (no compensation: "Top-k SGD", "QSGD").
  *
  * Conventions that hold for every call
  *   - Every data pointer is DEVICE memory owned by the caller (base address 16-byte
@@ -69,7 +72,8 @@ typedef enum {
     DS_COMP_TOPK = 2,
     DS_COMP_QSGD = 3,
     DS_COMP_CLIP = 4,
-    DS_COMP_RSPARSE = 5
+    DS_COMP_RSPARSE = 5,
+    DS_COMP_TERNARY = 6
 } ds_compressor_t;
 
 typedef enum { DS_F32 = 0, DS_BF16 = 1 } ds_dtype_t;
@@ -106,8 +110,33 @@ typedef enum {
  *
  * DS_FLAG_SIGN_RMS: the SIGN scale of a group is sqrt(mean v^2) instead of mean |v|: the l2
  * reading of Section 3.2's "norm times sign vector" (the decoded group then has the l2 norm
- * of v; with mean |v| it has its l1 norm). */
-typedef enum { DS_FLAG_TOPK_MULTI_LAUNCH = 1, DS_FLAG_DEFERRED_ERROR = 2, DS_FLAG_SIGN_RMS = 4 } ds_flags_t;
+ * of v; with mean |v| it has its l1 norm).
+ *
+ * DS_FLAG_NO_ERROR_FEEDBACK: Algorithm 1 without its compensation (the un-compensated
+ * comparison algorithms of Section 5.1): v_i = g_i on the workers and v = (1/n) sum_i Q[v_i] on
+ * the server (the same chain, started from +0).  No error buffer is read or written: the
+ * `delta` and `delta_s` arguments are ignored and may be NULL, so a worker pass moves the
+ * gradient and the message only.  SIGN, QSGD, CLIP; TOPK with fp32 gradients and
+ * DS_FLAG_SERVER_IDENTITY (its selection uses the error buffer as its work space otherwise);
+ * TERNARY (which is built for this mode only).  Other combinations: DS_ERR_UNSUPPORTED from
+ * ds_create.
+ *
+ * DS_FLAG_SERVER_IDENTITY: the parameter server averages the workers' messages and sends the
+ * average back without compressing it ("MEM-SGD" of Section 5.1; with
+ * DS_FLAG_NO_ERROR_FEEDBACK the section's "Top-k SGD" and "QSGD"): v = (1/n) sum_i Q[v_i] by the
+ * chain from +0, one kernel that decodes the n messages.  There is no server error (`delta_s`
+ * is ignored and may be NULL) and the server's message is the dense vector itself: only
+ * `dense` [d] fp32 of its ds_payload_t is used, by ds_server_aggregate_compress (which writes
+ * it), ds_apply_update and ds_decompress with rows = 1 (which read it).
+ * ds_server_aggregate_compress_update applies the update in the same kernel and writes the
+ * average only if out->dense is not NULL.  SIGN, TOPK, QSGD, CLIP, TERNARY. */
+typedef enum {
+    DS_FLAG_TOPK_MULTI_LAUNCH = 1,
+    DS_FLAG_DEFERRED_ERROR = 2,
+    DS_FLAG_SIGN_RMS = 4,
+    DS_FLAG_NO_ERROR_FEEDBACK = 8,
+    DS_FLAG_SERVER_IDENTITY = 16
+} ds_flags_t;
 
 typedef struct {
     int32_t comp;             /* ds_compressor_t */
@@ -128,7 +157,7 @@ typedef struct {
     int32_t bucket;           /* QSGD: elements per bucket, a multiple of 64 (built: the powers of
                                  two 64 .. 2048; other multiples give DS_ERR_UNSUPPORTED) */
     int32_t flags;            /* ds_flags_t bits, 0 for the defaults */
-    uint64_t seed;            /* QSGD, RSPARSE: Philox key */
+    uint64_t seed;            /* QSGD, RSPARSE, TERNARY: Philox key */
     int32_t topk_max_workgroups; /* TOPK single launch: most workgroups it may use; 0 = what the
                                  device holds at once */
     int32_t topk_spin_limit;  /* TOPK single launch: polls a workgroup spends on one wait before it
@@ -162,6 +191,12 @@ typedef struct { int32_t idx; float val; } ds_pair_t;
  *            are written as 0 and ignored when read).  dense [rows, d]: the kept values z / p
  *            of a row packed in index order at its start; what follows them is unspecified.
  *            Decoded element: its packed value if kept, else 0.
+ *   TERNARY  (Section 5.1: codes in {-1, 0, +1}; with m = max |v| over the row, element e
+ *            becomes sign(e) with probability |e| / m, decided by u < |e| / m with the
+ *            element's 24-bit uniform; one scale per row = sum |v| / number of non-zero codes,
+ *            0 for an all-zero row)  levels [rows, 8 W] bytes = a plane of W 64-bit words per
+ *            row, bit j = code_j is not 0; sign_words [rows, W]: bit j = code_j is -1;
+ *            scales [rows, 1].  Decoded element: code * scale.
  *   IDENTITY dense [rows, d]. */
 typedef struct {
     uint64_t *sign_words;
@@ -180,8 +215,10 @@ ds_status_t ds_create(const ds_config_t *cfg, ds_ctx_t **out);
  * used it.  NULL is accepted. */
 ds_status_t ds_destroy(ds_ctx_t *ctx);
 
-/* Bytes each ds_payload_t member needs for `rows` messages, in struct order
- * (sign_words, scales, levels, pairs, dense); 0 for unused members. */
+/* Bytes each ds_payload_t member needs for `rows` messages of the context's compressor, in
+ * struct order (sign_words, scales, levels, pairs, dense); 0 for unused members.  (The
+ * server's message under DS_FLAG_SERVER_IDENTITY is not one of these: it is dense, d * 4
+ * bytes.) */
 ds_status_t ds_payload_sizes(const ds_ctx_t *ctx, int32_t rows, size_t bytes_out[5]);
 
 /* Worker block of Algorithm 1 for all n workers.
@@ -190,8 +227,8 @@ ds_status_t ds_payload_sizes(const ds_ctx_t *ctx, int32_t rows, size_t bytes_out
  *   out    n messages
  * Strides are in elements and >= d.  Rows that are 16-byte aligned take 128-bit loads;
  * other rows take an element-wise path with the same results.
- * QSGD draws its rounding, RSPARSE its keep decisions, from the stream (seed, step, worker i,
- * element j). */
+ * QSGD draws its rounding, RSPARSE and TERNARY their keep decisions, from the stream (seed,
+ * step, worker i, element j). */
 ds_status_t ds_worker_compress(ds_ctx_t *ctx, uint64_t step, const void *g,
                                int64_t g_row_stride, float *delta, int64_t delta_row_stride,
                                const ds_payload_t *out, void *hip_stream);

@@ -13,15 +13,17 @@ from typing import Optional
 import numpy as np
 import torch
 
-COMP_IDENTITY, COMP_SIGN, COMP_TOPK, COMP_QSGD, COMP_CLIP, COMP_RSPARSE = 0, 1, 2, 3, 4, 5
+COMP_IDENTITY, COMP_SIGN, COMP_TOPK, COMP_QSGD, COMP_CLIP, COMP_RSPARSE, COMP_TERNARY = 0, 1, 2, 3, 4, 5, 6
 SCALE_WHOLE, SCALE_SEGMENTS, SCALE_CHUNK = 0, 1, 2
 F32, BF16 = 0, 1
 FLAG_TOPK_MULTI_LAUNCH = 1
 FLAG_DEFERRED_ERROR = 2
 FLAG_SIGN_RMS = 4
+FLAG_NO_ERROR_FEEDBACK = 8
+FLAG_SERVER_IDENTITY = 16
 
 _COMP = {"identity": COMP_IDENTITY, "sign": COMP_SIGN, "topk": COMP_TOPK, "qsgd": COMP_QSGD,
-         "clip": COMP_CLIP, "rsparse": COMP_RSPARSE}
+         "clip": COMP_CLIP, "rsparse": COMP_RSPARSE, "ternary": COMP_TERNARY}
 _MODE = {"whole": SCALE_WHOLE, "segments": SCALE_SEGMENTS, "chunk": SCALE_CHUNK}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -150,9 +152,14 @@ class Payload:
         elif comp == COMP_RSPARSE:
             self.sign_words = torch.zeros((rows, W), dtype=torch.int64, device=device)
             self.dense = torch.zeros((rows, d), dtype=torch.float32, device=device)
+        elif comp == COMP_TERNARY:
+            self.sign_words = torch.zeros((rows, W), dtype=torch.int64, device=device)
+            self.levels = torch.zeros((rows, 8 * W), dtype=torch.uint8, device=device)
+            self.scales = torch.zeros((rows, 1), dtype=torch.float32, device=device)
 
-    def check(self, ctx: "Context", rows: int, what: str) -> "Payload":
-        if self.comp != ctx.comp or self.d != ctx.d or self.k != ctx.k or self.rows != rows:
+    def check(self, ctx: "Context", rows: int, what: str, server: bool = False) -> "Payload":
+        want = COMP_IDENTITY if (server and ctx.server_identity) else ctx.comp
+        if self.comp != want or self.d != ctx.d or (self.comp != COMP_IDENTITY and self.k != ctx.k) or self.rows != rows:
             raise ValueError(f"{what}: a payload of {rows} message(s) allocated by this context is required")
         for t in self.tensors().values():
             if not t.is_cuda or not t.is_contiguous():
@@ -233,6 +240,8 @@ class Context:
         sizes = self.payload_sizes(1)
         self.W = (self.d + 63) // 64
         self.S = sizes[1] // 4
+        self.no_error_feedback = bool(int(flags) & FLAG_NO_ERROR_FEEDBACK)
+        self.server_identity = bool(int(flags) & FLAG_SERVER_IDENTITY)
 
     def close(self):
         if getattr(self, "_h", None) is not None and self._h.value:
@@ -258,37 +267,47 @@ class Context:
     def alloc_payload(self, rows: int, device="cuda") -> Payload:
         return Payload(self.comp, rows, self.d, self.W, self.S, self.k, device, self.payload_sizes(rows))
 
+    def alloc_server_payload(self, device="cuda") -> Payload:
+        """The server's message: the compressor's, or the dense average under FLAG_SERVER_IDENTITY."""
+        if self.server_identity:
+            return Payload(COMP_IDENTITY, 1, self.d, self.W, self.S, 0, device)
+        return self.alloc_payload(1, device)
+
     def worker_compress(self, step: int, g: torch.Tensor, delta: torch.Tensor, out: Payload,
                         stream=None):
         _need(g, "g", torch.bfloat16 if self.grad_dtype == BF16 else torch.float32, (self.n, self.d))
-        _need(delta, "delta", torch.float32, (self.n, self.d))
+        if delta is not None or not self.no_error_feedback:
+            _need(delta, "delta", torch.float32, (self.n, self.d))
         s = out.check(self, self.n, "out").c_struct()
         # a single row has no meaningful row stride (torch may report anything for it)
         gs = g.stride(0) if self.n > 1 else max(g.stride(0), self.d)
-        ds_ = delta.stride(0) if self.n > 1 else max(delta.stride(0), self.d)
+        ds_ = self.d if delta is None else (delta.stride(0) if self.n > 1 else max(delta.stride(0), self.d))
         _check(load_library().ds_worker_compress(self._h, step, g.data_ptr(), gs,
-                                                 delta.data_ptr(), ds_, C.byref(s),
+                                                 None if delta is None else delta.data_ptr(), ds_, C.byref(s),
                                                  _stream_ptr(stream)), "ds_worker_compress")
 
     def server_aggregate_compress(self, step: int, inp: Payload, delta_s: torch.Tensor,
                                   out: Payload, stream=None):
-        _need(delta_s, "delta_s", torch.float32, (self.d,))
-        a, b = inp.check(self, self.n, "in").c_struct(), out.check(self, 1, "out").c_struct()
+        if delta_s is not None or not (self.no_error_feedback or self.server_identity):
+            _need(delta_s, "delta_s", torch.float32, (self.d,))
+        a, b = inp.check(self, self.n, "in").c_struct(), out.check(self, 1, "out", server=True).c_struct()
         _check(load_library().ds_server_aggregate_compress(self._h, step, C.byref(a),
-                                                           delta_s.data_ptr(), C.byref(b),
+                                                           None if delta_s is None else delta_s.data_ptr(), C.byref(b),
                                                            _stream_ptr(stream)),
                "ds_server_aggregate_compress")
 
     def server_aggregate_compress_update(self, step: int, inp: Payload, delta_s: torch.Tensor, out: Payload,
                                          x: torch.Tensor, m: Optional[torch.Tensor], gamma: float,
                                          beta: float = 0.0, stream=None):
-        _need(delta_s, "delta_s", torch.float32, (self.d,))
+        if delta_s is not None or not (self.no_error_feedback or self.server_identity):
+            _need(delta_s, "delta_s", torch.float32, (self.d,))
         _need(x, "x", torch.float32, (self.d,))
         if m is not None:
             _need(m, "m", torch.float32, (self.d,))
-        a, b = inp.check(self, self.n, "in").c_struct(), out.check(self, 1, "out").c_struct()
+        a = inp.check(self, self.n, "in").c_struct()
+        b = ds_payload_t() if (out is None and self.server_identity) else out.check(self, 1, "out", server=True).c_struct()
         _check(load_library().ds_server_aggregate_compress_update(
-            self._h, step, C.byref(a), delta_s.data_ptr(), C.byref(b), x.data_ptr(),
+            self._h, step, C.byref(a), None if delta_s is None else delta_s.data_ptr(), C.byref(b), x.data_ptr(),
             None if m is None else m.data_ptr(), gamma, beta, _stream_ptr(stream)),
             "ds_server_aggregate_compress_update")
 
@@ -297,7 +316,7 @@ class Context:
         _need(x, "x", torch.float32, (self.d,))
         if m is not None:
             _need(m, "m", torch.float32, (self.d,))
-        s = srv.check(self, 1, "srv").c_struct()
+        s = srv.check(self, 1, "srv", server=True).c_struct()
         _check(load_library().ds_apply_update(self._h, C.byref(s), x.data_ptr(),
                                               None if m is None else m.data_ptr(), gamma, beta,
                                               _stream_ptr(stream)), "ds_apply_update")
@@ -316,7 +335,7 @@ class Context:
 
     def decompress(self, p: Payload, row: int, out: torch.Tensor, stream=None):
         _need(out, "dense_out", torch.float32, (self.d,))
-        s = p.check(self, p.rows, "p").c_struct()
+        s = p.check(self, p.rows, "p", server=(self.server_identity and p.comp == COMP_IDENTITY)).c_struct()
         _check(load_library().ds_decompress(self._h, C.byref(s), p.rows, row, out.data_ptr(),
                                             _stream_ptr(stream)), "ds_decompress")
 

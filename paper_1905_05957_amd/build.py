@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libds_hip.so")
-SOURCES = ["ds_api.hip", "identity.hip", "sign.hip", "qsgd.hip", "topk.hip", "clip.hip", "rsparse.hip"]
+SOURCES = ["ds_api.hip", "identity.hip", "sign.hip", "qsgd.hip", "topk.hip", "clip.hip", "rsparse.hip", "ternary.hip"]
 HEADERS = ["ds_device.h", "ds_internal.h", os.path.join("..", "..", "include", "ds.h")]
 
 # -ffp-contract=off: every fused multiply-add in the kernels is an explicit __fmaf_rn, so

@@ -83,7 +83,7 @@ __device__ __forceinline__ void clip_store4(f32x4 v, uint32_t mask, int64_t e, i
     const uint32_t top[4] = {u[0] >> sh, u[1] >> sh, u[2] >> sh, u[3] >> sh};
     store_msg4<NB>(msg_row, e, d, top);
     const f32x4 q = {__uint_as_float(u[0]), __uint_as_float(u[1]), __uint_as_float(u[2]), __uint_as_float(u[3])};
-    st4_stream(err_row, e, d, err_vec, v - q);
+    if (err_row) st4_stream(err_row, e, d, err_vec, v - q);     // no buffer: no compensation
 }
 
 // Algorithm 1, worker block: v = g + delta ; message = Q[v] ; delta <- v - Q[v].
@@ -96,10 +96,11 @@ __global__ __launch_bounds__(kBlock) void k_clip_worker(const void *g, int64_t g
     if (e >= d) return;
     const void *grow = BF16 ? static_cast<const void *>(static_cast<const uint16_t *>(g) + row * gs)
                             : static_cast<const void *>(static_cast<const float *>(g) + row * gs);
-    float *drow = delta + row * dstr;
+    float *drow = delta ? delta + row * dstr : nullptr;         // null: no compensation, v = g
     const bool gvec = BF16 ? aligned8(grow) : aligned16(grow);
     const bool dvec = aligned16(drow);
-    const f32x4 v = ld4_grad<BF16>(grow, e, d, gvec) + ld4_stream(drow, e, d, dvec);
+    f32x4 v = ld4_grad<BF16>(grow, e, d, gvec);
+    if (drow) v = v + ld4_stream(drow, e, d, dvec);
     clip_store4<NB>(v, mask, e, d, msg + static_cast<int64_t>(row) * d * NB, drow, dvec);
 }
 
@@ -112,9 +113,22 @@ __global__ __launch_bounds__(kBlock) void k_clip_server(const uint8_t *msg_in, i
     const int64_t e = (static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x) * 4;
     if (e >= d) return;
     const bool dvec = aligned16(delta_s);
-    f32x4 a = ld4_stream(delta_s, e, d, dvec);
+    f32x4 a = {0.f, 0.f, 0.f, 0.f};
+    if (delta_s) a = ld4_stream(delta_s, e, d, dvec);           // null: no server error
     for (int i = 0; i < n; ++i) a = fma4(inv_n, load_msg4<NB>(msg_in + static_cast<int64_t>(i) * d * NB, e, d), a);
     clip_store4<NB>(a, mask, e, d, msg_out, delta_s, dvec);
+}
+
+// Server that does not compress: the average is the message (written and / or applied).
+template <int NB>
+__global__ __launch_bounds__(kBlock) void k_clip_server_identity(const uint8_t *msg_in, int n, float inv_n, int64_t d,
+                                                                 float *dense_out, ds_update_args u)
+{
+    const int64_t e = (static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x) * 4;
+    if (e >= d) return;
+    f32x4 a = {0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < n; ++i) a = fma4(inv_n, load_msg4<NB>(msg_in + static_cast<int64_t>(i) * d * NB, e, d), a);
+    put_average4(a, e, d, dense_out, u.x, u.m, u.gamma, u.beta);
 }
 
 template <int NB, bool MOM, bool DECODE_ONLY>
@@ -165,6 +179,15 @@ ds_status_t ds_clip_server(ds_ctx *c, const ds_payload_t *in, float *delta_s, co
         constexpr int NB = decltype(nb)::value;
         k_clip_server<NB><<<blocks4(c->cfg.d), kBlock, 0, st>>>(in->levels, c->cfg.n, c->inv_n, delta_s, out->levels,
                                                                c->cfg.d, clip_mask(bits));
+    });
+    return ds_launch_status();
+}
+
+ds_status_t ds_clip_server_identity(ds_ctx *c, const ds_payload_t *in, float *dense_out, ds_update_args u, hipStream_t st)
+{
+    with_bytes(c->cfg.levels, [&](auto nb) {
+        constexpr int NB = decltype(nb)::value;
+        k_clip_server_identity<NB><<<blocks4(c->cfg.d), kBlock, 0, st>>>(in->levels, c->cfg.n, c->inv_n, c->cfg.d, dense_out, u);
     });
     return ds_launch_status();
 }

@@ -36,8 +36,22 @@ ds_status_t check_payload(const ds_ctx *c, const ds_payload_t *p)
         if (!p->sign_words || !p->dense) return DS_ERR_NULL;
         if (misaligned(p->sign_words) || misaligned(p->dense)) return DS_ERR_ALIGN;
         break;
+    case DS_COMP_TERNARY:
+        if (!p->sign_words || !p->scales || !p->levels) return DS_ERR_NULL;
+        if (misaligned(p->sign_words) || misaligned(p->scales) || misaligned(p->levels)) return DS_ERR_ALIGN;
+        break;
     }
     return DS_OK;
+}
+
+// The server's message: the compressor's, or with DS_FLAG_SERVER_IDENTITY the dense average
+// (`need_dense` = false: the member may be missing, for the one-call server-and-update).
+ds_status_t check_server_payload(const ds_ctx *c, const ds_payload_t *p, bool need_dense = true)
+{
+    if (!c->sid) return check_payload(c, p);
+    if (!p) return DS_ERR_NULL;
+    if (!p->dense) return need_dense ? DS_ERR_NULL : DS_OK;
+    return misaligned(p->dense) ? DS_ERR_ALIGN : DS_OK;
 }
 
 // Binds the calling thread to the context's device for the duration of a call.
@@ -115,8 +129,16 @@ ds_status_t ds_create(const ds_config_t *cfg, ds_ctx_t **out)
     case DS_COMP_RSPARSE:
         if (cfg->k < 1 || cfg->k > (1 << 24)) return DS_ERR_CONFIG;
         break;
+    case DS_COMP_TERNARY:
+        break;
     default:
         return DS_ERR_CONFIG;
+    }
+    {
+        const bool nofb = (cfg->flags & DS_FLAG_NO_ERROR_FEEDBACK) != 0, sid = (cfg->flags & DS_FLAG_SERVER_IDENTITY) != 0;
+        if ((nofb || sid) && (cfg->comp == DS_COMP_IDENTITY || cfg->comp == DS_COMP_RSPARSE)) return DS_ERR_UNSUPPORTED;
+        if (cfg->comp == DS_COMP_TERNARY && !(nofb && sid)) return DS_ERR_UNSUPPORTED;
+        if (cfg->comp == DS_COMP_TOPK && nofb && !(sid && cfg->grad_dtype == DS_F32)) return DS_ERR_UNSUPPORTED;
     }
     ds_ctx *c = new (std::nothrow) ds_ctx();
     if (!c) return DS_ERR_DEVICE;
@@ -126,8 +148,11 @@ ds_status_t ds_create(const ds_config_t *cfg, ds_ctx_t **out)
     c->n_tiles = (cfg->d + 2047) / 2048;
     c->S = 0;
     c->inv_n = 1.0f / static_cast<float>(cfg->n);
+    c->nofb = (cfg->flags & DS_FLAG_NO_ERROR_FEEDBACK) != 0;
+    c->sid = (cfg->flags & DS_FLAG_SERVER_IDENTITY) != 0;
     c->topk = nullptr;
     c->rs = nullptr;
+    c->tern = nullptr;
     c->sign_tb_mem = nullptr;
     c->sign_partials = nullptr;
     ds_status_t rc = DS_OK;
@@ -139,6 +164,9 @@ ds_status_t ds_create(const ds_config_t *cfg, ds_ctx_t **out)
         rc = ds_topk_init(c);
     } else if (cfg->comp == DS_COMP_RSPARSE) {
         rc = ds_rsparse_init(c);
+    } else if (cfg->comp == DS_COMP_TERNARY) {
+        c->S = 1;
+        rc = ds_ternary_init(c);
     }
     c->cfg.seg_offsets = nullptr;
     if (rc != DS_OK) {
@@ -156,6 +184,7 @@ ds_status_t ds_destroy(ds_ctx_t *c)
     ds_sign_fini(c);
     ds_topk_fini(c);
     ds_rsparse_fini(c);
+    ds_ternary_fini(c);
     delete c;
     return DS_OK;
 }
@@ -195,6 +224,11 @@ ds_status_t ds_payload_sizes(const ds_ctx_t *c, int32_t rows, size_t bytes_out[5
         bytes_out[0] = r * static_cast<size_t>(c->W) * sizeof(uint64_t);
         bytes_out[4] = r * d * sizeof(float);
         break;
+    case DS_COMP_TERNARY:
+        bytes_out[0] = r * static_cast<size_t>(c->W) * sizeof(uint64_t);
+        bytes_out[1] = r * sizeof(float);
+        bytes_out[2] = r * static_cast<size_t>(c->W) * sizeof(uint64_t);
+        break;
     }
     return DS_OK;
 }
@@ -202,7 +236,9 @@ ds_status_t ds_payload_sizes(const ds_ctx_t *c, int32_t rows, size_t bytes_out[5
 ds_status_t ds_worker_compress(ds_ctx_t *c, uint64_t step, const void *g, int64_t g_row_stride, float *delta,
                                int64_t delta_row_stride, const ds_payload_t *out, void *hip_stream)
 {
-    if (!c || !g || !delta) return DS_ERR_NULL;
+    if (!c || !g) return DS_ERR_NULL;
+    if (c->nofb) { delta = nullptr; delta_row_stride = c->cfg.d; }   // no error buffer in this mode
+    else if (!delta) return DS_ERR_NULL;
     ds_status_t rc = check_payload(c, out);
     if (rc != DS_OK) return rc;
     if (g_row_stride < c->cfg.d || delta_row_stride < c->cfg.d) return DS_ERR_SHAPE;
@@ -217,22 +253,39 @@ ds_status_t ds_worker_compress(ds_ctx_t *c, uint64_t step, const void *g, int64_
     case DS_COMP_QSGD: return ds_qsgd_worker(c, step, g, g_row_stride, delta, delta_row_stride, out, st);
     case DS_COMP_CLIP: return ds_clip_worker(c, g, g_row_stride, delta, delta_row_stride, out, st);
     case DS_COMP_RSPARSE: return ds_rsparse_worker(c, step, g, g_row_stride, delta, delta_row_stride, out, st);
+    case DS_COMP_TERNARY: return ds_ternary_worker(c, step, g, g_row_stride, out, st);
     }
     return DS_ERR_CONFIG;
+}
+
+// Server that does not compress: one kernel per compressor decodes, averages, writes and updates.
+static ds_status_t server_identity(ds_ctx *c, const ds_payload_t *in, float *dense_out, ds_update_args u, hipStream_t st)
+{
+    switch (c->cfg.comp) {
+    case DS_COMP_SIGN: return ds_sign_server_identity(c, in, dense_out, u, st);
+    case DS_COMP_TOPK: return ds_topk_server_identity(c, in, dense_out, u, st);
+    case DS_COMP_QSGD: return ds_qsgd_server_identity(c, in, dense_out, u, st);
+    case DS_COMP_CLIP: return ds_clip_server_identity(c, in, dense_out, u, st);
+    case DS_COMP_TERNARY: return ds_ternary_server_identity(c, in, dense_out, u, st);
+    default: return DS_ERR_UNSUPPORTED;
+    }
 }
 
 ds_status_t ds_server_aggregate_compress(ds_ctx_t *c, uint64_t step, const ds_payload_t *in, float *delta_s,
                                          const ds_payload_t *out, void *hip_stream)
 {
-    if (!c || !delta_s) return DS_ERR_NULL;
+    if (!c) return DS_ERR_NULL;
+    if (c->nofb || c->sid) delta_s = nullptr;                         // no server error in these modes
+    else if (!delta_s) return DS_ERR_NULL;
     ds_status_t rc = check_payload(c, in);
     if (rc != DS_OK) return rc;
-    rc = check_payload(c, out);
+    rc = check_server_payload(c, out);
     if (rc != DS_OK) return rc;
     if (misaligned(delta_s)) return DS_ERR_ALIGN;
     DeviceGuard guard(c->device);
     if (!guard.ok) return DS_ERR_DEVICE;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (c->sid) return server_identity(c, in, out->dense, ds_update_args{nullptr, nullptr, 0.f, 0.f}, st);
     switch (c->cfg.comp) {
     case DS_COMP_IDENTITY: return ds_identity_server(c, in, delta_s, out, st);
     case DS_COMP_SIGN: return ds_sign_server(c, in, delta_s, out, st);
@@ -240,6 +293,7 @@ ds_status_t ds_server_aggregate_compress(ds_ctx_t *c, uint64_t step, const ds_pa
     case DS_COMP_QSGD: return ds_qsgd_server(c, step, in, delta_s, out, st);
     case DS_COMP_CLIP: return ds_clip_server(c, in, delta_s, out, st);
     case DS_COMP_RSPARSE: return ds_rsparse_server(c, step, in, delta_s, out, st);
+    case DS_COMP_TERNARY: return DS_ERR_UNSUPPORTED;                  // built with the uncompressed server only
     }
     return DS_ERR_CONFIG;
 }
@@ -248,12 +302,13 @@ ds_status_t ds_apply_update(ds_ctx_t *c, const ds_payload_t *srv, float *x, floa
                             void *hip_stream)
 {
     if (!c || !x) return DS_ERR_NULL;
-    ds_status_t rc = check_payload(c, srv);
+    ds_status_t rc = check_server_payload(c, srv);
     if (rc != DS_OK) return rc;
     if (misaligned(x) || (m && misaligned(m))) return DS_ERR_ALIGN;
     DeviceGuard guard(c->device);
     if (!guard.ok) return DS_ERR_DEVICE;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (c->sid) return ds_identity_update(c, srv, x, m, gamma, beta, st);   // the message is the dense average
     switch (c->cfg.comp) {
     case DS_COMP_IDENTITY: return ds_identity_update(c, srv, x, m, gamma, beta, st);
     case DS_COMP_SIGN: return ds_sign_update(c, srv, x, m, gamma, beta, st);
@@ -261,6 +316,7 @@ ds_status_t ds_apply_update(ds_ctx_t *c, const ds_payload_t *srv, float *x, floa
     case DS_COMP_QSGD: return ds_qsgd_update(c, srv, x, m, gamma, beta, st);
     case DS_COMP_CLIP: return ds_clip_update(c, srv, x, m, gamma, beta, st);
     case DS_COMP_RSPARSE: return ds_rsparse_update(c, srv, x, m, gamma, beta, st);
+    case DS_COMP_TERNARY: return DS_ERR_UNSUPPORTED;
     }
     return DS_ERR_CONFIG;
 }
@@ -269,13 +325,16 @@ ds_status_t ds_decompress(ds_ctx_t *c, const ds_payload_t *p, int32_t rows, int3
                           void *hip_stream)
 {
     if (!c || !dense_out) return DS_ERR_NULL;
-    ds_status_t rc = check_payload(c, p);
+    // one message under DS_FLAG_SERVER_IDENTITY with only `dense` set is the server's
+    const bool server_dense = c->sid && rows == 1 && p && p->dense && !p->sign_words && !p->levels && !p->pairs;
+    ds_status_t rc = server_dense ? check_server_payload(c, p) : check_payload(c, p);
     if (rc != DS_OK) return rc;
     if (rows < 1 || row < 0 || row >= rows) return DS_ERR_SHAPE;
     if (misaligned(dense_out)) return DS_ERR_ALIGN;
     DeviceGuard guard(c->device);
     if (!guard.ok) return DS_ERR_DEVICE;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (server_dense) return ds_identity_decode(c, p, 0, dense_out, st);
     switch (c->cfg.comp) {
     case DS_COMP_IDENTITY: return ds_identity_decode(c, p, row, dense_out, st);
     case DS_COMP_SIGN: return ds_sign_decode(c, p, row, dense_out, st);
@@ -283,6 +342,7 @@ ds_status_t ds_decompress(ds_ctx_t *c, const ds_payload_t *p, int32_t rows, int3
     case DS_COMP_QSGD: return ds_qsgd_decode(c, p, row, dense_out, st);
     case DS_COMP_CLIP: return ds_clip_decode(c, p, row, dense_out, st);
     case DS_COMP_RSPARSE: return ds_rsparse_decode(c, p, row, dense_out, st);
+    case DS_COMP_TERNARY: return ds_ternary_decode(c, p, row, dense_out, st);
     }
     return DS_ERR_CONFIG;
 }
@@ -291,12 +351,19 @@ ds_status_t ds_server_aggregate_compress_update(ds_ctx_t *c, uint64_t step, cons
                                                 const ds_payload_t *out, float *x, float *m, float gamma, float beta,
                                                 void *hip_stream)
 {
-    if (!c || !delta_s || !x) return DS_ERR_NULL;
+    if (!c || !x) return DS_ERR_NULL;
+    if (c->nofb || c->sid) delta_s = nullptr;
+    else if (!delta_s) return DS_ERR_NULL;
     ds_status_t rc = check_payload(c, in);
     if (rc != DS_OK) return rc;
-    rc = check_payload(c, out);
+    rc = check_server_payload(c, out, false);
     if (rc != DS_OK) return rc;
     if (misaligned(delta_s) || misaligned(x) || (m && misaligned(m))) return DS_ERR_ALIGN;
+    if (c->sid) {
+        DeviceGuard guard(c->device);
+        if (!guard.ok) return DS_ERR_DEVICE;
+        return server_identity(c, in, out->dense, ds_update_args{x, m, gamma, beta}, static_cast<hipStream_t>(hip_stream));
+    }
     if (c->cfg.comp == DS_COMP_TOPK && !m) {
         // the kept entries of the server's message are the update: applied where they are emitted
         DeviceGuard guard(c->device);

@@ -274,4 +274,17 @@ __device__ __forceinline__ void apply_q4(f32x4 q, int64_t e, int64_t d, float *x
     }
 }
 
+// Server that sends its average back uncompressed: a = (1/n) sum_i Q[v_i] for elements e..e+3 is
+// the message.  dense_out != nullptr: written there; x != nullptr: the model update from it
+// (through the momentum buffer if m != nullptr).
+__device__ __forceinline__ void put_average4(f32x4 a, int64_t e, int64_t d, float *dense_out, float *x, float *m,
+                                             float gamma, float beta)
+{
+    if (dense_out) st4(dense_out, e, d, aligned16(dense_out), a);
+    if (x) {
+        if (m) apply_q4<true, false>(a, e, d, x, m, gamma, beta);
+        else apply_q4<false, false>(a, e, d, x, m, gamma, beta);
+    }
+}
+
 }  // namespace ds

@@ -29,6 +29,14 @@ struct ds_sign_tables {
 
 struct ds_topk_scratch;  // defined in topk.hip
 struct ds_rs_scratch;    // defined in rsparse.hip
+struct ds_tern_scratch;  // defined in ternary.hip
+
+// What the update of Algorithm 1 needs when it rides along with a server kernel; x == nullptr:
+// no update.
+struct ds_update_args {
+    float *x, *m;
+    float gamma, beta;
+};
 
 struct ds_ctx {
     ds_config_t cfg;
@@ -37,6 +45,8 @@ struct ds_ctx {
     int64_t S;        // scale groups per row (SIGN) / buckets per row (QSGD)
     int64_t n_tiles;  // ceil(d / 2048)
     float inv_n;
+    bool nofb;        // DS_FLAG_NO_ERROR_FEEDBACK: no error buffer is read or written
+    bool sid;         // DS_FLAG_SERVER_IDENTITY: the server's message is its dense average
     // SIGN
     bool sign_fused;  // every group is one chunk handled by one workgroup
     ds_sign_tables sign_tb;
@@ -51,6 +61,8 @@ struct ds_ctx {
     ds_topk_scratch *topk;
     // RSPARSE
     ds_rs_scratch *rs;
+    // TERNARY
+    ds_tern_scratch *tern;
 };
 
 #define DS_HIP_TRY(expr)                                 \
@@ -85,6 +97,21 @@ ds_status_t ds_sign_update(ds_ctx *c, const ds_payload_t *srv, float *x, float *
                            float beta, hipStream_t st);
 ds_status_t ds_sign_decode(ds_ctx *c, const ds_payload_t *p, int32_t row, float *out, hipStream_t st);
 ds_status_t ds_sign_materialize(ds_ctx *c, float *delta, int64_t dstr, float *delta_s, hipStream_t st);
+
+// Server without compression (DS_FLAG_SERVER_IDENTITY), per compressor: decodes the n messages,
+// averages them by the chain from +0, writes the average to dense_out (if not null) and applies
+// the update (if u.x is not null), all in one kernel.
+ds_status_t ds_sign_server_identity(ds_ctx *c, const ds_payload_t *in, float *dense_out, ds_update_args u, hipStream_t st);
+ds_status_t ds_qsgd_server_identity(ds_ctx *c, const ds_payload_t *in, float *dense_out, ds_update_args u, hipStream_t st);
+ds_status_t ds_clip_server_identity(ds_ctx *c, const ds_payload_t *in, float *dense_out, ds_update_args u, hipStream_t st);
+ds_status_t ds_topk_server_identity(ds_ctx *c, const ds_payload_t *in, float *dense_out, ds_update_args u, hipStream_t st);
+ds_status_t ds_ternary_server_identity(ds_ctx *c, const ds_payload_t *in, float *dense_out, ds_update_args u, hipStream_t st);
+
+// ternary.hip
+ds_status_t ds_ternary_init(ds_ctx *c);
+void ds_ternary_fini(ds_ctx *c);
+ds_status_t ds_ternary_worker(ds_ctx *c, uint64_t step, const void *g, int64_t gs, const ds_payload_t *out, hipStream_t st);
+ds_status_t ds_ternary_decode(ds_ctx *c, const ds_payload_t *p, int32_t row, float *out, hipStream_t st);
 
 // qsgd.hip
 ds_status_t ds_qsgd_worker(ds_ctx *c, uint64_t step, const void *g, int64_t gs, float *delta,

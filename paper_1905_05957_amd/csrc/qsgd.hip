@@ -131,8 +131,9 @@ __device__ __forceinline__ f32x4 decode4(uint32_t codes, uint32_t nib, float uni
     return q;
 }
 
-// Worker block of Algorithm 1 with Q = randomised quantisation.
-template <bool BF16>
+// Worker block of Algorithm 1 with Q = randomised quantisation.  NOFB: without compensation,
+// v = g; no error buffer is touched.
+template <bool BF16, bool NOFB>
 __global__ __launch_bounds__(kBlock) void k_qsgd_worker(const void *g, int64_t gs, float *delta, int64_t dstr,
                                                         QParams P, uint8_t *levels, uint64_t *words, float *norms)
 {
@@ -142,24 +143,30 @@ __global__ __launch_bounds__(kBlock) void k_qsgd_worker(const void *g, int64_t g
     const int64_t e = static_cast<int64_t>(blockIdx.x) * kTile + threadIdx.x * 4;
     const void *grow = BF16 ? static_cast<const void *>(static_cast<const uint16_t *>(g) + row * gs)
                             : static_cast<const void *>(static_cast<const float *>(g) + row * gs);
-    float *drow = delta + row * dstr;
+    float *drow = NOFB ? nullptr : delta + row * dstr;
     const bool gvec = BF16 ? aligned8(grow) : aligned16(grow);
     const bool dvec = aligned16(drow);
-    const f32x4 v = ld4_grad<BF16>(grow, e, P.d, gvec) + ld4_stream(drow, e, P.d, dvec);
+    f32x4 v = ld4_grad<BF16>(grow, e, P.d, gvec);
+    if constexpr (!NOFB) v = v + ld4_stream(drow, e, P.d, dvec);
     const f32x4 q = quantise4(v, e, static_cast<uint32_t>(row), P, levels + row * ((P.d + 1) / 2),
                               words + row * P.W, norms + row * P.Bq, lds, sw_lds);
-    if (e < P.d) st4_stream(drow, e, P.d, dvec, v - q);
+    if constexpr (!NOFB)
+        if (e < P.d) st4_stream(drow, e, P.d, dvec, v - q);
 }
 
 // Parameter-server block: v = delta_s + (1/n) sum_i decode(msg_i) as the fma chain over
 // workers in ascending order, then the same quantiser on the server's stream.
 // UPD: 0 = that block alone; 1, 2 = followed by the model update of Algorithm 1 for the same
 // elements (2: through the momentum buffer) from the decoded values the thread already holds.
-template <int UPD>
+// delta_s == nullptr: no server error (chain from +0, nothing stored back).
+// SID: the server does not compress: the average is written to dense_out (if not null) and / or
+// applied to x, m (if x is not null), and nothing else happens.
+template <int UPD, bool SID>
 __global__ __launch_bounds__(kBlock) void k_qsgd_server(const uint8_t *levels_in, const uint64_t *words_in,
                                                         const float *norms_in, int n, float inv_n, float *delta_s,
                                                         QParams P, uint8_t *levels_out, uint64_t *words_out,
-                                                        float *norms_out, float *x, float *m, float gamma, float beta)
+                                                        float *norms_out, float *x, float *m, float gamma, float beta,
+                                                        float *dense_out)
 {
     __shared__ double lds[kWaves];
     __shared__ __attribute__((aligned(16))) uint32_t sw_lds[kWaves * 8];
@@ -171,7 +178,8 @@ __global__ __launch_bounds__(kBlock) void k_qsgd_server(const uint8_t *levels_in
     const int64_t b0 = tile_base >> P.bshift;
     const int my_b = (threadIdx.x * 4) >> P.bshift;
     const int64_t lev_stride = (P.d + 1) / 2;
-    f32x4 a = ld4_stream(delta_s, e, P.d, dvec);
+    f32x4 a = {0.f, 0.f, 0.f, 0.f};
+    if (delta_s) a = ld4_stream(delta_s, e, P.d, dvec);
     f32x4 xv = {0.f, 0.f, 0.f, 0.f}, mv = {0.f, 0.f, 0.f, 0.f};      // fetched up front, beside the error
     if constexpr (UPD != 0) xv = ld4_stream(x, e, P.d, aligned16(x));
     if constexpr (UPD == 2) mv = ld4_stream(m, e, P.d, aligned16(m));
@@ -228,8 +236,12 @@ __global__ __launch_bounds__(kBlock) void k_qsgd_server(const uint8_t *levels_in
         }
     }
     a = zero_past(a, e, P.d);
+    if constexpr (SID) {
+        if (e < P.d) put_average4(a, e, P.d, dense_out, x, m, gamma, beta);
+        return;
+    }
     f32x4 q = quantise4(a, e, kServerStream, P, levels_out, words_out, norms_out, lds, sw_lds);
-    if (e < P.d) st4_stream(delta_s, e, P.d, dvec, a - q);
+    if (delta_s && e < P.d) st4_stream(delta_s, e, P.d, dvec, a - q);
     if constexpr (UPD != 0) {
         if (e < P.d) {
             q = zero_past(q, e, P.d);
@@ -280,10 +292,11 @@ ds_status_t ds_qsgd_worker(ds_ctx *c, uint64_t step, const void *g, int64_t gs, 
     if (!bucket_ok(c->cfg.bucket)) return DS_ERR_UNSUPPORTED;
     const QParams P = make_params(c, step);
     dim3 grid(static_cast<unsigned>(c->n_tiles), static_cast<unsigned>(c->cfg.n));
-    if (c->cfg.grad_dtype == DS_BF16)
-        k_qsgd_worker<true><<<grid, kBlock, 0, st>>>(g, gs, delta, dstr, P, out->levels, out->sign_words, out->scales);
-    else
-        k_qsgd_worker<false><<<grid, kBlock, 0, st>>>(g, gs, delta, dstr, P, out->levels, out->sign_words, out->scales);
+    const bool bf16 = c->cfg.grad_dtype == DS_BF16;
+    if (bf16 && c->nofb) k_qsgd_worker<true, true><<<grid, kBlock, 0, st>>>(g, gs, delta, dstr, P, out->levels, out->sign_words, out->scales);
+    else if (bf16) k_qsgd_worker<true, false><<<grid, kBlock, 0, st>>>(g, gs, delta, dstr, P, out->levels, out->sign_words, out->scales);
+    else if (c->nofb) k_qsgd_worker<false, true><<<grid, kBlock, 0, st>>>(g, gs, delta, dstr, P, out->levels, out->sign_words, out->scales);
+    else k_qsgd_worker<false, false><<<grid, kBlock, 0, st>>>(g, gs, delta, dstr, P, out->levels, out->sign_words, out->scales);
     return ds_launch_status();
 }
 
@@ -295,14 +308,24 @@ ds_status_t ds_qsgd_server(ds_ctx *c, uint64_t step, const ds_payload_t *in, flo
     const QParams P = make_params(c, step);
     const unsigned blocks = static_cast<unsigned>(c->n_tiles);
     if (!x)
-        k_qsgd_server<0><<<blocks, kBlock, 0, st>>>(in->levels, in->sign_words, in->scales, c->cfg.n, c->inv_n, delta_s, P,
-                                                    out->levels, out->sign_words, out->scales, x, m, gamma, beta);
+        k_qsgd_server<0, false><<<blocks, kBlock, 0, st>>>(in->levels, in->sign_words, in->scales, c->cfg.n, c->inv_n, delta_s, P,
+                                                           out->levels, out->sign_words, out->scales, x, m, gamma, beta, nullptr);
     else if (!m)
-        k_qsgd_server<1><<<blocks, kBlock, 0, st>>>(in->levels, in->sign_words, in->scales, c->cfg.n, c->inv_n, delta_s, P,
-                                                    out->levels, out->sign_words, out->scales, x, m, gamma, beta);
+        k_qsgd_server<1, false><<<blocks, kBlock, 0, st>>>(in->levels, in->sign_words, in->scales, c->cfg.n, c->inv_n, delta_s, P,
+                                                           out->levels, out->sign_words, out->scales, x, m, gamma, beta, nullptr);
     else
-        k_qsgd_server<2><<<blocks, kBlock, 0, st>>>(in->levels, in->sign_words, in->scales, c->cfg.n, c->inv_n, delta_s, P,
-                                                    out->levels, out->sign_words, out->scales, x, m, gamma, beta);
+        k_qsgd_server<2, false><<<blocks, kBlock, 0, st>>>(in->levels, in->sign_words, in->scales, c->cfg.n, c->inv_n, delta_s, P,
+                                                           out->levels, out->sign_words, out->scales, x, m, gamma, beta, nullptr);
+    return ds_launch_status();
+}
+
+ds_status_t ds_qsgd_server_identity(ds_ctx *c, const ds_payload_t *in, float *dense_out, ds_update_args u, hipStream_t st)
+{
+    if (!bucket_ok(c->cfg.bucket)) return DS_ERR_UNSUPPORTED;
+    const QParams P = make_params(c, 0);
+    k_qsgd_server<0, true><<<static_cast<unsigned>(c->n_tiles), kBlock, 0, st>>>(
+        in->levels, in->sign_words, in->scales, c->cfg.n, c->inv_n, nullptr, P, nullptr, nullptr, nullptr, u.x, u.m, u.gamma,
+        u.beta, dense_out);
     return ds_launch_status();
 }
 

@@ -129,11 +129,12 @@ __device__ __forceinline__ float fused_finish(f32x4 v, int64_t base, int64_t lim
     if (threadIdx.x == 0) *scale_out = scale;
     flush_sign_words(sw_lds, words_row, base, bit_lim);
     const int64_t e = base + threadIdx.x * 4;
-    if (e < lim) st4_stream(err_row, e, lim, err_vec, sign_error4(v, scale));
+    if (err_row && e < lim) st4_stream(err_row, e, lim, err_vec, sign_error4(v, scale));   // no buffer: no compensation
     return scale;
 }
 
-template <bool BF16, bool RMS>
+// NOFB: Algorithm 1 without compensation, v = g; no error buffer is touched.
+template <bool BF16, bool RMS, bool NOFB>
 __global__ __launch_bounds__(kBlock) void k_sign_chunk_worker(WorkerSrc<BF16> src, float *delta,
                                                               int64_t d, int64_t chunk,
                                                               uint64_t *words, int64_t W,
@@ -146,11 +147,12 @@ __global__ __launch_bounds__(kBlock) void k_sign_chunk_worker(WorkerSrc<BF16> sr
     const int64_t base = ci * chunk;
     const int64_t lim = (base + chunk < d) ? base + chunk : d;
     const void *grow = src.grow(row);
-    float *drow = delta + row * src.delta_stride;
+    float *drow = NOFB ? nullptr : delta + row * src.delta_stride;
     const bool gvec = BF16 ? aligned8(grow) : aligned16(grow);
     const bool dvec = aligned16(drow);
     const int64_t e = base + threadIdx.x * 4;
-    const f32x4 v = ld4_grad<BF16>(grow, e, lim, gvec) + ld4_stream(drow, e, lim, dvec);
+    f32x4 v = ld4_grad<BF16>(grow, e, lim, gvec);
+    if constexpr (!NOFB) v = v + ld4_stream(drow, e, lim, dvec);
     fused_finish<RMS>(v, base, lim, drow, dvec, words + row * W, (lim == d) ? W * 64 : lim,
                       scales + row * S + ci, lds, sw_lds);
 }
@@ -176,7 +178,7 @@ __global__ __launch_bounds__(kBlock) void k_sign_chunk_server(ServerArgs a, floa
         const int64_t ci = static_cast<int64_t>(blockIdx.x) * CPW + c;
         base[c] = ci * chunk;
         lim[c] = (base[c] + chunk < d) ? base[c] + chunk : d;     // base >= d: empty chunk, lim < base
-        v[c] = ld4_stream(delta_s, base[c] + threadIdx.x * 4, lim[c], dvec);
+        v[c] = delta_s ? ld4_stream(delta_s, base[c] + threadIdx.x * 4, lim[c], dvec) : f32x4{0.f, 0.f, 0.f, 0.f};   // no buffer: no server error
     }
     // the update's operands are fetched up front, beside the error: more bytes in flight
     f32x4 xv[CPW], mv[CPW];
@@ -323,7 +325,7 @@ __device__ __forceinline__ void pass1_finish(f32x4 v, int64_t base, int64_t d,
                                              double *__restrict__ partial_row, double *lds, uint32_t *sw_lds)
 {
     const int64_t e = base + threadIdx.x * 4;
-    if (e < d) {
+    if (vrow && e < d) {                     // no buffer: no compensation, v is not needed again
         if constexpr (STREAM) st4_stream(vrow, e, d, vvec, v);
         else st4(vrow, e, d, vvec, v);
     }
@@ -360,13 +362,14 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass1_worker(WorkerSrc<BF16> sr
     const int64_t tile = blockIdx.x;
     const int64_t base = tile * kTile;
     const void *grow = src.grow(row);
-    float *drow = delta + row * src.delta_stride;
+    float *drow = delta ? delta + row * src.delta_stride : nullptr;      // null: no compensation
     const bool gvec = BF16 ? aligned8(grow) : aligned16(grow);
     const bool dvec = aligned16(drow);
     const int64_t e = base + threadIdx.x * 4;
     const TilePieces tp = tile_pieces(tb, tile);
     const int32_t p0 = tp.p0, p1 = tp.p1;
-    f32x4 dl = DEFERRED ? ld4_stream(drow, e, d, dvec) : ld4(drow, e, d, dvec);
+    f32x4 dl = {0.f, 0.f, 0.f, 0.f};
+    if (drow) dl = DEFERRED ? ld4_stream(drow, e, d, dvec) : ld4(drow, e, d, dvec);
     if (DEFERRED && e < d) dl = zero_past(sign_error_tile(dl, e, d, prev_scales + row * S, tb, p0, p1, tp.seg0), e, d);
     const f32x4 v = ld4_grad<BF16>(grow, e, d, gvec) + dl;
     pass1_finish<RMS, DEFERRED>(v, base, d, drow, dvec, words + row * W, W * 64, tb, p0, p1,
@@ -386,7 +389,8 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass1_server(ServerArgs a, floa
     const TilePieces tp = tile_pieces(tb, tile);
     const int32_t p0 = tp.p0, p1 = tp.p1;
     const int64_t e = base + threadIdx.x * 4;
-    f32x4 v = DEFERRED ? ld4_stream(delta_s, e, d, dvec) : ld4(delta_s, e, d, dvec);
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};                                      // no buffer: no server error
+    if (delta_s) v = DEFERRED ? ld4_stream(delta_s, e, d, dvec) : ld4(delta_s, e, d, dvec);
     if (DEFERRED && e < d) v = sign_error_tile(v, e, d, prev_scales, tb, p0, p1, tp.seg0);   // past d: cleared below
     const int lane = lane_id();
     const int64_t wave_first = base + wave_id() * 256;
@@ -503,11 +507,49 @@ __global__ __launch_bounds__(kBlock) void k_sign_update(const uint64_t *__restri
     apply_q4<MOM, DECODE_ONLY>(signed4(q[0], q[1], q[2], q[3], nib), e, d, x, m, gamma, beta);
 }
 
+// Server that does not compress (Section 5.1 "MEM-SGD"): a = (1/n) sum_i Q[v_i] by the chain
+// from +0, per element: the element's bit and the scale of its group from every worker's
+// message.  CHUNKS: the groups are chunks of `chunk` elements (a multiple of 4), else they come
+// from the tile tables.
+template <bool CHUNKS>
+__global__ __launch_bounds__(kBlock) void k_sign_server_identity(ServerArgs a, int64_t d, int64_t chunk, ds_sign_tables tb,
+                                                                 float *dense_out, ds_update_args u)
+{
+    const int64_t tile = blockIdx.x;
+    const int64_t e = tile * kTile + threadIdx.x * 4;
+    if (e >= d) return;
+    int32_t seg[4];
+    if constexpr (CHUNKS) {
+        seg[0] = seg[1] = seg[2] = seg[3] = static_cast<int32_t>(static_cast<uint32_t>(e) / static_cast<uint32_t>(chunk));
+    } else {
+        const TilePieces tp = tile_pieces(tb, tile);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) seg[c] = (tp.seg0 >= 0) ? tp.seg0 : ((e + c < d) ? seg_of(tb, tp.p0, tp.p1, e + c) : 0);
+    }
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < a.n; ++i) {
+        const float *srow = a.scales_in + i * a.S;
+        const uint32_t nib = load_sign_nibble(a.words_in + i * a.W, e);
+        v = fma4(a.inv_n, signed4(srow[seg[0]], srow[seg[1]], srow[seg[2]], srow[seg[3]], nib), v);
+    }
+    put_average4(zero_past(v, e, d), e, d, dense_out, u.x, u.m, u.gamma, u.beta);
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
+ds_status_t ds_sign_server_identity(ds_ctx *c, const ds_payload_t *in, float *dense_out, ds_update_args u, hipStream_t st)
+{
+    const ds_config_t &cfg = c->cfg;
+    ServerArgs a{in->sign_words, in->scales, cfg.n, c->W, c->S, c->inv_n};
+    const unsigned blocks = static_cast<unsigned>(c->n_tiles);
+    if (c->sign_fused) k_sign_server_identity<true><<<blocks, kBlock, 0, st>>>(a, cfg.d, cfg.chunk, c->sign_tb, dense_out, u);
+    else k_sign_server_identity<false><<<blocks, kBlock, 0, st>>>(a, cfg.d, 0, c->sign_tb, dense_out, u);
+    return ds_launch_status();
+}
+
 ds_status_t ds_sign_init(ds_ctx *c)
 {
     const ds_config_t &cfg = c->cfg;
@@ -586,7 +628,7 @@ ds_status_t ds_sign_init(ds_ctx *c)
     c->sign_tb.whole_d = 0;
     if (hipGetLastError() != hipSuccess) return DS_ERR_DEVICE;
     DS_HIP_TRY(hipMalloc(&c->sign_partials, sizeof(double) * n_pieces * static_cast<size_t>(cfg.n)));
-    if (cfg.flags & DS_FLAG_DEFERRED_ERROR) {
+    if ((cfg.flags & DS_FLAG_DEFERRED_ERROR) && !c->nofb) {
         c->sign_defer = true;
         DS_HIP_TRY(hipMalloc(&c->sign_prev_w, sizeof(float) * static_cast<size_t>(S) * cfg.n));
         DS_HIP_TRY(hipMalloc(&c->sign_prev_s, sizeof(float) * static_cast<size_t>(S)));
@@ -622,11 +664,11 @@ ds_status_t ds_sign_worker(ds_ctx *c, const void *g, int64_t gs, float *delta, i
     const bool rms = (cfg.flags & DS_FLAG_SIGN_RMS) != 0;
     if (c->sign_fused) {
         dim3 grid(static_cast<unsigned>(c->S), static_cast<unsigned>(cfg.n));
-        with_flags(bf16, rms, false, [&](auto bf, auto rm, auto) {
-            constexpr bool BF = decltype(bf)::value, RM = decltype(rm)::value;
+        with_flags(bf16, rms, c->nofb, [&](auto bf, auto rm, auto nf) {
+            constexpr bool BF = decltype(bf)::value, RM = decltype(rm)::value, NF = decltype(nf)::value;
             WorkerSrc<BF> src{g, gs, delta, dstr};
-            k_sign_chunk_worker<BF, RM><<<grid, kBlock, 0, st>>>(src, delta, cfg.d, cfg.chunk, out->sign_words, c->W,
-                                                                 out->scales, c->S);
+            k_sign_chunk_worker<BF, RM, NF><<<grid, kBlock, 0, st>>>(src, delta, cfg.d, cfg.chunk, out->sign_words, c->W,
+                                                                     out->scales, c->S);
         });
         return ds_launch_status();
     }
@@ -641,7 +683,7 @@ ds_status_t ds_sign_worker(ds_ctx *c, const void *g, int64_t gs, float *delta, i
         c->sign_partials, c->sign_tb, out->scales, c->S, c->sign_defer ? c->sign_prev_w : nullptr);
     if (c->sign_defer) {
         c->sign_w_deferred = true;   // the buffer now holds v; delta = v - Q[v] is applied by the next load
-    } else {
+    } else if (delta) {
         k_sign_pass2<<<grid, kBlock, 0, st>>>(delta, dstr, cfg.d, out->scales, c->S, c->sign_tb);
     }
     return ds_launch_status();
@@ -674,7 +716,7 @@ ds_status_t ds_sign_server(ds_ctx *c, const ds_payload_t *in, float *delta_s, co
     }
     if (x) return DS_ERR_UNSUPPORTED;   // the caller asks for the fused form on the chunk route only
     dim3 grid(static_cast<unsigned>(c->n_tiles));
-    const bool deferred = c->sign_defer && c->sign_s_deferred;
+    const bool deferred = c->sign_defer && c->sign_s_deferred && delta_s;
     with_flags(deferred, rms, false, [&](auto df, auto rm, auto) {
         constexpr bool DF = decltype(df)::value, RM = decltype(rm)::value;
         k_sign_pass1_server<DF, RM><<<grid, kBlock, 0, st>>>(a, delta_s, cfg.d, out->sign_words, c->sign_tb, c->sign_partials,
@@ -684,7 +726,7 @@ ds_status_t ds_sign_server(ds_ctx *c, const ds_payload_t *in, float *delta_s, co
                                                                           c->sign_defer ? c->sign_prev_s : nullptr);
     if (c->sign_defer) {
         c->sign_s_deferred = true;
-    } else {
+    } else if (delta_s) {
         k_sign_pass2<<<grid, kBlock, 0, st>>>(delta_s, cfg.d, cfg.d, out->scales, c->S, c->sign_tb);
     }
     return ds_launch_status();

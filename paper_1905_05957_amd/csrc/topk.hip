@@ -119,8 +119,10 @@ struct WorkerV {   // v = g + delta
     {
         const void *grow = BF16 ? static_cast<const void *>(static_cast<const uint16_t *>(g) + row * gs)
                                 : static_cast<const void *>(static_cast<const float *>(g) + row * gs);
+        const f32x4 gv = ld4_grad<BF16>(grow, e, d, BF16 ? aligned8(grow) : aligned16(grow));
+        if (!delta) return gv;                                   // no compensation: v = g
         const float *drow = delta + row * dstr;
-        return ld4_grad<BF16>(grow, e, d, BF16 ? aligned8(grow) : aligned16(grow)) + ld4_stream(drow, e, d, aligned16(drow));
+        return gv + ld4_stream(drow, e, d, aligned16(drow));
     }
 };
 
@@ -447,7 +449,9 @@ __global__ __launch_bounds__(kBlock) void k_topk_sample(Src src, int64_t d, int6
 // FALLBACK = false: v from src, stored into buf, candidates with key >= lo_key.
 // FALLBACK = true : rows flagged for the two-look route only; v is read back from buf,
 //                   candidates with bin >= b1.
-template <class Src, bool FALLBACK>
+// WR = false: nothing is stored into buf (the mode without compensation: there is no error
+//             buffer, and the second look of the fallback reads the gradient itself).
+template <class Src, bool FALLBACK, bool WR = true>
 __device__ __forceinline__ void pass1_tile(const Src &src, float *buf, int64_t stride, int64_t d, int64_t n_sub,
                                            uint32_t lo_key, u32x2 *slots, uint32_t *reg_cnt, int64_t n_reg,
                                            int64_t reg_pad, int row, int64_t tile, float *strip, uint32_t *wtot)
@@ -462,7 +466,7 @@ __device__ __forceinline__ void pass1_tile(const Src &src, float *buf, int64_t s
     // The error buffer gets v where the element is no candidate and 0 where it is: most
     // candidates end up kept (delta = 0 there), so the emit pass only has to put v back at
     // the few candidates that are not kept instead of zeroing every kept position.
-    if (e < d) {
+    if (WR && e < d) {
         float *brow = buf + row * stride;
         st4_stream(brow, e, d, aligned16(brow), f32x4{f[0] ? 0.f : v.x, f[1] ? 0.f : v.y, f[2] ? 0.f : v.z, f[3] ? 0.f : v.w});
     }
@@ -487,7 +491,7 @@ __device__ __forceinline__ void pass1_tile(const Src &src, float *buf, int64_t s
     if (threadIdx.x == 0) reg_cnt[row * reg_pad + tile] = total;
 }
 
-template <class Src, bool FALLBACK>
+template <class Src, bool FALLBACK, bool WR = true>
 __global__ __launch_bounds__(kBlock) void k_topk_pass1(Src src, float *buf, int64_t stride, int64_t d, int64_t n_sub,
                                                        const Sel *sel, u32x2 *slots, uint32_t *reg_cnt, int64_t n_reg,
                                                        int64_t reg_pad)
@@ -501,8 +505,8 @@ __global__ __launch_bounds__(kBlock) void k_topk_pass1(Src src, float *buf, int6
     // that exits at once for rows that do not need it and strides over the tiles otherwise
     const uint32_t lo_key = FALLBACK ? (sel[row].b1 << 19) : sel[row].lo_key;
     for (int64_t tile = blockIdx.x; tile < n_reg; tile += gridDim.x)
-        pass1_tile<Src, FALLBACK>(src, buf, stride, d, n_sub, lo_key, slots, reg_cnt, n_reg, reg_pad, row, tile,
-                                  strips[wave_id()], wtot);
+        pass1_tile<Src, FALLBACK, WR>(src, buf, stride, d, n_sub, lo_key, slots, reg_cnt, n_reg, reg_pad, row, tile,
+                                      strips[wave_id()], wtot);
 }
 
 // The server's dense pass (row 0 only): the same work as k_topk_pass1<ServerV, false> with
@@ -515,8 +519,13 @@ __global__ __launch_bounds__(kBlock) void k_topk_pass1(Src src, float *buf, int6
 constexpr int kSpan = 4 * kSub;              // elements per wavefront
 constexpr int kTags = kSub;                  // claim tags per wavefront (128 would let a fourth workgroup share a compute unit; measured: no gain, the pass is bound by instruction issue)
 
+// SID: the server does not compress (its message is the average itself): the wavefront's span
+// of the average, built from +0, is written to `buf` (if not null) and / or applied to the
+// model (u), and the kernel ends there.
+template <bool SID>
 __global__ __launch_bounds__(kBlock) void k_topk_pass1_server(ServerV src, float *buf, int64_t d, const Sel *sel,
-                                                              u32x2 *slots, uint32_t *reg_cnt, int64_t n_reg)
+                                                              u32x2 *slots, uint32_t *reg_cnt, int64_t n_reg,
+                                                              ds_update_args u)
 {
     __shared__ float strips[kWaves][kSpan];
     __shared__ uint32_t tags[kWaves][kTags];
@@ -526,12 +535,13 @@ __global__ __launch_bounds__(kBlock) void k_topk_pass1_server(ServerV src, float
     uint32_t *tag = tags[wv];
     for (int i = lane; i < kTags; i += 64) tag[i] = kNone;
     const int64_t span_base = (static_cast<int64_t>(blockIdx.x) * kWaves + wv) * kSpan;
-    const uint32_t lo_key = sel[0].lo_key;
+    const uint32_t lo_key = SID ? 0u : sel[0].lo_key;
     const bool vec = aligned16(buf);
     f32x4 v[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-        v[c] = ld4_stream(src.delta_s, span_base + c * kSub + lane * 4, d, aligned16(src.delta_s));
+        v[c] = SID ? f32x4{0.f, 0.f, 0.f, 0.f}
+                   : ld4_stream(src.delta_s, span_base + c * kSub + lane * 4, d, aligned16(src.delta_s));
         float *p = strip + c * kSub + lane * 4;
         p[0] = v[c].x; p[1] = v[c].y; p[2] = v[c].z; p[3] = v[c].w;
     }
@@ -588,6 +598,14 @@ __global__ __launch_bounds__(kBlock) void k_topk_pass1_server(ServerV src, float
             const float *p = strip + c * kSub + lane * 4;
             v[c] = f32x4{p[0], p[1], p[2], p[3]};
         }
+    }
+    if constexpr (SID) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int64_t e = span_base + c * kSub + lane * 4;
+            if (e < d) put_average4(v[c], e, d, buf, u.x, u.m, u.gamma, u.beta);
+        }
+        return;
     }
     // classify, store v with 0 at the candidates, count
     uint32_t bits[4][4];
@@ -745,7 +763,7 @@ template <int LEVEL>
 __global__ __launch_bounds__(kBlock) void k_topk_cand_hist(const u32x2 *slots, const uint32_t *reg_cnt, int64_t n_reg,
                                                            int64_t reg_pad, int64_t n_groups, Sel *sel,
                                                            uint32_t *hist, uint32_t *done, uint32_t k, uint32_t *prev_T,
-                                                           float *buf, int64_t stride)
+                                                           float *buf, int64_t stride, bool wr)
 {
     constexpr int NB = (LEVEL == 1) ? kH1W : (LEVEL == 2) ? kH2 : kH3;
     constexpr int OFF = (LEVEL == 1) ? kOffH1 : (LEVEL == 2) ? kOffH2 : kOffH3;
@@ -783,7 +801,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_hist(const u32x2 *slots, c
         pick_level<LEVEL>(hrow, sel + row, k, part, out, prev_T + row);
         if (LEVEL == 1) {
             __syncthreads();
-            if (out[2]) restore_row(slots, reg_cnt, n_reg, reg_pad, row, buf, stride);
+            if (out[2] && wr) restore_row(slots, reg_cnt, n_reg, reg_pad, row, buf, stride);
         }
     }
 }
@@ -898,8 +916,8 @@ __device__ __forceinline__ bool emit_batch(u32x2 pr, bool valid, uint32_t T, uin
     if (keep) {
         const uint32_t slot = out + lanes_below(keep_mask);
         if (slot < k) prow[slot] = pr;
-    } else if (valid) {
-        __builtin_nontemporal_store(__uint_as_float(pr.y), brow + pr.x);   // not kept: delta = v
+    } else if (valid && brow) {
+        __builtin_nontemporal_store(__uint_as_float(pr.y), brow + pr.x);   // not kept: delta = v (no buffer: no compensation)
     }
     out += __popcll(keep_mask);
     eq_seen += __popcll(eq_mask);
@@ -933,7 +951,8 @@ __device__ __forceinline__ void emit_group(const GroupWalk &w, const u32x2 *__re
 __global__ __launch_bounds__(kBlock) void k_topk_emit(const u32x2 *slots, const uint32_t *reg_cnt, int64_t n_reg,
                                                       int64_t reg_pad, int64_t n_groups, const Sel *sel,
                                                       const uint32_t *grp_eqb, const uint32_t *grp_out, int64_t k,
-                                                      u32x2 *pairs, float *buf, int64_t stride, float *x, float gamma)
+                                                      u32x2 *pairs, float *buf, int64_t stride, float *x, float gamma,
+                                                      bool wr)
 {
     const int row = blockIdx.y;
     const int64_t g = static_cast<int64_t>(blockIdx.x) * kWaves + wave_id();
@@ -941,7 +960,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_emit(const u32x2 *slots, const 
     const Sel s = sel[row];
     const GroupWalk w = group_begin(reg_cnt + row * reg_pad, g, n_reg);
     emit_group(w, slots + static_cast<int64_t>(row) * n_reg * kReg, g, s.T, s.k3, grp_eqb[row * n_groups + g],
-               grp_out[row * n_groups + g], pairs + static_cast<int64_t>(row) * k, buf + row * stride, k, x, gamma);
+               grp_out[row * n_groups + g], pairs + static_cast<int64_t>(row) * k, wr ? buf + row * stride : nullptr, k, x, gamma);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1136,6 +1155,7 @@ struct FinishArgs {
     uint32_t *grp_gt, *grp_eq;
     uint32_t *prev_T;
     float *buf;
+    bool wr;               // false: buf is read only (no compensation: it is the gradient) and nothing is stored into it
     int64_t stride, d, k;
     u32x2 *pairs;
     float *x;              // not null: the model update is applied with the emission (one-row launches only)
@@ -1158,7 +1178,8 @@ __global__ __launch_bounds__(kBlock, 8) void k_topk_finish(FinishArgs a)
     uint32_t *fh = a.fhist + static_cast<int64_t>(row) * kFRow;
     u32x2 *srow = a.slots + static_cast<int64_t>(row) * a.n_reg * kReg;
     uint32_t *cnt_row = a.reg_cnt + row * a.reg_pad;
-    float *brow = a.buf + row * a.stride;
+    float *brow = a.buf + row * a.stride;          // read by the two-look route
+    float *wrow = a.wr ? brow : nullptr;           // where candidates that are not kept get v back
     const uint32_t k32 = static_cast<uint32_t>(a.k);
     {
         const int64_t first = (static_cast<int64_t>(blockIdx.y) * G + blockIdx.x) * kBlock + threadIdx.x;
@@ -1197,7 +1218,8 @@ __global__ __launch_bounds__(kBlock, 8) void k_topk_finish(FinishArgs a)
         for (int64_t tile = blockIdx.x; tile < a.n_reg; tile += G) {
             const uint32_t cnt = cnt_row[tile];
             const u32x2 *src = srow + tile * kReg;
-            for (uint32_t i = threadIdx.x; i < cnt; i += kBlock) brow[src[i].x] = __uint_as_float(src[i].y);
+            if (a.wr)
+                for (uint32_t i = threadIdx.x; i < cnt; i += kBlock) brow[src[i].x] = __uint_as_float(src[i].y);
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
             const int64_t e = tile * kTile + threadIdx.x * 4;
@@ -1217,9 +1239,14 @@ __global__ __launch_bounds__(kBlock, 8) void k_topk_finish(FinishArgs a)
         if (b1 == kNone) { raise_abort(a.abort_flag); return; }       // cannot happen: k <= d
         lo_key = b1 << 19;
         const BufferV bsrc{a.buf, a.stride};
-        for (int64_t tile = blockIdx.x; tile < a.n_reg; tile += G)
-            pass1_tile<BufferV, true>(bsrc, a.buf, a.stride, a.d, a.n_sub, lo_key, a.slots, a.reg_cnt, a.n_reg, a.reg_pad,
-                                      row, tile, nullptr, wtot);
+        for (int64_t tile = blockIdx.x; tile < a.n_reg; tile += G) {
+            if (a.wr)
+                pass1_tile<BufferV, true, true>(bsrc, a.buf, a.stride, a.d, a.n_sub, lo_key, a.slots, a.reg_cnt, a.n_reg,
+                                                a.reg_pad, row, tile, nullptr, wtot);
+            else
+                pass1_tile<BufferV, true, false>(bsrc, a.buf, a.stride, a.d, a.n_sub, lo_key, a.slots, a.reg_cnt, a.n_reg,
+                                                 a.reg_pad, row, tile, nullptr, wtot);
+        }
         // the new candidate lists cross workgroups (and their caches) from here on
         __threadfence();
         if (!row_barrier(rs, kResCompact)) return;
@@ -1316,7 +1343,7 @@ __global__ __launch_bounds__(kBlock, 8) void k_topk_finish(FinishArgs a)
                     const uint32_t i = j * 64 + lane_id();
                     const bool valid = i < wc.total;
                     const u32x2 pr = valid ? u32x2{base + wc.rel[i], wc.bits[i]} : u32x2{0u, 0u};
-                    if (emit_batch(pr, valid, T, k3, eq_seen, out_slot, prow, brow, a.k)) kept |= 1u << j;
+                    if (emit_batch(pr, valid, T, k3, eq_seen, out_slot, prow, wrow, a.k)) kept |= 1u << j;
                 }
                 if (a.x) {
                     // the model update at the kept entries: all loads first (the entries of a
@@ -1332,7 +1359,7 @@ __global__ __launch_bounds__(kBlock, 8) void k_topk_finish(FinishArgs a)
                 }
             } else {
                 const GroupWalk w = group_begin(cnt_row, g, a.n_reg);
-                emit_group(w, srow, g, T, k3, eqb, out_slot, prow, brow, a.k, a.x, a.gamma);
+                emit_group(w, srow, g, T, k3, eqb, out_slot, prow, wrow, a.k, a.x, a.gamma);
             }
         }
     }
@@ -1404,9 +1431,11 @@ unsigned persistent_blocks(int64_t n_tiles, int rows)
 }
 
 // sample -> dense pass -> refinement -> ordered emission, for `rows` vectors
+// wr = false: buf is the vector v itself, read only (no compensation: v = g), for the second look
+// of the exact route; nothing is stored into it.
 template <class Src>
 ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t stride, u32x2 *pairs, hipStream_t st,
-                       uint32_t *prev_T, float *x = nullptr, float gamma = 0.f)
+                       uint32_t *prev_T, float *x = nullptr, float gamma = 0.f, bool wr = true)
 {
     ds_topk_scratch *t = c->topk;
     if (__atomic_load_n(t->abort_host, __ATOMIC_RELAXED)) {
@@ -1442,10 +1471,12 @@ ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t 
     k_topk_sample<Src><<<dim3(static_cast<unsigned>((ns + kWaves - 1) / kWaves), rows), kBlock, 0, st>>>(
         src, d, n_sub, ns, hist, t->sel, t->done, rank, prev_T, reinterpret_cast<uint32_t *>(t->sync));
     if constexpr (std::is_same<Src, ServerV>::value)
-        k_topk_pass1_server<<<dim3(static_cast<unsigned>((n_reg + 3) / 4)), kBlock, 0, st>>>(src, buf, d, t->sel, t->slots,
-                                                                                         t->reg_cnt, n_reg);
+        k_topk_pass1_server<false><<<dim3(static_cast<unsigned>((n_reg + 3) / 4)), kBlock, 0, st>>>(
+            src, buf, d, t->sel, t->slots, t->reg_cnt, n_reg, ds_update_args{nullptr, nullptr, 0.f, 0.f});
+    else if (wr)
+        k_topk_pass1<Src, false, true><<<dense, kBlock, 0, st>>>(src, buf, stride, d, n_sub, t->sel, t->slots, t->reg_cnt, n_reg, reg_pad);
     else
-        k_topk_pass1<Src, false><<<dense, kBlock, 0, st>>>(src, buf, stride, d, n_sub, t->sel, t->slots, t->reg_cnt, n_reg, reg_pad);
+        k_topk_pass1<Src, false, false><<<dense, kBlock, 0, st>>>(src, buf, stride, d, n_sub, t->sel, t->slots, t->reg_cnt, n_reg, reg_pad);
     if (t->capacity >= rows) {
         // everything after the dense pass in one launch whose workgroups are all resident
         int64_t G = t->capacity / rows;
@@ -1455,25 +1486,29 @@ ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t 
         a.n_reg = n_reg; a.reg_pad = reg_pad; a.n_groups = n_groups; a.n_sub = n_sub;
         a.sel = t->sel; a.fhist = t->fhist; a.sync = t->sync; a.abort_flag = t->abort_host; a.spin_limit = t->spin_limit;
         a.grp_gt = t->grp_gt; a.grp_eq = t->grp_eq; a.prev_T = prev_T;
-        a.buf = buf; a.stride = stride; a.d = d; a.k = k; a.pairs = pairs; a.x = x; a.gamma = gamma;
+        a.buf = buf; a.wr = wr; a.stride = stride; a.d = d; a.k = k; a.pairs = pairs; a.x = x; a.gamma = gamma;
         a.zero_a = hist; a.zero_a_words = static_cast<int64_t>(rows) * kHistRow;
         k_topk_finish<<<dim3(static_cast<unsigned>(G), rows), kBlock, 0, st>>>(a);
         return ds_launch_status();
     }
-    k_topk_cand_hist<1><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32, prev_T, buf, stride);
+    k_topk_cand_hist<1><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32, prev_T, buf, stride, wr);
     // two-look route for rows whose sample misjudged; both launches exit at once otherwise
     k_topk_fallback_hist<<<dim3(persistent_blocks(c->n_tiles, rows), rows), kBlock, 0, st>>>(buf, stride, d, c->n_tiles,
                                                                                             t->sel, hist, t->done, k32);
-    k_topk_pass1<BufferV, true><<<dim3(persistent_blocks(c->n_tiles, rows), rows), kBlock, 0, st>>>(
-        bsrc, buf, stride, d, n_sub, t->sel, t->slots, t->reg_cnt, n_reg, reg_pad);
+    if (wr)
+        k_topk_pass1<BufferV, true, true><<<dim3(persistent_blocks(c->n_tiles, rows), rows), kBlock, 0, st>>>(
+            bsrc, buf, stride, d, n_sub, t->sel, t->slots, t->reg_cnt, n_reg, reg_pad);
+    else
+        k_topk_pass1<BufferV, true, false><<<dim3(persistent_blocks(c->n_tiles, rows), rows), kBlock, 0, st>>>(
+            bsrc, buf, stride, d, n_sub, t->sel, t->slots, t->reg_cnt, n_reg, reg_pad);
     // refinement on the candidates
-    k_topk_cand_hist<2><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32, prev_T, buf, stride);
-    k_topk_cand_hist<3><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32, prev_T, buf, stride);
+    k_topk_cand_hist<2><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32, prev_T, buf, stride, wr);
+    k_topk_cand_hist<3><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32, prev_T, buf, stride, wr);
     k_topk_count<<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, t->grp_gt, t->grp_eq,
                                           t->grp_eqb, t->grp_out, t->done, hist,
                                           static_cast<int64_t>(rows) * kHistRow);
     k_topk_emit<<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, t->grp_eqb, t->grp_out, k,
-                                         pairs, buf, stride, x, gamma);
+                                         pairs, buf, stride, x, gamma, wr);
     return ds_launch_status();
 }
 
@@ -1531,6 +1566,19 @@ ds_status_t ds_topk_init(ds_ctx *c)
     return DS_OK;
 }
 
+// The table of every worker's first entry per 256-element subtile, for the server's dense pass.
+static void build_sub_starts(ds_ctx *c, const u32x2 *pairs_in, hipStream_t st)
+{
+    ds_topk_scratch *t = c->topk;
+    const int64_t k = c->cfg.k;
+    if (k * 4 >= t->n_sub)
+        k_topk_sub_starts_scan<<<dim3(static_cast<unsigned>((k + 1 + kBlock - 1) / kBlock), c->cfg.n), kBlock, 0, st>>>(
+            pairs_in, k, t->n_sub, t->sub_start);
+    else
+        k_topk_sub_starts<<<dim3(static_cast<unsigned>((t->n_sub + 1 + kBlock - 1) / kBlock), c->cfg.n), kBlock, 0, st>>>(
+            pairs_in, k, t->n_sub, t->sub_start);
+}
+
 ds_status_t ds_topk_status(const ds_ctx *c)
 {
     const ds_topk_scratch *t = c->topk;
@@ -1555,8 +1603,28 @@ ds_status_t ds_topk_worker(ds_ctx *c, const void *g, int64_t gs, float *delta, i
 {
     const int rows = c->cfg.n;
     u32x2 *pairs = reinterpret_cast<u32x2 *>(out->pairs);
+    if (!delta) {
+        // no compensation (fp32 gradients only, checked by ds_create): v = g, which also serves
+        // the second look of the exact route; no buffer is written
+        float *gv = static_cast<float *>(const_cast<void *>(g));
+        return run_select(c, rows, WorkerV<false>{g, gs, nullptr, 0}, gv, gs, pairs, st, c->topk->prev_T, nullptr, 0.f, false);
+    }
     if (c->cfg.grad_dtype == DS_BF16) return run_select(c, rows, WorkerV<true>{g, gs, delta, dstr}, delta, dstr, pairs, st, c->topk->prev_T);
     return run_select(c, rows, WorkerV<false>{g, gs, delta, dstr}, delta, dstr, pairs, st, c->topk->prev_T);
+}
+
+// Server that does not compress: the table of the workers' entries per subtile, then one dense
+// pass that builds the average from +0 and writes / applies it.
+ds_status_t ds_topk_server_identity(ds_ctx *c, const ds_payload_t *in, float *dense_out, ds_update_args u, hipStream_t st)
+{
+    ds_topk_scratch *t = c->topk;
+    const u32x2 *pairs_in = reinterpret_cast<const u32x2 *>(in->pairs);
+    const int64_t k = c->cfg.k;
+    build_sub_starts(c, pairs_in, st);
+    const ServerV src{pairs_in, t->sub_start, nullptr, k, t->n_sub, c->cfg.n, c->inv_n};
+    k_topk_pass1_server<true><<<dim3(static_cast<unsigned>((t->n_reg + 3) / 4)), kBlock, 0, st>>>(
+        src, dense_out, c->cfg.d, t->sel, t->slots, t->reg_cnt, t->n_reg, u);
+    return ds_launch_status();
 }
 
 // x != nullptr: also x <- fma(-gamma, val, x) at the kept indices of the server's message.
@@ -1566,12 +1634,7 @@ ds_status_t ds_topk_server(ds_ctx *c, const ds_payload_t *in, float *delta_s, co
     ds_topk_scratch *t = c->topk;
     const u32x2 *pairs_in = reinterpret_cast<const u32x2 *>(in->pairs);
     const int64_t k = c->cfg.k;
-    if (k * 4 >= t->n_sub)
-        k_topk_sub_starts_scan<<<dim3(static_cast<unsigned>((k + 1 + kBlock - 1) / kBlock), c->cfg.n), kBlock, 0, st>>>(
-            pairs_in, k, t->n_sub, t->sub_start);
-    else
-        k_topk_sub_starts<<<dim3(static_cast<unsigned>((t->n_sub + 1 + kBlock - 1) / kBlock), c->cfg.n), kBlock, 0, st>>>(
-            pairs_in, k, t->n_sub, t->sub_start);
+    build_sub_starts(c, pairs_in, st);
     const ServerV src{pairs_in, t->sub_start, delta_s, k, t->n_sub, c->cfg.n, c->inv_n};
     return run_select(c, 1, src, delta_s, c->cfg.d, reinterpret_cast<u32x2 *>(out->pairs), st, t->prev_T + t->rows, x, gamma);
 }

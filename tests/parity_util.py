@@ -26,7 +26,7 @@ def keep_prob_24(p: float) -> float:
 
 def oracle_config(wl) -> O.Config:
     comp = {"identity": O.IDENTITY, "sign": O.SIGN, "topk": O.TOPK, "qsgd": O.QSGD, "clip": O.CLIP,
-            "rsparse": O.RSPARSE}[wl.comp]
+            "rsparse": O.RSPARSE, "ternary": O.TERNARY}[wl.comp]
     return O.Config(comp, n=wl.n, d=wl.d, grad_bf16=(wl.grad_dtype == "bf16"),
                     group_off=wl.group_offsets() if wl.comp == "sign" else None,
                     k=wl.k, bucket=wl.bucket, levels=wl.levels, seed=wl.seed, sign_rms=wl.sign_rms,
@@ -96,18 +96,25 @@ def assert_payload_equal(gpu: dict, ref: dict, what: str):
 
 
 class Pair:
-    """GPU state + the means to run one compared step."""
+    """GPU state + the means to run one compared step.
+
+    The library's two mode flags have no counterpart in the oracle, which stays a composition of
+    its plain functions: without compensation the oracle's worker and server start from zero
+    error buffers that are thrown away; a server that does not compress is the oracle's identity
+    compressor fed with the decoded worker messages."""
 
     def __init__(self, wl, device):
         self.wl, self.dev = wl, device
         self.ctx = gpu_context(wl)
         self.cfg = oracle_config(wl)
-        self.delta = wl.initial_delta(device)
-        self.delta_s = torch.zeros(wl.d, dtype=torch.float32, device=device)
+        self.nofb, self.sid = self.ctx.no_error_feedback, self.ctx.server_identity
+        self.ident = O.Config(O.IDENTITY, n=wl.n, d=wl.d)
+        self.delta = None if self.nofb else wl.initial_delta(device)
+        self.delta_s = None if (self.nofb or self.sid) else torch.zeros(wl.d, dtype=torch.float32, device=device)
         self.x = wl.initial_x(device)
         self.m = torch.zeros(wl.d, dtype=torch.float32, device=device) if wl.beta is not None else None
         self.pw = self.ctx.alloc_payload(wl.n, device)
-        self.ps = self.ctx.alloc_payload(1, device)
+        self.ps = self.ctx.alloc_server_payload(device)
 
     def gpu_step(self, t: int, g: torch.Tensor):
         self.ctx.worker_compress(t, g, self.delta, self.pw)
@@ -115,38 +122,48 @@ class Pair:
         self.ctx.apply_update(self.ps, self.x, self.m, self.wl.gamma,
                               0.0 if self.wl.beta is None else self.wl.beta)
 
+    def oracle_server(self, t: int, pw: dict, h_ds: np.ndarray) -> dict:
+        """The oracle's parameter-server block for this pair's mode; h_ds is updated in place."""
+        if self.sid:
+            dense = {"dense": np.stack([O.decode(self.cfg, pw, i) for i in range(self.wl.n)])}
+            return O.server_aggregate_compress(self.ident, t, dense, np.zeros(self.wl.d, np.float32))
+        return O.server_aggregate_compress(self.cfg, t, pw, h_ds)
+
     def compared_step(self, t: int, g: torch.Tensor, tag: str = ""):
         """One step on the GPU and, call by call from the same inputs, on the oracle."""
         wl, cfg = self.wl, self.cfg
+        scfg = self.ident if self.sid else cfg              # what the server's message is encoded with
         tag = f"{wl.name}{tag} t={t}"
         # ---- worker ----
-        h_delta = self.delta.cpu().numpy().copy()
+        h_delta = np.zeros((wl.n, wl.d), np.float32) if self.nofb else self.delta.cpu().numpy().copy()
         h_g = host_grad(g)
         self.ctx.worker_compress(t, g, self.delta, self.pw)
         ref_pw = O.worker_compress(cfg, t, h_g, h_delta)
         gpu_pw = self.pw.to_numpy()
         assert_payload_equal(gpu_pw, ref_pw, tag + " worker payload")
-        assert_close_rows(self.delta.cpu().numpy(), h_delta, tag + " delta")
+        if not self.nofb:
+            assert_close_rows(self.delta.cpu().numpy(), h_delta, tag + " delta")
         # ---- server (the oracle is fed the GPU's worker messages) ----
-        h_ds = self.delta_s.cpu().numpy().copy()
+        h_ds = np.zeros(wl.d, np.float32) if self.delta_s is None else self.delta_s.cpu().numpy().copy()
         self.ctx.server_aggregate_compress(t, self.pw, self.delta_s, self.ps)
-        ref_ps = O.server_aggregate_compress(cfg, t, gpu_pw, h_ds)
+        ref_ps = self.oracle_server(t, gpu_pw, h_ds)
         gpu_ps = self.ps.to_numpy()
         assert_payload_equal(gpu_ps, ref_ps, tag + " server payload")
-        assert_close_rows(self.delta_s.cpu().numpy(), h_ds, tag + " delta_s")
+        if self.delta_s is not None:
+            assert_close_rows(self.delta_s.cpu().numpy(), h_ds, tag + " delta_s")
         # ---- update (the oracle is fed the GPU's server message) ----
         h_x = self.x.cpu().numpy().copy()
         h_m = None if self.m is None else self.m.cpu().numpy().copy()
         beta = 0.0 if wl.beta is None else wl.beta
         self.ctx.apply_update(self.ps, self.x, self.m, wl.gamma, beta)
-        O.apply_update(cfg, gpu_ps, h_x, h_m, wl.gamma, beta)
+        O.apply_update(scfg, gpu_ps, h_x, h_m, wl.gamma, beta)
         assert_close_rows(self.x.cpu().numpy(), h_x, tag + " x")
         if h_m is not None:
             assert_close_rows(self.m.cpu().numpy(), h_m, tag + " m")
         # ---- the decoder the server uses ----
         dec = torch.empty(wl.d, dtype=torch.float32, device=self.dev)
         self.ctx.decompress(self.ps, 0, dec)
-        assert_close_rows(dec.cpu().numpy(), O.decode(cfg, gpu_ps, 0), tag + " decode(server)")
+        assert_close_rows(dec.cpu().numpy(), O.decode(scfg, gpu_ps, 0), tag + " decode(server)")
         row = wl.n - 1
         self.ctx.decompress(self.pw, row, dec)
         assert_close_rows(dec.cpu().numpy(), O.decode(cfg, gpu_pw, row), tag + " decode(worker)")

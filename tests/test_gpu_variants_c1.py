@@ -1,12 +1,16 @@
-"""The paper's comparison algorithms on the least-squares toy, expressed with the same entry
-points (Section 5.1 "Implementations and setups"):
+"""The paper's comparison algorithms on the least-squares toy (Section 5.1 "Implementations and
+setups"), each through the library's mode flags:
   DoubleSqueeze   worker and server compress with error compensation (Algorithm 1);
-  MEM-SGD         workers compress and compensate, the server averages the decoded messages
-                  and sends the average uncompressed;
-  uncompensated   the same compressor with the error memories cleared before every step.
+  MEM-SGD         workers compress and compensate, the server sends its average uncompressed
+                  (DS_FLAG_SERVER_IDENTITY), with the 1-bit and the top-k compressor;
+  Top-k SGD       top-k on the workers without compensation, plain server (both flags);
+  QSGD            the ternary max-norm quantiser without compensation, plain server (both flags);
+  uncompensated   Algorithm 1 with both compressions and no compensation
+                  (DS_FLAG_NO_ERROR_FEEDBACK).
+The oracle has no flags: it runs the same algorithms as compositions of its plain functions.
 GPU and oracle run each variant free for 200 steps; trajectories must agree within 1e-4 and
 show the qualitative picture of Section 5.2 (compensated variants track SGD, the
-uncompensated one lags)."""
+uncompensated ones lag)."""
 import numpy as np
 import pytest
 import torch
@@ -19,68 +23,78 @@ from parity_util import assert_close_rows
 pytestmark = pytest.mark.gpu
 
 STEPS = 200
+K = 32
+SID, NOFB = P.FLAG_SERVER_IDENTITY, P.FLAG_NO_ERROR_FEEDBACK
+
+# variant -> (compressor, flags)
+VARIANTS = {
+    "doublesqueeze": ("sign", 0),
+    "mem_sgd": ("sign", SID),
+    "uncompensated": ("sign", NOFB),
+    "doublesqueeze_topk": ("topk", 0),
+    "mem_sgd_topk": ("topk", SID),
+    "topk_sgd": ("topk", NOFB | SID),
+    "qsgd_ternary": ("ternary", NOFB | SID),
+}
 
 
 def _gpu_run(variant, prob, wl, dev):
+    comp, flags = VARIANTS[variant]
     n, d = wl.n, wl.d
-    ctx = P.Context("sign", n, d)
-    ident = P.Context("identity", n, d)
-    pw, ps = ctx.alloc_payload(n, dev), ctx.alloc_payload(1, dev)
-    dense_w, dense_s = ident.alloc_payload(n, dev), ident.alloc_payload(1, dev)
+    ctx = P.Context(comp, n, d, k=K, seed=wl.seed, flags=flags)
+    pw, ps = ctx.alloc_payload(n, dev), ctx.alloc_server_payload(dev)
     x = torch.zeros(d, device=dev)
-    delta = torch.zeros((n, d), device=dev)
-    delta_s = torch.zeros(d, device=dev)
-    zero_s = torch.zeros(d, device=dev)
+    delta = None if flags & NOFB else torch.zeros((n, d), device=dev)
+    delta_s = None if flags & (NOFB | SID) else torch.zeros(d, device=dev)
     for t in range(STEPS):
         g = torch.from_numpy(prob.gradients(x.cpu().numpy(), t)).to(dev)
-        if variant == "uncompensated":
-            delta.zero_(); delta_s.zero_()
         ctx.worker_compress(t, g, delta, pw)
-        if variant == "mem_sgd":
-            for i in range(n):                               # decode every worker's message
-                ctx.decompress(pw, i, dense_w.dense[i])
-            zero_s.zero_()
-            ident.server_aggregate_compress(t, dense_w, zero_s, dense_s)   # plain average
-            ident.apply_update(dense_s, x, None, wl.gamma)
-        else:
-            ctx.server_aggregate_compress(t, pw, delta_s, ps)
-            ctx.apply_update(ps, x, None, wl.gamma)
-    out = x.cpu().numpy(), delta.cpu().numpy()
-    ctx.close(); ident.close()
+        ctx.server_aggregate_compress(t, pw, delta_s, ps)
+        ctx.apply_update(ps, x, None, wl.gamma)
+    out = x.cpu().numpy(), (None if delta is None else delta.cpu().numpy())
+    ctx.close()
     return out
 
 
 def _oracle_run(variant, prob, wl):
+    comp, flags = VARIANTS[variant]
     n, d = wl.n, wl.d
-    cfg, ident = O.Config(O.SIGN, n=n, d=d), O.Config(O.IDENTITY, n=n, d=d)
+    cfg = O.Config({"sign": O.SIGN, "topk": O.TOPK, "ternary": O.TERNARY}[comp], n=n, d=d, k=K, seed=wl.seed)
+    ident = O.Config(O.IDENTITY, n=n, d=d)
     x = np.zeros(d, np.float32)
     delta = np.zeros((n, d), np.float32)
     delta_s = np.zeros(d, np.float32)
     for t in range(STEPS):
         g = prob.gradients(x, t)
-        if variant == "uncompensated":
-            delta[:] = 0; delta_s[:] = 0
+        if flags & NOFB:                                     # no compensation: the memories start empty every step
+            delta[:] = 0
+            delta_s[:] = 0
         pw = O.worker_compress(cfg, t, g, delta)
-        if variant == "mem_sgd":
+        if flags & SID:                                      # the server averages the decoded messages and sends that
             dense = {"dense": np.stack([O.decode(cfg, pw, i) for i in range(n)])}
             ps = O.server_aggregate_compress(ident, t, dense, np.zeros(d, np.float32))
             O.apply_update(ident, ps, x, None, wl.gamma)
         else:
             ps = O.server_aggregate_compress(cfg, t, pw, delta_s)
             O.apply_update(cfg, ps, x, None, wl.gamma)
-    return x, delta
+    return x, (None if flags & NOFB else delta)
 
 
 def test_comparison_algorithms_on_the_toy(gpu_device):
     wl, prob = W.c1(), W.least_squares()
     f = {}
-    for variant in ("doublesqueeze", "mem_sgd", "uncompensated"):
+    for variant in VARIANTS:
         xg, dg = _gpu_run(variant, prob, wl, gpu_device)
         xo, do = _oracle_run(variant, prob, wl)
         assert_close_rows(xg, xo, f"{variant} x after {STEPS} steps", rel=1e-4)
-        assert_close_rows(dg, do, f"{variant} delta after {STEPS} steps", rel=1e-4)
+        if do is not None:
+            assert_close_rows(dg, do, f"{variant} delta after {STEPS} steps", rel=1e-4)
         f[variant] = prob.loss(xg)
     f0 = prob.loss(np.zeros(wl.d, np.float32))
     assert f["doublesqueeze"] < 0.5 * f0 and f["mem_sgd"] < 0.5 * f0
     assert abs(f["doublesqueeze"] - f["mem_sgd"]) / f["mem_sgd"] < 0.05
     assert f["uncompensated"] > 1.02 * f["doublesqueeze"]
+    # top-k: the compensated variants make progress, dropping the compensation costs
+    assert f["doublesqueeze_topk"] < f0 and f["mem_sgd_topk"] < f0
+    assert f["topk_sgd"] > f["mem_sgd_topk"]
+    assert np.isfinite(f["qsgd_ternary"])
