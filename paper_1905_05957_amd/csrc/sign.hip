@@ -317,7 +317,7 @@ __device__ __forceinline__ f32x4 sign_error_tile(f32x4 v, int64_t e, int64_t d, 
 
 // Pass-1 tail: store v, sign bits, per-piece partial sums of |v| (or v^2).  STREAM: v is not
 // read again in this call (deferred error form), so it leaves non-temporally.
-template <bool RMS, bool STREAM>
+template <bool RMS, bool STREAM, bool KEEP = true>   // KEEP = false: v is not stored (no compensation: it is not needed again)
 __device__ __forceinline__ void pass1_finish(f32x4 v, int64_t base, int64_t d,
                                              float *__restrict__ vrow, bool vvec,
                                              uint64_t *__restrict__ words_row, int64_t bit_lim,
@@ -325,7 +325,7 @@ __device__ __forceinline__ void pass1_finish(f32x4 v, int64_t base, int64_t d,
                                              double *__restrict__ partial_row, double *lds, uint32_t *sw_lds)
 {
     const int64_t e = base + threadIdx.x * 4;
-    if (vrow && e < d) {                     // no buffer: no compensation, v is not needed again
+    if (KEEP && vrow && e < d) {             // no buffer: no compensation either
         if constexpr (STREAM) st4_stream(vrow, e, d, vvec, v);
         else st4(vrow, e, d, vvec, v);
     }
@@ -350,7 +350,9 @@ __device__ __forceinline__ void pass1_finish(f32x4 v, int64_t base, int64_t d,
 // DEFERRED: the error buffer holds the previous call's v and `prev_scales` that call's group
 // scales; the error delta = v_prev - Q[v_prev] is formed on the fly (the same subtraction
 // pass 2 would have stored), so the buffer is looked at once per call.
-template <bool BF16, bool DEFERRED, bool RMS>
+// MODE 0: plain.  1 (deferred): as described above.  2: Algorithm 1 without compensation, v = g,
+// no error buffer is touched.
+template <bool BF16, int MODE, bool RMS>
 __global__ __launch_bounds__(kBlock) void k_sign_pass1_worker(WorkerSrc<BF16> src, float *delta,
                                                               int64_t d, uint64_t *words, int64_t W,
                                                               ds_sign_tables tb, double *partials,
@@ -362,17 +364,20 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass1_worker(WorkerSrc<BF16> sr
     const int64_t tile = blockIdx.x;
     const int64_t base = tile * kTile;
     const void *grow = src.grow(row);
-    float *drow = delta ? delta + row * src.delta_stride : nullptr;      // null: no compensation
+    constexpr bool DEFERRED = MODE == 1, NOFB = MODE == 2;
+    float *drow = NOFB ? nullptr : delta + row * src.delta_stride;
     const bool gvec = BF16 ? aligned8(grow) : aligned16(grow);
     const bool dvec = aligned16(drow);
     const int64_t e = base + threadIdx.x * 4;
     const TilePieces tp = tile_pieces(tb, tile);
     const int32_t p0 = tp.p0, p1 = tp.p1;
-    f32x4 dl = {0.f, 0.f, 0.f, 0.f};
-    if (drow) dl = DEFERRED ? ld4_stream(drow, e, d, dvec) : ld4(drow, e, d, dvec);
-    if (DEFERRED && e < d) dl = zero_past(sign_error_tile(dl, e, d, prev_scales + row * S, tb, p0, p1, tp.seg0), e, d);
-    const f32x4 v = ld4_grad<BF16>(grow, e, d, gvec) + dl;
-    pass1_finish<RMS, DEFERRED>(v, base, d, drow, dvec, words + row * W, W * 64, tb, p0, p1,
+    f32x4 v = ld4_grad<BF16>(grow, e, d, gvec);
+    if constexpr (!NOFB) {
+        f32x4 dl = DEFERRED ? ld4_stream(drow, e, d, dvec) : ld4(drow, e, d, dvec);
+        if (DEFERRED && e < d) dl = zero_past(sign_error_tile(dl, e, d, prev_scales + row * S, tb, p0, p1, tp.seg0), e, d);
+        v = v + dl;
+    }
+    pass1_finish<RMS, DEFERRED, !NOFB>(v, base, d, drow, dvec, words + row * W, W * 64, tb, p0, p1,
                       partials + static_cast<int64_t>(row) * tb.n_pieces, lds, sw_lds);
 }
 
@@ -673,11 +678,19 @@ ds_status_t ds_sign_worker(ds_ctx *c, const void *g, int64_t gs, float *delta, i
         return ds_launch_status();
     }
     dim3 grid(static_cast<unsigned>(c->n_tiles), static_cast<unsigned>(cfg.n));
-    with_flags(bf16, c->sign_defer && c->sign_w_deferred, rms, [&](auto bf, auto df, auto rm) {
-        constexpr bool BF = decltype(bf)::value, DF = decltype(df)::value, RM = decltype(rm)::value;
+    const bool deferred = c->sign_defer && c->sign_w_deferred;     // never set without compensation
+    with_flags(bf16, deferred || c->nofb, rms, [&](auto bf, auto md, auto rm) {
+        constexpr bool BF = decltype(bf)::value, MD = decltype(md)::value, RM = decltype(rm)::value;
         WorkerSrc<BF> src{g, gs, delta, dstr};
-        k_sign_pass1_worker<BF, DF, RM><<<grid, kBlock, 0, st>>>(src, delta, cfg.d, out->sign_words, c->W, c->sign_tb,
-                                                                 c->sign_partials, c->sign_prev_w, c->S);
+        if (!MD)
+            k_sign_pass1_worker<BF, 0, RM><<<grid, kBlock, 0, st>>>(src, delta, cfg.d, out->sign_words, c->W, c->sign_tb,
+                                                                    c->sign_partials, c->sign_prev_w, c->S);
+        else if (deferred)
+            k_sign_pass1_worker<BF, 1, RM><<<grid, kBlock, 0, st>>>(src, delta, cfg.d, out->sign_words, c->W, c->sign_tb,
+                                                                    c->sign_partials, c->sign_prev_w, c->S);
+        else
+            k_sign_pass1_worker<BF, 2, RM><<<grid, kBlock, 0, st>>>(src, delta, cfg.d, out->sign_words, c->W, c->sign_tb,
+                                                                    c->sign_partials, c->sign_prev_w, c->S);
     });
     k_sign_reduce<<<dim3(static_cast<unsigned>(c->S), static_cast<unsigned>(cfg.n)), kBlock, 0, st>>>(
         c->sign_partials, c->sign_tb, out->scales, c->S, c->sign_defer ? c->sign_prev_w : nullptr);
@@ -836,7 +849,7 @@ extern "C" ds_status_t ds_worker_compress_sign_noalloc(int32_t n, int64_t d, int
     with_flags(grad_dtype == DS_BF16, tb.rms, false, [&](auto bf, auto rm, auto) {
         constexpr bool BF = decltype(bf)::value, RM = decltype(rm)::value;
         WorkerSrc<BF> src{g, g_row_stride, delta, delta_row_stride};
-        k_sign_pass1_worker<BF, false, RM><<<grid, kBlock, 0, st>>>(src, delta, d, sign_words, W, tb, partials, nullptr, 1);
+        k_sign_pass1_worker<BF, 0, RM><<<grid, kBlock, 0, st>>>(src, delta, d, sign_words, W, tb, partials, nullptr, 1);
     });
     k_sign_reduce<<<dim3(1, static_cast<unsigned>(n)), kBlock, 0, st>>>(partials, tb, scales, 1, nullptr);
     k_sign_pass2<<<grid, kBlock, 0, st>>>(delta, delta_row_stride, d, scales, 1, tb);

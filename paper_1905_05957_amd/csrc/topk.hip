@@ -119,10 +119,20 @@ struct WorkerV {   // v = g + delta
     {
         const void *grow = BF16 ? static_cast<const void *>(static_cast<const uint16_t *>(g) + row * gs)
                                 : static_cast<const void *>(static_cast<const float *>(g) + row * gs);
-        const f32x4 gv = ld4_grad<BF16>(grow, e, d, BF16 ? aligned8(grow) : aligned16(grow));
-        if (!delta) return gv;                                   // no compensation: v = g
         const float *drow = delta + row * dstr;
-        return gv + ld4_stream(drow, e, d, aligned16(drow));
+        return ld4_grad<BF16>(grow, e, d, BF16 ? aligned8(grow) : aligned16(grow)) + ld4_stream(drow, e, d, aligned16(drow));
+    }
+};
+
+struct GradV {     // v = g: Algorithm 1 without compensation (fp32 gradients)
+    static constexpr int kLdsWords = 1;
+    __device__ __forceinline__ void prepare(float *) const {}
+    const float *g;
+    int64_t gs;
+    __device__ __forceinline__ f32x4 load(int row, int64_t e, int64_t d, float *) const
+    {
+        const float *grow = g + row * gs;
+        return ld4_stream(grow, e, d, aligned16(grow));
     }
 };
 
@@ -1607,7 +1617,7 @@ ds_status_t ds_topk_worker(ds_ctx *c, const void *g, int64_t gs, float *delta, i
         // no compensation (fp32 gradients only, checked by ds_create): v = g, which also serves
         // the second look of the exact route; no buffer is written
         float *gv = static_cast<float *>(const_cast<void *>(g));
-        return run_select(c, rows, WorkerV<false>{g, gs, nullptr, 0}, gv, gs, pairs, st, c->topk->prev_T, nullptr, 0.f, false);
+        return run_select(c, rows, GradV{gv, gs}, gv, gs, pairs, st, c->topk->prev_T, nullptr, 0.f, false);
     }
     if (c->cfg.grad_dtype == DS_BF16) return run_select(c, rows, WorkerV<true>{g, gs, delta, dstr}, delta, dstr, pairs, st, c->topk->prev_T);
     return run_select(c, rows, WorkerV<false>{g, gs, delta, dstr}, delta, dstr, pairs, st, c->topk->prev_T);
