@@ -309,6 +309,13 @@ ds_status_t ds_worker_compress_sign_noalloc(int32_t n, int64_t d, int32_t grad_d
  * captured again after that call. */
 ds_status_t ds_status(const ds_ctx_t *ctx);
 
+/* Measurement aid, not part of the method: copies `bytes` (a multiple of 16, at most 2^40) of
+ * device memory with the plain streaming kernel the dense passes are shaped like (one
+ * non-temporal 128-bit load and one such store per thread, 512 threads per workgroup).  Its
+ * rate is the practical HBM ceiling that the benchmark reports beside the 8 TB/s peak.  src and
+ * dst: 16-byte aligned device pointers, not overlapping. */
+ds_status_t ds_probe_copy(const void *src, void *dst, size_t bytes, void *hip_stream);
+
 /* Static string for a status code. */
 const char *ds_status_string(ds_status_t s);
 

@@ -51,7 +51,7 @@ class ds_payload_t(C.Structure):
 
 EXPORTS = ["ds_create", "ds_destroy", "ds_payload_sizes", "ds_worker_compress",
            "ds_server_aggregate_compress", "ds_apply_update", "ds_decompress", "ds_materialize_error",
-           "ds_server_aggregate_compress_update", "ds_worker_compress_sign_noalloc", "ds_status",
+           "ds_server_aggregate_compress_update", "ds_worker_compress_sign_noalloc", "ds_status", "ds_probe_copy",
            "ds_status_string", "ds_version"]
 
 _lib = None
@@ -85,6 +85,7 @@ def load_library():
     L.ds_server_aggregate_compress_update.argtypes = [vp, u64, C.POINTER(ds_payload_t), vp, C.POINTER(ds_payload_t),
                                                       vp, vp, f32, f32, vp]
     L.ds_status.argtypes = [vp]
+    L.ds_probe_copy.argtypes = [vp, vp, C.c_size_t, vp]
     L.ds_worker_compress_sign_noalloc.argtypes = [i32, i64, i32, i32, vp, i64, vp, i64, vp, vp, vp]
     for name in EXPORTS:
         if name not in ("ds_status_string", "ds_version"):
@@ -375,6 +376,16 @@ def ds_apply_update(ctx: Context, srv, x, m, gamma, beta=0.0, stream=None):
 
 def ds_decompress(ctx: Context, p, row, out, stream=None):
     ctx.decompress(p, row, out, stream)
+
+
+def ds_probe_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
+    """The library's plain streaming copy kernel (measurement aid)."""
+    if not (src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()):
+        raise ValueError("contiguous device tensors are required")
+    nbytes = src.numel() * src.element_size()
+    if nbytes != dst.numel() * dst.element_size():
+        raise ValueError("source and destination differ in size")
+    _check(load_library().ds_probe_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream_ptr(stream)), "ds_probe_copy")
 
 
 def ds_worker_compress_sign_noalloc(g: torch.Tensor, delta: torch.Tensor, sign_words: torch.Tensor,

@@ -71,7 +71,26 @@ __global__ __launch_bounds__(kBlock) void k_identity_update(const float *q_in, f
 
 unsigned blocks4(int64_t d) { return static_cast<unsigned>((d + kBlock * 4 - 1) / (kBlock * 4)); }
 
+// Measurement aid: a plain copy in the shape of the library's dense passes (512 threads, one
+// non-temporal 128-bit load and store per thread).
+__global__ __launch_bounds__(kBlock) void k_probe_copy(const f32x4 *__restrict__ src, f32x4 *__restrict__ dst, int64_t n16)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (i < n16) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
 }  // namespace
+
+extern "C" ds_status_t ds_probe_copy(const void *src, void *dst, size_t bytes, void *hip_stream)
+{
+    if (!src || !dst) return DS_ERR_NULL;
+    if (bytes == 0 || (bytes & 15u) != 0 || bytes > (static_cast<size_t>(1) << 40)) return DS_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(src) & 15u) || (reinterpret_cast<uintptr_t>(dst) & 15u)) return DS_ERR_ALIGN;
+    const int64_t n16 = static_cast<int64_t>(bytes / 16);
+    k_probe_copy<<<static_cast<unsigned>((n16 + kBlock - 1) / kBlock), kBlock, 0, static_cast<hipStream_t>(hip_stream)>>>(
+        static_cast<const f32x4 *>(src), static_cast<f32x4 *>(dst), n16);
+    return ds_launch_status();
+}
 
 ds_status_t ds_identity_worker(ds_ctx *c, const void *g, int64_t gs, float *delta, int64_t dstr,
                                const ds_payload_t *out, hipStream_t st)

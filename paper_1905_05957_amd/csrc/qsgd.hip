@@ -132,26 +132,37 @@ __device__ __forceinline__ f32x4 decode4(uint32_t codes, uint32_t nib, float uni
 }
 
 // Worker block of Algorithm 1 with Q = randomised quantisation.  NOFB: without compensation,
-// v = g; no error buffer is touched.
-template <bool BF16, bool NOFB>
+// v = g; no error buffer is touched.  TPW tiles per workgroup, all loads issued before the
+// first is used.
+template <bool BF16, bool NOFB, int TPW>
 __global__ __launch_bounds__(kBlock) void k_qsgd_worker(const void *g, int64_t gs, float *delta, int64_t dstr,
                                                         QParams P, uint8_t *levels, uint64_t *words, float *norms)
 {
-    __shared__ double lds[kWaves];
-    __shared__ __attribute__((aligned(16))) uint32_t sw_lds[kWaves * 8];
+    __shared__ double lds[TPW][kWaves];
+    __shared__ __attribute__((aligned(16))) uint32_t sw_lds[TPW][kWaves * 8];
     const int row = blockIdx.y;
-    const int64_t e = static_cast<int64_t>(blockIdx.x) * kTile + threadIdx.x * 4;
     const void *grow = BF16 ? static_cast<const void *>(static_cast<const uint16_t *>(g) + row * gs)
                             : static_cast<const void *>(static_cast<const float *>(g) + row * gs);
     float *drow = NOFB ? nullptr : delta + row * dstr;
     const bool gvec = BF16 ? aligned8(grow) : aligned16(grow);
     const bool dvec = aligned16(drow);
-    f32x4 v = ld4_grad<BF16>(grow, e, P.d, gvec);
-    if constexpr (!NOFB) v = v + ld4_stream(drow, e, P.d, dvec);
-    const f32x4 q = quantise4(v, e, static_cast<uint32_t>(row), P, levels + row * ((P.d + 1) / 2),
-                              words + row * P.W, norms + row * P.Bq, lds, sw_lds);
-    if constexpr (!NOFB)
-        if (e < P.d) st4_stream(drow, e, P.d, dvec, v - q);
+    f32x4 v[TPW];
+#pragma unroll
+    for (int c = 0; c < TPW; ++c) {
+        const int64_t e = (static_cast<int64_t>(blockIdx.x) * TPW + c) * kTile + threadIdx.x * 4;
+        v[c] = ld4_grad<BF16>(grow, e, P.d, gvec);
+        if constexpr (!NOFB) v[c] = v[c] + ld4_stream(drow, e, P.d, dvec);
+    }
+#pragma unroll
+    for (int c = 0; c < TPW; ++c) {
+        const int64_t tile_first = (static_cast<int64_t>(blockIdx.x) * TPW + c) * kTile;
+        if (tile_first >= P.d) break;                                  // uniform over the workgroup
+        const int64_t e = tile_first + threadIdx.x * 4;
+        const f32x4 q = quantise4(v[c], e, static_cast<uint32_t>(row), P, levels + row * ((P.d + 1) / 2),
+                                  words + row * P.W, norms + row * P.Bq, lds[c], sw_lds[c]);
+        if constexpr (!NOFB)
+            if (e < P.d) st4_stream(drow, e, P.d, dvec, v[c] - q);
+    }
 }
 
 // Parameter-server block: v = delta_s + (1/n) sum_i decode(msg_i) as the fma chain over
@@ -292,11 +303,14 @@ ds_status_t ds_qsgd_worker(ds_ctx *c, uint64_t step, const void *g, int64_t gs, 
     if (!bucket_ok(c->cfg.bucket)) return DS_ERR_UNSUPPORTED;
     const QParams P = make_params(c, step);
     dim3 grid(static_cast<unsigned>(c->n_tiles), static_cast<unsigned>(c->cfg.n));
+    // two tiles per workgroup: 1.5 % on the 16 x 25.6 M workload (fewer, longer-lived workgroups)
+    constexpr int TPW = 2;
+    grid.x = static_cast<unsigned>((c->n_tiles + TPW - 1) / TPW);
     const bool bf16 = c->cfg.grad_dtype == DS_BF16;
-    if (bf16 && c->nofb) k_qsgd_worker<true, true><<<grid, kBlock, 0, st>>>(g, gs, delta, dstr, P, out->levels, out->sign_words, out->scales);
-    else if (bf16) k_qsgd_worker<true, false><<<grid, kBlock, 0, st>>>(g, gs, delta, dstr, P, out->levels, out->sign_words, out->scales);
-    else if (c->nofb) k_qsgd_worker<false, true><<<grid, kBlock, 0, st>>>(g, gs, delta, dstr, P, out->levels, out->sign_words, out->scales);
-    else k_qsgd_worker<false, false><<<grid, kBlock, 0, st>>>(g, gs, delta, dstr, P, out->levels, out->sign_words, out->scales);
+    if (bf16 && c->nofb) k_qsgd_worker<true, true, TPW><<<grid, kBlock, 0, st>>>(g, gs, delta, dstr, P, out->levels, out->sign_words, out->scales);
+    else if (bf16) k_qsgd_worker<true, false, TPW><<<grid, kBlock, 0, st>>>(g, gs, delta, dstr, P, out->levels, out->sign_words, out->scales);
+    else if (c->nofb) k_qsgd_worker<false, true, TPW><<<grid, kBlock, 0, st>>>(g, gs, delta, dstr, P, out->levels, out->sign_words, out->scales);
+    else k_qsgd_worker<false, false, TPW><<<grid, kBlock, 0, st>>>(g, gs, delta, dstr, P, out->levels, out->sign_words, out->scales);
     return ds_launch_status();
 }
 
