@@ -106,7 +106,11 @@ typedef enum {
  * the plain form).  The caller must pass the same logical buffers to consecutive calls and
  * call ds_materialize_error before it reads, copies, checkpoints or edits them.  Contexts for
  * which the flag has no effect (other compressors, chunk scales handled in one pass) ignore
- * it.
+ * it.  Which form a buffer is in is host-side state of the context, and it selects the kernel
+ * when a call is enqueued, so a captured graph has the form of its capture time baked in:
+ * capture a step only when the buffers are already in deferred form (after at least one
+ * eager call), replay it only on buffers in that form, and after ds_materialize_error run one
+ * eager call (or capture again) before replaying.
  *
  * DS_FLAG_SIGN_RMS: the SIGN scale of a group is sqrt(mean v^2) instead of mean |v|: the l2
  * reading of Section 3.2's "norm times sign vector" (the decoded group then has the l2 norm

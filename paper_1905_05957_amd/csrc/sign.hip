@@ -709,12 +709,10 @@ ds_status_t ds_sign_worker(ds_ctx *c, const void *g, int64_t gs, float *delta, i
     });
     k_sign_reduce<<<dim3(static_cast<unsigned>(c->S), static_cast<unsigned>(cfg.n)), kBlock, 0, st>>>(
         c->sign_partials, c->sign_tb, out->scales, c->S, c->sign_defer ? c->sign_prev_w : nullptr);
-    if (c->sign_defer) {
-        c->sign_w_deferred = true;   // the buffer now holds v; delta = v - Q[v] is applied by the next load
-    } else if (delta) {
-        k_sign_pass2<<<grid, kBlock, 0, st>>>(delta, dstr, cfg.d, out->scales, c->S, c->sign_tb);
-    }
-    return ds_launch_status();
+    if (!c->sign_defer && delta) k_sign_pass2<<<grid, kBlock, 0, st>>>(delta, dstr, cfg.d, out->scales, c->S, c->sign_tb);
+    const ds_status_t rc = ds_launch_status();
+    if (rc == DS_OK && c->sign_defer) c->sign_w_deferred = true;   // the buffer now holds v; delta = v - Q[v] is applied by the next load
+    return rc;
 }
 
 // x != nullptr (chunk route only): the model update for the same elements in the same kernel.
@@ -752,12 +750,10 @@ ds_status_t ds_sign_server(ds_ctx *c, const ds_payload_t *in, float *delta_s, co
     });
     k_sign_reduce<<<dim3(static_cast<unsigned>(c->S), 1), kBlock, 0, st>>>(c->sign_partials, c->sign_tb, out->scales, c->S,
                                                                           c->sign_defer ? c->sign_prev_s : nullptr);
-    if (c->sign_defer) {
-        c->sign_s_deferred = true;
-    } else if (delta_s) {
-        k_sign_pass2<<<grid, kBlock, 0, st>>>(delta_s, cfg.d, cfg.d, out->scales, c->S, c->sign_tb);
-    }
-    return ds_launch_status();
+    if (!c->sign_defer && delta_s) k_sign_pass2<<<grid, kBlock, 0, st>>>(delta_s, cfg.d, cfg.d, out->scales, c->S, c->sign_tb);
+    const ds_status_t rc = ds_launch_status();
+    if (rc == DS_OK && c->sign_defer) c->sign_s_deferred = true;
+    return rc;
 }
 
 // Deferred error form -> plain form, in place; a no-op for buffers that are in plain form.
