@@ -92,3 +92,22 @@ def test_library_error_codes_on_a_live_context(gpu_device):
         assert delta[:, :d].any() and not delta[:, d:].any()
     finally:
         ctx.close()
+
+
+def test_probe_copy_copies_and_checks_its_arguments(gpu_device):
+    """The measurement aid ds_probe_copy: a plain copy, refused for sizes and pointers it cannot take."""
+    import ctypes as C
+    lib = P.load_library()
+    src = torch.arange(0, 1 << 20, dtype=torch.float32, device=gpu_device)
+    dst = torch.zeros_like(src)
+    P.ds_probe_copy(src, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    tail = torch.zeros(12, dtype=torch.float32, device=gpu_device)             # 48 bytes: three 16-byte units
+    P.ds_probe_copy(src[:12].contiguous(), tail)
+    torch.cuda.synchronize()
+    assert torch.equal(tail, src[:12])
+    p, q = src.data_ptr(), dst.data_ptr()
+    assert lib.ds_probe_copy(None, q, 64, None) == 1                            # DS_ERR_NULL
+    assert lib.ds_probe_copy(p, q, 0, None) == 2 and lib.ds_probe_copy(p, q, 40, None) == 2    # DS_ERR_SHAPE
+    assert lib.ds_probe_copy(p + 4, q, 64, None) == 4                           # DS_ERR_ALIGN
