@@ -562,59 +562,102 @@ __global__ __launch_bounds__(kBlock) void k_topk_pass1_server(ServerV src, float
     const int64_t span_base = (static_cast<int64_t>(blockIdx.x) * kWaves + wv) * kSpan;
     const uint32_t lo_key = SID ? 0u : sel[0].lo_key;
     const bool vec = aligned16(buf);
+    const bool live = span_base < d;                       // uniform over the wavefront
+    const int64_t sub0 = span_base >> 8;
+    const int64_t sub1 = (sub0 + 4 < src.n_sub) ? sub0 + 4 : src.n_sub;
+    const uint32_t base = static_cast<uint32_t>(span_base);
+    const int n = src.n;
+
+    // The loads are issued in the order of the dependent chain, longest first: the workers'
+    // entry ranges (which the entries' addresses wait for), then the span of the server's
+    // error, then the first batch of entries; only then is anything used.  (With the error
+    // copied into the strip first, the range look-up waited for it: 4.5 us of latency in a row
+    // per wavefront instead of 2.5.)
+    struct Ranges {
+        uint32_t s0, c, P, total;
+        int nw, nsteps;
+    };
+    auto load_bounds = [&](int w0, uint32_t &s0, uint32_t &s1) {
+        const int nw = (n - w0 < 64) ? n - w0 : 64;
+        s0 = s1 = 0u;
+        if (live && lane < nw) {
+            s0 = src.sub_start[sub0 * n + w0 + lane];
+            s1 = src.sub_start[sub1 * n + w0 + lane];
+        }
+    };
+    auto make_ranges = [&](int w0, uint32_t s0, uint32_t s1) -> Ranges {
+        Ranges r;
+        r.nw = (n - w0 < 64) ? n - w0 : 64;
+        r.nsteps = (r.nw <= 1) ? 0 : 32 - __builtin_clz(static_cast<uint32_t>(r.nw - 1));
+        if (s1 > static_cast<uint32_t>(src.k)) s1 = static_cast<uint32_t>(src.k);
+        r.s0 = s0;
+        r.c = (lane < r.nw && s1 > s0) ? s1 - s0 : 0u;
+        uint32_t P = r.c;                                  // inclusive prefix over workers
+        for (int o = 1; o < r.nw; o <<= 1) {
+            const uint32_t up = __shfl_up(P, o, 64);
+            if (lane >= o) P += up;
+        }
+        r.P = P;
+        r.total = __shfl(P, r.nw - 1, 64);
+        return r;
+    };
+    // entry number i0 + lane of the workers w0 .. w0 + nw - 1, flattened in worker order
+    auto fetch = [&](const Ranges &r, int w0, uint32_t i0, bool &valid) -> u32x2 {
+        const uint32_t i = i0 + lane;
+        valid = i < r.total;
+        int lo = 0, hi = r.nw - 1;                         // first worker w with P_w > i
+        for (int step = 0; step < r.nsteps; ++step) {
+            const int mid = (lo + hi) >> 1;
+            if (__shfl(r.P, mid, 64) > (valid ? i : 0u)) hi = mid; else lo = mid + 1;
+        }
+        const uint32_t pw = __shfl(r.P, lo, 64), cw = __shfl(r.c, lo, 64), sw = __shfl(r.s0, lo, 64);
+        u32x2 pr = {0u, 0u};
+        if (valid) pr = src.pairs_in[static_cast<int64_t>(w0 + lo) * src.k + sw + (i - (pw - cw))];
+        return pr;
+    };
+    auto apply = [&](u32x2 pr, bool valid) {
+        const uint32_t rel = pr.x - base;
+        bool pending = valid && rel < static_cast<uint32_t>(kSpan);
+        while (__ballot(pending)) {
+            if (pending) atomicMin(&tag[rel & (kTags - 1)], static_cast<uint32_t>(lane));
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            const bool win = pending && tag[rel & (kTags - 1)] == static_cast<uint32_t>(lane);
+            if (win) {
+                strip[rel] = __fmaf_rn(__uint_as_float(pr.y), src.inv_n, strip[rel]);
+                tag[rel & (kTags - 1)] = kNone;
+            }
+            pending = pending && !win;
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        }
+    };
+
+    uint32_t b0, b1;
+    load_bounds(0, b0, b1);
     f32x4 v[4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
+    for (int c = 0; c < 4; ++c)
         v[c] = SID ? f32x4{0.f, 0.f, 0.f, 0.f}
                    : ld4_stream(src.delta_s, span_base + c * kSub + lane * 4, d, aligned16(src.delta_s));
+    Ranges r = make_ranges(0, b0, b1);
+    bool valid0 = false;
+    u32x2 pr0 = {0u, 0u};
+    if (live && r.total > 0) pr0 = fetch(r, 0, 0u, valid0);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
         float *p = strip + c * kSub + lane * 4;
         p[0] = v[c].x; p[1] = v[c].y; p[2] = v[c].z; p[3] = v[c].w;
     }
-    if (span_base < d) {                                   // uniform over the wavefront
-        const int64_t sub0 = span_base >> 8;
-        const int64_t sub1 = (sub0 + 4 < src.n_sub) ? sub0 + 4 : src.n_sub;
-        const uint32_t base = static_cast<uint32_t>(span_base);
-        const int n = src.n;
+    if (live) {
         for (int w0 = 0; w0 < n; w0 += 64) {
-            const int nw = (n - w0 < 64) ? n - w0 : 64;
-            const int nsteps = (nw <= 1) ? 0 : 32 - __builtin_clz(static_cast<uint32_t>(nw - 1));
-            uint32_t s0 = 0u, c = 0u;
-            if (lane < nw) {
-                s0 = src.sub_start[sub0 * n + w0 + lane];
-                uint32_t s1 = src.sub_start[sub1 * n + w0 + lane];
-                if (s1 > static_cast<uint32_t>(src.k)) s1 = static_cast<uint32_t>(src.k);
-                c = (s1 > s0) ? s1 - s0 : 0u;
+            if (w0 > 0) {
+                load_bounds(w0, b0, b1);
+                r = make_ranges(w0, b0, b1);
             }
-            uint32_t P = c;
-            for (int o = 1; o < nw; o <<= 1) {
-                const uint32_t up = __shfl_up(P, o, 64);
-                if (lane >= o) P += up;
-            }
-            const uint32_t total = __shfl(P, nw - 1, 64);
-            for (uint32_t i0 = 0; i0 < total; i0 += 64) {
-                const uint32_t i = i0 + lane;
-                const bool valid = i < total;
-                int lo = 0, hi = nw - 1;
-                for (int step = 0; step < nsteps; ++step) {
-                    const int mid = (lo + hi) >> 1;
-                    if (__shfl(P, mid, 64) > (valid ? i : 0u)) hi = mid; else lo = mid + 1;
-                }
-                const uint32_t pw = __shfl(P, lo, 64), cw = __shfl(c, lo, 64), sw = __shfl(s0, lo, 64);
-                u32x2 pr = {0u, 0u};
-                if (valid) pr = src.pairs_in[static_cast<int64_t>(w0 + lo) * src.k + sw + (i - (pw - cw))];
-                const uint32_t rel = pr.x - base;
-                bool pending = valid && rel < static_cast<uint32_t>(kSpan);
-                while (__ballot(pending)) {
-                    if (pending) atomicMin(&tag[rel & (kTags - 1)], static_cast<uint32_t>(lane));
-                    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-                    const bool win = pending && tag[rel & (kTags - 1)] == static_cast<uint32_t>(lane);
-                    if (win) {
-                        strip[rel] = __fmaf_rn(__uint_as_float(pr.y), src.inv_n, strip[rel]);
-                        tag[rel & (kTags - 1)] = kNone;
-                    }
-                    pending = pending && !win;
-                    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-                }
+            for (uint32_t i0 = 0; i0 < r.total; i0 += 64) {
+                bool valid = valid0;
+                u32x2 pr = pr0;
+                if (w0 > 0 || i0 > 0) pr = fetch(r, w0, i0, valid);
+                apply(pr, valid);
             }
         }
         __builtin_amdgcn_wave_barrier();
