@@ -111,3 +111,16 @@ def test_probe_copy_copies_and_checks_its_arguments(gpu_device):
     assert lib.ds_probe_copy(None, q, 64, None) == 1                            # DS_ERR_NULL
     assert lib.ds_probe_copy(p, q, 0, None) == 2 and lib.ds_probe_copy(p, q, 40, None) == 2    # DS_ERR_SHAPE
     assert lib.ds_probe_copy(p + 4, q, 64, None) == 4                           # DS_ERR_ALIGN
+
+
+def test_status_of_contexts_that_cannot_fail_asynchronously(gpu_device):
+    """ds_status: DS_OK for every compressor whose kernels wait for nothing, DS_ERR_NULL without a context."""
+    lib = P.load_library()
+    assert lib.ds_status(None) == 1
+    for kw in (dict(comp="sign", n=2, d=5000, scale_mode="chunk", chunk=1024), dict(comp="qsgd", n=2, d=5000),
+               dict(comp="topk", n=2, d=5000, k=50, flags=P.FLAG_TOPK_MULTI_LAUNCH), dict(comp="topk", n=2, d=5000, k=50)):
+        ctx = P.Context(**kw)
+        try:
+            assert ctx.status() == 0
+        finally:
+            ctx.close()
