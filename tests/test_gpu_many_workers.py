@@ -36,3 +36,28 @@ def test_worker_counts(gpu_device, n, which):
             pair.compared_step(t, wl.gradients(t, gpu_device))
     finally:
         pair.close()
+
+
+@pytest.mark.parametrize("n", [1, 13, 70, 1000])
+@pytest.mark.parametrize("which", ["sign_whole", "sign_chunk", "topk", "qsgd", "clip", "ternary"])
+def test_worker_counts_plain_server(gpu_device, n, which):
+    """The same counts through the kernels of a server that does not compress
+    (DS_FLAG_SERVER_IDENTITY; the ternary quantiser exists in that mode only)."""
+    import paper_1905_05957_amd as P
+    import parity_util
+    names = ["sign_whole", "sign_chunk", "topk", "qsgd", "clip"]
+    if which == "ternary":
+        wl = W.Workload(f"ternary_n{n}", "ternary", n=n, d=3 * 2048 + 517, dist="normal", sigma=1e-3, gamma=0.05)
+        flags = P.FLAG_SERVER_IDENTITY | P.FLAG_NO_ERROR_FEEDBACK
+    else:
+        wl, flags = _workloads(n)[names.index(which)], P.FLAG_SERVER_IDENTITY
+    parity_util.CONTEXT_FLAGS = flags
+    try:
+        pair = Pair(wl, gpu_device)
+    finally:
+        parity_util.CONTEXT_FLAGS = 0
+    try:
+        for t in range(2):
+            pair.compared_step(t, wl.gradients(t, gpu_device))
+    finally:
+        pair.close()

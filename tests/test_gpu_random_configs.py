@@ -20,9 +20,17 @@ CASES = int(os.environ.get("DS_RANDOM_CASES", "72"))      # a wider hunt: DS_RAN
 MAX_D = int(os.environ.get("DS_RANDOM_MAX_D", "60000"))   # and longer vectors: DS_RANDOM_MAX_D=3000000
 
 
-def _draw(case: int):
-    r = np.random.default_rng(20_000 + case)
-    comp = ["sign", "topk", "qsgd", "clip", "rsparse", "identity"][case % 6]
+MODE_CASES = int(os.environ.get("DS_RANDOM_MODE_CASES", "60"))
+SID, NOFB = P.FLAG_SERVER_IDENTITY, P.FLAG_NO_ERROR_FEEDBACK
+
+
+def _draw(case: int, modes: bool = False):
+    """modes=False: Algorithm 1 itself over the six compressors; modes=True: the comparison
+    algorithms of Section 5.1 (one or both mode flags set) over the compressors that have them,
+    the ternary quantiser included."""
+    r = np.random.default_rng((50_000 if modes else 20_000) + case)
+    comp = (["sign", "topk", "qsgd", "clip", "ternary"][case % 5] if modes
+            else ["sign", "topk", "qsgd", "clip", "rsparse", "identity"][case % 6])
     n = int(r.choice([1, 2, 3, 4, 7, 8, 9, 16, 17]))
     d = int(np.exp(r.uniform(np.log(1), np.log(MAX_D)))) + int(r.integers(0, 4))
     kw = dict(n=n, d=d, gamma=float(r.choice([0.05, 0.1, 1.0])), dist="normal", sigma=float(10.0 ** r.uniform(-4, 0)))
@@ -56,6 +64,15 @@ def _draw(case: int):
         kw["clip_bits"] = int(r.choice([1, 8, 15, 16, 17, 23, 24, 31]))
     elif comp == "rsparse":
         kw["keep_prob"] = float(r.choice([0.6, 0.75, 0.99, 1.0, 0.05]))
+    if modes:
+        if comp == "ternary":
+            flags |= NOFB | SID
+        elif comp == "topk":
+            flags |= int(r.choice([SID, NOFB | SID]))
+            if flags & NOFB:
+                kw.pop("grad_dtype", None)                   # the uncompensated top-k reads fp32 gradients only
+        else:
+            flags |= int(r.choice([SID, NOFB, NOFB | SID]))
     first_step = int(r.choice([0, 1, 12345, (1 << 32) - 1, (1 << 40) + 3]))
     # row strides of g and of the worker errors: d (contiguous) or d plus a few elements, so
     # that rows start on 16-, 8-, 4- and (bf16) 2-byte boundaries
@@ -71,18 +88,29 @@ def _with_row_stride(t: torch.Tensor, pad: int) -> torch.Tensor:
     return buf[:, :t.shape[1]]
 
 
-@pytest.mark.parametrize("case", range(CASES))
-def test_random_configuration(gpu_device, case):
-    wl, flags, t0, (pad_g, pad_delta) = _draw(case)
+def _run(gpu_device, wl, flags, t0, pad_g, pad_delta):
     parity_util.CONTEXT_FLAGS = flags
     try:
         pair = Pair(wl, gpu_device)
     finally:
         parity_util.CONTEXT_FLAGS = 0
     try:
-        pair.delta = _with_row_stride(pair.delta, pad_delta)
+        if pair.delta is not None:
+            pair.delta = _with_row_stride(pair.delta, pad_delta)
         for t in range(2):
             pair.compared_step(t0 + t, _with_row_stride(wl.gradients(t, gpu_device), pad_g),
                                tag=f" flags={flags} pads={pad_g},{pad_delta}")
     finally:
         pair.close()
+
+
+@pytest.mark.parametrize("case", range(CASES))
+def test_random_configuration(gpu_device, case):
+    wl, flags, t0, (pad_g, pad_delta) = _draw(case)
+    _run(gpu_device, wl, flags, t0, pad_g, pad_delta)
+
+
+@pytest.mark.parametrize("case", range(MODE_CASES))
+def test_random_mode_configuration(gpu_device, case):
+    wl, flags, t0, (pad_g, pad_delta) = _draw(case, modes=True)
+    _run(gpu_device, wl, flags, t0, pad_g, pad_delta)
