@@ -410,19 +410,33 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass1_server(ServerArgs a, floa
     const int64_t e = base + threadIdx.x * 4;
     f32x4 v = {0.f, 0.f, 0.f, 0.f};                                      // no buffer: no server error
     if (delta_s) v = DEFERRED ? ld4_stream(delta_s, e, d, dvec) : ld4(delta_s, e, d, dvec);
-    if (DEFERRED && e < d) v = sign_error_tile(v, e, d, prev_scales, tb, p0, p1, tp.seg0);   // past d: cleared below
     const int lane = lane_id();
     const int64_t wave_first = base + wave_id() * 256;
+    // sign words of the first eight workers (lane L: word L & 7 of worker L >> 3): their
+    // addresses do not depend on the tile's pieces, so they leave together with the table
+    // entry and the error instead of after the scales that the entry leads to
+    const bool word_in = wave_first + 32 * (lane & 7) < a.W * 64;
+    uint32_t word0 = 0u;
+    if ((lane >> 3) < a.n && word_in)
+        word0 = reinterpret_cast<const uint32_t *>(a.words_in + (lane >> 3) * a.W)[(wave_first >> 5) + (lane & 7)];
+    // scales of the first eight workers (lane i: worker i), asked for before the previous
+    // call's scale below is waited for: both hang on the table entry alone
+    float sc0 = 0.f;
+    if (tp.seg0 >= 0 && lane < a.n && lane < 8) sc0 = a.scales_in[lane * a.S + tp.seg0];
+    if (DEFERRED && e < d) v = sign_error_tile(v, e, d, prev_scales, tb, p0, p1, tp.seg0);   // past d: cleared below
     if (p1 - p0 == 1) {
         // the whole tile lies in one scale group: same batched loads as the chunk route
-        // (lane L: sign word L & 7 of worker L >> 3; lane i: scale of worker i)
         const int32_t sg = tp.seg0;
         for (int i0 = 0; i0 < a.n; i0 += 8) {
             const int nb = (a.n - i0 < 8) ? a.n - i0 : 8;
-            uint32_t word = 0u;
-            if ((lane >> 3) < nb && wave_first + 32 * (lane & 7) < a.W * 64)
-                word = reinterpret_cast<const uint32_t *>(a.words_in + (i0 + (lane >> 3)) * a.W)[(wave_first >> 5) + (lane & 7)];
-            const float sc = (lane < nb) ? a.scales_in[(i0 + lane) * a.S + sg] : 0.f;
+            uint32_t word = word0;
+            float sc = sc0;
+            if (i0 > 0) {
+                word = 0u;
+                if ((lane >> 3) < nb && word_in)
+                    word = reinterpret_cast<const uint32_t *>(a.words_in + (i0 + (lane >> 3)) * a.W)[(wave_first >> 5) + (lane & 7)];
+                sc = (lane < nb) ? a.scales_in[(i0 + lane) * a.S + sg] : 0.f;
+            }
             // lanes past d run the chain too (cleared below); a full batch is unrolled so that
             // its eight cross-lane fetches are in flight together
             const int top_shift = 28 - 4 * (lane & 7);
@@ -461,7 +475,7 @@ __global__ __launch_bounds__(kBlock) void k_sign_pass1_server(ServerArgs a, floa
 __global__ __launch_bounds__(kBlock) void k_sign_reduce(const double *__restrict__ partials,
                                                         ds_sign_tables tb, float *scales, int64_t S, float *keep)
 {
-    __shared__ double lds[kBlock];
+    __shared__ double lds[kWaves];
     const int32_t s = blockIdx.x;
     const int row = blockIdx.y;
     const double *prow = partials + static_cast<int64_t>(row) * tb.n_pieces;
@@ -469,15 +483,10 @@ __global__ __launch_bounds__(kBlock) void k_sign_reduce(const double *__restrict
     const int32_t p0 = whole ? 0 : tb.seg_piece_first[s], p1 = whole ? tb.n_pieces : tb.seg_piece_first[s + 1];
     double acc = 0.0;
     for (int32_t p = p0 + threadIdx.x; p < p1; p += kBlock) acc += prow[p];
-    lds[threadIdx.x] = acc;
-    __syncthreads();
-    for (int o = kBlock / 2; o > 0; o >>= 1) {
-        if (threadIdx.x < o) lds[threadIdx.x] += lds[threadIdx.x + o];
-        __syncthreads();
-    }
+    const double total = block_sum(acc, lds, false);
     if (threadIdx.x == 0) {
         const double len = static_cast<double>(whole ? tb.whole_d : tb.seg_off[s + 1] - tb.seg_off[s]);
-        const float sc = group_scale(lds[0], len, tb.rms);
+        const float sc = group_scale(total, len, tb.rms);
         scales[row * S + s] = sc;
         if (keep) keep[row * S + s] = sc;
     }
@@ -513,6 +522,14 @@ __global__ __launch_bounds__(kBlock) void k_sign_update(const uint64_t *__restri
     const TilePieces tp = tile_pieces(tb, tile);
     const int64_t e = tile * kTile + threadIdx.x * 4;
     if (e >= d) return;
+    // the model (and momentum) words leave before the scale that the table entry leads to is
+    // waited for
+    const bool xvec = aligned16(x), mvec = aligned16(m);
+    f32x4 xv = {0.f, 0.f, 0.f, 0.f}, mv = xv;
+    if constexpr (!DECODE_ONLY) {
+        xv = ld4_stream(x, e, d, xvec);
+        if constexpr (MOM) mv = ld4_stream(m, e, d, mvec);
+    }
     const uint32_t nib = load_sign_nibble(words, e);
     float q[4];
     if (tp.seg0 >= 0) {
@@ -523,7 +540,16 @@ __global__ __launch_bounds__(kBlock) void k_sign_update(const uint64_t *__restri
 #pragma unroll
         for (int c = 0; c < 4; ++c) q[c] = (e + c < d) ? scales[seg_of(tb, tp.p0, tp.p1, e + c)] : 0.f;
     }
-    apply_q4<MOM, DECODE_ONLY>(signed4(q[0], q[1], q[2], q[3], nib), e, d, x, m, gamma, beta);
+    f32x4 qv = signed4(q[0], q[1], q[2], q[3], nib);
+    if constexpr (DECODE_ONLY) {
+        st4_stream(x, e, d, xvec, qv);
+    } else {
+        if constexpr (MOM) {                       // m <- beta m + q ; x <- x - gamma m
+            qv = fma4(beta, mv, qv);
+            st4_stream(m, e, d, mvec, qv);
+        }
+        st4_stream(x, e, d, xvec, fma4(-gamma, qv, xv));
+    }
 }
 
 // Server that does not compress (Section 5.1 "MEM-SGD"): a = (1/n) sum_i Q[v_i] by the chain
