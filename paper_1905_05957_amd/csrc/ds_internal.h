@@ -76,6 +76,15 @@ static inline ds_status_t ds_launch_status()
     return hipGetLastError() == hipSuccess ? DS_OK : DS_ERR_DEVICE;
 }
 
+// Whether a d-element fp32 buffer that one call reads and writes once (the server's error, the
+// model, the momentum) should pass the caches non-temporally.  Above 64 MB it should (measured
+// at 500 MB); at 45 MB ordinary accesses were faster: short kernels end when their stores are
+// in the write-back cache, and the buffers of one call fit the 256 MB memory-side cache.
+static inline bool ds_stream_worthwhile(int64_t d)
+{
+    return d * 4 > (static_cast<int64_t>(64) << 20);
+}
+
 // identity.hip
 ds_status_t ds_identity_worker(ds_ctx *c, const void *g, int64_t gs, float *delta, int64_t dstr,
                                const ds_payload_t *out, hipStream_t st);
