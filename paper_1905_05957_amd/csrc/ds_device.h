@@ -122,11 +122,44 @@ __device__ __forceinline__ f32x4 ld4_grad(const void *__restrict__ row, int64_t 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
 __device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
 
-// Butterfly sum over the 64 lanes; every lane returns the same value, the order is fixed.
+// Lane exchange inside a row of 16 lanes by data-parallel-primitive controls: no index
+// arithmetic and no trip through the LDS crossbar.  Every lane of the wavefront must be active.
+constexpr int kDppXor1 = 0xB1;         // quad_perm [1,0,3,2]: lane i reads lane i ^ 1
+constexpr int kDppXor2 = 0x4E;         // quad_perm [2,3,0,1]: lane i reads lane i ^ 2
+constexpr int kDppHalfMirror = 0x141;  // lane i of an 8-lane group reads lane 7 - i: the other quad
+constexpr int kDppRowMirror = 0x140;   // lane i of a 16-lane row reads lane 15 - i: the other 8-lane group
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t x)
+{
+    return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), CTRL, 0xF, 0xF, true));
+}
+
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double x)
+{
+    const uint64_t b = __double_as_longlong(x);
+    const uint64_t lo = dpp_u32<CTRL>(static_cast<uint32_t>(b)), hi = dpp_u32<CTRL>(static_cast<uint32_t>(b >> 32));
+    return __longlong_as_double(static_cast<long long>(lo | (hi << 32)));
+}
+
+// Sum over each aligned group of 16 lanes; every lane of a group returns the same value (each
+// step adds the same two partial sums on both sides), the order is fixed.
+__device__ __forceinline__ double row_sum(double x)
+{
+    x += dpp_f64<kDppXor1>(x);
+    x += dpp_f64<kDppXor2>(x);
+    x += dpp_f64<kDppHalfMirror>(x);
+    x += dpp_f64<kDppRowMirror>(x);
+    return x;
+}
+
+// Sum over the 64 lanes; every lane returns the same value, the order is fixed.
 __device__ __forceinline__ double wave_sum(double x)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+    x = row_sum(x);
+    x += __shfl_xor(x, 16, 64);
+    x += __shfl_xor(x, 32, 64);
     return x;
 }
 
@@ -152,10 +185,6 @@ __device__ __forceinline__ double block_sum(double x, double *lds, bool guard = 
     return t;
 }
 
-// Sign-plane packing by wavefront ballot.  Each lane passes the "negative" flags of its
-// four consecutive elements; the wavefront's 256 elements form eight 32-bit words of the
-// plane (element j of the wavefront = bit j & 31 of word j >> 5).  Lane q < 8 returns word q
-// (it covers lanes 8q .. 8q+7); lanes 8..63 return the words again (q & 7).
 __device__ __forceinline__ uint32_t spread4(uint32_t x)   // bit i of the low byte -> bit 4 i
 {
     x = (x | (x << 12)) & 0x000F000Fu;
@@ -164,13 +193,20 @@ __device__ __forceinline__ uint32_t spread4(uint32_t x)   // bit i of the low by
     return x;
 }
 
+// Sign-plane packing.  Each lane passes the "negative" flags of its four consecutive elements;
+// the wavefront's 256 elements form eight 32-bit words of the plane (element j of the wavefront
+// = bit j & 31 of word j >> 5), word q from lanes 8q .. 8q+7.  Every lane returns the word of
+// its own 8-lane group: the lane's four bits are shifted to their place and the eight lanes
+// are OR-ed together in three cross-lane steps.  Every lane of the wavefront must be active.
 __device__ __forceinline__ uint32_t wave_sign_word(bool n0, bool n1, bool n2, bool n3)
 {
-    const uint64_t m0 = __ballot(n0), m1 = __ballot(n1), m2 = __ballot(n2), m3 = __ballot(n3);
-    const int sh = (lane_id() & 7) * 8;
-    const uint32_t x0 = static_cast<uint32_t>(m0 >> sh) & 0xFFu, x1 = static_cast<uint32_t>(m1 >> sh) & 0xFFu;
-    const uint32_t x2 = static_cast<uint32_t>(m2 >> sh) & 0xFFu, x3 = static_cast<uint32_t>(m3 >> sh) & 0xFFu;
-    return spread4(x0) | (spread4(x1) << 1) | (spread4(x2) << 2) | (spread4(x3) << 3);
+    const uint32_t nib = static_cast<uint32_t>(n0) | (static_cast<uint32_t>(n1) << 1) |
+                         (static_cast<uint32_t>(n2) << 2) | (static_cast<uint32_t>(n3) << 3);
+    uint32_t w = nib << (4 * (lane_id() & 7));
+    w |= dpp_u32<kDppXor1>(w);
+    w |= dpp_u32<kDppXor2>(w);
+    w |= dpp_u32<kDppHalfMirror>(w);
+    return w;
 }
 
 // Every wavefront deposits its eight words in `sw_lds` (64 words, 16-byte aligned) with stash_sign_words BEFORE a workgroup barrier; AFTER it, flush_sign_words writes
@@ -186,7 +222,7 @@ __device__ __forceinline__ uint32_t wave_sign_word(bool n0, bool n1, bool n2, bo
 // that reads them next: 1.668 ms with a plain store here against 1.682 ms non-temporal.
 __device__ __forceinline__ void stash_sign_words(uint32_t *sw_lds, uint32_t word)
 {
-    if (lane_id() < 8) sw_lds[wave_id() * 8 + lane_id()] = word;
+    if ((lane_id() & 7) == 0) sw_lds[wave_id() * 8 + (lane_id() >> 3)] = word;
 }
 
 __device__ __forceinline__ void flush_sign_words(const uint32_t *sw_lds, uint64_t *__restrict__ words_row,

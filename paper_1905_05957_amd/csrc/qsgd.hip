@@ -34,19 +34,18 @@ struct QParams {
     int64_t W, Bq;
 };
 
-// Sum of x over the lanes of this thread's bucket; every lane of the bucket returns it.
-// lds: kWaves doubles.
+// Sum of x over the lanes of this thread's bucket (16 lanes or more, a power of two); every
+// lane of the bucket returns it.  lds: kWaves doubles.
 __device__ __forceinline__ double bucket_sum(double x, int lanes_per_bucket, double *lds)
 {
-    if (lanes_per_bucket <= 64) {
-        for (int o = lanes_per_bucket >> 1; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
-        return x;
-    }
-    const double w = wave_sum(x);
-    if (lane_id() == 0) lds[wave_id()] = w;
+    x = row_sum(x);
+    if (lanes_per_bucket >= 32) x += __shfl_xor(x, 16, 64);
+    if (lanes_per_bucket >= 64) x += __shfl_xor(x, 32, 64);
+    if (lanes_per_bucket <= 64) return x;
+    if (lane_id() == 0) lds[wave_id()] = x;
     __syncthreads();
-    const int wpb = lanes_per_bucket >> 6;            // wavefronts per bucket
-    const int first = (wave_id() / wpb) * wpb;
+    const int wpb = lanes_per_bucket >> 6;            // wavefronts per bucket, a power of two
+    const int first = wave_id() & ~(wpb - 1);
     double t = lds[first];
     for (int i = 1; i < wpb; ++i) t += lds[first + i];
     return t;
