@@ -154,12 +154,35 @@ __device__ __forceinline__ double row_sum(double x)
     return x;
 }
 
+// x of this lane plus x of the lane 16 (ROWS = 16) or 32 (ROWS = 32) away, lane i ^ ROWS: the
+// gfx950 row-swap instruction exchanges the odd rows of one copy with the even rows of another,
+// after which one copy holds the even row's value in both rows of a pair and the other the odd
+// row's.  Both lanes of a pair add the same two numbers in the same order.
+template <int ROWS>
+__device__ __forceinline__ double pair_row_sum(double x)
+{
+    const uint64_t b = __double_as_longlong(x);
+    const uint32_t lo = static_cast<uint32_t>(b), hi = static_cast<uint32_t>(b >> 32);
+    uint32_t lo0, lo1, hi0, hi1;
+    if constexpr (ROWS == 16) {
+        const auto l = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+        const auto h = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+        lo0 = l[0]; lo1 = l[1]; hi0 = h[0]; hi1 = h[1];
+    } else {
+        const auto l = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+        const auto h = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+        lo0 = l[0]; lo1 = l[1]; hi0 = h[0]; hi1 = h[1];
+    }
+    return __longlong_as_double(static_cast<long long>(lo0 | (static_cast<uint64_t>(hi0) << 32))) +
+           __longlong_as_double(static_cast<long long>(lo1 | (static_cast<uint64_t>(hi1) << 32)));
+}
+
 // Sum over the 64 lanes; every lane returns the same value, the order is fixed.
 __device__ __forceinline__ double wave_sum(double x)
 {
     x = row_sum(x);
-    x += __shfl_xor(x, 16, 64);
-    x += __shfl_xor(x, 32, 64);
+    x = pair_row_sum<16>(x);
+    x = pair_row_sum<32>(x);
     return x;
 }
 

@@ -39,8 +39,8 @@ struct QParams {
 __device__ __forceinline__ double bucket_sum(double x, int lanes_per_bucket, double *lds)
 {
     x = row_sum(x);
-    if (lanes_per_bucket >= 32) x += __shfl_xor(x, 16, 64);
-    if (lanes_per_bucket >= 64) x += __shfl_xor(x, 32, 64);
+    if (lanes_per_bucket >= 32) x = pair_row_sum<16>(x);
+    if (lanes_per_bucket >= 64) x = pair_row_sum<32>(x);
     if (lanes_per_bucket <= 64) return x;
     if (lane_id() == 0) lds[wave_id()] = x;
     __syncthreads();
@@ -51,11 +51,12 @@ __device__ __forceinline__ double bucket_sum(double x, int lanes_per_bucket, dou
     return t;
 }
 
-// Quantise the four values a thread holds; returns the decoded values q (so the caller can
-// form v - q) and writes codes, sign bits and the bucket norm.
+// Quantise the four values a thread holds; returns the decoded values q, hands back
+// err = v - q and writes codes, sign bits and the bucket norm.  Every thread of the workgroup
+// calls it (cross-lane exchanges and barriers inside).
 __device__ __forceinline__ f32x4 quantise4(f32x4 v, int64_t e, uint32_t stream, const QParams &P,
                                            uint8_t *__restrict__ levels_row, uint64_t *__restrict__ words_row,
-                                           float *__restrict__ norms_row, double *lds, uint32_t *sw_lds)
+                                           float *__restrict__ norms_row, double *lds, uint32_t *sw_lds, f32x4 &err)
 {
     const int lpb = P.bucket >> 2;
     const double ss = ((static_cast<double>(v.x) * static_cast<double>(v.x) +
@@ -65,10 +66,17 @@ __device__ __forceinline__ f32x4 quantise4(f32x4 v, int64_t e, uint32_t stream, 
     const float norm = static_cast<float>(sqrt(bucket_sum(ss, lpb, lds)));
     const bool live = e < P.d;
     if (live && (threadIdx.x & (lpb - 1)) == 0) norms_row[e >> P.bshift] = norm;
+    // The two correctly rounded divisions a bucket needs, s / norm (to quantise) and norm / s (to
+    // decode), in one: even lanes form the first, odd lanes the second, and each lane then reads
+    // both from its pair (a pair of lanes lies in one bucket).
+    const float sf = static_cast<float>(P.s);
+    const bool odd = (threadIdx.x & 1) != 0;
+    const float quot = __fdiv_rn(odd ? norm : sf, odd ? sf : norm);
+    const float inv = __uint_as_float(dpp_u32<0xA0>(__float_as_uint(quot)));    // quad_perm [0,0,2,2]
+    const float unit = __uint_as_float(dpp_u32<0xF5>(__float_as_uint(quot)));   // quad_perm [1,1,3,3]
 
     uint32_t code[4] = {0u, 0u, 0u, 0u};
     if (live && norm > 0.f) {
-        const float inv = __fdiv_rn(static_cast<float>(P.s), norm);
         const uint32_t blk = static_cast<uint32_t>(e >> 2);
         const u32x4 rnd = philox4x32_10(u32x4{blk, 0u, stream, P.step_lo}, P.key0, P.key1);
         const float vv[4] = {v.x, v.y, v.z, v.w};
@@ -76,10 +84,11 @@ __device__ __forceinline__ f32x4 quantise4(f32x4 v, int64_t e, uint32_t stream, 
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const float r = fabsf(vv[c]) * inv;
-            const float fl = floorf(r);
-            const float p = r - fl;
+            // r >= 0: r - floor(r) is exact and is what the fraction instruction returns; the
+            // conversion truncates, which is floor(r)
+            const float p = __builtin_amdgcn_fractf(r);
             const float u = static_cast<float>(rr[c] >> 8) * 0x1p-24f;
-            int k = static_cast<int>(fl) + ((u < p) ? 1 : 0);
+            int k = static_cast<int>(r) + ((u < p) ? 1 : 0);
             k = (k > P.s) ? P.s : k;
             code[c] = static_cast<uint32_t>(k);
         }
@@ -98,14 +107,21 @@ __device__ __forceinline__ f32x4 quantise4(f32x4 v, int64_t e, uint32_t stream, 
     stash_sign_words(sw_lds, wave_sign_word(v.x < 0.f, v.y < 0.f, v.z < 0.f, v.w < 0.f));
     __syncthreads();
     flush_sign_words(sw_lds, words_row, (e >> 11) << 11, P.W * 64);
-    // decoded message: +-(code * norm/s)
-    const float unit = __fdiv_rn(norm, static_cast<float>(P.s));
-    f32x4 q;
-    q.x = static_cast<float>(code[0]) * unit; q.x = (v.x < 0.f) ? -q.x : q.x;
-    q.y = static_cast<float>(code[1]) * unit; q.y = (v.y < 0.f) ? -q.y : q.y;
-    q.z = static_cast<float>(code[2]) * unit; q.z = (v.z < 0.f) ? -q.z : q.z;
-    q.w = static_cast<float>(code[3]) * unit; q.w = (v.w < 0.f) ? -q.w : q.w;
-    return q;
+    // decoded message q = +-(code * norm/s) with the sign of v, and v - q = +-(|v| - code * norm/s)
+    // with the same sign: the magnitudes are subtracted and the sign bit of v is put back (for
+    // v = -0, where q = +0, that is -0 - 0 = -0 as well)
+    const float mag[4] = {static_cast<float>(code[0]) * unit, static_cast<float>(code[1]) * unit,
+                          static_cast<float>(code[2]) * unit, static_cast<float>(code[3]) * unit};
+    const float vv[4] = {v.x, v.y, v.z, v.w};
+    float qq[4], ee[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const uint32_t sb = __float_as_uint(vv[c]) & 0x80000000u;
+        qq[c] = (vv[c] < 0.f) ? -mag[c] : mag[c];
+        ee[c] = __uint_as_float(__float_as_uint(fabsf(vv[c]) - mag[c]) ^ sb);
+    }
+    err = f32x4{ee[0], ee[1], ee[2], ee[3]};
+    return f32x4{qq[0], qq[1], qq[2], qq[3]};
 }
 
 // The four 4-bit codes of elements e..e+3 (e a multiple of 4, e < d).
@@ -157,10 +173,11 @@ __global__ __launch_bounds__(kBlock) void k_qsgd_worker(const void *g, int64_t g
         const int64_t tile_first = (static_cast<int64_t>(blockIdx.x) * TPW + c) * kTile;
         if (tile_first >= P.d) break;                                  // uniform over the workgroup
         const int64_t e = tile_first + threadIdx.x * 4;
-        const f32x4 q = quantise4(v[c], e, static_cast<uint32_t>(row), P, levels + row * ((P.d + 1) / 2),
-                                  words + row * P.W, norms + row * P.Bq, lds[c], sw_lds[c]);
+        f32x4 err;
+        quantise4(v[c], e, static_cast<uint32_t>(row), P, levels + row * ((P.d + 1) / 2), words + row * P.W,
+                  norms + row * P.Bq, lds[c], sw_lds[c], err);
         if constexpr (!NOFB)
-            if (e < P.d) st4_stream(drow, e, P.d, dvec, v[c] - q);
+            if (e < P.d) st4_stream(drow, e, P.d, dvec, err);
     }
 }
 
@@ -250,8 +267,9 @@ __global__ __launch_bounds__(kBlock) void k_qsgd_server(const uint8_t *levels_in
         if (e < P.d) put_average4(a, e, P.d, dense_out, x, m, gamma, beta);
         return;
     }
-    f32x4 q = quantise4(a, e, kServerStream, P, levels_out, words_out, norms_out, lds, sw_lds);
-    if (delta_s && e < P.d) st4_stream(delta_s, e, P.d, dvec, a - q);
+    f32x4 err;
+    f32x4 q = quantise4(a, e, kServerStream, P, levels_out, words_out, norms_out, lds, sw_lds, err);
+    if (delta_s && e < P.d) st4_stream(delta_s, e, P.d, dvec, err);
     if constexpr (UPD != 0) {
         if (e < P.d) {
             q = zero_past(q, e, P.d);
