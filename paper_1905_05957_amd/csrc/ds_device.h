@@ -188,8 +188,28 @@ __device__ __forceinline__ double wave_sum(double x)
 
 __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+    x += dpp_u32<kDppXor1>(x);
+    x += dpp_u32<kDppXor2>(x);
+    x += dpp_u32<kDppHalfMirror>(x);
+    x += dpp_u32<kDppRowMirror>(x);
+    const auto a = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+    x = a[0] + a[1];
+    const auto b = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+    return b[0] + b[1];
+}
+
+// Inclusive prefix sum over the 64 lanes: four shifted adds inside each row of 16 lanes (lanes
+// shifted in from outside the row read 0), then the total of row 0 (its lane 15) goes to row 1
+// and that of row 2 to row 3, then the total of rows 0-1 (lane 31) to rows 2 and 3.  Every lane
+// of the wavefront must be active.
+__device__ __forceinline__ uint32_t wave_inclusive_scan_u32(uint32_t x)
+{
+    x += dpp_u32<0x111>(x);   // row_shr:1
+    x += dpp_u32<0x112>(x);   // row_shr:2
+    x += dpp_u32<0x114>(x);   // row_shr:4
+    x += dpp_u32<0x118>(x);   // row_shr:8
+    x += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), 0x142, 0xA, 0xF, false));   // row_bcast:15 into rows 1, 3
+    x += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), 0x143, 0xC, 0xF, false));   // row_bcast:31 into rows 2, 3
     return x;
 }
 

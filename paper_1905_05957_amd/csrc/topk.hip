@@ -189,11 +189,7 @@ struct ServerV {
                 if (s1 > static_cast<uint32_t>(k)) s1 = static_cast<uint32_t>(k);
                 c = (s1 > s0) ? s1 - s0 : 0u;
             }
-            uint32_t P = c;                                   // inclusive prefix over workers
-            for (int o = 1; o < nw; o <<= 1) {
-                const uint32_t up = __shfl_up(P, o, 64);
-                if (lane >= o) P += up;
-            }
+            const uint32_t P = wave_inclusive_scan_u32(c);    // inclusive prefix over workers (c = 0 past them)
             const uint32_t total = __shfl(P, nw - 1, 64);
             for (uint32_t i0 = 0; i0 < total; i0 += 64) {
                 const uint32_t i = i0 + lane;
@@ -325,12 +321,9 @@ __device__ __forceinline__ void pick_bin(const uint32_t *__restrict__ hist, uint
     }
     // suffix sums over the threads: shuffles inside a wavefront, wavefront totals through LDS
     const int lane = lane_id();
-    uint32_t incl = sum;                                        // sum over lanes >= mine of my wavefront
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t dn = __shfl_down(incl, o, 64);
-        if (lane + o < 64) incl += dn;
-    }
+    // sum over lanes >= mine of my wavefront: the wavefront's total less what lies before me
+    const uint32_t pre = wave_inclusive_scan_u32(sum);
+    const uint32_t incl = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(pre), 63)) - pre + sum;
     __syncthreads();                                            // part[] may still be read by an earlier pick
     if (lane == 0) part[wave_id()] = incl;
     __syncthreads();
@@ -592,11 +585,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_pass1_server(ServerV src, float
         if (s1 > static_cast<uint32_t>(src.k)) s1 = static_cast<uint32_t>(src.k);
         r.s0 = s0;
         r.c = (lane < r.nw && s1 > s0) ? s1 - s0 : 0u;
-        uint32_t P = r.c;                                  // inclusive prefix over workers
-        for (int o = 1; o < r.nw; o <<= 1) {
-            const uint32_t up = __shfl_up(P, o, 64);
-            if (lane >= o) P += up;
-        }
+        const uint32_t P = wave_inclusive_scan_u32(r.c);   // inclusive prefix over workers (c = 0 past them)
         r.P = P;
         r.total = __shfl(P, r.nw - 1, 64);
         return r;
@@ -759,12 +748,7 @@ __device__ __forceinline__ GroupWalk group_begin(const uint32_t *__restrict__ cn
     const int lane = lane_id();
     const int64_t reg = g * kGroupRegs + lane;
     w.c = (lane < kGroupRegs && reg < n_reg) ? cnt_row[reg] : 0u;
-    uint32_t p = w.c;
-#pragma unroll
-    for (int o = 1; o < kGroupRegs; o <<= 1) {
-        const uint32_t up = __shfl_up(p, o, 64);
-        if (lane >= o) p += up;
-    }
+    const uint32_t p = wave_inclusive_scan_u32(w.c);            // c = 0 past the group's regions
     w.P = p;
     w.total = __shfl(p, kGroupRegs - 1, 64);
     return w;
@@ -878,12 +862,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_hist(const u32x2 *slots, c
 __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t x, uint32_t *tmp)
 {
     const int lane = lane_id();
-    uint32_t p = x;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t up = __shfl_up(p, o, 64);
-        if (lane >= o) p += up;
-    }
+    const uint32_t p = wave_inclusive_scan_u32(x);
     __syncthreads();
     if (lane == 63) tmp[wave_id()] = p;
     __syncthreads();
