@@ -456,7 +456,7 @@ def main():
         except Exception as e:  # a workload whose compressor is not built yet
             others.append({"workload": name, "error": str(e)})
         torch.cuda.empty_cache()
-    if not a.no_modes:
+    if not a.no_modes and wl.comp not in ("rsparse", "identity"):   # those two have no mode without compensation
         modes.append(run_uncompensated_worker(wl, 20, 3, head_S))
 
     line = {
