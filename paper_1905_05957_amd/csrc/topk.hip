@@ -226,18 +226,36 @@ struct ServerV {
 // small kernels
 // ---------------------------------------------------------------------------------------
 // "The last workgroup finishes the row": data that workgroups of one kernel hand to the last
-// of them travels only through device-scope atomics (atomicAdd into histograms, dev_store /
-// dev_load below), which are performed at the device's coherence point, so no cache
+// of them travels only through device-scope atomics (adds into histograms, stores and loads
+// of counts and picks), which are performed at the device's coherence point, so no cache
 // write-back or invalidation is needed -- an agent-scope fence per workgroup costs a full L2
 // write-back on this GPU and tripled the step time when tried.
-__device__ __forceinline__ void dev_store(uint32_t *p, uint32_t v)
-{
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ uint32_t dev_load(const uint32_t *p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
+//
+// DevShared<T> is the type of every word that workgroups of ONE launch hand to each other
+// (histograms, group counts, arrival counters, published picks): it offers device-scope
+// operations only, so a plain load or store on that path does not compile.  The memory is
+// allocated and cleared as plain words by the host and by other launches (a launch boundary
+// makes those visible); `as_shared` is the one place where such a pointer becomes typed.
+template <class T>
+class DevShared {
+    T w_;
+
+public:
+    DevShared() = delete;
+    __device__ __forceinline__ T load() const { return __hip_atomic_load(&w_, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+    __device__ __forceinline__ void store(T v) { __hip_atomic_store(&w_, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+    __device__ __forceinline__ T fetch_add(T v) { return __hip_atomic_fetch_add(&w_, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+    __device__ __forceinline__ void add(T v) { (void)__hip_atomic_fetch_add(&w_, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+    // Plain store of zero, for the one case where the word is dead for the rest of this launch
+    // (nothing of it reads or adds to it any more) and the next launch expects it cleared.
+    __device__ __forceinline__ void clear_for_next_launch() { w_ = T(0); }
+};
+using DevWord = DevShared<uint32_t>;
+using DevWord64 = DevShared<uint64_t>;
+static_assert(sizeof(DevWord) == 4 && sizeof(DevWord64) == 8, "a shared word is just the word");
+
+template <class T>
+__host__ __device__ __forceinline__ DevShared<T> *as_shared(T *p) { return reinterpret_cast<DevShared<T> *>(p); }
 
 // True in exactly one workgroup of those that call it with the same counter: the last of
 // `expected` to arrive.  Every wavefront first waits until the memory system has acknowledged
@@ -247,14 +265,14 @@ __device__ __forceinline__ uint32_t dev_load(const uint32_t *p)
 // channels), the barrier collects the wavefronts, then one device-scope increment announces
 // the workgroup.  The counter is left at zero for its next use.  All threads of the
 // workgroup must call.
-__device__ __forceinline__ bool last_workgroup(uint32_t *counter, uint32_t expected, uint32_t *flag_sh)
+__device__ __forceinline__ bool last_workgroup(DevWord *counter, uint32_t expected, uint32_t *flag_sh)
 {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (threadIdx.x == 0) {
-        const uint32_t prev = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t prev = counter->fetch_add(1u);
         const bool last = prev + 1u == expected;
-        if (last) dev_store(counter, 0u);
+        if (last) counter->store(0u);
         *flag_sh = last ? 1u : 0u;
     }
     __syncthreads();
@@ -306,7 +324,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_sub_starts_scan(const u32x2 *pa
 // One workgroup; the thread that owns b writes the outputs (untouched if the histogram
 // holds fewer than `need` keys).
 template <int NB>
-__device__ __forceinline__ void pick_bin(const uint32_t *__restrict__ hist, uint32_t need, uint32_t *part,
+__device__ __forceinline__ void pick_bin(const DevWord *__restrict__ hist, uint32_t need, uint32_t *part,
                                          uint32_t *b_out, uint32_t *rem_out, uint32_t *cnt_out = nullptr)
 {
     constexpr int PER = (NB >= kBlock) ? NB / kBlock : 1;
@@ -316,7 +334,7 @@ __device__ __forceinline__ void pick_bin(const uint32_t *__restrict__ hist, uint
     uint32_t sum = 0;
 #pragma unroll
     for (int j = 0; j < PER; ++j) {
-        local[j] = active ? dev_load(&hist[t * PER + j]) : 0u;
+        local[j] = active ? hist[t * PER + j].load() : 0u;
         sum += local[j];
     }
     // suffix sums over the threads: shuffles inside a wavefront, wavefront totals through LDS
@@ -347,7 +365,7 @@ __device__ __forceinline__ void pick_bin(const uint32_t *__restrict__ hist, uint
 // LEVEL 0: sample -> lo_bin.  1: candidates' 12-bit histogram -> b1, k1 or fallback.
 // 2: -> b2, k2.  3: -> T, k3.  4: dense 12-bit histogram of a fallback row -> b1, k1.
 template <int LEVEL>
-__device__ __forceinline__ void pick_level(const uint32_t *hrow, Sel *s, uint32_t need0, uint32_t *part, uint32_t *out,
+__device__ __forceinline__ void pick_level(const DevWord *hrow, Sel *s, uint32_t need0, uint32_t *part, uint32_t *out,
                                            uint32_t *prev_T = nullptr)
 {
     if (threadIdx.x == 0) { out[0] = kNone; out[1] = 0u; }
@@ -392,14 +410,14 @@ __device__ __forceinline__ int64_t sample_subtile(int64_t j, int64_t ns, int64_t
 
 // 12-bit histogram of v over the sampled subtiles.
 template <class Src>
-__global__ __launch_bounds__(kBlock) void k_topk_sample(Src src, int64_t d, int64_t n_sub, int64_t ns, uint32_t *hist,
-                                                        Sel *sel, uint32_t *done, uint32_t rank, const uint32_t *prev_T,
-                                                        uint32_t *sync_words)
+__global__ __launch_bounds__(kBlock) void k_topk_sample(Src src, int64_t d, int64_t n_sub, int64_t ns, DevWord *hist,
+                                                        Sel *sel, DevWord *done, uint32_t rank, const uint32_t *prev_T,
+                                                        DevWord *sync_words)
 {
     // the single-launch refinement of this call finds its row's synchronisation words at zero
     // (its own previous launch is complete by stream order and did not clear them itself)
     if (blockIdx.x == 0 && threadIdx.x < kSyncStride / 4)
-        __hip_atomic_store(&sync_words[blockIdx.y * (kSyncStride / 4) + threadIdx.x], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sync_words[blockIdx.y * (kSyncStride / 4) + threadIdx.x].store(0u);
     __shared__ uint32_t h[kH1];        // 12-bit bins
     __shared__ uint32_t hf[kH1];       // fine window: kFineBins 12-bit bins x 256 sub-bins (key bits 18..11)
     __shared__ uint32_t part[kBlock], out[2], flag;
@@ -424,10 +442,10 @@ __global__ __launch_bounds__(kBlock) void k_topk_sample(Src src, int64_t d, int6
         }
     }
     __syncthreads();
-    uint32_t *hrow = hist + static_cast<int64_t>(row) * kHistRow;
+    DevWord *hrow = hist + static_cast<int64_t>(row) * kHistRow;
     for (int i = threadIdx.x; i < kH1; i += kBlock) {
-        if (h[i]) atomicAdd(&hrow[kOffSample + i], h[i]);
-        if (hf[i]) atomicAdd(&hrow[kOffFine + i], hf[i]);
+        if (h[i]) hrow[kOffSample + i].add(h[i]);
+        if (hf[i]) hrow[kOffFine + i].add(hf[i]);
     }
     if (last_workgroup(done + row * kStages + kStageSample, gridDim.x, &flag)) {
         Sel *s = sel + row;
@@ -705,8 +723,8 @@ __global__ __launch_bounds__(kBlock) void k_topk_pass1_server(ServerV src, float
 
 // Fallback rows: dense 12-bit histogram of the stored v.  Persistent workgroups.
 __global__ __launch_bounds__(kBlock) void k_topk_fallback_hist(const float *buf, int64_t stride, int64_t d,
-                                                               int64_t n_tiles, Sel *sel, uint32_t *hist,
-                                                               uint32_t *done, uint32_t k)
+                                                               int64_t n_tiles, Sel *sel, DevWord *hist,
+                                                               DevWord *done, uint32_t k)
 {
     __shared__ uint32_t h[kH1];
     __shared__ uint32_t part[kBlock], out[3], flag;
@@ -726,9 +744,9 @@ __global__ __launch_bounds__(kBlock) void k_topk_fallback_hist(const float *buf,
         if (e + 3 < d) atomicAdd(&h[key_of(v.w) >> 19], 1u);
     }
     __syncthreads();
-    uint32_t *hrow = hist + static_cast<int64_t>(row) * kHistRow;
+    DevWord *hrow = hist + static_cast<int64_t>(row) * kHistRow;
     for (int i = threadIdx.x; i < kH1; i += kBlock)
-        if (h[i]) atomicAdd(&hrow[kOffH1F + i], h[i]);
+        if (h[i]) hrow[kOffH1F + i].add(h[i]);
     if (last_workgroup(done + row * kStages + kStageFallback, gridDim.x, &flag))
         pick_level<4>(hrow, sel + row, k, part, out);
 }
@@ -814,7 +832,7 @@ __device__ __forceinline__ void restore_row(const u32x2 *slots, const uint32_t *
 template <int LEVEL>
 __global__ __launch_bounds__(kBlock) void k_topk_cand_hist(const u32x2 *slots, const uint32_t *reg_cnt, int64_t n_reg,
                                                            int64_t reg_pad, int64_t n_groups, Sel *sel,
-                                                           uint32_t *hist, uint32_t *done, uint32_t k, uint32_t *prev_T,
+                                                           DevWord *hist, DevWord *done, uint32_t k, uint32_t *prev_T,
                                                            float *buf, int64_t stride, bool wr)
 {
     constexpr int NB = (LEVEL == 1) ? kH1W : (LEVEL == 2) ? kH2 : kH3;
@@ -846,9 +864,9 @@ __global__ __launch_bounds__(kBlock) void k_topk_cand_hist(const u32x2 *slots, c
         }
     }
     __syncthreads();
-    uint32_t *hrow = hist + static_cast<int64_t>(row) * kHistRow;
+    DevWord *hrow = hist + static_cast<int64_t>(row) * kHistRow;
     for (int i = threadIdx.x; i < NB; i += kBlock)
-        if (h[i]) atomicAdd(&hrow[OFF + i], h[i]);
+        if (h[i]) hrow[OFF + i].add(h[i]);
     if (last_workgroup(done + row * kStages + kStageHist, gridDim.x, &flag)) {
         pick_level<LEVEL>(hrow, sel + row, k, part, out, prev_T + row);
         if (LEVEL == 1) {
@@ -873,20 +891,20 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t x, uint32_t *t
 
 // Per row, in group order: ties seen before each group, and each group's first output slot.
 // Run by one whole workgroup.
-__device__ __forceinline__ void scan_row(int row, const Sel *sel, int64_t n_groups, const uint32_t *grp_gt,
-                                         const uint32_t *grp_eq, uint32_t *grp_eqb, uint32_t *grp_out, uint32_t *tmp)
+__device__ __forceinline__ void scan_row(int row, const Sel *sel, int64_t n_groups, const DevWord *grp_gt,
+                                         const DevWord *grp_eq, uint32_t *grp_eqb, uint32_t *grp_out, uint32_t *tmp)
 {
     const uint32_t k3 = sel[row].k3;
     const int64_t per = (n_groups + kBlock - 1) / kBlock;
     const int64_t t0 = threadIdx.x * per, t1 = (t0 + per < n_groups) ? t0 + per : n_groups;
-    const uint32_t *gt = grp_gt + row * n_groups, *eq = grp_eq + row * n_groups;
+    const DevWord *gt = grp_gt + row * n_groups, *eq = grp_eq + row * n_groups;
     uint32_t *eqb = grp_eqb + row * n_groups, *out = grp_out + row * n_groups;
     uint32_t s = 0;
-    for (int64_t t = t0; t < t1; ++t) s += dev_load(&eq[t]);
+    for (int64_t t = t0; t < t1; ++t) s += eq[t].load();
     uint32_t run = block_exclusive_scan(s, tmp);
     uint32_t sel_sum = 0;
     for (int64_t t = t0; t < t1; ++t) {
-        const uint32_t e_t = dev_load(&eq[t]), g_t = dev_load(&gt[t]);
+        const uint32_t e_t = eq[t].load(), g_t = gt[t].load();
         eqb[t] = run;
         const uint32_t left = (k3 > run) ? k3 - run : 0u;
         sel_sum += g_t + ((e_t < left) ? e_t : left);
@@ -894,7 +912,7 @@ __device__ __forceinline__ void scan_row(int row, const Sel *sel, int64_t n_grou
     }
     uint32_t o = block_exclusive_scan(sel_sum, tmp);
     for (int64_t t = t0; t < t1; ++t) {
-        const uint32_t e_t = dev_load(&eq[t]), g_t = dev_load(&gt[t]);
+        const uint32_t e_t = eq[t].load(), g_t = gt[t].load();
         out[t] = o;
         const uint32_t left = (k3 > eqb[t]) ? k3 - eqb[t] : 0u;
         o += g_t + ((e_t < left) ? e_t : left);
@@ -907,8 +925,8 @@ __device__ __forceinline__ void scan_row(int row, const Sel *sel, int64_t n_grou
 // clearing launch and leaves no host-side state behind (calls can be captured and replayed).
 __global__ __launch_bounds__(kBlock) void k_topk_count(const u32x2 *slots, const uint32_t *reg_cnt, int64_t n_reg,
                                                        int64_t reg_pad, int64_t n_groups, const Sel *sel,
-                                                       uint32_t *grp_gt, uint32_t *grp_eq, uint32_t *grp_eqb,
-                                                       uint32_t *grp_out, uint32_t *done, uint32_t *zero,
+                                                       DevWord *grp_gt, DevWord *grp_eq, uint32_t *grp_eqb,
+                                                       uint32_t *grp_out, DevWord *done, uint32_t *zero,
                                                        int64_t zero_words)
 {
     __shared__ uint32_t tmp[kWaves], flag;
@@ -935,8 +953,8 @@ __global__ __launch_bounds__(kBlock) void k_topk_count(const u32x2 *slots, const
         gt = wave_sum_u32(gt);
         eq = wave_sum_u32(eq);
         if (lane_id() == 0) {
-            dev_store(&grp_gt[row * n_groups + g], gt);
-            dev_store(&grp_eq[row * n_groups + g], eq);
+            grp_gt[row * n_groups + g].store(gt);
+            grp_eq[row * n_groups + g].store(eq);
         }
     }
     if (last_workgroup(done + row * kStages + kStageCount, gridDim.x, &flag))
@@ -1052,8 +1070,8 @@ constexpr uint32_t kSpinLimit = 1u << 22;     // polls per wait before a workgro
 constexpr uint64_t kResValid = 1ull << 63;
 
 struct RowSync {
-    uint32_t *bar;         // arrival counter of the row, 0 between launches
-    uint64_t *res;         // kResSlots published picks of the row, 0 between launches
+    DevWord *bar;          // arrival counter of the row, 0 between launches
+    DevWord64 *res;        // kResSlots published picks of the row, 0 between launches
     uint32_t *abort_flag;  // host memory
     uint32_t *sh;          // 3 LDS words
     uint32_t G;            // workgroups per row
@@ -1073,7 +1091,7 @@ __device__ __forceinline__ bool row_arrive(RowSync &rs)
     __syncthreads();
     rs.rounds++;
     if (threadIdx.x == 0) {
-        const uint32_t prev = __hip_atomic_fetch_add(rs.bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t prev = rs.bar->fetch_add(1u);
         rs.sh[0] = (prev + 1u == rs.rounds * rs.G) ? 1u : 0u;
     }
     __syncthreads();
@@ -1086,7 +1104,7 @@ __device__ __forceinline__ bool row_arrive(RowSync &rs)
 __device__ __forceinline__ void row_publish(RowSync &rs, int slot, uint32_t bin, uint32_t rem)
 {
     const uint64_t enc = kResValid | (static_cast<uint64_t>((bin == kNone) ? 0u : bin + 1u) << 32) | rem;
-    __hip_atomic_store(rs.res + slot, enc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    rs.res[slot].store(enc);
 }
 
 __device__ __forceinline__ bool row_wait_result(RowSync &rs, int slot, uint32_t *bin, uint32_t *rem)
@@ -1095,7 +1113,7 @@ __device__ __forceinline__ bool row_wait_result(RowSync &rs, int slot, uint32_t 
         uint64_t v = 0;
         uint32_t ok = 1u;
         for (uint32_t spins = 0;; ++spins) {
-            v = __hip_atomic_load(rs.res + slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            v = rs.res[slot].load();
             if (v & kResValid) break;
             __builtin_amdgcn_s_sleep(1);
             if (spins >= rs.spin_limit) { ok = 0u; raise_abort(rs.abort_flag); break; }
@@ -1123,7 +1141,7 @@ __device__ __forceinline__ bool row_barrier(RowSync &rs, int slot)
 
 // Run by the workgroup that completed the round.
 template <int NB>
-__device__ __forceinline__ void row_pick_publish(RowSync &rs, int slot, const uint32_t *hist, uint32_t need,
+__device__ __forceinline__ void row_pick_publish(RowSync &rs, int slot, const DevWord *hist, uint32_t need,
                                                  uint32_t *part, uint32_t *out)
 {
     if (threadIdx.x == 0) { out[0] = kNone; out[1] = 0u; }
@@ -1184,10 +1202,10 @@ __device__ __forceinline__ void for_each_candidate(const u32x2 *__restrict__ sro
     }
 }
 
-__device__ __forceinline__ void flush_hist(const uint32_t *h, uint32_t *gh, int nb)
+__device__ __forceinline__ void flush_hist(const uint32_t *h, DevWord *gh, int nb)
 {
     for (int i = threadIdx.x; i < nb; i += kBlock)
-        if (h[i]) atomicAdd(&gh[i], h[i]);
+        if (h[i]) gh[i].add(h[i]);
 }
 
 struct FinishArgs {
@@ -1195,11 +1213,11 @@ struct FinishArgs {
     uint32_t *reg_cnt;
     int64_t n_reg, reg_pad, n_groups, n_sub;
     const Sel *sel;
-    uint32_t *fhist;       // [rows][kFRow], zero on entry
+    DevWord *fhist;        // [rows][kFRow], zero on entry
     char *sync;            // [rows][kSyncStride] arrival counter and published words, zero on entry
     uint32_t *abort_flag;
     uint32_t spin_limit;
-    uint32_t *grp_gt, *grp_eq;
+    DevWord *grp_gt, *grp_eq;
     uint32_t *prev_T;
     float *buf;
     bool wr;               // false: buf is read only (no compensation: it is the gradient) and nothing is stored into it
@@ -1220,9 +1238,9 @@ __global__ __launch_bounds__(kBlock, 8) void k_topk_finish(FinishArgs a)
     const int row = blockIdx.y;
     const uint32_t G = gridDim.x;
     WaveCache wc{cache_bits[wave_id()], cache_rel[wave_id()], 0u, false};
-    RowSync rs{reinterpret_cast<uint32_t *>(a.sync + row * kSyncStride), reinterpret_cast<uint64_t *>(a.sync + row * kSyncStride + 128),
+    RowSync rs{reinterpret_cast<DevWord *>(a.sync + row * kSyncStride), reinterpret_cast<DevWord64 *>(a.sync + row * kSyncStride + 128),
                a.abort_flag, sh, G, 0u, a.spin_limit};
-    uint32_t *fh = a.fhist + static_cast<int64_t>(row) * kFRow;
+    DevWord *fh = a.fhist + static_cast<int64_t>(row) * kFRow;
     u32x2 *srow = a.slots + static_cast<int64_t>(row) * a.n_reg * kReg;
     uint32_t *cnt_row = a.reg_cnt + row * a.reg_pad;
     float *brow = a.buf + row * a.stride;          // read by the two-look route
@@ -1236,7 +1254,7 @@ __global__ __launch_bounds__(kBlock, 8) void k_topk_finish(FinishArgs a)
     uint32_t lo_key = a.sel[row].lo_key;
     uint32_t bA = kNone, kA = 0u;
 
-    auto level_a = [&](uint32_t *gh, int slot) -> bool {
+    auto level_a = [&](DevWord *gh, int slot) -> bool {
         for (int i = threadIdx.x; i < kHA; i += kBlock) h[i] = 0u;
         __syncthreads();
         for_each_candidate<true>(srow, cnt_row, a.n_reg, a.n_groups, G, wc, [&](uint32_t key) {
@@ -1318,7 +1336,7 @@ __global__ __launch_bounds__(kBlock, 8) void k_topk_finish(FinishArgs a)
     const uint32_t T = lo_key + (bA << kShiftA) + bB;
 
     // per group: candidates above T, candidates tying with T
-    uint32_t *gtr = a.grp_gt + row * a.n_groups, *eqr = a.grp_eq + row * a.n_groups;
+    DevWord *gtr = a.grp_gt + row * a.n_groups, *eqr = a.grp_eq + row * a.n_groups;
     {
         const int64_t g0 = static_cast<int64_t>(blockIdx.x) * kWaves + wave_id();
         for (int64_t g = g0; g < a.n_groups; g += static_cast<int64_t>(G) * kWaves) {
@@ -1347,8 +1365,8 @@ __global__ __launch_bounds__(kBlock, 8) void k_topk_finish(FinishArgs a)
             gt = wave_sum_u32(gt);
             eq = wave_sum_u32(eq);
             if (lane_id() == 0) {
-                dev_store(&gtr[g], gt);
-                dev_store(&eqr[g], eq);
+                gtr[g].store(gt);
+                eqr[g].store(eq);
             }
         }
     }
@@ -1364,11 +1382,11 @@ __global__ __launch_bounds__(kBlock, 8) void k_topk_finish(FinishArgs a)
     for (int64_t gb = static_cast<int64_t>(blockIdx.x) * kWaves; gb < a.n_groups; gb += static_cast<int64_t>(G) * kWaves) {
         const int64_t g = gb + wave_id();
         uint32_t wg = 0, we = 0;                               // groups gb .. g-1 of this workgroup's round
-        if (g < a.n_groups && lane_id() < wave_id()) { wg = dev_load(&gtr[gb + lane_id()]); we = dev_load(&eqr[gb + lane_id()]); }
+        if (g < a.n_groups && lane_id() < wave_id()) { wg = gtr[gb + lane_id()].load(); we = eqr[gb + lane_id()].load(); }
         uint32_t pg = 0, pe = 0;
         for (int64_t t = upto + threadIdx.x; t < gb; t += kBlock) {
-            pg += dev_load(&gtr[t]);
-            pe += dev_load(&eqr[t]);
+            pg += gtr[t].load();
+            pe += eqr[t].load();
         }
         pg = wave_sum_u32(pg);
         pe = wave_sum_u32(pe);
@@ -1415,7 +1433,7 @@ __global__ __launch_bounds__(kBlock, 8) void k_topk_finish(FinishArgs a)
     // flushed before the pick it waited for: clear the row's histograms for the next call.  The
     // row's synchronisation words are cleared by the next call's sample kernel, which no
     // workgroup of this launch can overlap with.
-    for (int i = blockIdx.x * kBlock + threadIdx.x; i < kFRow; i += G * kBlock) fh[i] = 0u;
+    for (int i = blockIdx.x * kBlock + threadIdx.x; i < kFRow; i += G * kBlock) fh[i].clear_for_next_launch();
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1512,11 +1530,15 @@ ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t 
     const dim3 dense(static_cast<unsigned>(c->n_tiles), rows), cand(grp_blocks, rows);
     const BufferV bsrc{buf, stride};
 
+    // The scratch memory is plain words to the host and to the clearing code; the launches whose
+    // workgroups hand those words to each other see them typed.
     uint32_t *hist = t->hist;
+    DevWord *s_hist = as_shared(t->hist), *s_done = as_shared(t->done);
+    DevWord *s_gt = as_shared(t->grp_gt), *s_eq = as_shared(t->grp_eq);
     const uint32_t k32 = static_cast<uint32_t>(k);
 
     k_topk_sample<Src><<<dim3(static_cast<unsigned>((ns + kWaves - 1) / kWaves), rows), kBlock, 0, st>>>(
-        src, d, n_sub, ns, hist, t->sel, t->done, rank, prev_T, reinterpret_cast<uint32_t *>(t->sync));
+        src, d, n_sub, ns, s_hist, t->sel, s_done, rank, prev_T, reinterpret_cast<DevWord *>(t->sync));
     if constexpr (std::is_same<Src, ServerV>::value)
         k_topk_pass1_server<false><<<dim3(static_cast<unsigned>((n_reg + 3) / 4)), kBlock, 0, st>>>(
             src, buf, d, t->sel, t->slots, t->reg_cnt, n_reg, ds_update_args{nullptr, nullptr, 0.f, 0.f});
@@ -1531,17 +1553,17 @@ ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t 
         FinishArgs a;
         a.slots = t->slots; a.reg_cnt = t->reg_cnt;
         a.n_reg = n_reg; a.reg_pad = reg_pad; a.n_groups = n_groups; a.n_sub = n_sub;
-        a.sel = t->sel; a.fhist = t->fhist; a.sync = t->sync; a.abort_flag = t->abort_host; a.spin_limit = t->spin_limit;
-        a.grp_gt = t->grp_gt; a.grp_eq = t->grp_eq; a.prev_T = prev_T;
+        a.sel = t->sel; a.fhist = as_shared(t->fhist); a.sync = t->sync; a.abort_flag = t->abort_host; a.spin_limit = t->spin_limit;
+        a.grp_gt = s_gt; a.grp_eq = s_eq; a.prev_T = prev_T;
         a.buf = buf; a.wr = wr; a.stride = stride; a.d = d; a.k = k; a.pairs = pairs; a.x = x; a.gamma = gamma;
         a.zero_a = hist; a.zero_a_words = static_cast<int64_t>(rows) * kHistRow;
         k_topk_finish<<<dim3(static_cast<unsigned>(G), rows), kBlock, 0, st>>>(a);
         return ds_launch_status();
     }
-    k_topk_cand_hist<1><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32, prev_T, buf, stride, wr);
+    k_topk_cand_hist<1><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, s_hist, s_done, k32, prev_T, buf, stride, wr);
     // two-look route for rows whose sample misjudged; both launches exit at once otherwise
     k_topk_fallback_hist<<<dim3(persistent_blocks(c->n_tiles, rows), rows), kBlock, 0, st>>>(buf, stride, d, c->n_tiles,
-                                                                                            t->sel, hist, t->done, k32);
+                                                                                            t->sel, s_hist, s_done, k32);
     if (wr)
         k_topk_pass1<BufferV, true, true><<<dim3(persistent_blocks(c->n_tiles, rows), rows), kBlock, 0, st>>>(
             bsrc, buf, stride, d, n_sub, t->sel, t->slots, t->reg_cnt, n_reg, reg_pad);
@@ -1549,10 +1571,10 @@ ds_status_t run_select(ds_ctx *c, int rows, const Src &src, float *buf, int64_t 
         k_topk_pass1<BufferV, true, false><<<dim3(persistent_blocks(c->n_tiles, rows), rows), kBlock, 0, st>>>(
             bsrc, buf, stride, d, n_sub, t->sel, t->slots, t->reg_cnt, n_reg, reg_pad);
     // refinement on the candidates
-    k_topk_cand_hist<2><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32, prev_T, buf, stride, wr);
-    k_topk_cand_hist<3><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, hist, t->done, k32, prev_T, buf, stride, wr);
-    k_topk_count<<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, t->grp_gt, t->grp_eq,
-                                          t->grp_eqb, t->grp_out, t->done, hist,
+    k_topk_cand_hist<2><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, s_hist, s_done, k32, prev_T, buf, stride, wr);
+    k_topk_cand_hist<3><<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, s_hist, s_done, k32, prev_T, buf, stride, wr);
+    k_topk_count<<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, s_gt, s_eq,
+                                          t->grp_eqb, t->grp_out, s_done, hist,
                                           static_cast<int64_t>(rows) * kHistRow);
     k_topk_emit<<<cand, kBlock, 0, st>>>(t->slots, t->reg_cnt, n_reg, reg_pad, n_groups, t->sel, t->grp_eqb, t->grp_out, k,
                                          pairs, buf, stride, x, gamma, wr);
