@@ -11,7 +11,7 @@
 // known before the first code, so the worker call looks at g twice:
 //   stats    per 2048-element tile: max |v| and sum |v| (fp64)
 //   rowstat  per row: the maximum, and the sum in a fixed order
-//   encode   codes from the second look: two bit planes by wavefront ballot, kept count per tile
+//   encode   codes from the second look: two bit planes packed like the sign words, kept count per tile
 //   scale    per row: sum / count, rounded once
 // The message is 2 bits per element: plane `levels` (bit j = code_j is not 0), plane
 // `sign_words` (bit j = code_j is -1), one fp32 scale.
