@@ -194,12 +194,7 @@ __global__ __launch_bounds__(kBlock) void k_rs_scan(uint32_t *tab, const uint32_
     for (int64_t t = threadIdx.x; t < n_before; t += kBlock) b += trow[t];
     b = wave_sum_u32(b);
     const int lane = lane_id();
-    uint32_t p = s;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t up = __shfl_up(p, o, 64);
-        if (lane >= o) p += up;
-    }
+    const uint32_t p = wave_inclusive_scan_u32(s);
     if (lane == 63) tmp[wave_id()] = p;
     if (lane == 0) pre[wave_id()] = b;
     __syncthreads();
