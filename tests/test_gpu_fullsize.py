@@ -8,9 +8,10 @@ error buffers a working distribution:
   C4  all 16 worker rows (16 random streams), the server pass and the update;
   C5  all 60,762 chunks of all 8 rows, the server pass and the momentum update (8 x 124,439,808);
   X1, X2 (clipping, randomised sparsification at 8 x 25.6 M): the whole step as well.
-Those comparisons go through the three calls of Algorithm 1; the last test runs the call
+Those comparisons go through the three calls of Algorithm 1; another test runs the call
 sequence that bench.py times (worker call + the one-call server-and-update, sign per segment in
-the deferred error form) beside them at full size and requires identical bits.
+the deferred error form) beside them at full size and requires identical bits; the last one
+compares the worker passes without compensation that bench.py times for C2 and C5.
 """
 import pytest
 import torch
@@ -115,3 +116,34 @@ def test_timed_call_sequence_equals_three_calls(gpu_device, which):
     finally:
         three.close()
         timed.close()
+
+
+@pytest.mark.parametrize("which", ["c2", "c5"])
+def test_uncompensated_worker_pass_full_size(gpu_device, which):
+    """bench.py also times the worker pass without compensation (DS_FLAG_NO_ERROR_FEEDBACK) at
+    the full sizes of C2 and C5: every word of every row's message against the oracle (which has
+    no such flag: its worker starts from a zero error that is thrown away)."""
+    import numpy as np
+    import oracle as O
+
+    wl = getattr(W, which)()
+    parity_util.CONTEXT_FLAGS = P.FLAG_NO_ERROR_FEEDBACK
+    try:
+        ctx = parity_util.gpu_context(wl)
+    finally:
+        parity_util.CONTEXT_FLAGS = 0
+    try:
+        cfg = parity_util.oracle_config(wl)
+        one = O.Config(cfg.comp, n=1, d=wl.d, grad_bf16=(wl.grad_dtype == "bf16"), group_off=wl.group_offsets(),
+                       sign_rms=wl.sign_rms)
+        pw = ctx.alloc_payload(wl.n, gpu_device)
+        g = wl.gradients(0, gpu_device)
+        ctx.worker_compress(5, g, None, pw)
+        got = pw.to_numpy()
+        h_g = parity_util.host_grad(g)
+        del g
+        for i in range(wl.n):                                     # row by row: bounded host memory
+            ref = O.worker_compress(one, 5, h_g[i:i + 1], np.zeros((1, wl.d), np.float32))
+            parity_util.assert_payload_equal({k: v[i:i + 1] for k, v in got.items()}, ref, f"{which} row {i}")
+    finally:
+        ctx.close()
